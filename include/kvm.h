@@ -1,0 +1,295 @@
+/*
+ * kvm.h — C ABI of the per-decode-step KV-cache management pass.
+ *
+ * The pass manages a paged KV cache whose eviction granularity is one
+ * (layer, KV-head, token-block) slice, called a *unit* here (head-granular
+ * eviction, paper section 3.4).  Per decode step it
+ *   1. folds observed reuse events into the 16 Beta posteriors  (section 3.3, Eq. 5)
+ *   2. scores every resident unit by the softmax attention mass it receives
+ *      from the step's queries                                   (Eq. 1, section 3.4)
+ *   3. folds the masses into an exponential moving average and forms an
+ *      eviction priority = head weight x EMA x posterior reuse probability
+ *   4. selects the k lowest-priority units under a capacity budget
+ *   5. moves victim / prefetch units between the HBM pool (tier 0) and
+ *      pinned host memory (tier 1)                               (section 3.2)
+ * kvm_size implements the architecture-aware sizing of section 3.1 (Eq. 3, 4).
+ *
+ * Conventions
+ *   - Plain C, no exceptions, no allocations handed across the boundary.  The
+ *     caller owns every buffer; the library keeps nothing between calls except
+ *     an optional pair of internal HIP events used for kernel timing.
+ *   - "dev" = pointer to device (HBM) memory, "host" = ordinary host memory,
+ *     "pinned" = page-locked host memory that the GPU can reach.
+ *   - Every function returns KVM_OK (0) or a negative KVM_E* code; a text for the
+ *     last failure on the calling thread is returned by kvm_last_error().
+ *     Arguments are validated on the host before anything is launched; a call
+ *     that returns an error has launched nothing.
+ *   - Device functions are asynchronous on the HIP stream passed as `stream`
+ *     (a hipStream_t cast to void*; NULL = the default stream).
+ *
+ * Data model
+ *   row   = (sequence, layer, KV head): one softmax domain of row_ntok tokens,
+ *           ceil(row_ntok / 16) blocks.
+ *   uid   = row_off[row] + block : index of a unit in all per-unit arrays
+ *           (slot_tbl, mass, S, prio, state, pair).  Rows must not overlap in
+ *           uid space; gaps are allowed (their state must be 0).
+ *   slot  = index of a unit-sized frame in the HBM pool.
+ *   slot_tbl[uid] >= 0 : the unit lives in pool frame slot_tbl[uid]
+ *   slot_tbl[uid] <  0 : not in HBM; -1 - slot_tbl[uid] is the caller's label of
+ *                        its place in the host tier.
+ *
+ * K unit layout (unit_k_bytes = 16 * dim * 2 bytes, 16-bit elements):
+ *   element (token t, channel c) sits at element index (c / 8) * 128 + t * 8 + c % 8,
+ *   i.e. [dim/8][16 tokens][8 channels]: the 16 tokens of one 8-channel group are
+ *   contiguous 16-byte vectors.  This is the key-cache layout of the original
+ *   PagedAttention kernel restricted to one head; a wavefront that reads 1 KiB
+ *   of it gets 16 tokens x 4 channel groups with no shuffling.
+ *   For MLA the unit holds the latent (d_latent + d_rope channels) in the same
+ *   layout and there is no V.  V units are opaque bytes to this library.
+ */
+#ifndef KVM_H
+#define KVM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- return codes ------------------------------------------------------ */
+#define KVM_OK       0
+#define KVM_EINVAL  (-1)   /* null pointer, negative count, value out of range   */
+#define KVM_ESHAPE  (-2)   /* a shape this build has no kernel for               */
+#define KVM_ENOSPC  (-3)   /* workspace / staging / output capacity too small    */
+#define KVM_EHIP    (-4)   /* a HIP runtime call failed                          */
+
+/* ---- element types of K and q ----------------------------------------- */
+#define KVM_BF16 0
+#define KVM_FP16 1
+
+/* ---- attention architectures (section 3.1) ----------------------------- */
+#define KVM_ARCH_MHA 0
+#define KVM_ARCH_GQA 1
+#define KVM_ARCH_MQA 2
+#define KVM_ARCH_MLA 3
+
+/* ---- per-unit state byte ------------------------------------------------ */
+#define KVM_ST_RESIDENT  1u   /* unit is in an HBM pool frame                    */
+#define KVM_ST_ON_HOST   2u   /* unit has been packed to the host tier           */
+#define KVM_ST_PROTECTED 4u   /* never a victim (e.g. the block being written)   */
+#define KVM_ST_SCORED    8u   /* S holds at least one observation                */
+
+/* ---- group aggregation in kvm_score_step -------------------------------- */
+#define KVM_AGG_MAX  0        /* max over the query heads sharing the KV head    */
+#define KVM_AGG_MEAN 1        /* mean over them (per-head masses then sum to 1)  */
+
+#define KVM_BLOCK_TOKENS 16
+#define KVM_N_PAIRS      16   /* 4 block types x 4 transition types              */
+
+/* ======================================================================== *
+ * Sizing — section 3.1, Eq. 3 and Eq. 4.  Host only, no device work.
+ * ======================================================================== */
+typedef struct kvm_model {
+    int32_t n_layers;       /* L                                                  */
+    int32_t n_q_heads;      /* h_q                                                */
+    int32_t n_kv_heads;     /* h_kv; must divide h_q                              */
+    int32_t head_dim;       /* d                                                  */
+    int32_t d_latent;       /* > 0 selects MLA                                    */
+    int32_t d_rope;         /* MLA rope channels stored beside the latent         */
+    int32_t bits_per_elem;  /* 16 (bf16/fp16), 8, 4 (p = 0.5 bytes)               */
+    int32_t block_tokens;   /* tokens per block, > 0                              */
+    int32_t head_divisor;   /* tensor-parallel divisor applied to KV heads, >= 1;
+                               ignored for MLA (the latent is not split)          */
+} kvm_model_t;
+
+typedef struct kvm_sizing {
+    int32_t  arch;                   /* KVM_ARCH_*                                */
+    int32_t  group_size;             /* g = h_q / h_kv (MLA: h_q)                 */
+    uint64_t bytes_per_token_layer;  /* B(1) of Eq. 3                             */
+    uint64_t bytes_per_token;        /* L * B(1)                                  */
+    uint64_t bytes_per_seq;          /* L * B(n_max)                              */
+    uint64_t max_batch;              /* floor(M_target / (L * B(n_max))), Eq. 4   */
+    uint32_t units_per_block;        /* units one token block spans: L * h_kv / head_divisor (MLA: L) */
+    uint32_t unit_k_bytes;           /* block_tokens * d * p (MLA: latent + rope) */
+    uint32_t unit_v_bytes;           /* same for V; 0 for MLA                     */
+    uint64_t pool_units;             /* floor(M_target / (unit_k + unit_v))       */
+} kvm_sizing_t;
+
+/* Architecture inference: d_latent > 0 -> MLA; else h_q == h_kv -> MHA;
+ * else h_kv == 1 -> MQA; else GQA.  Byte counts with fractional p are exact
+ * when the product is a whole number of bytes, else KVM_EINVAL.
+ * n_max = 0 is allowed (bytes_per_seq = 0, max_batch = 0).
+ * Errors: KVM_EINVAL for null pointers, non-positive dimensions,
+ * h_q % h_kv != 0, h_kv % head_divisor != 0, bits not in {4, 8, 16, 32}.      */
+int kvm_size(const kvm_model_t* model, uint64_t n_max, uint64_t mem_target_bytes,
+             kvm_sizing_t* out /* host */);
+
+/* ======================================================================== *
+ * Pool and row descriptors shared by the device entry points
+ * ======================================================================== */
+typedef struct kvm_pool {
+    void*    k_pool;        /* dev: n_slots frames of unit_k_bytes                */
+    void*    v_pool;        /* dev: n_slots frames of unit_v_bytes; NULL iff unit_v_bytes == 0 */
+    uint64_t n_slots;
+    int32_t  dim;           /* channels per token in a K unit (head_dim, or 576 for MLA); multiple of 32 */
+    int32_t  dtype;         /* KVM_BF16 / KVM_FP16                                */
+    uint32_t unit_k_bytes;  /* must equal 16 * dim * 2                            */
+    uint32_t unit_v_bytes;  /* multiple of 16                                     */
+} kvm_pool_t;
+
+typedef struct kvm_rows {
+    int32_t        n_rows;
+    int32_t        g;          /* queries per row (heads sharing the KV head), 1..128 */
+    int64_t        n_uids;     /* length of every per-unit array                  */
+    const int32_t* row_ntok;   /* dev [n_rows] valid tokens in the row, >= 0      */
+    const int64_t* row_off;    /* dev [n_rows] uid of the row's block 0           */
+    const int64_t* row_q_off;  /* dev [n_rows] element offset of the row's g x dim queries in q;
+                                  multiple of 8; unused for inactive rows         */
+    const uint8_t* row_active; /* dev [n_rows] or NULL (= all active). 0 marks a row that is not
+                                  decoding this step: it is not scored and its S is left alone  */
+    const int32_t* slot_tbl;   /* dev [n_uids]                                    */
+} kvm_rows_t;
+/* A fleet that mixes architectures passes one kvm_rows_t per architecture
+ * (different g) over the same per-unit arrays. */
+
+/* ======================================================================== *
+ * 2. Scoring — Eq. 1 restricted to the HBM-resident tokens of each row.
+ *
+ * For an active row with n = row_ntok tokens and resident blocks R, for each
+ * query j < g:   z_t = softmax_scale * <q_j, k_t>  for tokens t < n in blocks of R,
+ * p = softmax(z) over those tokens, m_j[b] = sum of p over block b.
+ * mass[uid(b)] = max_j m_j[b] (KVM_AGG_MAX; the GQA grouping rule of section 3.4)
+ * or mean_j.  Entries of non-resident blocks, of blocks beyond the row's
+ * length and of inactive rows are not written.  Tokens at or beyond n in the
+ * last block are ignored whatever bytes the pool holds there.
+ * fp32 accumulation; masses agree with an exact evaluation to ~1e-5 relative.
+ *
+ * q: dev, dtype of the pool, g x dim contiguous per row at row_q_off.
+ * ws: dev scratch of at least kvm_workspace_bytes(KVM_OP_SCORE, ...) bytes,
+ *     256-byte aligned; contents are garbage afterwards.
+ * Errors: KVM_EINVAL (null pointers, agg), KVM_ESHAPE (dim % 32, g out of
+ * range, dtype, unit_k_bytes mismatch), KVM_ENOSPC (ws_bytes too small),
+ * KVM_EHIP.  n_rows == 0 or n_uids == 0 is a successful no-op.              */
+int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
+                   float softmax_scale, int agg, float* mass /* dev [n_uids] */,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* ======================================================================== *
+ * 1. Beta posteriors — section 3.3, Eq. 5.
+ *
+ * pair = 4 * block_type + transition_type, types numbered in the order the
+ * paper lists them (system_prompt, tool_context, user_context,
+ * intermediate_reasoning; same_tool_repeat, tool_switch, reasoning_step,
+ * agent_handoff).  For each event: outcome 1 (reuse) -> hits[pair] += 1,
+ * outcome 0 (miss) -> misses[pair] += 1.  Events with pair >= 16 or
+ * outcome > 1 change no counter and are counted in *n_bad (if not NULL).
+ * Then p_hat[i] = (alpha0 + hits[i]) / (alpha0 + beta0 + hits[i] + misses[i]).
+ * Counters are exact integers (order-independent); p_hat is fp32.
+ * n_events == 0 just refreshes p_hat.
+ * Errors: KVM_EINVAL (null pointers, n_events < 0, alpha0/beta0 not > 0).   */
+int kvm_beta_update(const uint8_t* ev_pair /* dev [n_events] */,
+                    const uint8_t* ev_outcome /* dev [n_events] */, int64_t n_events,
+                    uint32_t* hits /* dev [16] in/out */, uint32_t* misses /* dev [16] in/out */,
+                    float alpha0, float beta0, float* p_hat /* dev [16] out */,
+                    uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+/* ======================================================================== *
+ * 3. EMA of the masses and eviction priority — section 3.4.
+ *
+ * For every block b < ceil(row_ntok/16) of every row r, uid = row_off[r] + b:
+ *   if the row is active and state[uid] has RESIDENT (the unit was scored this step):
+ *       first observation (SCORED clear):  S[uid] = mass[uid], set SCORED
+ *       otherwise:                         S[uid] = decay * S[uid] + (1 - decay) * mass[uid]
+ *   prio[uid] = row_weight[r] * S[uid] * p_hat[pair[uid]]  if SCORED, else +inf.
+ * row_weight carries the architecture-dependent head weight (1 for MHA and MLA,
+ * the group size for GQA/MQA) times any per-head multiplier.
+ * Errors: KVM_EINVAL (null pointers, decay outside [0, 1]).                 */
+int kvm_ema_update(const kvm_rows_t* rows, const float* mass /* dev [n_uids] */, float ema_decay,
+                   const float* row_weight /* dev [n_rows] */, const uint8_t* pair /* dev [n_uids], < 16 */,
+                   const float* p_hat /* dev [16] */, uint8_t* state /* dev [n_uids] in/out */,
+                   float* S /* dev [n_uids] in/out */, float* prio /* dev [n_uids] out */, void* stream);
+
+/* ======================================================================== *
+ * 4. Victim selection — "lowest weighted aggregate importance", section 3.4,
+ *    generalised to the k lowest under a capacity budget.
+ *
+ * eligible = RESIDENT and not PROTECTED and SCORED.
+ * k = k_or_neg1 if >= 0, else max(0, #RESIDENT - budget_units);
+ * k is then clipped to #eligible and to victims_cap.
+ * Output: the k eligible uids smallest under the total order (prio, uid)
+ * (NaN priorities rank as +inf, -0 as +0), written in ascending uid order to
+ * victims[0..k), and k to *n_victims.  Both on the device; nothing is copied
+ * to the host.  ws as for kvm_score_step with KVM_OP_SELECT.
+ * Errors: KVM_EINVAL (null pointers, negative sizes, k < -1), KVM_ENOSPC.   */
+int kvm_select_victims(const float* prio /* dev [n_uids] */, const uint8_t* state /* dev [n_uids] */,
+                       int64_t n_uids, int64_t k_or_neg1, int64_t budget_units,
+                       int64_t* victims /* dev [victims_cap] */, int64_t victims_cap,
+                       int64_t* n_victims /* dev [1] */, void* ws, size_t ws_bytes, void* stream);
+
+/* ======================================================================== *
+ * 5. Pack / unpack — tier 0 (HBM pool) <-> tier 1 (pinned host), section 3.2.
+ *
+ * kvm_pack, for i < n in list order, uid = uids[i], slot = slot_tbl[uid]:
+ *   staging[i] = K frame `slot` (unit_k_bytes) followed by V frame `slot`
+ *   (unit_v_bytes); freed_slots[i] = slot; slot_tbl[uid] = -1 - host_slots[i];
+ *   state[uid]: clear RESIDENT, set ON_HOST.
+ * Entries whose uid is outside [0, n_uids) or not resident (or whose slot is
+ * outside the pool) move nothing, get freed_slots[i] = -1, leave their staging
+ * record untouched and are counted in *n_bad.  uids must be distinct.
+ * The records are gathered into staging_dev in chunks and copied to
+ * staging_host with hipMemcpyAsync on `stream`; when staging_dev is NULL the
+ * gather kernel writes the pinned host buffer directly.
+ * staging_host must hold n * (unit_k_bytes + unit_v_bytes) bytes;
+ * staging_dev_bytes must hold at least one record.
+ *
+ * kvm_unpack is the inverse: record i of staging_host goes to pool frame
+ * dst_slots[i]; slot_tbl[uid] = dst_slots[i]; state: set RESIDENT, clear
+ * ON_HOST.  Entries with a bad uid, an already-resident uid or a dst slot
+ * outside the pool are skipped and counted.
+ * Both are asynchronous: staging_host may be read (pack) or reused (unpack)
+ * once `stream` has drained.
+ * Errors: KVM_EINVAL (null pointers, n < 0), KVM_ENOSPC (staging too small). */
+int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+             int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n,
+             const int32_t* host_slots /* dev [n] */, int32_t* freed_slots /* dev [n] out */,
+             void* staging_dev /* dev or NULL */, size_t staging_dev_bytes,
+             void* staging_host /* pinned */, size_t staging_host_bytes,
+             uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+               int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n,
+               const int32_t* dst_slots /* dev [n] */,
+               void* staging_dev /* dev or NULL */, size_t staging_dev_bytes,
+               const void* staging_host /* pinned */, size_t staging_host_bytes,
+               uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+/* ======================================================================== *
+ * Helpers
+ * ======================================================================== */
+#define KVM_OP_SCORE  0
+#define KVM_OP_SELECT 1
+/* Bytes of device scratch the op needs for these sizes (g, dim ignored by SELECT). */
+size_t kvm_workspace_bytes(int op, int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim);
+
+/* Text describing the last error returned on this thread ("" if none). */
+const char* kvm_last_error(void);
+
+/* Library version, "major.minor". */
+const char* kvm_version(void);
+
+/* Kernel timing.  While enabled, the device entry points bracket each kernel
+ * they launch with HIP events on the caller's stream.  kvm_timing_read
+ * synchronises on the recorded events, adds up the elapsed time of every
+ * launch of the kernel called `name` since the last kvm_timing_reset, and
+ * returns the launch count (0 if the name is unknown); *total_ms gets the sum.
+ * Names: "score_partial", "score_finalize", "score_plan", "ema_prio",
+ * "beta", "select_hist", "select_scan", "select_emit", "pack", "unpack".    */
+int  kvm_timing_enable(int on);
+void kvm_timing_reset(void);
+int  kvm_timing_read(const char* name, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVM_H */

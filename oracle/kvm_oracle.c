@@ -1,0 +1,380 @@
+/*
+ * kvm_oracle.c — plain CPU reference for the KV-cache management pass.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the yardstick the GPU library is
+ * checked against; nothing in the product path may call it.  It shares no code
+ * with the GPU library: formats (bf16/fp16 decoding, the K unit layout, the
+ * state bits) are restated here from their definitions.
+ *
+ * Everything is written as the defining formula, in double precision, with no
+ * blocking or reordering beyond "for each row, for each query, for each
+ * token".  The only parallelism is an OpenMP loop over rows in the scorer.
+ *
+ * What each function follows:
+ *   kvm_ref_size            section 3.1, Eq. 3 (per-layer bytes) and Eq. 4 / the
+ *                           max-batch formula that follows it
+ *   kvm_ref_score_step      Eq. 1 (softmax(q k^T / sqrt(d))) summed per token block;
+ *                           group maximum of section 3.4
+ *   kvm_ref_ema_update      section 3.4 (EMA importance, head weights) times the
+ *                           posterior mean of Eq. 5
+ *   kvm_ref_beta_update     section 3.3, Eq. 5 and the update rule after it
+ *   kvm_ref_select_victims  section 3.4 ("lowest weighted aggregate importance"),
+ *                           as a full sort
+ *   kvm_ref_pack / unpack   section 3.2 (tier 0 <-> tier 1 moves), as memcpy
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * (paper tables, closed forms, library routines, brute force); none is
+ * "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define REF_OK      0
+#define REF_EINVAL (-1)
+
+enum { ST_RESIDENT = 1, ST_ON_HOST = 2, ST_PROTECTED = 4, ST_SCORED = 8 };
+
+/* ---------------------------------------------------------------- formats */
+
+/* bfloat16: the upper 16 bits of an IEEE binary32. */
+static double bf16_to_double(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+static double fp16_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1f;
+    int frac = h & 0x3ff;
+    double v;
+    if (expo == 0)
+        v = ldexp((double)frac, -24);                 /* subnormal: frac * 2^-10 * 2^-14 */
+    else if (expo == 31)
+        v = frac ? NAN : INFINITY;
+    else
+        v = ldexp(1.0 + (double)frac / 1024.0, expo - 15);
+    return sign ? -v : v;
+}
+
+static double elem_to_double(const uint16_t* p, int dtype) {
+    return dtype == 0 ? bf16_to_double(*p) : fp16_to_double(*p);
+}
+
+/* Exposed so that the decoders can be checked exhaustively against a library. */
+double kvm_ref_decode(uint16_t bits, int dtype) { return elem_to_double(&bits, dtype); }
+
+/* Index of (token t, channel c) inside a K unit laid out as
+ * [dim/8][block_tokens][8]. */
+static size_t k_elem_index(int t, int c, int block_tokens) {
+    return (size_t)(c / 8) * (size_t)block_tokens * 8 + (size_t)t * 8 + (size_t)(c % 8);
+}
+
+/* ----------------------------------------------------------------- sizing */
+
+typedef struct {
+    int32_t n_layers, n_q_heads, n_kv_heads, head_dim, d_latent, d_rope;
+    int32_t bits_per_elem, block_tokens, head_divisor;
+} ref_model_t;
+
+typedef struct {
+    int32_t  arch, group_size;
+    uint64_t bytes_per_token_layer, bytes_per_token, bytes_per_seq, max_batch;
+    uint32_t units_per_block, unit_k_bytes, unit_v_bytes;
+    uint64_t pool_units;
+} ref_sizing_t;
+
+int kvm_ref_size(const ref_model_t* m, uint64_t n_max, uint64_t mem_target, ref_sizing_t* o) {
+    if (!m || !o) return REF_EINVAL;
+    if (m->n_layers <= 0 || m->block_tokens <= 0 || m->head_divisor <= 0) return REF_EINVAL;
+    if (m->bits_per_elem != 4 && m->bits_per_elem != 8 && m->bits_per_elem != 16 &&
+        m->bits_per_elem != 32)
+        return REF_EINVAL;
+    memset(o, 0, sizeof *o);
+    uint64_t bits_tok_layer;      /* B(1) in bits */
+    uint64_t k_channels, v_channels, heads;
+    if (m->d_latent > 0) {                                   /* MLA */
+        if (m->d_rope < 0 || m->n_q_heads <= 0) return REF_EINVAL;
+        o->arch = 3;
+        o->group_size = m->n_q_heads;
+        k_channels = (uint64_t)m->d_latent + (uint64_t)m->d_rope;
+        v_channels = 0;
+        heads = 1;
+        bits_tok_layer = k_channels * (uint64_t)m->bits_per_elem;
+    } else {
+        if (m->n_q_heads <= 0 || m->n_kv_heads <= 0 || m->head_dim <= 0) return REF_EINVAL;
+        if (m->n_q_heads % m->n_kv_heads) return REF_EINVAL;
+        if (m->n_kv_heads % m->head_divisor) return REF_EINVAL;
+        if (m->n_q_heads == m->n_kv_heads) o->arch = 0;      /* MHA */
+        else if (m->n_kv_heads == 1)       o->arch = 2;      /* MQA */
+        else                               o->arch = 1;      /* GQA */
+        o->group_size = m->n_q_heads / m->n_kv_heads;
+        heads = (uint64_t)(m->n_kv_heads / m->head_divisor);
+        k_channels = v_channels = (uint64_t)m->head_dim;
+        bits_tok_layer = 2 * heads * (uint64_t)m->head_dim * (uint64_t)m->bits_per_elem;
+    }
+    if (bits_tok_layer % 8) return REF_EINVAL;
+    uint64_t unit_k_bits = (uint64_t)m->block_tokens * k_channels * (uint64_t)m->bits_per_elem;
+    uint64_t unit_v_bits = (uint64_t)m->block_tokens * v_channels * (uint64_t)m->bits_per_elem;
+    if (unit_k_bits % 8 || unit_v_bits % 8) return REF_EINVAL;
+    o->bytes_per_token_layer = bits_tok_layer / 8;
+    o->bytes_per_token = o->bytes_per_token_layer * (uint64_t)m->n_layers;
+    o->bytes_per_seq = o->bytes_per_token * n_max;
+    o->max_batch = o->bytes_per_seq ? mem_target / o->bytes_per_seq : 0;
+    o->units_per_block = (uint32_t)((uint64_t)m->n_layers * heads);
+    o->unit_k_bytes = (uint32_t)(unit_k_bits / 8);
+    o->unit_v_bytes = (uint32_t)(unit_v_bits / 8);
+    o->pool_units = mem_target / ((uint64_t)o->unit_k_bytes + o->unit_v_bytes);
+    return REF_OK;
+}
+
+/* ---------------------------------------------------------------- scoring */
+
+/* mass_q (optional, may be NULL): per-query block masses in double,
+ * mass_q[uid * g + j]; written for the same units as mass. */
+int kvm_ref_score_step(const uint16_t* k_pool, uint64_t n_slots, int dim, int dtype, int block_tokens,
+                       int n_rows, int g, int64_t n_uids,
+                       const int32_t* row_ntok, const int64_t* row_off, const int64_t* row_q_off,
+                       const uint8_t* row_active, const int32_t* slot_tbl,
+                       const uint16_t* q, double softmax_scale, int agg,
+                       float* mass, double* mass_q) {
+    if (!k_pool || !row_ntok || !row_off || !row_q_off || !slot_tbl || !q || !mass) return REF_EINVAL;
+    if (dim <= 0 || dim % 8 || g <= 0 || block_tokens <= 0 || (agg != 0 && agg != 1)) return REF_EINVAL;
+    const size_t unit_elems = (size_t)block_tokens * (size_t)dim;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(|:bad)
+    for (int r = 0; r < n_rows; ++r) {
+        if (row_active && !row_active[r]) continue;
+        const int n = row_ntok[r];
+        if (n <= 0) continue;
+        const int nb = (n + block_tokens - 1) / block_tokens;
+        if (row_off[r] < 0 || row_off[r] + nb > n_uids) { bad = 1; continue; }
+        double* z = (double*)malloc(sizeof(double) * (size_t)n);
+        double* mb = (double*)malloc(sizeof(double) * (size_t)nb * (size_t)g);
+        for (int j = 0; j < g; ++j) {
+            const uint16_t* qj = q + row_q_off[r] + (int64_t)j * dim;
+            /* logits of the resident tokens */
+            double zmax = -INFINITY;
+            for (int t = 0; t < n; ++t) {
+                const int b = t / block_tokens;
+                const int32_t slot = slot_tbl[row_off[r] + b];
+                if (slot < 0) continue;
+                if ((uint64_t)slot >= n_slots) { bad = 1; continue; }
+                const uint16_t* unit = k_pool + (size_t)slot * unit_elems;
+                double dot = 0.0;
+                for (int c = 0; c < dim; ++c)
+                    dot += elem_to_double(qj + c, dtype) *
+                           elem_to_double(unit + k_elem_index(t % block_tokens, c, block_tokens), dtype);
+                z[t] = softmax_scale * dot;
+                if (z[t] > zmax) zmax = z[t];
+            }
+            /* softmax normaliser over the resident tokens */
+            double Z = 0.0;
+            for (int t = 0; t < n; ++t) {
+                const int32_t slot = slot_tbl[row_off[r] + t / block_tokens];
+                if (slot < 0 || (uint64_t)slot >= n_slots) continue;
+                Z += exp(z[t] - zmax);
+            }
+            /* mass per block */
+            for (int b = 0; b < nb; ++b) {
+                double s = 0.0;
+                const int32_t slot = slot_tbl[row_off[r] + b];
+                if (slot >= 0 && (uint64_t)slot < n_slots) {
+                    for (int t = b * block_tokens; t < n && t < (b + 1) * block_tokens; ++t)
+                        s += exp(z[t] - zmax);
+                    s /= Z;
+                }
+                mb[(size_t)b * g + j] = s;
+            }
+        }
+        for (int b = 0; b < nb; ++b) {
+            const int64_t uid = row_off[r] + b;
+            const int32_t slot = slot_tbl[uid];
+            if (slot < 0 || (uint64_t)slot >= n_slots) continue;
+            double a = (agg == 0) ? -INFINITY : 0.0;
+            for (int j = 0; j < g; ++j) {
+                const double v = mb[(size_t)b * g + j];
+                if (agg == 0) { if (v > a) a = v; } else a += v;
+                if (mass_q) mass_q[uid * g + j] = v;
+            }
+            if (agg == 1) a /= (double)g;
+            mass[uid] = (float)a;
+        }
+        free(z);
+        free(mb);
+    }
+    return bad ? REF_EINVAL : REF_OK;
+}
+
+/* ------------------------------------------------------------------- beta */
+
+int kvm_ref_beta_update(const uint8_t* ev_pair, const uint8_t* ev_outcome, int64_t n_events,
+                        uint32_t* hits, uint32_t* misses, double alpha0, double beta0,
+                        float* p_hat, uint32_t* n_bad) {
+    if (n_events < 0 || !hits || !misses || !p_hat) return REF_EINVAL;
+    if (n_events > 0 && (!ev_pair || !ev_outcome)) return REF_EINVAL;
+    if (!(alpha0 > 0.0) || !(beta0 > 0.0)) return REF_EINVAL;
+    for (int64_t e = 0; e < n_events; ++e) {
+        if (ev_pair[e] >= 16 || ev_outcome[e] > 1) { if (n_bad) ++*n_bad; continue; }
+        if (ev_outcome[e]) hits[ev_pair[e]] += 1; else misses[ev_pair[e]] += 1;
+    }
+    for (int i = 0; i < 16; ++i) {
+        const double a = alpha0 + (double)hits[i];
+        const double b = beta0 + (double)misses[i];
+        p_hat[i] = (float)(a / (a + b));
+    }
+    return REF_OK;
+}
+
+/* -------------------------------------------------------- EMA + priority */
+
+int kvm_ref_ema_update(int n_rows, int block_tokens, int64_t n_uids,
+                       const int32_t* row_ntok, const int64_t* row_off, const uint8_t* row_active,
+                       const float* mass, double decay, const float* row_weight,
+                       const uint8_t* pair, const float* p_hat,
+                       uint8_t* state, float* S, float* prio) {
+    if (!row_ntok || !row_off || !mass || !row_weight || !pair || !p_hat || !state || !S || !prio)
+        return REF_EINVAL;
+    if (!(decay >= 0.0 && decay <= 1.0) || block_tokens <= 0) return REF_EINVAL;
+    for (int r = 0; r < n_rows; ++r) {
+        const int n = row_ntok[r];
+        const int nb = n > 0 ? (n + block_tokens - 1) / block_tokens : 0;
+        if (nb && (row_off[r] < 0 || row_off[r] + nb > n_uids)) return REF_EINVAL;
+        const int active = row_active ? row_active[r] != 0 : 1;
+        for (int b = 0; b < nb; ++b) {
+            const int64_t uid = row_off[r] + b;
+            if (active && (state[uid] & ST_RESIDENT)) {
+                const double x = (double)mass[uid];
+                if (!(state[uid] & ST_SCORED)) {
+                    S[uid] = (float)x;
+                    state[uid] |= ST_SCORED;
+                } else {
+                    S[uid] = (float)(decay * (double)S[uid] + (1.0 - decay) * x);
+                }
+            }
+            if (state[uid] & ST_SCORED)
+                prio[uid] = (float)((double)row_weight[r] * (double)S[uid] * (double)p_hat[pair[uid] & 15]);
+            else
+                prio[uid] = INFINITY;
+        }
+    }
+    return REF_OK;
+}
+
+/* ----------------------------------------------------------------- select */
+
+typedef struct { float prio; int64_t uid; } cand_t;
+
+static int cand_cmp(const void* a, const void* b) {
+    const cand_t* x = (const cand_t*)a;
+    const cand_t* y = (const cand_t*)b;
+    if (x->prio < y->prio) return -1;
+    if (x->prio > y->prio) return 1;
+    return (x->uid > y->uid) - (x->uid < y->uid);
+}
+
+static int i64_cmp(const void* a, const void* b) {
+    const int64_t x = *(const int64_t*)a, y = *(const int64_t*)b;
+    return (x > y) - (x < y);
+}
+
+int kvm_ref_select_victims(const float* prio, const uint8_t* state, int64_t n_uids,
+                           int64_t k_or_neg1, int64_t budget_units,
+                           int64_t* victims, int64_t victims_cap, int64_t* n_victims) {
+    if (!prio || !state || !victims || !n_victims || n_uids < 0 || k_or_neg1 < -1 ||
+        budget_units < 0 || victims_cap < 0)
+        return REF_EINVAL;
+    cand_t* c = (cand_t*)malloc(sizeof(cand_t) * (size_t)(n_uids ? n_uids : 1));
+    int64_t n_el = 0, n_res = 0;
+    for (int64_t u = 0; u < n_uids; ++u) {
+        if (state[u] & ST_RESIDENT) ++n_res;
+        if ((state[u] & ST_RESIDENT) && !(state[u] & ST_PROTECTED) && (state[u] & ST_SCORED)) {
+            float p = prio[u];
+            if (isnan(p)) p = INFINITY;      /* NaN ranks last */
+            c[n_el].prio = p;                /* -0 == +0 under float comparison */
+            c[n_el].uid = u;
+            ++n_el;
+        }
+    }
+    int64_t k = k_or_neg1 >= 0 ? k_or_neg1 : (n_res > budget_units ? n_res - budget_units : 0);
+    if (k > n_el) k = n_el;
+    if (k > victims_cap) k = victims_cap;
+    qsort(c, (size_t)n_el, sizeof(cand_t), cand_cmp);
+    for (int64_t i = 0; i < k; ++i) victims[i] = c[i].uid;
+    qsort(victims, (size_t)k, sizeof(int64_t), i64_cmp);
+    *n_victims = k;
+    free(c);
+    return REF_OK;
+}
+
+/* ---------------------------------------------------------- pack / unpack */
+
+int kvm_ref_pack(const uint8_t* k_pool, const uint8_t* v_pool, uint64_t n_slots,
+                 uint32_t unit_k_bytes, uint32_t unit_v_bytes,
+                 int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                 const int64_t* uids, int64_t n, const int32_t* host_slots,
+                 int32_t* freed_slots, uint8_t* staging, uint32_t* n_bad) {
+    if (!k_pool || (unit_v_bytes && !v_pool) || !slot_tbl || !state || n < 0) return REF_EINVAL;
+    if (n > 0 && (!uids || !host_slots || !freed_slots || !staging)) return REF_EINVAL;
+    const size_t rec = (size_t)unit_k_bytes + unit_v_bytes;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t uid = uids[i];
+        int32_t slot = -1;
+        if (uid >= 0 && uid < n_uids && (state[uid] & ST_RESIDENT)) slot = slot_tbl[uid];
+        if (slot < 0 || (uint64_t)slot >= n_slots) {
+            freed_slots[i] = -1;
+            if (n_bad) ++*n_bad;
+            continue;
+        }
+        memcpy(staging + (size_t)i * rec, k_pool + (size_t)slot * unit_k_bytes, unit_k_bytes);
+        if (unit_v_bytes)
+            memcpy(staging + (size_t)i * rec + unit_k_bytes, v_pool + (size_t)slot * unit_v_bytes,
+                   unit_v_bytes);
+        freed_slots[i] = slot;
+        slot_tbl[uid] = -1 - host_slots[i];
+        state[uid] = (uint8_t)((state[uid] & ~ST_RESIDENT) | ST_ON_HOST);
+    }
+    return REF_OK;
+}
+
+int kvm_ref_unpack(uint8_t* k_pool, uint8_t* v_pool, uint64_t n_slots,
+                   uint32_t unit_k_bytes, uint32_t unit_v_bytes,
+                   int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                   const int64_t* uids, int64_t n, const int32_t* dst_slots,
+                   const uint8_t* staging, uint32_t* n_bad) {
+    if (!k_pool || (unit_v_bytes && !v_pool) || !slot_tbl || !state || n < 0) return REF_EINVAL;
+    if (n > 0 && (!uids || !dst_slots || !staging)) return REF_EINVAL;
+    const size_t rec = (size_t)unit_k_bytes + unit_v_bytes;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t uid = uids[i];
+        const int32_t slot = dst_slots[i];
+        if (uid < 0 || uid >= n_uids || (state[uid] & ST_RESIDENT) || slot < 0 ||
+            (uint64_t)slot >= n_slots) {
+            if (n_bad) ++*n_bad;
+            continue;
+        }
+        memcpy(k_pool + (size_t)slot * unit_k_bytes, staging + (size_t)i * rec, unit_k_bytes);
+        if (unit_v_bytes)
+            memcpy(v_pool + (size_t)slot * unit_v_bytes, staging + (size_t)i * rec + unit_k_bytes,
+                   unit_v_bytes);
+        slot_tbl[uid] = slot;
+        state[uid] = (uint8_t)((state[uid] & ~ST_ON_HOST) | ST_RESIDENT);
+    }
+    return REF_OK;
+}
+
+/* Number of OpenMP threads the scorer will use (for reporting). */
+int kvm_ref_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,229 @@
+"""Seeded synthetic inputs for the KV-cache management pass.
+
+This module only *makes data*: random pools, queries, block tables, event
+streams, with the shapes of the benchmark configurations.  It contains none of
+the method's arithmetic (no softmax, EMA, posterior, selection) and is the one
+module that both the GPU tests and the CPU oracle tests draw inputs from.
+
+16-bit floating point data is carried as ``uint16`` bit patterns in numpy.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+BF16, FP16 = 0, 1
+BLOCK = 16
+
+
+# ----------------------------------------------------------------- formats
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns, round to nearest even (NaN kept quiet)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    rounded = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    nan = np.isnan(x)
+    out = rounded.astype(np.uint16)
+    if np.any(nan):
+        out = np.where(nan, np.uint16(0x7FC0), out)
+    return out
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def to_bits(x: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == BF16:
+        return f32_to_bf16_bits(x)
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def from_bits(b: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == BF16:
+        return bf16_bits_to_f32(b)
+    return b.view(np.float16).astype(np.float32)
+
+
+def unit_from_tokens(tok_bits: np.ndarray) -> np.ndarray:
+    """[16, dim] token-major bit patterns -> one K unit in pool layout [dim/8][16][8], flattened."""
+    t, dim = tok_bits.shape
+    assert t == BLOCK and dim % 8 == 0
+    return np.ascontiguousarray(tok_bits.reshape(BLOCK, dim // 8, 8).transpose(1, 0, 2)).reshape(-1)
+
+
+def tokens_from_unit(unit_bits: np.ndarray, dim: int) -> np.ndarray:
+    """Inverse of :func:`unit_from_tokens`: flattened unit -> [16, dim]."""
+    return np.ascontiguousarray(unit_bits.reshape(dim // 8, BLOCK, 8).transpose(1, 0, 2)).reshape(BLOCK, dim)
+
+
+# ------------------------------------------------------------------- cases
+@dataclass
+class Shape:
+    """One architecture's share of a workload."""
+    n_layers: int
+    n_q_heads: int
+    n_kv_heads: int          # 1 for MLA (the single latent head)
+    dim: int                 # head_dim, or d_latent + d_rope for MLA
+    dtype: int = BF16
+    has_v: bool = True
+    seq_lens: List[int] = field(default_factory=list)
+
+    @property
+    def g(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+    @property
+    def unit_k_bytes(self) -> int:
+        return BLOCK * self.dim * 2
+
+    @property
+    def unit_v_bytes(self) -> int:
+        return BLOCK * self.dim * 2 if self.has_v else 0
+
+
+@dataclass
+class Case:
+    shape: Shape
+    n_slots: int
+    k_pool: np.ndarray        # uint16 [n_slots, 16*dim]
+    v_pool: Optional[np.ndarray]  # uint16 [n_slots, 16*dim] or None
+    row_ntok: np.ndarray      # int32 [n_rows]
+    row_off: np.ndarray       # int64 [n_rows]
+    row_q_off: np.ndarray     # int64 [n_rows]
+    row_seq: np.ndarray       # int32 [n_rows] sequence index of the row
+    slot_tbl: np.ndarray      # int32 [n_uids]
+    state: np.ndarray         # uint8 [n_uids]
+    pair: np.ndarray          # uint8 [n_uids]
+    row_weight: np.ndarray    # float32 [n_rows]
+    n_uids: int
+
+    @property
+    def n_rows(self) -> int:
+        return len(self.row_ntok)
+
+
+def make_case(shape: Shape, seed: int, spare_slots: int = 0, uid_gap: int = 0,
+              pair_weights: Optional[np.ndarray] = None, protect_last: bool = True,
+              poison_tail: bool = False) -> Case:
+    """Build a fully resident paged cache for ``shape``.
+
+    Rows are ordered (sequence, layer, kv head).  Every unit gets a random pool
+    slot (a random permutation, so neighbouring blocks are scattered).  K and V
+    are i.i.d. N(0, 1) rounded to the element type.  ``uid_gap`` leaves that
+    many unused uids after every row.  ``pair`` is drawn per (sequence, block)
+    and shared by the units of that block.  The last block of every sequence
+    is marked PROTECTED when ``protect_last``.  With ``poison_tail`` the token
+    positions past a row's length hold NaN bit patterns.
+    """
+    rng = np.random.default_rng(seed)
+    L, H, dim = shape.n_layers, shape.n_kv_heads, shape.dim
+    n_seq = len(shape.seq_lens)
+    rows_ntok, rows_seq = [], []
+    for s, n in enumerate(shape.seq_lens):
+        for _ in range(L * H):
+            rows_ntok.append(n)
+            rows_seq.append(s)
+    row_ntok = np.asarray(rows_ntok, np.int32)
+    row_seq = np.asarray(rows_seq, np.int32)
+    nb = (row_ntok.astype(np.int64) + BLOCK - 1) // BLOCK
+    row_off = np.zeros(len(nb), np.int64)
+    if len(nb):
+        row_off[1:] = np.cumsum(nb[:-1] + uid_gap)
+    n_uids = int((nb + uid_gap).sum()) if len(nb) else 0
+    n_units = int(nb.sum())
+    n_slots = n_units + spare_slots
+    unit_elems = BLOCK * dim
+
+    k_pool = to_bits(rng.standard_normal((n_slots, unit_elems), dtype=np.float32), shape.dtype)
+    v_pool = (to_bits(rng.standard_normal((n_slots, unit_elems), dtype=np.float32), shape.dtype)
+              if shape.has_v else None)
+
+    perm = rng.permutation(n_slots)[:n_units].astype(np.int32)
+    slot_tbl = np.full(n_uids, -1, np.int32)
+    state = np.zeros(n_uids, np.uint8)
+    pair = np.zeros(n_uids, np.uint8)
+    if pair_weights is None:
+        pair_weights = np.full(16, 1.0 / 16)
+    seq_pairs = [rng.choice(16, size=(n + BLOCK - 1) // BLOCK, p=pair_weights).astype(np.uint8)
+                 for n in shape.seq_lens]
+    u = 0
+    for r in range(len(nb)):
+        o, k = int(row_off[r]), int(nb[r])
+        slot_tbl[o:o + k] = perm[u:u + k]
+        u += k
+        state[o:o + k] = 1
+        pair[o:o + k] = seq_pairs[row_seq[r]]
+        if protect_last and k:
+            state[o + k - 1] |= 4
+        tail = int(row_ntok[r]) % BLOCK
+        if poison_tail and tail:
+            unit = k_pool[slot_tbl[o + k - 1]].reshape(dim // 8, BLOCK, 8)
+            unit[:, tail:, :] = 0x7FC1 if shape.dtype == BF16 else 0x7E01
+    g = shape.g
+    row_q_off = (np.arange(len(nb), dtype=np.int64) * g * dim)
+    # head weight: group size for GQA/MQA, 1 for MHA; a single latent head (MLA) also gets 1
+    w = float(g) if (shape.has_v and g > 1) else 1.0
+    row_weight = np.full(len(nb), w, np.float32)
+    return Case(shape, n_slots, k_pool, v_pool, row_ntok, row_off, row_q_off, row_seq, slot_tbl,
+                state, pair, row_weight, n_uids)
+
+
+def make_queries(case: Case, seed: int, scale: float = 1.0) -> np.ndarray:
+    """Fresh N(0, scale^2) queries for every row: uint16 [n_rows * g * dim]."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal(case.n_rows * case.shape.g * case.shape.dim, dtype=np.float32) * scale
+    return to_bits(x, case.shape.dtype)
+
+
+def make_events(n: int, seed: int, pair_weights: Optional[np.ndarray] = None,
+                reuse_prob: Optional[np.ndarray] = None):
+    """n reuse events: pair ~ categorical(pair_weights) (uniform by default),
+    outcome ~ Bernoulli(reuse_prob[pair]) (0.5 by default)."""
+    rng = np.random.default_rng(seed)
+    if pair_weights is None:
+        pair_weights = np.full(16, 1.0 / 16)
+    if reuse_prob is None:
+        reuse_prob = np.full(16, 0.5)
+    p = rng.choice(16, size=n, p=pair_weights).astype(np.uint8)
+    o = (rng.random(n) < reuse_prob[p]).astype(np.uint8)
+    return p, o
+
+
+def categorical_weights(seed: int, n: int = 16) -> np.ndarray:
+    """A fixed seeded probability vector (normalised gamma draws)."""
+    rng = np.random.default_rng(seed)
+    w = rng.gamma(1.0, 1.0, size=n)
+    return w / w.sum()
+
+
+def uniform_lengths(n_seq: int, lo: int, hi: int, seed: int) -> List[int]:
+    rng = np.random.default_rng(seed)
+    return [int(v) for v in rng.integers(lo, hi + 1, size=n_seq)]
+
+
+# ------------------------------------------------------- named workloads
+def tiny_gqa(seed: int = 1) -> Case:
+    """1 layer, 4 q / 2 KV heads, d 64, fp16, one 512-token sequence."""
+    return make_case(Shape(1, 4, 2, 64, FP16, True, [512]), seed, protect_last=False)
+
+
+def llama8b_twin(seed: int = 11, n_seq: int = 3, n_layers: int = 2) -> Case:
+    """Row shapes of the Llama-3-8B-shaped workload (8 KV heads, g 4, d 128, lengths in
+    [2048, 8192]) with few sequences and layers."""
+    lens = uniform_lengths(n_seq, 2048, 8192, seed + 1)
+    return make_case(Shape(n_layers, 32, 8, 128, BF16, True, lens), seed,
+                     pair_weights=categorical_weights(seed + 2), spare_slots=64)
+
+
+def llama70b_twin(seed: int = 21, n_tok: int = 131072, n_layers: int = 1, n_kv: int = 1) -> Case:
+    """One very long row family (8192 blocks per row, g 8, d 128)."""
+    return make_case(Shape(n_layers, 8 * n_kv, n_kv, 128, BF16, True, [n_tok]), seed,
+                     pair_weights=categorical_weights(seed + 2))
+
+
+def mla_twin(seed: int = 31, n_seq: int = 1, n_tok: int = 4096, n_layers: int = 1) -> Case:
+    """Latent KV of 576 channels scored by 128 absorbed queries, no V."""
+    return make_case(Shape(n_layers, 128, 1, 576, BF16, False, [n_tok] * n_seq), seed,
+                     pair_weights=categorical_weights(seed + 2))
