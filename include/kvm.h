@@ -142,6 +142,7 @@ typedef struct kvm_rows {
     int32_t        n_rows;
     int32_t        g;          /* queries per row (heads sharing the KV head), 1..128 */
     int64_t        n_uids;     /* length of every per-unit array                  */
+    int64_t        q_elems;    /* length of q in elements (bounds check only)     */
     const int32_t* row_ntok;   /* dev [n_rows] valid tokens in the row, >= 0      */
     const int64_t* row_off;    /* dev [n_rows] uid of the row's block 0           */
     const int64_t* row_q_off;  /* dev [n_rows] element offset of the row's g x dim queries in q;
@@ -162,7 +163,9 @@ typedef struct kvm_rows {
  * mass[uid(b)] = max_j m_j[b] (KVM_AGG_MAX; the GQA grouping rule of section 3.4)
  * or mean_j.  Entries of non-resident blocks, of blocks beyond the row's
  * length and of inactive rows are not written.  Tokens at or beyond n in the
- * last block are ignored whatever bytes the pool holds there.
+ * last block are ignored whatever bytes the pool holds there.  A row whose
+ * blocks would leave [0, n_uids) or whose queries would leave [0, q_elems) is
+ * treated as inactive; table entries >= n_slots are treated as not resident.
  * fp32 accumulation; masses agree with an exact evaluation to ~1e-5 relative.
  *
  * q: dev, dtype of the pool, g x dim contiguous per row at row_q_off.

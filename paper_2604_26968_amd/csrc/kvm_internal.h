@@ -1,0 +1,67 @@
+// Internal helpers shared by the translation units of libkvm (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "kvm.h"
+
+namespace kvm {
+
+// ---- error reporting -------------------------------------------------------
+// Stores a printf-style message for kvm_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+#define KVM_HIP_TRY(expr)                                                                 \
+    do {                                                                                  \
+        hipError_t kvm_e_ = (expr);                                                       \
+        if (kvm_e_ != hipSuccess)                                                         \
+            return ::kvm::fail(KVM_EHIP, "%s: %s", #expr, hipGetErrorString(kvm_e_));     \
+    } while (0)
+
+#define KVM_REQUIRE(cond, code, ...)                     \
+    do {                                                 \
+        if (!(cond)) return ::kvm::fail(code, __VA_ARGS__); \
+    } while (0)
+
+// ---- kernel timing ---------------------------------------------------------
+// Scope object: records a start event now and a stop event when it goes out of
+// scope, both on `stream`, if timing is enabled.  Does nothing otherwise.
+class TimedLaunch {
+  public:
+    TimedLaunch(const char* name, hipStream_t stream);
+    ~TimedLaunch();
+    TimedLaunch(const TimedLaunch&) = delete;
+    TimedLaunch& operator=(const TimedLaunch&) = delete;
+
+  private:
+    int slot_;
+    hipStream_t stream_;
+};
+
+// Error of the most recent kernel launch on this thread, as a KVM code.
+inline int launch_status(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(KVM_EHIP, "launch of %s: %s", what, hipGetErrorString(e));
+    return KVM_OK;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- shapes ----------------------------------------------------------------
+constexpr int kWave = 64;
+constexpr int kTileBlocks = 64;  // token blocks of one row handled by one workgroup of the scorer
+
+// Upper bound on the number of scorer tiles: rows do not overlap in uid space,
+// so sum(ceil(nb_r / T)) <= n_uids / T + n_rows.
+inline int64_t max_tiles(int64_t n_uids, int64_t n_rows) { return n_uids / kTileBlocks + n_rows; }
+
+// Workspace sizes, defined next to the kernels that use them.
+size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g);
+size_t select_workspace_bytes(int64_t n_uids);
+
+}  // namespace kvm

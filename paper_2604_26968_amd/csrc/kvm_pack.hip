@@ -1,0 +1,187 @@
+// kvm_pack / kvm_unpack: head-granular moves between the HBM pool (tier 0) and
+// pinned host memory (tier 1), section 3.2 of the paper.
+//
+// A record is one unit's K frame followed by its V frame.  pack gathers the
+// records of a uid list into a contiguous staging buffer with 16-byte loads and
+// stores (one workgroup per record), flips the table / state entries, and the
+// staging buffer travels to the host with hipMemcpyAsync; when no device
+// staging buffer is given the gather writes pinned host memory directly.
+// unpack is the mirror image.
+#include "kvm_internal.h"
+
+namespace kvm {
+namespace {
+
+constexpr int kThreads = 256;
+
+// first .. first + count of the list; record i lands at staging + (i - first) * rec.
+__global__ __launch_bounds__(kThreads) void pack_kernel(const uint4* __restrict__ k_pool,
+                                                        const uint4* __restrict__ v_pool, uint32_t n_slots,
+                                                        uint32_t k_v4, uint32_t v_v4, int32_t* __restrict__ slot_tbl,
+                                                        uint8_t* __restrict__ state, int64_t n_uids,
+                                                        const int64_t* __restrict__ uids,
+                                                        const int32_t* __restrict__ host_slots,
+                                                        int32_t* __restrict__ freed_slots, int64_t first,
+                                                        uint4* __restrict__ staging, uint32_t* n_bad) {
+    __shared__ int32_t s_slot;
+    const int64_t i = first + blockIdx.x;
+    if (threadIdx.x == 0) {
+        const int64_t uid = uids[i];
+        int32_t slot = -1;
+        if (uid >= 0 && uid < n_uids && (state[uid] & KVM_ST_RESIDENT)) slot = slot_tbl[uid];
+        if ((uint32_t)slot >= n_slots) slot = -1;
+        s_slot = slot;
+        freed_slots[i] = slot;
+        if (slot >= 0) {
+            slot_tbl[uid] = -1 - host_slots[i];
+            state[uid] = (uint8_t)((state[uid] & ~KVM_ST_RESIDENT) | KVM_ST_ON_HOST);
+        } else if (n_bad) {
+            atomicAdd(n_bad, 1u);
+        }
+    }
+    __syncthreads();
+    const int32_t slot = s_slot;
+    if (slot < 0) return;
+    uint4* dst = staging + (size_t)blockIdx.x * (k_v4 + v_v4);
+    const uint4* ks = k_pool + (size_t)slot * k_v4;
+    for (uint32_t v = threadIdx.x; v < k_v4; v += kThreads) dst[v] = ks[v];
+    if (v_v4) {
+        const uint4* vs = v_pool + (size_t)slot * v_v4;
+        for (uint32_t v = threadIdx.x; v < v_v4; v += kThreads) dst[k_v4 + v] = vs[v];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void unpack_kernel(uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
+                                                          uint32_t n_slots, uint32_t k_v4, uint32_t v_v4,
+                                                          int32_t* __restrict__ slot_tbl, uint8_t* __restrict__ state,
+                                                          int64_t n_uids, const int64_t* __restrict__ uids,
+                                                          const int32_t* __restrict__ dst_slots, int64_t first,
+                                                          const uint4* __restrict__ staging, uint32_t* n_bad) {
+    __shared__ int32_t s_slot;
+    const int64_t i = first + blockIdx.x;
+    if (threadIdx.x == 0) {
+        const int64_t uid = uids[i];
+        int32_t slot = dst_slots[i];
+        if (uid < 0 || uid >= n_uids || (state[uid] & KVM_ST_RESIDENT) || (uint32_t)slot >= n_slots) slot = -1;
+        s_slot = slot;
+        if (slot >= 0) {
+            slot_tbl[uid] = slot;
+            state[uid] = (uint8_t)((state[uid] & ~KVM_ST_ON_HOST) | KVM_ST_RESIDENT);
+        } else if (n_bad) {
+            atomicAdd(n_bad, 1u);
+        }
+    }
+    __syncthreads();
+    const int32_t slot = s_slot;
+    if (slot < 0) return;
+    const uint4* src = staging + (size_t)blockIdx.x * (k_v4 + v_v4);
+    uint4* kd = k_pool + (size_t)slot * k_v4;
+    for (uint32_t v = threadIdx.x; v < k_v4; v += kThreads) kd[v] = src[v];
+    if (v_v4) {
+        uint4* vd = v_pool + (size_t)slot * v_v4;
+        for (uint32_t v = threadIdx.x; v < v_v4; v += kThreads) vd[v] = src[k_v4 + v];
+    }
+}
+
+int check_common(const char* who, const kvm_pool_t* pool, const void* slot_tbl, const void* state, int64_t n_uids,
+                 const void* uids, int64_t n, const void* slots, const void* staging_dev, size_t staging_dev_bytes,
+                 const void* staging_host, size_t staging_host_bytes) {
+    KVM_REQUIRE(pool, KVM_EINVAL, "%s: null pool", who);
+    KVM_REQUIRE(n >= 0 && n_uids >= 0, KVM_EINVAL, "%s: negative count", who);
+    KVM_REQUIRE(pool->unit_k_bytes > 0 && pool->unit_k_bytes % 16 == 0 && pool->unit_v_bytes % 16 == 0, KVM_ESHAPE,
+                "%s: unit sizes (%u, %u) must be multiples of 16", who, pool->unit_k_bytes, pool->unit_v_bytes);
+    KVM_REQUIRE(pool->n_slots <= 0x7fffffffull, KVM_EINVAL, "%s: n_slots exceeds int32 slot ids", who);
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(pool->k_pool && (pool->v_pool || pool->unit_v_bytes == 0), KVM_EINVAL, "%s: null pool memory", who);
+    KVM_REQUIRE(slot_tbl && state && uids && slots && staging_host, KVM_EINVAL, "%s: null buffer", who);
+    const size_t rec = (size_t)pool->unit_k_bytes + pool->unit_v_bytes;
+    KVM_REQUIRE(staging_host_bytes / rec >= (size_t)n, KVM_ENOSPC, "%s: host staging %zu bytes < %lld records of %zu",
+                who, staging_host_bytes, (long long)n, rec);
+    KVM_REQUIRE(!staging_dev || staging_dev_bytes >= rec, KVM_ENOSPC, "%s: device staging smaller than one record", who);
+    KVM_REQUIRE(reinterpret_cast<uintptr_t>(staging_host) % 16 == 0 && reinterpret_cast<uintptr_t>(staging_dev) % 16 == 0,
+                KVM_EINVAL, "%s: staging buffers must be 16-byte aligned", who);
+    return KVM_OK;
+}
+
+}  // namespace
+}  // namespace kvm
+
+extern "C" int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids, const int64_t* uids,
+                        int64_t n, const int32_t* host_slots, int32_t* freed_slots, void* staging_dev,
+                        size_t staging_dev_bytes, void* staging_host, size_t staging_host_bytes, uint32_t* n_bad,
+                        void* stream) {
+    using namespace kvm;
+    clear_error();
+    if (int rc = check_common("kvm_pack", pool, slot_tbl, state, n_uids, uids, n, host_slots, staging_dev,
+                              staging_dev_bytes, staging_host, staging_host_bytes))
+        return rc;
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(freed_slots, KVM_EINVAL, "kvm_pack: null freed_slots");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t k_v4 = pool->unit_k_bytes / 16, v_v4 = pool->unit_v_bytes / 16;
+    const size_t rec = (size_t)pool->unit_k_bytes + pool->unit_v_bytes;
+    const uint4* kp = static_cast<const uint4*>(pool->k_pool);
+    const uint4* vp = static_cast<const uint4*>(pool->v_pool);
+    TimedLaunch tl("pack", st);
+    if (!staging_dev) {
+        for (int64_t first = 0; first < n; first += 0x40000000ll) {
+            const int64_t cnt = n - first < 0x40000000ll ? n - first : 0x40000000ll;
+            pack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
+                                                           n_uids, uids, host_slots, freed_slots, first,
+                                                           reinterpret_cast<uint4*>(static_cast<char*>(staging_host) + first * rec),
+                                                           n_bad);
+        }
+        return launch_status("pack");
+    }
+    int64_t per_chunk = (int64_t)(staging_dev_bytes / rec);
+    if (per_chunk > 0x40000000ll) per_chunk = 0x40000000ll;
+    for (int64_t first = 0; first < n; first += per_chunk) {
+        const int64_t cnt = n - first < per_chunk ? n - first : per_chunk;
+        pack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
+                                                       n_uids, uids, host_slots, freed_slots, first,
+                                                       static_cast<uint4*>(staging_dev), n_bad);
+        if (int rc = launch_status("pack")) return rc;
+        KVM_HIP_TRY(hipMemcpyAsync(static_cast<char*>(staging_host) + first * rec, staging_dev, (size_t)cnt * rec,
+                                   hipMemcpyDeviceToHost, st));
+    }
+    return KVM_OK;
+}
+
+extern "C" int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                          const int64_t* uids, int64_t n, const int32_t* dst_slots, void* staging_dev,
+                          size_t staging_dev_bytes, const void* staging_host, size_t staging_host_bytes,
+                          uint32_t* n_bad, void* stream) {
+    using namespace kvm;
+    clear_error();
+    if (int rc = check_common("kvm_unpack", pool, slot_tbl, state, n_uids, uids, n, dst_slots, staging_dev,
+                              staging_dev_bytes, staging_host, staging_host_bytes))
+        return rc;
+    if (n == 0) return KVM_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t k_v4 = pool->unit_k_bytes / 16, v_v4 = pool->unit_v_bytes / 16;
+    const size_t rec = (size_t)pool->unit_k_bytes + pool->unit_v_bytes;
+    uint4* kp = static_cast<uint4*>(pool->k_pool);
+    uint4* vp = static_cast<uint4*>(pool->v_pool);
+    TimedLaunch tl("unpack", st);
+    if (!staging_dev) {
+        for (int64_t first = 0; first < n; first += 0x40000000ll) {
+            const int64_t cnt = n - first < 0x40000000ll ? n - first : 0x40000000ll;
+            unpack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(
+                kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state, n_uids, uids, dst_slots, first,
+                reinterpret_cast<const uint4*>(static_cast<const char*>(staging_host) + first * rec), n_bad);
+        }
+        return launch_status("unpack");
+    }
+    int64_t per_chunk = (int64_t)(staging_dev_bytes / rec);
+    if (per_chunk > 0x40000000ll) per_chunk = 0x40000000ll;
+    for (int64_t first = 0; first < n; first += per_chunk) {
+        const int64_t cnt = n - first < per_chunk ? n - first : per_chunk;
+        KVM_HIP_TRY(hipMemcpyAsync(staging_dev, static_cast<const char*>(staging_host) + first * rec, (size_t)cnt * rec,
+                                   hipMemcpyHostToDevice, st));
+        unpack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
+                                                         n_uids, uids, dst_slots, first,
+                                                         static_cast<const uint4*>(staging_dev), n_bad);
+        if (int rc = launch_status("unpack")) return rc;
+    }
+    return KVM_OK;
+}

@@ -1,0 +1,160 @@
+"""Shared plumbing for the GPU parity tests: puts a synthetic case on the device,
+drives the library stage by stage through the binding, and runs the same
+stages on the oracle.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2604_26968_amd import synth
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+class DeviceCase:
+    """Device copies of a synth.Case plus the per-unit state the pass keeps."""
+
+    def __init__(self, case: synth.Case, staging_records: int = 0):
+        from paper_2604_26968_amd import kvm
+        self.kvm = kvm
+        self.case = case
+        sh = case.shape
+        self.k_pool = _dev(case.k_pool.view(np.int16))
+        self.v_pool = _dev(case.v_pool.view(np.int16)) if case.v_pool is not None else None
+        self.pool = kvm.make_pool(self.k_pool, self.v_pool, sh.dim, sh.dtype)
+        self.row_ntok = _dev(case.row_ntok)
+        self.row_off = _dev(case.row_off)
+        self.row_q_off = _dev(case.row_q_off)
+        self.slot_tbl = _dev(case.slot_tbl)
+        self.state = _dev(case.state)
+        self.pair = _dev(case.pair)
+        self.row_weight = _dev(case.row_weight)
+        n = case.n_uids
+        self.mass = torch.zeros(n, dtype=torch.float32, device="cuda")
+        self.S = torch.zeros(n, dtype=torch.float32, device="cuda")
+        self.prio = torch.zeros(n, dtype=torch.float32, device="cuda")
+        self.hits = torch.zeros(16, dtype=torch.int32, device="cuda")
+        self.misses = torch.zeros(16, dtype=torch.int32, device="cuda")
+        self.p_hat = torch.zeros(16, dtype=torch.float32, device="cuda")
+        self.n_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+        self.victims = torch.zeros(max(n, 1), dtype=torch.int64, device="cuda")
+        self.n_victims = torch.zeros(1, dtype=torch.int64, device="cuda")
+        self.q_elems = case.n_rows * sh.g * sh.dim
+        ws_bytes = max(kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, case.n_rows, sh.g, sh.dim),
+                       kvm.kvm_workspace_bytes(kvm.OP_SELECT, n), 256)
+        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
+        self.rec = sh.unit_k_bytes + sh.unit_v_bytes
+        self.staging_records = staging_records
+        self.row_active = None
+
+    def rows(self, row_active=None):
+        ra = None if row_active is None else _dev(row_active)
+        self._ra = ra
+        return self.kvm.make_rows(self.row_ntok, self.row_off, self.row_q_off, self.slot_tbl,
+                                  self.case.shape.g, self.q_elems, ra)
+
+    # ---- stages -------------------------------------------------------------
+    def score(self, q_bits, scale, agg=0, row_active=None, fill=None):
+        if fill is not None:
+            self.mass.fill_(fill)
+        q = _dev(q_bits.view(np.int16))
+        self.kvm.kvm_score_step(self.pool, self.rows(row_active), q, float(scale), self.mass, self.ws, agg=agg)
+        torch.cuda.synchronize()
+        return self.mass.cpu().numpy()
+
+    def beta(self, ev_pair, ev_outcome, alpha0=1.0, beta0=1.0):
+        p = _dev(ev_pair) if len(ev_pair) else None
+        o = _dev(ev_outcome) if len(ev_outcome) else None
+        self.kvm.kvm_beta_update(p, o, self.hits, self.misses, self.p_hat, alpha0, beta0, n_bad=self.n_bad)
+        torch.cuda.synchronize()
+        return (self.hits.cpu().numpy().view(np.uint32), self.misses.cpu().numpy().view(np.uint32),
+                self.p_hat.cpu().numpy())
+
+    def ema(self, decay, row_active=None):
+        self.kvm.kvm_ema_update(self.rows(row_active), self.mass, float(decay), self.row_weight, self.pair,
+                                self.p_hat, self.state, self.S, self.prio)
+        torch.cuda.synchronize()
+        return self.S.cpu().numpy(), self.prio.cpu().numpy(), self.state.cpu().numpy()
+
+    def select(self, k=-1, budget=0, cap=None):
+        victims = self.victims if cap is None else self.victims[:cap]
+        self.kvm.kvm_select_victims(self.prio, self.state, victims, self.n_victims, self.ws, k=k,
+                                    budget_units=budget)
+        torch.cuda.synchronize()
+        nv = int(self.n_victims.item())
+        return self.victims[:nv].cpu().numpy()
+
+    def pack(self, uids, host_slots, direct=False):
+        n = len(uids)
+        u = _dev(np.asarray(uids, np.int64)) if n else torch.zeros(1, dtype=torch.int64, device="cuda")
+        hs = _dev(np.asarray(host_slots, np.int32)) if n else torch.zeros(1, dtype=torch.int32, device="cuda")
+        freed = torch.full((max(n, 1),), -9, dtype=torch.int32, device="cuda")
+        host = torch.zeros(max(n, 1) * self.rec, dtype=torch.uint8).pin_memory()
+        sdev = None
+        if not direct:
+            recs = self.staging_records or max(n, 1)
+            sdev = torch.zeros(recs * self.rec, dtype=torch.uint8, device="cuda")
+        self.kvm.kvm_pack(self.pool, self.slot_tbl, self.state, u, n, hs, freed, sdev, host, n_bad=self.n_bad)
+        torch.cuda.synchronize()
+        return host.numpy().reshape(-1, self.rec)[:n].copy(), freed[:n].cpu().numpy()
+
+    def unpack(self, uids, dst_slots, staging, direct=False):
+        n = len(uids)
+        u = _dev(np.asarray(uids, np.int64)) if n else torch.zeros(1, dtype=torch.int64, device="cuda")
+        ds = _dev(np.asarray(dst_slots, np.int32)) if n else torch.zeros(1, dtype=torch.int32, device="cuda")
+        host = torch.zeros(max(n, 1) * self.rec, dtype=torch.uint8).pin_memory()
+        host.numpy().reshape(-1, self.rec)[:n] = staging
+        sdev = None
+        if not direct:
+            recs = self.staging_records or max(n, 1)
+            sdev = torch.zeros(recs * self.rec, dtype=torch.uint8, device="cuda")
+        self.kvm.kvm_unpack(self.pool, self.slot_tbl, self.state, u, n, ds, sdev, host, n_bad=self.n_bad)
+        torch.cuda.synchronize()
+
+    def pools_host(self):
+        k = self.k_pool.cpu().numpy().view(np.uint8).reshape(self.case.n_slots, -1)
+        v = self.v_pool.cpu().numpy().view(np.uint8).reshape(self.case.n_slots, -1) if self.v_pool is not None else None
+        return k, v
+
+
+def host_pools(case: synth.Case):
+    """uint8 views (copies) of a case's pools for the pack / unpack oracle."""
+    k = case.k_pool.view(np.uint8).reshape(case.n_slots, -1).copy()
+    v = case.v_pool.view(np.uint8).reshape(case.n_slots, -1).copy() if case.v_pool is not None else None
+    return k, v
+
+
+def oracle_score(o, case: synth.Case, q_bits, scale, agg=0, row_active=None, fill=0.0, slot_tbl=None):
+    mass = np.full(case.n_uids, fill, np.float32)
+    o.score_step(case.k_pool, case.shape.dim, case.shape.dtype, case.row_ntok, case.row_off, case.row_q_off,
+                 case.slot_tbl if slot_tbl is None else slot_tbl, q_bits, case.shape.g, scale, mass, agg=agg,
+                 row_active=row_active)
+    return mass
+
+
+def run_step_gpu(dev: DeviceCase, q_bits, events, scale, decay, k):
+    """beta -> score -> ema -> select k -> pack -> unpack back into the freed frames."""
+    hits, misses, p_hat = dev.beta(*events)
+    mass = dev.score(q_bits, scale)
+    S, prio, state = dev.ema(decay)
+    victims = dev.select(k=k)
+    staging, freed = dev.pack(victims, np.arange(len(victims), dtype=np.int32))
+    dev.unpack(victims, freed, staging)
+    return dict(hits=hits, misses=misses, p_hat=p_hat, mass=mass, S=S, prio=prio, victims=victims,
+                staging=staging, freed=freed)
+
+
+def run_step_oracle(o, case: synth.Case, q_bits, events, S, prio, hits, misses, scale, decay, k):
+    p_hat = o.beta_update(events[0], events[1], hits, misses)
+    mass = oracle_score(o, case, q_bits, scale)
+    o.ema_update(case.row_ntok, case.row_off, mass, decay, case.row_weight, case.pair, p_hat, case.state, S, prio)
+    victims = o.select_victims(prio, case.state, k=k)
+    k8, v8 = host_pools(case)
+    sh = case.shape
+    staging, freed = o.pack(k8, v8, sh.unit_k_bytes, sh.unit_v_bytes, case.slot_tbl, case.state, victims,
+                            np.arange(len(victims), dtype=np.int32))
+    o.unpack(k8, v8, sh.unit_k_bytes, sh.unit_v_bytes, case.slot_tbl, case.state, victims, freed, staging)
+    return dict(hits=hits.copy(), misses=misses.copy(), p_hat=p_hat, mass=mass, S=S.copy(), prio=prio.copy(),
+                victims=victims, staging=staging, freed=freed)
