@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-decode-step KV-cache management pass on one MI355X.
+
+One step = beta update -> scoring of every resident unit -> EMA + priority ->
+budget victim selection -> pack of the victims to pinned host -> unpack of an
+equal number of host units into the freed frames, all through the C ABI on one
+stream.  Workload: the Llama-3-8B-shaped configuration (32 layers, 32 q / 8 KV
+heads, d 128, bf16, 64 sequences of uniform [2048, 8192] tokens, block 16,
+EMA decay 0.95, budget = 60 % of the initially resident units, 4096 reuse
+events per step).  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E published peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--n-seq", type=int, default=64, help="sequences in the batch (64 = the named workload)")
+    ap.add_argument("--swap-units", type=int, default=1024, help="units evicted and prefetched per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the pass has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_26968_amd import kvm, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    t_setup = time.time()
+    shape = synth.llama8b_shape(args.n_seq, seed=2)
+    pair_w = synth.categorical_weights(3)
+    reuse_p = np.linspace(0.15, 0.95, 16)
+    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=pair_w)
+    n, n_rows, g, dim = wl.n_uids, wl.n_rows, shape.g, shape.dim
+    rec = shape.unit_k_bytes + shape.unit_v_bytes
+    pool = kvm.make_pool(wl.k_pool.view(torch.int16), wl.v_pool.view(torch.int16), dim, shape.dtype)
+    rows = kvm.make_rows(wl.row_ntok, wl.row_off, wl.row_q_off, wl.slot_tbl, g, wl.q_elems)
+    scale = 1.0 / float(np.sqrt(dim))
+    decay = 0.95
+
+    mass = torch.zeros(n, dtype=torch.float32, device=dev)
+    S = torch.zeros(n, dtype=torch.float32, device=dev)
+    prio = torch.zeros(n, dtype=torch.float32, device=dev)
+    hits = torch.zeros(16, dtype=torch.int32, device=dev)
+    misses = torch.zeros(16, dtype=torch.int32, device=dev)
+    p_hat = torch.zeros(16, dtype=torch.float32, device=dev)
+    n_bad = torch.zeros(1, dtype=torch.int32, device=dev)
+    n_victims = torch.zeros(1, dtype=torch.int64, device=dev)
+    ws_bytes = max(kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, n_rows, g, dim),
+                   kvm.kvm_workspace_bytes(kvm.OP_SELECT, n))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    n_q_sets = 4
+    qs = [wl.queries(100 + i) for i in range(n_q_sets)]
+    evs = []
+    for i in range(n_q_sets):
+        p, o = synth.make_events(4096, 200 + i, pair_weights=pair_w, reuse_prob=reuse_p)
+        evs.append((torch.from_numpy(p).to(dev), torch.from_numpy(o).to(dev)))
+
+    n_res0 = int((wl.state & 1).sum().item())
+    budget = int(0.6 * n_res0)
+    k0 = n_res0 - budget
+    swap = args.swap_units
+    total_steps = args.warmup + args.steps
+    assert swap * (total_steps + 1) <= k0, "not enough host-resident units for this many steps"
+
+    victims = torch.zeros(k0, dtype=torch.int64, device=dev)
+    freed = torch.full((k0,), -1, dtype=torch.int32, device=dev)
+    host_slots = torch.arange(k0, dtype=torch.int32, device=dev)
+    host_tier = torch.empty(k0 * rec, dtype=torch.uint8, pin_memory=True)    # tier 1
+    staging_dev = torch.empty(min(k0, 32768) * rec, dtype=torch.uint8, device=dev)
+
+    def management_pass(i, k_arg, budget_arg):
+        ev = evs[i % n_q_sets]
+        kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
+        kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
+        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_select_victims(prio, wl.state, victims, n_victims, ws, k=k_arg, budget_units=budget_arg)
+
+    # ---- step 0: everything resident; evict down to the budget in one go ------------------------
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+    t0 = time.time()
+    management_pass(0, -1, budget)
+    torch.cuda.synchronize()
+    t_pass0 = time.time() - t0
+    assert int(n_victims.item()) == k0, (int(n_victims.item()), k0)
+    # shuffle the victim list so that later prefetch segments are random samples of the host tier
+    perm = torch.randperm(k0, generator=wl.gen, device=dev)
+    victims.copy_(victims[perm])
+    torch.cuda.synchronize()
+    t0 = time.time()
+    kvm.kvm_pack(pool, wl.slot_tbl, wl.state, victims, k0, host_slots, freed, staging_dev, host_tier, n_bad=n_bad)
+    torch.cuda.synchronize()
+    t_bulk_pack = time.time() - t0
+    host_uids = victims.clone()                 # uid stored in host record i
+    free_frames = freed.clone()
+    assert int(n_bad.item()) == 0
+    assert int((wl.state & 1).sum().item()) == budget
+
+    # bring the first `swap` units back so that every timed step starts `swap` over budget
+    def prefetch(seg):
+        lo = seg * swap
+        kvm.kvm_unpack(pool, wl.slot_tbl, wl.state, host_uids[lo:lo + swap], swap, free_frames[lo:lo + swap],
+                       staging_dev, host_tier[lo * rec:(lo + swap) * rec], n_bad=n_bad)
+
+    step_victims = torch.zeros(swap, dtype=torch.int64, device=dev)
+    step_freed = torch.full((swap,), -1, dtype=torch.int32, device=dev)
+
+    def step(i):
+        """One full pass.  Resident units at entry: budget + swap."""
+        ev = evs[i % n_q_sets]
+        kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
+        kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
+        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
+        lo = i * swap
+        seg_host = host_tier[lo * rec:(lo + swap) * rec]
+        # the segment's old records were prefetched by the previous step, so it is free to take the victims
+        kvm.kvm_pack(pool, wl.slot_tbl, wl.state, step_victims, swap, host_slots[lo:lo + swap], step_freed,
+                     staging_dev, seg_host, n_bad=n_bad, n_dev=n_victims)
+        nxt = (i + 1) * swap
+        kvm.kvm_unpack(pool, wl.slot_tbl, wl.state, host_uids[nxt:nxt + swap], swap, step_freed, staging_dev,
+                       host_tier[nxt * rec:(nxt + swap) * rec], n_bad=n_bad, n_dev=n_victims)
+
+    prefetch(0)
+    # the frames of segment 0 came from the bulk list; from now on each step reuses the frames it frees
+    torch.cuda.synchronize()
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    resident = int((wl.state & 1).sum().item())
+    assert resident == budget + swap, (resident, budget, swap)
+    assert int(n_bad.item()) == 0, int(n_bad.item())
+
+    kvm.kvm_timing_reset()
+    kvm.kvm_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, total_steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kvm.kvm_timing_enable(False)
+    assert int(n_bad.item()) == 0, int(n_bad.item())
+    assert int(n_victims.item()) == swap
+    assert int((wl.state & 1).sum().item()) == budget + swap
+
+    ms_per_step = elapsed / args.steps * 1e3
+    scored_units = budget + swap
+    scored_bytes = scored_units * shape.unit_k_bytes
+    value = scored_bytes / (elapsed / args.steps) / 1e9
+
+    kernels = {}
+    for name in ("score_plan", "score_partial", "score_finalize", "ema_prio", "beta", "select_hist", "select_emit",
+                 "pack", "unpack"):
+        cnt, ms = kvm.kvm_timing_read(name)
+        kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
+    kvm.kvm_timing_reset()
+    # dominant kernel: score_partial.  Algorithmic bytes per launch = per resident unit the K frame
+    # (16 * dim * 2), its table entry (4) and its g (max, sum) pairs (8 g), plus per row the g queries.
+    per_unit = shape.unit_k_bytes + 4 + 8 * g
+    algo_bytes = scored_units * per_unit + n_rows * g * dim * 2
+    sp = kernels["score_partial"]["avg_ms"]
+    achieved = algo_bytes / (sp * 1e-3) / 1e9
+    roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}
+
+    out = {
+        "metric": "KV scored GB/s (whole management pass, 1 MI355X)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3-8b-shaped GQA: 32 layers, 32q/8kv heads, d128, bf16, %d seqs U[2048,8192] tok, "
+                               "block 16, decay 0.95, budget 60%%, 4096 events/step" % args.n_seq,
+                   "units_total": n, "units_scored_per_step": scored_units, "rows": n_rows,
+                   "swap_units_per_step": swap, "resident_fraction": round(scored_units / n, 4)},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "evicted_units_per_s": round(swap / (elapsed / args.steps), 1),
+        "prefetched_units_per_s": round(swap / (elapsed / args.steps), 1),
+        "roofline": roofline,
+        "kernels_avg_ms": {k: (round(v["avg_ms"], 4) if v["avg_ms"] is not None else None) for k, v in kernels.items()},
+        "step0": {"pass_ms_all_resident": round(t_pass0 * 1e3, 3),
+                  "scored_GBps_all_resident": round(n_res0 * shape.unit_k_bytes / t_pass0 / 1e9, 1),
+                  "bulk_evict_units": k0, "bulk_pack_s": round(t_bulk_pack, 4),
+                  "bulk_pack_GBps": round(k0 * rec / t_bulk_pack / 1e9, 2),
+                  "bulk_pack_units_per_s": round(k0 / t_bulk_pack, 1)},
+        "setup_s": round(setup_s, 1),
+    }
+
+    # ---- host link measured in the same run (pinned, 1 GiB, both directions) -----------------------
+    link_n = 1 << 30
+    hbuf = host_tier[:link_n] if host_tier.numel() >= link_n else torch.empty(link_n, dtype=torch.uint8, pin_memory=True)
+    dbuf = torch.empty(link_n, dtype=torch.uint8, device=dev)
+    link = {}
+    for name, dst, src in (("d2h", hbuf, dbuf), ("h2d", dbuf, hbuf)):
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        link[name + "_GBps"] = round(3 * link_n / (time.perf_counter() - t0) / 1e9, 2)
+    out["host_link"] = link
+    out["step0"]["bulk_pack_frac_of_link"] = round(out["step0"]["bulk_pack_GBps"] / link["d2h_GBps"], 3)
+
+    # ---- CPU baseline: the oracle on a bounded sample of the same workload -------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        sample_seqs = list(range(min(16, args.n_seq)))
+        # score once more (untimed) so that the masses belong to the table as it stands now
+        kvm.kvm_score_step(pool, rows, qs[0], scale, mass, ws)
+        torch.cuda.synchronize()
+        case = wl.host_sample(sample_seqs)
+        q_host = qs[0].view(torch.int16).cpu().numpy().view(np.uint16)
+        q_rows = np.concatenate([q_host[r * g * dim:(r + 1) * g * dim] for r in case.sample_rows])
+        ref_mass = np.zeros(case.n_uids, np.float32)
+        t0 = time.perf_counter()
+        oracle.score_step(case.k_pool, dim, shape.dtype, case.row_ntok, case.row_off, case.row_q_off, case.slot_tbl,
+                          q_rows, g, scale, ref_mass)
+        S_ref = np.zeros(case.n_uids, np.float32)
+        prio_ref = np.zeros(case.n_uids, np.float32)
+        st_ref = case.state.copy()
+        ph = p_hat.cpu().numpy()
+        oracle.ema_update(case.row_ntok, case.row_off, ref_mass, decay, case.row_weight, case.pair, ph, st_ref, S_ref,
+                          prio_ref)
+        oracle.select_victims(prio_ref, st_ref, k=-1, budget_units=int(0.6 * case.n_uids))
+        t_cpu = time.perf_counter() - t0
+        res = case.slot_tbl >= 0
+        cpu_bytes = int(res.sum()) * shape.unit_k_bytes
+        gpu_mass = mass[torch.from_numpy(case.sample_uids).to(dev)].cpu().numpy()
+        rel = np.abs(gpu_mass[res] - ref_mass[res]) / np.maximum(np.abs(ref_mass[res]), 1e-9)
+        out["cpu_baseline"] = {"value": round(cpu_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(),
+                               "kind": "oracle",
+                               "sample": "all %d rows of sequences %s (%d resident units, %.2f GB of K): score + ema + "
+                                         "select, %.1f s" % (case.n_rows, sample_seqs, int(res.sum()), cpu_bytes / 1e9,
+                                                            t_cpu)}
+        out["parity_sample_max_rel_err"] = float(rel.max())
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

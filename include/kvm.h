@@ -240,6 +240,10 @@ int kvm_select_victims(const float* prio /* dev [n_uids] */, const uint8_t* stat
  * Entries whose uid is outside [0, n_uids) or not resident (or whose slot is
  * outside the pool) move nothing, get freed_slots[i] = -1, leave their staging
  * record untouched and are counted in *n_bad.  uids must be distinct.
+ * n_dev, if not NULL, is a device-side list length (e.g. kvm_select_victims'
+ * n_victims): entries i >= *n_dev are ignored entirely (their freed_slots and
+ * staging records are not written), so a victim list can be packed without a
+ * host round trip to learn its length; n is then the upper bound the host knows.
  * The records are gathered into staging_dev in chunks and copied to
  * staging_host with hipMemcpyAsync on `stream`; when staging_dev is NULL the
  * gather kernel writes the pinned host buffer directly.
@@ -249,19 +253,19 @@ int kvm_select_victims(const float* prio /* dev [n_uids] */, const uint8_t* stat
  * kvm_unpack is the inverse: record i of staging_host goes to pool frame
  * dst_slots[i]; slot_tbl[uid] = dst_slots[i]; state: set RESIDENT, clear
  * ON_HOST.  Entries with a bad uid, an already-resident uid or a dst slot
- * outside the pool are skipped and counted.
+ * outside the pool are skipped and counted; n_dev as for kvm_pack.
  * Both are asynchronous: staging_host may be read (pack) or reused (unpack)
  * once `stream` has drained.
  * Errors: KVM_EINVAL (null pointers, n < 0), KVM_ENOSPC (staging too small). */
 int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
-             int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n,
+             int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n, const int64_t* n_dev /* dev [1] or NULL */,
              const int32_t* host_slots /* dev [n] */, int32_t* freed_slots /* dev [n] out */,
              void* staging_dev /* dev or NULL */, size_t staging_dev_bytes,
              void* staging_host /* pinned */, size_t staging_host_bytes,
              uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
 int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
-               int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n,
+               int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n, const int64_t* n_dev /* dev [1] or NULL */,
                const int32_t* dst_slots /* dev [n] */,
                void* staging_dev /* dev or NULL */, size_t staging_dev_bytes,
                const void* staging_host /* pinned */, size_t staging_host_bytes,

@@ -22,9 +22,11 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const uint4* __restrict_
                                                         const int64_t* __restrict__ uids,
                                                         const int32_t* __restrict__ host_slots,
                                                         int32_t* __restrict__ freed_slots, int64_t first,
+                                                        const int64_t* __restrict__ n_dev,
                                                         uint4* __restrict__ staging, uint32_t* n_bad) {
     __shared__ int32_t s_slot;
     const int64_t i = first + blockIdx.x;
+    if (n_dev && i >= *n_dev) return;      // list shorter than the launch (uniform for the workgroup)
     if (threadIdx.x == 0) {
         const int64_t uid = uids[i];
         int32_t slot = -1;
@@ -56,9 +58,11 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(uint4* __restrict__ k_
                                                           int32_t* __restrict__ slot_tbl, uint8_t* __restrict__ state,
                                                           int64_t n_uids, const int64_t* __restrict__ uids,
                                                           const int32_t* __restrict__ dst_slots, int64_t first,
+                                                          const int64_t* __restrict__ n_dev,
                                                           const uint4* __restrict__ staging, uint32_t* n_bad) {
     __shared__ int32_t s_slot;
     const int64_t i = first + blockIdx.x;
+    if (n_dev && i >= *n_dev) return;
     if (threadIdx.x == 0) {
         const int64_t uid = uids[i];
         int32_t slot = dst_slots[i];
@@ -107,7 +111,7 @@ int check_common(const char* who, const kvm_pool_t* pool, const void* slot_tbl, 
 }  // namespace kvm
 
 extern "C" int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids, const int64_t* uids,
-                        int64_t n, const int32_t* host_slots, int32_t* freed_slots, void* staging_dev,
+                        int64_t n, const int64_t* n_dev, const int32_t* host_slots, int32_t* freed_slots, void* staging_dev,
                         size_t staging_dev_bytes, void* staging_host, size_t staging_host_bytes, uint32_t* n_bad,
                         void* stream) {
     using namespace kvm;
@@ -127,7 +131,7 @@ extern "C" int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* stat
         for (int64_t first = 0; first < n; first += 0x40000000ll) {
             const int64_t cnt = n - first < 0x40000000ll ? n - first : 0x40000000ll;
             pack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
-                                                           n_uids, uids, host_slots, freed_slots, first,
+                                                           n_uids, uids, host_slots, freed_slots, first, n_dev,
                                                            reinterpret_cast<uint4*>(static_cast<char*>(staging_host) + first * rec),
                                                            n_bad);
         }
@@ -138,7 +142,7 @@ extern "C" int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* stat
     for (int64_t first = 0; first < n; first += per_chunk) {
         const int64_t cnt = n - first < per_chunk ? n - first : per_chunk;
         pack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
-                                                       n_uids, uids, host_slots, freed_slots, first,
+                                                       n_uids, uids, host_slots, freed_slots, first, n_dev,
                                                        static_cast<uint4*>(staging_dev), n_bad);
         if (int rc = launch_status("pack")) return rc;
         KVM_HIP_TRY(hipMemcpyAsync(static_cast<char*>(staging_host) + first * rec, staging_dev, (size_t)cnt * rec,
@@ -148,7 +152,8 @@ extern "C" int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* stat
 }
 
 extern "C" int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
-                          const int64_t* uids, int64_t n, const int32_t* dst_slots, void* staging_dev,
+                          const int64_t* uids, int64_t n, const int64_t* n_dev, const int32_t* dst_slots,
+                          void* staging_dev,
                           size_t staging_dev_bytes, const void* staging_host, size_t staging_host_bytes,
                           uint32_t* n_bad, void* stream) {
     using namespace kvm;
@@ -167,7 +172,7 @@ extern "C" int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* st
         for (int64_t first = 0; first < n; first += 0x40000000ll) {
             const int64_t cnt = n - first < 0x40000000ll ? n - first : 0x40000000ll;
             unpack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(
-                kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state, n_uids, uids, dst_slots, first,
+                kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state, n_uids, uids, dst_slots, first, n_dev,
                 reinterpret_cast<const uint4*>(static_cast<const char*>(staging_host) + first * rec), n_bad);
         }
         return launch_status("unpack");
@@ -179,7 +184,7 @@ extern "C" int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* st
         KVM_HIP_TRY(hipMemcpyAsync(staging_dev, static_cast<const char*>(staging_host) + first * rec, (size_t)cnt * rec,
                                    hipMemcpyHostToDevice, st));
         unpack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
-                                                         n_uids, uids, dst_slots, first,
+                                                         n_uids, uids, dst_slots, first, n_dev,
                                                          static_cast<const uint4*>(staging_dev), n_bad);
         if (int rc = launch_status("unpack")) return rc;
     }

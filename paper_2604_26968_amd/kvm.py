@@ -77,10 +77,10 @@ def _load() -> C.CDLL:
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_select_victims.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                        C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-    lib.kvm_pack.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+    lib.kvm_pack.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                              C.c_void_p, C.c_void_p]
-    lib.kvm_unpack.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+    lib.kvm_unpack.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
@@ -180,18 +180,18 @@ def _nbytes(t: Optional[torch.Tensor]) -> int:
 
 
 def kvm_pack(pool: Pool, slot_tbl, state, uids, n: int, host_slots, freed_slots, staging_dev,
-             staging_host, n_bad=None, stream=None):
+             staging_host, n_bad=None, n_dev=None, stream=None):
     _check(lib.kvm_pack(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
-                        _ptr(uids, torch.int64), n, _ptr(host_slots, torch.int32),
+                        _ptr(uids, torch.int64), n, _ptr(n_dev, torch.int64), _ptr(host_slots, torch.int32),
                         _ptr(freed_slots, torch.int32), _ptr(staging_dev), _nbytes(staging_dev),
                         _ptr(staging_host, None, "cpu"), _nbytes(staging_host),
                         _ptr(n_bad, torch.int32), _stream(stream)))
 
 
 def kvm_unpack(pool: Pool, slot_tbl, state, uids, n: int, dst_slots, staging_dev, staging_host,
-               n_bad=None, stream=None):
+               n_bad=None, n_dev=None, stream=None):
     _check(lib.kvm_unpack(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
-                          _ptr(uids, torch.int64), n, _ptr(dst_slots, torch.int32),
+                          _ptr(uids, torch.int64), n, _ptr(n_dev, torch.int64), _ptr(dst_slots, torch.int32),
                           _ptr(staging_dev), _nbytes(staging_dev),
                           _ptr(staging_host, None, "cpu"), _nbytes(staging_host),
                           _ptr(n_bad, torch.int32), _stream(stream)))

@@ -227,3 +227,115 @@ def mla_twin(seed: int = 31, n_seq: int = 1, n_tok: int = 4096, n_layers: int = 
     """Latent KV of 576 channels scored by 128 absorbed queries, no V."""
     return make_case(Shape(n_layers, 128, 1, 576, BF16, False, [n_tok] * n_seq), seed,
                      pair_weights=categorical_weights(seed + 2))
+
+
+# ------------------------------------------------- full-size device workloads
+class DeviceWorkload:
+    """A fully resident paged cache of a given Shape built directly in GPU memory.
+
+    Same structure as :func:`make_case` (rows ordered (sequence, layer, kv head),
+    random slot permutation, pair bytes per (sequence, block), last block of
+    every sequence PROTECTED) but K and V are drawn on the device with a seeded
+    torch generator, so pools of tens of GB never pass through the host.
+    """
+
+    def __init__(self, shape: Shape, seed: int, pair_weights: Optional[np.ndarray] = None,
+                 spare_slots: int = 0, device: str = "cuda"):
+        import torch
+        self.torch = torch
+        self.shape = shape
+        rng = np.random.default_rng(seed)
+        L, H, dim = shape.n_layers, shape.n_kv_heads, shape.dim
+        lens = np.asarray(shape.seq_lens, np.int64)
+        rows_per_seq = L * H
+        row_ntok = np.repeat(lens, rows_per_seq).astype(np.int32)
+        self.row_seq = np.repeat(np.arange(len(lens)), rows_per_seq).astype(np.int32)
+        nb = (row_ntok.astype(np.int64) + BLOCK - 1) // BLOCK
+        row_off = np.zeros(len(nb), np.int64)
+        row_off[1:] = np.cumsum(nb[:-1])
+        self.n_rows = len(nb)
+        self.n_uids = int(nb.sum())
+        self.n_slots = self.n_uids + spare_slots
+        self.nb = nb
+        g = shape.g
+        if pair_weights is None:
+            pair_weights = np.full(16, 1.0 / 16)
+        pair = np.empty(self.n_uids, np.uint8)
+        state = np.full(self.n_uids, 1, np.uint8)
+        for s, n in enumerate(lens):
+            k = int((n + BLOCK - 1) // BLOCK)
+            sp = rng.choice(16, size=k, p=pair_weights).astype(np.uint8)
+            r0 = s * rows_per_seq
+            o = int(row_off[r0])
+            pair[o:o + k * rows_per_seq] = np.tile(sp, rows_per_seq)
+            state[o + k - 1:o + k * rows_per_seq:k] |= 4
+        self.host = dict(row_ntok=row_ntok, row_off=row_off, pair=pair, state=state)
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        self.gen = gen
+        unit_elems = BLOCK * dim
+        tdt = torch.bfloat16 if shape.dtype == BF16 else torch.float16
+        self.tdtype = tdt
+
+        def filled(n):
+            t = torch.empty((n, unit_elems), dtype=tdt, device=device)
+            step = max(1, (1 << 27) // unit_elems)
+            for i in range(0, n, step):
+                j = min(n, i + step)
+                t[i:j] = torch.randn((j - i, unit_elems), generator=gen, device=device, dtype=torch.float32).to(tdt)
+            return t
+
+        self.k_pool = filled(self.n_slots)
+        self.v_pool = filled(self.n_slots) if shape.has_v else None
+        perm = torch.randperm(self.n_slots, generator=gen, device=device)[: self.n_uids].to(torch.int32)
+        self.slot_tbl = perm.contiguous()
+        self.row_ntok = torch.from_numpy(row_ntok).to(device)
+        self.row_off = torch.from_numpy(row_off).to(device)
+        self.row_q_off = (torch.arange(self.n_rows, dtype=torch.int64, device=device) * (g * dim))
+        self.state = torch.from_numpy(state).to(device)
+        self.pair = torch.from_numpy(pair).to(device)
+        w = float(g) if (shape.has_v and g > 1) else 1.0
+        self.row_weight = torch.full((self.n_rows,), w, dtype=torch.float32, device=device)
+        self.q_elems = self.n_rows * g * dim
+
+    def queries(self, seed: int):
+        torch = self.torch
+        gen = torch.Generator(device=self.k_pool.device)
+        gen.manual_seed(seed)
+        return torch.randn(self.q_elems, generator=gen, device=self.k_pool.device,
+                           dtype=torch.float32).to(self.tdtype)
+
+    def host_sample(self, seq_ids) -> "Case":
+        """Host copy of the rows of the given sequences with their units compacted into a
+        small pool (slot ids renumbered), for the CPU oracle."""
+        torch = self.torch
+        rows = np.nonzero(np.isin(self.row_seq, np.asarray(seq_ids)))[0]
+        nb = self.nb[rows]
+        new_off = np.zeros(len(rows), np.int64)
+        new_off[1:] = np.cumsum(nb[:-1])
+        n_u = int(nb.sum())
+        old_uids = np.concatenate([np.arange(self.host["row_off"][r], self.host["row_off"][r] + k)
+                                   for r, k in zip(rows, nb)])
+        uids_dev = torch.from_numpy(old_uids).to(self.k_pool.device)
+        slots = self.slot_tbl[uids_dev]
+        res = slots >= 0
+        res_slots = slots[res].long()
+        k_host = self.k_pool[res_slots].view(torch.int16).cpu().numpy().view(np.uint16)
+        new_tbl = np.full(n_u, -1, np.int32)
+        new_tbl[res.cpu().numpy()] = np.arange(int(res.sum().item()), dtype=np.int32)
+        state = self.state[uids_dev].cpu().numpy()
+        pair = self.pair[uids_dev].cpu().numpy()
+        g, dim = self.shape.g, self.shape.dim
+        sample_shape = Shape(self.shape.n_layers, self.shape.n_q_heads, self.shape.n_kv_heads, dim,
+                             self.shape.dtype, self.shape.has_v, [self.shape.seq_lens[s] for s in seq_ids])
+        case = Case(sample_shape, k_host.shape[0], k_host, None, self.host["row_ntok"][rows].copy(), new_off,
+                    np.arange(len(rows), dtype=np.int64) * g * dim, self.row_seq[rows].copy(), new_tbl, state,
+                    pair, self.row_weight[torch.from_numpy(rows).to(self.k_pool.device)].cpu().numpy(), n_u)
+        case.sample_rows = rows
+        case.sample_uids = old_uids
+        return case
+
+
+def llama8b_shape(n_seq: int = 64, seed: int = 2) -> Shape:
+    """32 layers, 32 q / 8 KV heads, d 128, bf16, n_seq sequences of uniform [2048, 8192] tokens."""
+    return Shape(32, 32, 8, 128, BF16, True, uniform_lengths(n_seq, 2048, 8192, seed))

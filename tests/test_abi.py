@@ -94,10 +94,10 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_ema_update(C.byref(rows), None, 1.5, None, None, None, None, None, None, None) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, -1, 0, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, 10, -2, 0, None, 0, None, None, 0, None) == kvm.EINVAL
-    assert lib.kvm_pack(None, None, None, 0, None, 0, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
-    assert lib.kvm_pack(C.byref(pool), None, None, 0, None, 0, None, None, None, 0, None, 0, None, None) == kvm.OK
-    assert lib.kvm_pack(C.byref(pool), None, None, 8, None, 3, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
-    assert lib.kvm_unpack(C.byref(pool), None, None, 8, None, -3, None, None, 0, None, 0, None, None) == kvm.EINVAL
+    assert lib.kvm_pack(None, None, None, 0, None, 0, None, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
+    assert lib.kvm_pack(C.byref(pool), None, None, 0, None, 0, None, None, None, None, 0, None, 0, None, None) == kvm.OK
+    assert lib.kvm_pack(C.byref(pool), None, None, 8, None, 3, None, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
+    assert lib.kvm_unpack(C.byref(pool), None, None, 8, None, -3, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
     assert kvm.kvm_workspace_bytes(kvm.OP_SCORE, 1000, 10, 4, 128) >= 1000 * 4 * 8
     assert kvm.kvm_workspace_bytes(kvm.OP_SELECT, 1000) > 0
     assert kvm.kvm_workspace_bytes(99, 1000) == 0
