@@ -54,7 +54,10 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- shapes ----------------------------------------------------------------
 constexpr int kWave = 64;
-constexpr int kTileBlocks = 64;  // token blocks of one row handled by one workgroup of the scorer
+#ifndef KVM_TILE_BLOCKS
+#define KVM_TILE_BLOCKS 512
+#endif
+constexpr int kTileBlocks = KVM_TILE_BLOCKS;  // token blocks of one row handled by one workgroup of the scorer (multiple of 256)
 
 // Upper bound on the number of scorer tiles: rows do not overlap in uid space,
 // so sum(ceil(nb_r / T)) <= n_uids / T + n_rows.

@@ -5,18 +5,24 @@
 // query heads that share the KV head (GQA grouping rule, section 3.4).
 //
 // Structure (all kernels in this file):
-//   plan_*           build the list of tiles = (row, first block) of at most 64 blocks
-//                    for the active rows, on the device, so the scorer's grid has no
-//                    idle workgroups whatever the spread of row lengths
-//   score_partial    one workgroup per tile, one wavefront per unit at a time:
-//                    per (unit, query) block maximum m and sum s = sum exp(z - m)
-//   score_finalize   one workgroup per row: combines the (m, s) pairs into the
-//                    row's softmax normaliser and writes the unit masses
+//   plan_*            build the list of tiles = (row, first block) of at most 512 blocks
+//                     for the active rows, on the device, so the scorer's grid has no
+//                     idle workgroups whatever the spread of row lengths
+//   score_tile        g in {1, 2, 4, 8}, queries in registers: one workgroup per tile, one
+//                     wavefront per unit at a time.  Per (unit, query) block maximum m and
+//                     sum s = sum exp(z - m) stay in LDS; the workgroup reduces them to the
+//                     tile's (M, Z).  A row that fits one tile is finished on the spot (only
+//                     the masses are written); otherwise the tile writes s*exp(m - M) per
+//                     (unit, query), coalesced, plus its (M, Z), and
+//   score_rowmerge    combines the tiles of such a row and writes its masses
+//   score_partial_generic / score_finalize
+//                     any g up to 128 and dim up to 576: queries staged in LDS, (m, s)
+//                     pairs through global memory, one workgroup per row to finish
 //
-// score_partial is the only kernel that touches K; it reads every resident unit
-// exactly once with 16-byte loads that cover 1 KiB contiguous per wavefront
-// instruction.  With the [dim/8][16][8] unit layout lane l holds token l%16,
-// channel group 4*kk + l/16 of load kk, so a lane accumulates its share of
+// The tile kernels are the only ones that touch K; they read every resident unit
+// exactly once with non-temporal 16-byte loads that cover 1 KiB contiguous per
+// wavefront instruction.  With the [dim/8][16][8] unit layout lane l holds token
+// l%16, channel group 4*kk + l/16 of load kk, so a lane accumulates its share of
 // q.k in registers and the only cross-lane traffic is a reduce-scatter over the
 // four 16-lane rows (two row-swap instructions per four queries) followed by
 // 16-lane DPP reductions for the block maximum and sum.
@@ -176,34 +182,102 @@ __global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(int n, uint32_t
     if (threadIdx.x == 0) *n_tiles = carry;
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, const uint32_t* wg_base, Tile* tiles) {
+__global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, const uint32_t* wg_base, Tile* tiles,
+                                                                 uint32_t* row_tile0) {
     const int r = blockIdx.x * kPlanThreads + threadIdx.x;
     const uint32_t nt = tiles_of_row(p, r);
     uint32_t total;
     const uint32_t first = wg_base[blockIdx.x] + wg_exclusive_scan(nt, &total);
+    if (r < p.n_rows) row_tile0[r] = first;
     for (uint32_t i = 0; i < nt; ++i) tiles[first + i] = Tile{r, (int32_t)(i * kTileBlocks)};
 }
 
-// ---- score_partial ------------------------------------------------------------
-// G     queries per row, compile-time when QREG (queries live in registers),
-//       otherwise a run-time value and the queries are staged in LDS
-// DIM   channels per token (multiple of 32)
-// DT    element type
-template <int G_CT, int DIM, int DT, bool QREG>
-__global__ __launch_bounds__(256) void score_partial_kernel(
-    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int g_rt,
-    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
-    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
-    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale,
-    float2* __restrict__ part) {
+// ---- shared pieces of the tile kernels ---------------------------------------------
+constexpr int kTileThreads = 256;
+constexpr int kEntriesPerThread = kTileBlocks / kTileThreads;
+static_assert(kTileBlocks % kTileThreads == 0, "whole table entries per thread");
+
+typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+
+// Resident units of a tile, compacted into LDS as (block index in tile, pool frame), in
+// block order: every thread looks at kEntriesPerThread table entries, a ballot + popcount
+// gives each resident entry its place.  Returns the list length.  Ends with a barrier.
+__device__ __forceinline__ int build_unit_list(const int32_t* __restrict__ slot_tbl, int64_t uid0, int nbt,
+                                               uint32_t n_slots, int2* s_list, int* s_cnt /* [entries * 4] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int slot[kEntriesPerThread], within[kEntriesPerThread];
+#pragma unroll
+    for (int e = 0; e < kEntriesPerThread; ++e) {
+        const int b = e * kTileThreads + threadIdx.x;
+        slot[e] = b < nbt ? slot_tbl[uid0 + b] : -1;
+        if ((uint32_t)slot[e] >= n_slots) slot[e] = -1;
+        const uint64_t bal = __ballot(slot[e] >= 0);
+        within[e] = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) s_cnt[e * 4 + wave] = __popcll(bal);
+    }
+    __syncthreads();
+    int total = 0;
+#pragma unroll
+    for (int e = 0; e < kEntriesPerThread; ++e) {
+        int base = total;
+        for (int w = 0; w < 4; ++w) {
+            const int c = s_cnt[e * 4 + w];
+            if (w < wave) base += c;
+            total += c;
+        }
+        if (slot[e] >= 0) s_list[base + within[e]] = make_int2(e * kTileThreads + threadIdx.x, slot[e]);
+    }
+    __syncthreads();
+    return total;
+}
+
+template <int NK>
+__device__ __forceinline__ void load_unit(uint4 (&dst)[NK], const uint4* __restrict__ k_pool, uint32_t slot,
+                                          int unit_v4, int lane) {
+    const v4u_t* p = reinterpret_cast<const v4u_t*>(k_pool + (size_t)slot * unit_v4 + lane);
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+        // K is read once per step and never again: non-temporal, so it does not displace the tables in L2
+        const v4u_t v = __builtin_nontemporal_load(p + kk * 64);
+        dst[kk] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+}
+
+__device__ __forceinline__ int2 list_entry(const int2* s_list, int idx) {      // wave-uniform LDS read
+    const int2 e = s_list[idx];
+    return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
+}
+
+// Running softmax statistics: maximum m and z = sum exp(x - m).
+struct MZ {
+    float m, z;
+};
+__device__ __forceinline__ MZ mz_combine(MZ a, MZ b) {
+    const float M = fmaxf(a.m, b.m);
+    if (M == -INFINITY) return MZ{M, 0.f};
+    return MZ{M, a.z * __expf(a.m - M) + b.z * __expf(b.m - M)};
+}
+
+// ---- score_tile: g in {1, 2, 4, 8}, queries in registers ----------------------------
+template <int G, int DIM, int DT>
+__global__ __launch_bounds__(kTileThreads) void score_tile_kernel(
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, const int32_t* __restrict__ row_ntok,
+    const int64_t* __restrict__ row_off, const int64_t* __restrict__ row_q_off,
+    const int32_t* __restrict__ slot_tbl, const uint4* __restrict__ k_pool, uint32_t n_slots,
+    const uint16_t* __restrict__ q, float scale, int agg, float* __restrict__ mass, float* __restrict__ part_r,
+    float2* __restrict__ tile_mz) {
+    static_assert(G == 1 || G == 2 || G == 4 || G == 8, "power-of-two group sizes only");
     constexpr int NK = DIM / 32;          // 16-byte loads per lane per unit
     constexpr int UNIT_V4 = DIM * 2;      // 16-byte vectors per unit
     constexpr int QROW_V4 = DIM / 8;      // 16-byte vectors per query
-    extern __shared__ uint4 q_lds[];      // [g][QROW_V4] when !QREG
+    constexpr int BS = kTileThreads / G;  // blocks per sweep of the epilogue
+    __shared__ float2 s_ms[kTileBlocks * G];   // (m, s) per (block, query); (-inf, 0) = not resident
+    __shared__ int2 s_list[kTileBlocks];
+    __shared__ int s_cnt[kEntriesPerThread * 4];
+    __shared__ float2 s_red[4][G];
 
     if (blockIdx.x >= *n_tiles) return;
     const Tile tile = tiles[blockIdx.x];
-    const int G = QREG ? G_CT : g_rt;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t = lane & 15, cg = lane >> 4;
     const int ntok = row_ntok[tile.row];
@@ -212,72 +286,190 @@ __global__ __launch_bounds__(256) void score_partial_kernel(
     const int64_t uid0 = row_off[tile.row] + tile.b0;
     const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[tile.row]);
 
-    constexpr int GR = QREG ? G_CT : 1;
-    uint4 qv[GR][NK];
-    if constexpr (QREG) {
+    uint4 qv[G][NK];
 #pragma unroll
-        for (int j = 0; j < G_CT; ++j)
+    for (int j = 0; j < G; ++j)
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) qv[j][kk] = qrow[j * QROW_V4 + 4 * kk + cg];
-    } else {
-        for (int i = threadIdx.x; i < G * QROW_V4; i += 256) q_lds[i] = qrow[i];
-        __syncthreads();
-    }
+        for (int kk = 0; kk < NK; ++kk) qv[j][kk] = qrow[j * QROW_V4 + 4 * kk + cg];
 
-    // Resident units of the tile; this wavefront takes every fourth one.
-    int my_slot = lane < nbt ? slot_tbl[uid0 + lane] : -1;
-    if ((uint32_t)my_slot >= n_slots) my_slot = -1;
-    uint64_t mine = 0;
-    {
-        int rank = 0;
-        for (uint64_t m = __ballot(my_slot >= 0); m; m &= m - 1)
-            if ((rank++ & 3) == wave) mine |= m & (~m + 1);
-    }
+    for (int i = threadIdx.x; i < nbt * G; i += kTileThreads) s_ms[i] = make_float2(-INFINITY, 0.f);
+    const int n_res = build_unit_list(slot_tbl, uid0, nbt, n_slots, s_list, s_cnt);
+    if (n_res == 0) return;                      // nothing resident in this tile (uniform)
 
-    auto pop = [&]() -> int {
-        if (!mine) return -1;
-        const int i = __builtin_ctzll(mine);
-        mine &= mine - 1;
-        return i;
-    };
-    auto load_unit = [&](uint4 (&dst)[NK], int i) {
-        const uint32_t slot = (uint32_t)__builtin_amdgcn_readlane(my_slot, i);
-        const uint4* p = k_pool + (size_t)slot * UNIT_V4 + lane;
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) dst[kk] = p[kk * 64];
-    };
-
+    // Wavefront w takes list entries w, w + 4, ...: balanced whatever the residency pattern.
+    // Two units in flight per wavefront.  The loads of the following unit are issued
+    // unconditionally (past the end of the list they re-read the last unit, a cache hit): a
+    // branch around them would make the compiler wait for every outstanding load before the
+    // first use of the current unit, which serialises load and compute.
     uint4 cur[NK], nxt[NK];
-    int i_cur = pop();
-    if (i_cur >= 0) load_unit(cur, i_cur);
+    int idx = wave;
+    int i_cur = -1;
+    if (idx < n_res) {
+        const int2 e = list_entry(s_list, idx);
+        i_cur = e.x;
+        load_unit<NK>(cur, k_pool, (uint32_t)e.y, UNIT_V4, lane);
+    }
     while (i_cur >= 0) {
-        const int i_nxt = pop();
-        if (i_nxt >= 0) load_unit(nxt, i_nxt);
+        idx += 4;
+        const int2 e_nxt = list_entry(s_list, idx < n_res ? idx : n_res - 1);
+        const int i_nxt = idx < n_res ? e_nxt.x : -1;
+        load_unit<NK>(nxt, k_pool, (uint32_t)e_nxt.y, UNIT_V4, lane);
 
         const int tok_in_block = min(16, ntok - 16 * (tile.b0 + i_cur));
         const bool valid = t < tok_in_block;
-        float2* out = part + (uid0 + i_cur) * G;
-
         // four queries at a time: each 16-lane row ends up owning one of them
 #pragma unroll
         for (int j0 = 0; j0 < G; j0 += 4) {
             float a[4] = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (QREG) {
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    if (j0 + jj < G_CT) {
+            for (int jj = 0; jj < 4; ++jj)
+                if (j0 + jj < G) {
 #pragma unroll
-                        for (int kk = 0; kk < NK; ++kk) a[jj] = dot8<DT>(cur[kk], qv[(j0 + jj) % GR][kk], a[jj]);
-                    }
-            } else {
+                    for (int kk = 0; kk < NK; ++kk) a[jj] = dot8<DT>(cur[kk], qv[(j0 + jj) % G][kk], a[jj]);
+                }
+            const float z = fold_rows(fold_halves(a[0], a[1]), fold_halves(a[2], a[3])) * scale;
+            const float zz = valid ? z : -INFINITY;
+            const float mx = row16_max(zz);
+            const float e = valid ? __expf(zz - mx) : 0.f;
+            const float s = row16_sum(e);
+            const int jq = j0 + query_of_row(cg);
+            if (t == 0 && jq < G) s_ms[i_cur * G + jq] = make_float2(mx, s);
+        }
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    if (j0 + jj < G) {
-                        const uint4* qj = q_lds + (j0 + jj) * QROW_V4 + cg;
+        for (int kk = 0; kk < NK; ++kk) cur[kk] = nxt[kk];
+        i_cur = i_nxt;
+    }
+    __syncthreads();
+
+    // Tile statistics per query: thread (bsub, j) sweeps blocks bsub, bsub + BS, ...
+    const int j = threadIdx.x & (G - 1), bsub = threadIdx.x / G;
+    MZ acc{-INFINITY, 0.f};
+    for (int b = bsub; b < nbt; b += BS) {
+        const float2 p = s_ms[b * G + j];
+        acc = mz_combine(acc, MZ{p.x, p.y});
+    }
 #pragma unroll
-                        for (int kk = 0; kk < NK; ++kk) a[jj] = dot8<DT>(cur[kk], qj[4 * kk], a[jj]);
-                    }
+    for (int d = G; d < 64; d <<= 1) acc = mz_combine(acc, MZ{__shfl_xor(acc.m, d), __shfl_xor(acc.z, d)});
+    if (lane < G) s_red[wave][lane] = make_float2(acc.m, acc.z);
+    __syncthreads();
+    MZ tot{s_red[0][j].x, s_red[0][j].y};
+#pragma unroll
+    for (int w = 1; w < 4; ++w) tot = mz_combine(tot, MZ{s_red[w][j].x, s_red[w][j].y});
+
+    if (nb <= kTileBlocks) {
+        // the row is this tile: finish it here
+        const float inv = 1.f / tot.z;                  // n_res > 0, so tot.z >= 1
+        for (int b0 = 0; b0 < nbt; b0 += BS) {
+            const int b = b0 + bsub;
+            const float2 p = b < nbt ? s_ms[b * G + j] : make_float2(-INFINITY, 0.f);
+            float v = p.y * __expf(p.x - tot.m) * inv;  // exp(-inf) = 0 for blocks that are not resident
+#pragma unroll
+            for (int d = G / 2; d >= 1; d >>= 1) {
+                const float o = __shfl_xor(v, d);
+                v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
             }
+            if (j == 0 && p.y > 0.f) mass[uid0 + b] = agg == KVM_AGG_MAX ? v : v * (1.f / G);
+        }
+    } else {
+        // s * exp(m - M_tile) per (unit, query), contiguous for the whole tile; 0 where not resident
+        for (int i = threadIdx.x; i < nbt * G; i += kTileThreads) {
+            const float2 p = s_ms[i];
+            part_r[uid0 * G + i] = p.y * __expf(p.x - tot.m);
+        }
+        if (threadIdx.x < G) tile_mz[(size_t)blockIdx.x * G + threadIdx.x] = make_float2(tot.m, tot.z);
+    }
+}
+
+// ---- score_rowmerge: rows of more than one tile, g in {1, 2, 4, 8} -------------------
+template <int G>
+__global__ __launch_bounds__(kTileThreads) void score_rowmerge_kernel(
+    PlanRows pr, const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots,
+    const float* __restrict__ part_r, const float2* __restrict__ tile_mz, int agg, float* __restrict__ mass) {
+    constexpr int BS = kTileThreads / G;
+    const int row = blockIdx.x;
+    if (!row_scorable(pr, row)) return;
+    const int nb = (pr.row_ntok[row] + 15) >> 4;
+    if (nb <= kTileBlocks) return;                   // finished by its tile
+    const int64_t uid0 = pr.row_off[row];
+    const float2* tmz = tile_mz + (size_t)row_tile0[row] * G;
+    const int n_t = (nb + kTileBlocks - 1) / kTileBlocks;
+    const int j = threadIdx.x & (G - 1), bsub = threadIdx.x / G;
+    MZ tot{-INFINITY, 0.f};
+    for (int i = 0; i < n_t; ++i) {
+        const float2 p = tmz[i * G + j];
+        tot = mz_combine(tot, MZ{p.x, p.y});
+    }
+    const float inv = tot.z > 0.f ? 1.f / tot.z : 0.f;
+    for (int b0 = 0; b0 < nb; b0 += BS) {
+        const int b = b0 + bsub;
+        const bool res = b < nb && (uint32_t)slot_tbl[uid0 + (b < nb ? b : 0)] < n_slots;
+        float v = 0.f;
+        if (res) {
+            const float m_tile = tmz[(b / kTileBlocks) * G + j].x;
+            v = part_r[(uid0 + b) * G + j] * __expf(m_tile - tot.m) * inv;
+        }
+#pragma unroll
+        for (int d = G / 2; d >= 1; d >>= 1) {
+            const float o = __shfl_xor(v, d);
+            v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
+        }
+        if (res && j == 0) mass[uid0 + b] = agg == KVM_AGG_MAX ? v : v * (1.f / G);
+    }
+}
+
+// ---- score_partial_generic: any g, queries staged in LDS, (m, s) pairs to global -----
+template <int DIM, int DT>
+__global__ __launch_bounds__(kTileThreads) void score_partial_generic_kernel(
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
+    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
+    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
+    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale,
+    float2* __restrict__ part) {
+    constexpr int NK = DIM / 32;
+    constexpr int UNIT_V4 = DIM * 2;
+    constexpr int QROW_V4 = DIM / 8;
+    extern __shared__ uint4 q_lds[];      // [g][QROW_V4]
+    __shared__ int2 s_list[kTileBlocks];
+    __shared__ int s_cnt[kEntriesPerThread * 4];
+
+    if (blockIdx.x >= *n_tiles) return;
+    const Tile tile = tiles[blockIdx.x];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = lane & 15, cg = lane >> 4;
+    const int ntok = row_ntok[tile.row];
+    const int nb = (ntok + 15) >> 4;
+    const int nbt = min(kTileBlocks, nb - tile.b0);
+    const int64_t uid0 = row_off[tile.row] + tile.b0;
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[tile.row]);
+    for (int i = threadIdx.x; i < G * QROW_V4; i += kTileThreads) q_lds[i] = qrow[i];
+    const int n_res = build_unit_list(slot_tbl, uid0, nbt, n_slots, s_list, s_cnt);   // barriers cover q_lds too
+
+    uint4 cur[NK], nxt[NK];
+    int idx = wave;
+    int i_cur = -1;
+    if (idx < n_res) {
+        const int2 e = list_entry(s_list, idx);
+        i_cur = e.x;
+        load_unit<NK>(cur, k_pool, (uint32_t)e.y, UNIT_V4, lane);
+    }
+    while (i_cur >= 0) {
+        idx += 4;
+        const int2 e_nxt = list_entry(s_list, idx < n_res ? idx : n_res - 1);
+        const int i_nxt = idx < n_res ? e_nxt.x : -1;
+        load_unit<NK>(nxt, k_pool, (uint32_t)e_nxt.y, UNIT_V4, lane);
+
+        const int tok_in_block = min(16, ntok - 16 * (tile.b0 + i_cur));
+        const bool valid = t < tok_in_block;
+        float2* out = part + (uid0 + i_cur) * G;
+        for (int j0 = 0; j0 < G; j0 += 4) {
+            float a[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                if (j0 + jj < G) {
+                    const uint4* qj = q_lds + (j0 + jj) * QROW_V4 + cg;
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) a[jj] = dot8<DT>(cur[kk], qj[4 * kk], a[jj]);
+                }
             const float z = fold_rows(fold_halves(a[0], a[1]), fold_halves(a[2], a[3])) * scale;
             const float zz = valid ? z : -INFINITY;
             const float mx = row16_max(zz);
@@ -368,68 +560,125 @@ struct ScoreWs {
     uint32_t* n_tiles;
     uint32_t* wg_sum;
     Tile* tiles;
-    float2* part;
+    uint32_t* row_tile0;
+    float2* tile_mz;
+    float2* part;       // (m, s) pairs [n_uids][g] (generic path) or floats [n_uids][g] (tile path)
     size_t bytes;
 };
 
 ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g) {
     const size_t n_wg = ((size_t)n_rows + kPlanThreads - 1) / kPlanThreads;
+    const size_t tiles_max = (size_t)max_tiles(n_uids, n_rows);
     const size_t off_sum = 256;
     const size_t off_tiles = off_sum + align_up(n_wg * sizeof(uint32_t), 256);
-    const size_t off_part = off_tiles + align_up((size_t)max_tiles(n_uids, n_rows) * sizeof(Tile), 256);
+    const size_t off_row0 = off_tiles + align_up(tiles_max * sizeof(Tile), 256);
+    const size_t off_tmz = off_row0 + align_up((size_t)n_rows * sizeof(uint32_t), 256);
+    const size_t off_part = off_tmz + align_up(tiles_max * (size_t)g * sizeof(float2), 256);
     const uintptr_t base = reinterpret_cast<uintptr_t>(ws);
     ScoreWs w;
     w.n_tiles = reinterpret_cast<uint32_t*>(base);
     w.wg_sum = reinterpret_cast<uint32_t*>(base + off_sum);
     w.tiles = reinterpret_cast<Tile*>(base + off_tiles);
+    w.row_tile0 = reinterpret_cast<uint32_t*>(base + off_row0);
+    w.tile_mz = reinterpret_cast<float2*>(base + off_tmz);
     w.part = reinterpret_cast<float2*>(base + off_part);
     w.bytes = off_part + align_up((size_t)n_uids * (size_t)g * sizeof(float2), 256);
     return w;
 }
 
+struct ScoreArgs {
+    const kvm_pool_t* pool;
+    const kvm_rows_t* rows;
+    const void* q;
+    float scale;
+    int agg;
+    float* mass;
+    PlanRows pr;
+    ScoreWs w;
+    unsigned grid;
+    hipStream_t st;
+};
+
+// g in {1, 2, 4, 8} with the queries small enough for registers: tile kernel + row merge.
+template <int G, int DIM, int DT>
+int launch_tile_path(const ScoreArgs& a) {
+    const uint4* kp = static_cast<const uint4*>(a.pool->k_pool);
+    const uint32_t ns = (uint32_t)a.pool->n_slots;
+    {
+        TimedLaunch tl("score_partial", a.st);
+        score_tile_kernel<G, DIM, DT><<<a.grid, kTileThreads, 0, a.st>>>(
+            a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off, a.rows->slot_tbl, kp, ns,
+            static_cast<const uint16_t*>(a.q), a.scale, a.agg, a.mass, reinterpret_cast<float*>(a.w.part),
+            a.w.tile_mz);
+        if (int rc = launch_status("score_tile")) return rc;
+    }
+    TimedLaunch tl("score_finalize", a.st);
+    score_rowmerge_kernel<G><<<a.rows->n_rows, kTileThreads, 0, a.st>>>(
+        a.pr, a.w.row_tile0, a.rows->slot_tbl, ns, reinterpret_cast<const float*>(a.w.part), a.w.tile_mz, a.agg,
+        a.mass);
+    return launch_status("score_rowmerge");
+}
+
 template <int DIM, int DT>
-int launch_partial(int g, dim3 grid, hipStream_t st, const ScoreWs& w, const kvm_rows_t* rows,
-                   const kvm_pool_t* pool, const void* q, float scale) {
-    const uint4* kp = static_cast<const uint4*>(pool->k_pool);
-    const uint16_t* qq = static_cast<const uint16_t*>(q);
-    const uint32_t ns = (uint32_t)pool->n_slots;
-#define KVM_LAUNCH_QREG(GG)                                                                            \
-    score_partial_kernel<GG, DIM, DT, true><<<grid, 256, 0, st>>>(                                     \
-        w.tiles, w.n_tiles, g, rows->row_ntok, rows->row_off, rows->row_q_off, rows->slot_tbl, kp, ns, \
-        qq, scale, w.part)
+int launch_generic_path(const ScoreArgs& a) {
+    const int g = a.rows->g;
+    const uint32_t ns = (uint32_t)a.pool->n_slots;
+    const size_t lds = (size_t)g * (DIM / 8) * sizeof(uint4);
+    auto kern = score_partial_generic_kernel<DIM, DT>;
+    if (lds + 8 * 1024 > 160 * 1024)
+        return fail(KVM_ESHAPE, "kvm_score_step: g %d x dim %d queries do not fit LDS", g, DIM);
+    if (lds > 32 * 1024)
+        KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    {
+        TimedLaunch tl("score_partial", a.st);
+        kern<<<a.grid, kTileThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, g, a.rows->row_ntok, a.rows->row_off,
+                                                  a.rows->row_q_off, a.rows->slot_tbl,
+                                                  static_cast<const uint4*>(a.pool->k_pool), ns,
+                                                  static_cast<const uint16_t*>(a.q), a.scale, a.w.part);
+        if (int rc = launch_status("score_partial_generic")) return rc;
+    }
+    TimedLaunch tl("score_finalize", a.st);
+    int gp = 1;
+    while (gp < g) gp <<= 1;
+#define KVM_FIN(GP)                                                                                             \
+    case GP:                                                                                                    \
+        score_finalize_kernel<GP><<<a.rows->n_rows, 256, 0, a.st>>>(a.pr, a.rows->slot_tbl, ns, a.w.part, a.agg, \
+                                                                    a.mass);                                    \
+        break;
+    switch (gp) {
+        KVM_FIN(1) KVM_FIN(2) KVM_FIN(4) KVM_FIN(8) KVM_FIN(16) KVM_FIN(32) KVM_FIN(64) KVM_FIN(128)
+        default: return fail(KVM_ESHAPE, "kvm_score_step: g %d", g);
+    }
+#undef KVM_FIN
+    return launch_status("score_finalize");
+}
+
+template <int DIM, int DT>
+int launch_dim(const ScoreArgs& a) {
     if constexpr (DIM <= 128) {
-        switch (g) {
-            case 1: KVM_LAUNCH_QREG(1); return launch_status("score_partial");
-            case 2: KVM_LAUNCH_QREG(2); return launch_status("score_partial");
-            case 4: KVM_LAUNCH_QREG(4); return launch_status("score_partial");
-            case 8: KVM_LAUNCH_QREG(8); return launch_status("score_partial");
+        switch (a.rows->g) {
+            case 1: return launch_tile_path<1, DIM, DT>(a);
+            case 2: return launch_tile_path<2, DIM, DT>(a);
+            case 4: return launch_tile_path<4, DIM, DT>(a);
+            case 8: return launch_tile_path<8, DIM, DT>(a);
             default: break;
         }
     }
-#undef KVM_LAUNCH_QREG
-    const size_t lds = (size_t)g * (DIM / 8) * sizeof(uint4);
-    auto kern = score_partial_kernel<0, DIM, DT, false>;
-    if (lds > 160 * 1024) return fail(KVM_ESHAPE, "kvm_score_step: g %d x dim %d queries do not fit LDS", g, DIM);
-    if (lds > 48 * 1024)
-        KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    kern<<<grid, 256, lds, st>>>(w.tiles, w.n_tiles, g, rows->row_ntok, rows->row_off, rows->row_q_off,
-                                 rows->slot_tbl, kp, ns, qq, scale, w.part);
-    return launch_status("score_partial");
+    return launch_generic_path<DIM, DT>(a);
 }
 
 template <int DT>
-int launch_partial_dim(int dim, int g, dim3 grid, hipStream_t st, const ScoreWs& w, const kvm_rows_t* rows,
-                       const kvm_pool_t* pool, const void* q, float scale) {
-    switch (dim) {
-        case 32: return launch_partial<32, DT>(g, grid, st, w, rows, pool, q, scale);
-        case 64: return launch_partial<64, DT>(g, grid, st, w, rows, pool, q, scale);
-        case 96: return launch_partial<96, DT>(g, grid, st, w, rows, pool, q, scale);
-        case 128: return launch_partial<128, DT>(g, grid, st, w, rows, pool, q, scale);
-        case 192: return launch_partial<192, DT>(g, grid, st, w, rows, pool, q, scale);
-        case 256: return launch_partial<256, DT>(g, grid, st, w, rows, pool, q, scale);
-        case 576: return launch_partial<576, DT>(g, grid, st, w, rows, pool, q, scale);
-        default: return fail(KVM_ESHAPE, "kvm_score_step: no kernel for dim %d", dim);
+int launch_dtype(const ScoreArgs& a) {
+    switch (a.pool->dim) {
+        case 32: return launch_dim<32, DT>(a);
+        case 64: return launch_dim<64, DT>(a);
+        case 96: return launch_dim<96, DT>(a);
+        case 128: return launch_dim<128, DT>(a);
+        case 192: return launch_dim<192, DT>(a);
+        case 256: return launch_dim<256, DT>(a);
+        case 576: return launch_dim<576, DT>(a);
+        default: return fail(KVM_ESHAPE, "kvm_score_step: no kernel for dim %d", a.pool->dim);
     }
 }
 
@@ -465,45 +714,28 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
     KVM_REQUIRE(reinterpret_cast<uintptr_t>(ws) % 256 == 0, KVM_EINVAL, "kvm_score_step: ws not 256-byte aligned");
     KVM_REQUIRE(reinterpret_cast<uintptr_t>(q) % 16 == 0 && reinterpret_cast<uintptr_t>(pool->k_pool) % 16 == 0,
                 KVM_EINVAL, "kvm_score_step: q and k_pool must be 16-byte aligned");
-    const ScoreWs w = carve(ws, rows->n_uids, rows->n_rows, rows->g);
-    KVM_REQUIRE(ws_bytes >= w.bytes, KVM_ENOSPC, "kvm_score_step: workspace %zu < %zu bytes", ws_bytes, w.bytes);
+    ScoreArgs a;
+    a.pool = pool;
+    a.rows = rows;
+    a.q = q;
+    a.scale = softmax_scale;
+    a.agg = agg;
+    a.mass = mass;
+    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g);
+    KVM_REQUIRE(ws_bytes >= a.w.bytes, KVM_ENOSPC, "kvm_score_step: workspace %zu < %zu bytes", ws_bytes, a.w.bytes);
     const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows);
     KVM_REQUIRE(tiles_max <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: too many tiles");
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    a.grid = (unsigned)tiles_max;
+    a.st = static_cast<hipStream_t>(stream);
+    a.pr = PlanRows{rows->n_rows, rows->g,        pool->dim,       rows->n_uids,    rows->q_elems,
+                    rows->row_ntok, rows->row_off, rows->row_q_off, rows->row_active};
     const int n_wg = (rows->n_rows + kPlanThreads - 1) / kPlanThreads;
-    const PlanRows pr{rows->n_rows, rows->g,        pool->dim,       rows->n_uids,    rows->q_elems,
-                      rows->row_ntok, rows->row_off, rows->row_q_off, rows->row_active};
     {
-        TimedLaunch tl("score_plan", st);
-        plan_count_kernel<<<n_wg, kPlanThreads, 0, st>>>(pr, w.wg_sum);
-        plan_scan_kernel<<<1, kPlanThreads, 0, st>>>(n_wg, w.wg_sum, w.n_tiles);
-        plan_emit_kernel<<<n_wg, kPlanThreads, 0, st>>>(pr, w.wg_sum, w.tiles);
+        TimedLaunch tl("score_plan", a.st);
+        plan_count_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum);
+        plan_scan_kernel<<<1, kPlanThreads, 0, a.st>>>(n_wg, a.w.wg_sum, a.w.n_tiles);
+        plan_emit_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum, a.w.tiles, a.w.row_tile0);
         if (int rc = launch_status("score_plan")) return rc;
     }
-    {
-        TimedLaunch tl("score_partial", st);
-        const dim3 grid((unsigned)tiles_max);
-        const int rc = pool->dtype == KVM_BF16
-                           ? launch_partial_dim<KVM_BF16>(pool->dim, rows->g, grid, st, w, rows, pool, q, softmax_scale)
-                           : launch_partial_dim<KVM_FP16>(pool->dim, rows->g, grid, st, w, rows, pool, q, softmax_scale);
-        if (rc) return rc;
-    }
-    {
-        TimedLaunch tl("score_finalize", st);
-        int gp = 1;
-        while (gp < rows->g) gp <<= 1;
-#define KVM_FIN(GP)                                                                                        \
-    case GP:                                                                                               \
-        score_finalize_kernel<GP><<<rows->n_rows, 256, 0, st>>>(pr, rows->slot_tbl, (uint32_t)pool->n_slots, \
-                                                                w.part, agg, mass);                          \
-        break;
-        switch (gp) {
-            KVM_FIN(1) KVM_FIN(2) KVM_FIN(4) KVM_FIN(8) KVM_FIN(16) KVM_FIN(32) KVM_FIN(64) KVM_FIN(128)
-            default: return fail(KVM_ESHAPE, "kvm_score_step: g %d", rows->g);
-        }
-#undef KVM_FIN
-        if (int rc = launch_status("score_finalize")) return rc;
-    }
-    return KVM_OK;
+    return pool->dtype == KVM_BF16 ? launch_dtype<KVM_BF16>(a) : launch_dtype<KVM_FP16>(a);
 }

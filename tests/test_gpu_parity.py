@@ -93,6 +93,21 @@ def test_score_sharp_softmax_large_logits(oracle):
     assert got.max() > 0.5 and np.isfinite(got).all()
 
 
+def test_score_tile_boundaries(oracle):
+    """Rows of exactly one tile (512 blocks), one block more, and several tiles, g = 4 and g = 2."""
+    for hq, hkv, dtype in ((4, 1, synth.BF16), (4, 2, synth.FP16)):
+        lens = [16 * 512, 16 * 512 + 1, 16 * 1024 + 3, 16 * 511 + 15, 16 * 1537]
+        case = synth.make_case(synth.Shape(1, hq, hkv, 64, dtype, True, lens), seed=77, uid_gap=1)
+        evict_some(case, 0.35, 3)
+        # a whole tile of the last row not resident
+        o = case.row_off[-1] + 512
+        case.slot_tbl[o:o + 512] = -9
+        case.state[o:o + 512] = HOST
+        q = synth.make_queries(case, 31)
+        check_mass(oracle, case, q, 0.125)
+        check_mass(oracle, case, q, 0.125, agg=1)
+
+
 def test_score_llama8b_twin(oracle):
     case = synth.llama8b_twin(n_seq=2, n_layers=1)
     evict_some(case, 0.4, 9)
