@@ -20,6 +20,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E published peak
+# FETCH_SIZE 6,609,933 x 2 KiB + WRITE_SIZE 21,527.7 x 1 KiB per launch of score_tile_kernel<4, 128, bf16>
+SCORE_TILE_TRAFFIC_BYTES = int(6609933 * 2048 + 21527.7 * 1024)
 
 
 def main():
@@ -30,6 +32,8 @@ def main():
     ap.add_argument("--n-seq", type=int, default=64, help="sequences in the batch (64 = the named workload)")
     ap.add_argument("--swap-units", type=int, default=1024, help="units evicted and prefetched per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the pass has no cross-GPU step); run with --gpus 1",
@@ -174,14 +178,18 @@ def main():
         cnt, ms = kvm.kvm_timing_read(name)
         kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
     kvm.kvm_timing_reset()
-    # dominant kernel: score_partial.  Algorithmic bytes per launch = per resident unit the K frame
-    # (16 * dim * 2), its table entry (4) and its g (max, sum) pairs (8 g), plus per row the g queries.
-    per_unit = shape.unit_k_bytes + 4 + 8 * g
-    algo_bytes = scored_units * per_unit + n_rows * g * dim * 2
+    # Dominant kernel: score_partial (the tile kernel).  Algorithmic bytes per launch: per resident unit its
+    # K frame (16 * dim * 2) and its mass (4); per block of an active row its table entry (4); per row its
+    # g queries.  Every row of this workload fits one 512-block tile, so no partials go through HBM.
+    n_blocks_active = n
+    algo_bytes = scored_units * (shape.unit_k_bytes + 4) + n_blocks_active * 4 + n_rows * g * dim * 2
     sp = kernels["score_partial"]["avg_ms"]
     achieved = algo_bytes / (sp * 1e-3) / 1e9
+    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload
+    # (profiles/score_tile_llama8b_pmc.md); valid for the default workload only.
+    traffic = SCORE_TILE_TRAFFIC_BYTES if (args.n_seq == 64 and swap == 1024) else None
     roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}
 
     out = {
@@ -206,6 +214,13 @@ def main():
         "setup_s": round(setup_s, 1),
     }
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)              # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- host link measured in the same run (pinned, 1 GiB, both directions) -----------------------
     link_n = 1 << 30
     hbuf = host_tier[:link_n] if host_tier.numel() >= link_n else torch.empty(link_n, dtype=torch.uint8, pin_memory=True)
@@ -226,7 +241,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        sample_seqs = list(range(min(16, args.n_seq)))
+        sample_seqs = list(range(min(32, args.n_seq)))
         # score once more (untimed) so that the masses belong to the table as it stands now
         kvm.kvm_score_step(pool, rows, qs[0], scale, mass, ws)
         torch.cuda.synchronize()

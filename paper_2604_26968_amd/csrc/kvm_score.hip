@@ -381,17 +381,22 @@ __global__ __launch_bounds__(kTileThreads) void score_tile_kernel(
 }
 
 // ---- score_rowmerge: rows of more than one tile, g in {1, 2, 4, 8} -------------------
+// One workgroup per tile again: it folds the (M, Z) of all tiles of its row (a few pairs,
+// read by every thread) and rescales its own tile's values into masses.
 template <int G>
 __global__ __launch_bounds__(kTileThreads) void score_rowmerge_kernel(
-    PlanRows pr, const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots,
-    const float* __restrict__ part_r, const float2* __restrict__ tile_mz, int agg, float* __restrict__ mass) {
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, const int32_t* __restrict__ row_ntok,
+    const int64_t* __restrict__ row_off, const uint32_t* __restrict__ row_tile0,
+    const int32_t* __restrict__ slot_tbl, uint32_t n_slots, const float* __restrict__ part_r,
+    const float2* __restrict__ tile_mz, int agg, float* __restrict__ mass) {
     constexpr int BS = kTileThreads / G;
-    const int row = blockIdx.x;
-    if (!row_scorable(pr, row)) return;
-    const int nb = (pr.row_ntok[row] + 15) >> 4;
+    if (blockIdx.x >= *n_tiles) return;
+    const Tile tile = tiles[blockIdx.x];
+    const int nb = (row_ntok[tile.row] + 15) >> 4;
     if (nb <= kTileBlocks) return;                   // finished by its tile
-    const int64_t uid0 = pr.row_off[row];
-    const float2* tmz = tile_mz + (size_t)row_tile0[row] * G;
+    const int nbt = min(kTileBlocks, nb - tile.b0);
+    const int64_t uid0 = row_off[tile.row] + tile.b0;
+    const float2* tmz = tile_mz + (size_t)row_tile0[tile.row] * G;
     const int n_t = (nb + kTileBlocks - 1) / kTileBlocks;
     const int j = threadIdx.x & (G - 1), bsub = threadIdx.x / G;
     MZ tot{-INFINITY, 0.f};
@@ -399,15 +404,24 @@ __global__ __launch_bounds__(kTileThreads) void score_rowmerge_kernel(
         const float2 p = tmz[i * G + j];
         tot = mz_combine(tot, MZ{p.x, p.y});
     }
-    const float inv = tot.z > 0.f ? 1.f / tot.z : 0.f;
-    for (int b0 = 0; b0 < nb; b0 += BS) {
-        const int b = b0 + bsub;
-        const bool res = b < nb && (uint32_t)slot_tbl[uid0 + (b < nb ? b : 0)] < n_slots;
-        float v = 0.f;
-        if (res) {
-            const float m_tile = tmz[(b / kTileBlocks) * G + j].x;
-            v = part_r[(uid0 + b) * G + j] * __expf(m_tile - tot.m) * inv;
-        }
+    // this tile's factor exp(M_tile - M_row) / Z_row
+    const float f = tot.z > 0.f ? __expf(tile_mz[(size_t)blockIdx.x * G + j].x - tot.m) / tot.z : 0.f;
+    // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
+    constexpr int SWEEPS = kTileBlocks / BS;
+    float r[SWEEPS];
+    int32_t slot[SWEEPS];
+#pragma unroll
+    for (int k = 0; k < SWEEPS; ++k) {
+        const int b = k * BS + bsub;
+        const int bc = b < nbt ? b : 0;
+        slot[k] = slot_tbl[uid0 + bc];
+        r[k] = part_r[(uid0 + bc) * G + j];
+    }
+#pragma unroll
+    for (int k = 0; k < SWEEPS; ++k) {
+        const int b = k * BS + bsub;
+        const bool res = b < nbt && (uint32_t)slot[k] < n_slots;
+        float v = res ? r[k] * f : 0.f;
 #pragma unroll
         for (int d = G / 2; d >= 1; d >>= 1) {
             const float o = __shfl_xor(v, d);
@@ -613,9 +627,9 @@ int launch_tile_path(const ScoreArgs& a) {
         if (int rc = launch_status("score_tile")) return rc;
     }
     TimedLaunch tl("score_finalize", a.st);
-    score_rowmerge_kernel<G><<<a.rows->n_rows, kTileThreads, 0, a.st>>>(
-        a.pr, a.w.row_tile0, a.rows->slot_tbl, ns, reinterpret_cast<const float*>(a.w.part), a.w.tile_mz, a.agg,
-        a.mass);
+    score_rowmerge_kernel<G><<<a.grid, kTileThreads, 0, a.st>>>(
+        a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl, ns,
+        reinterpret_cast<const float*>(a.w.part), a.w.tile_mz, a.agg, a.mass);
     return launch_status("score_rowmerge");
 }
 
