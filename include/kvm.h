@@ -276,7 +276,7 @@ int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8
  * ======================================================================== */
 #define KVM_OP_SCORE  0
 #define KVM_OP_SELECT 1
-/* Bytes of device scratch the op needs for these sizes (g, dim ignored by SELECT). */
+/* Bytes of device scratch the op needs for these sizes (n_rows, g, dim ignored by SELECT). */
 size_t kvm_workspace_bytes(int op, int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim);
 
 /* Text describing the last error returned on this thread ("" if none). */

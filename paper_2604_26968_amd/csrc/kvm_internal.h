@@ -54,17 +54,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- shapes ----------------------------------------------------------------
 constexpr int kWave = 64;
-#ifndef KVM_TILE_BLOCKS
-#define KVM_TILE_BLOCKS 512
-#endif
-constexpr int kTileBlocks = KVM_TILE_BLOCKS;  // token blocks of one row handled by one workgroup of the scorer (multiple of 256)
-
-// Upper bound on the number of scorer tiles: rows do not overlap in uid space,
-// so sum(ceil(nb_r / T)) <= n_uids / T + n_rows.
-inline int64_t max_tiles(int64_t n_uids, int64_t n_rows) { return n_uids / kTileBlocks + n_rows; }
-
 // Workspace sizes, defined next to the kernels that use them.
-size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g);
+size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim);
 size_t select_workspace_bytes(int64_t n_uids);
 
 }  // namespace kvm

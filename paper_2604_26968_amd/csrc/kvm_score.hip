@@ -5,27 +5,30 @@
 // query heads that share the KV head (GQA grouping rule, section 3.4).
 //
 // Structure (all kernels in this file):
-//   plan_*            build the list of tiles = (row, first block) of at most 512 blocks
-//                     for the active rows, on the device, so the scorer's grid has no
-//                     idle workgroups whatever the spread of row lengths
-//   score_tile        g in {1, 2, 4, 8}, queries in registers: one workgroup per tile, one
-//                     wavefront per unit at a time.  Per (unit, query) block maximum m and
-//                     sum s = sum exp(z - m) stay in LDS; the workgroup reduces them to the
-//                     tile's (M, Z).  A row that fits one tile is finished on the spot (only
-//                     the masses are written); otherwise the tile writes s*exp(m - M) per
-//                     (unit, query), coalesced, plus its (M, Z), and
-//   score_rowmerge    combines the tiles of such a row and writes its masses
+//   plan_*          build the list of tiles = (row, first block) of at most T blocks for the
+//                   active rows, on the device, so the scorer's grid has no idle workgroups
+//                   whatever the spread of row lengths.  T depends on the kernel (32 .. 512).
+//   score_tile_*    one workgroup per tile, one wavefront per unit at a time.  Per
+//                   (unit, query) the block maximum m and s = sum exp(z - m) stay in LDS;
+//                   the workgroup reduces them to the tile's (M, Z) per query.  A row that
+//                   fits one tile is finished on the spot (only its masses are written);
+//                   otherwise the tile writes s * exp(m - M) per (unit, query), coalesced,
+//                   plus its (M, Z), and score_rowmerge combines the tiles of the row.
+//       _dot2       g in {1, 2, 4, 8}: queries in registers, v_dot2 with fp32 accumulate
+//       _mfma       any g <= 128, dim <= 256: queries as matrix-core operands in registers
 //   score_partial_generic / score_finalize
-//                     any g up to 128 and dim up to 576: queries staged in LDS, (m, s)
-//                     pairs through global memory, one workgroup per row to finish
+//                   any g and dim up to 576: queries staged in LDS, (m, s) pairs through
+//                   global memory, one workgroup per row to finish
 //
 // The tile kernels are the only ones that touch K; they read every resident unit
 // exactly once with non-temporal 16-byte loads that cover 1 KiB contiguous per
-// wavefront instruction.  With the [dim/8][16][8] unit layout lane l holds token
-// l%16, channel group 4*kk + l/16 of load kk, so a lane accumulates its share of
-// q.k in registers and the only cross-lane traffic is a reduce-scatter over the
-// four 16-lane rows (two row-swap instructions per four queries) followed by
-// 16-lane DPP reductions for the block maximum and sum.
+// wavefront instruction.  With the [dim/8][16][8] frame layout lane l of load kk
+// holds token l%16, channels 32*kk + 8*(l/16) .. +7, which is at once
+//   - a lane-private share of q.k for the dot2 kernel (cross-lane work: a reduce-scatter
+//     over the four 16-lane rows with two row swaps per four queries, then 16-lane DPP
+//     reductions for the block maximum and sum), and
+//   - the A operand of v_mfma_f32_16x16x32 for k-step kk (row = token, k = channel), so
+//     K goes from the load straight into the matrix core.
 #include "kvm_internal.h"
 
 namespace kvm {
@@ -36,9 +39,16 @@ struct Tile {
     int32_t b0;
 };
 
+constexpr int kThreads = 256;   // workgroup size of every scorer kernel (4 wavefronts)
+
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
 
+// ---- arithmetic on 16-bit pairs -------------------------------------------------
 template <int DT>
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c);
 template <>
@@ -57,6 +67,16 @@ __device__ __forceinline__ float dot8(const uint4& k, const uint4& q, float c) {
     c = dot2<DT>(k.z, q.z, c);
     c = dot2<DT>(k.w, q.w, c);
     return c;
+}
+
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
+    if constexpr (DT == KVM_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                       0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0,
+                                                      0, 0);
 }
 
 // ---- cross-lane helpers -------------------------------------------------------
@@ -81,29 +101,69 @@ __device__ __forceinline__ float row16_sum(float v) {
     v += dpp_f<0x140>(v);
     return v;
 }
-// The row-swap builtins return both swapped registers.  hipcc 7.2 folds r[0] + r[1]
-// into r[0] + r[0] when the two results feed one add directly; passing them through an
-// empty asm statement keeps them in distinct registers (the compiler still inserts the
+
+// v_permlane32_swap exchanges rows 2,3 of its first operand with rows 0,1 of its second;
+// v_permlane16_swap exchanges the odd rows of the first with the even rows of the second
+// (a row = 16 lanes).  The builtins return both registers.  hipcc 7.2 folds r[0] + r[1]
+// into r[0] + r[0] when the two results feed one operation directly; passing them through
+// an empty asm statement keeps them in distinct registers (the compiler still inserts the
 // wait states the instruction needs).
-__device__ __forceinline__ float add_swapped(unsigned x, unsigned y) {
-    asm volatile("" : "+v"(x), "+v"(y));
-    return __builtin_bit_cast(float, x) + __builtin_bit_cast(float, y);
+__device__ __forceinline__ void swap32(float a, float b, float& x, float& y) {
+    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
+    unsigned u = r[0], v = r[1];
+    asm volatile("" : "+v"(u), "+v"(v));
+    x = __builtin_bit_cast(float, u);
+    y = __builtin_bit_cast(float, v);
+}
+__device__ __forceinline__ void swap16(float a, float b, float& x, float& y) {
+    auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
+    unsigned u = r[0], v = r[1];
+    asm volatile("" : "+v"(u), "+v"(v));
+    x = __builtin_bit_cast(float, u);
+    y = __builtin_bit_cast(float, v);
 }
 // a, b hold partial sums in all four 16-lane rows.  Returns, in rows 0 and 1,
 // a summed over row pairs (0,2) and (1,3); in rows 2 and 3 the same for b.
 __device__ __forceinline__ float fold_halves(float a, float b) {
-    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
-    return add_swapped(r[0], r[1]);
+    float x, y;
+    swap32(a, b, x, y);
+    return x + y;
 }
 // a, b as returned by fold_halves.  Row 0 gets a's rows 0+1, row 1 b's rows 0+1,
 // row 2 a's rows 2+3, row 3 b's rows 2+3.
 __device__ __forceinline__ float fold_rows(float a, float b) {
-    auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
-    return add_swapped(r[0], r[1]);
+    float x, y;
+    swap16(a, b, x, y);
+    return x + y;
 }
 // After fold_rows(fold_halves(a0, a1), fold_halves(a2, a3)) the 16-lane row
-// `cg` holds the complete sum of a_{kQueryOfRow[cg]}.
+// `cg` holds the complete sum of a_{query_of_row(cg)}.
 __device__ __forceinline__ int query_of_row(int cg) { return ((cg & 1) << 1) | (cg >> 1); }
+// All-reduce over the four rows (lanes l, l^16, l^32, l^48).
+__device__ __forceinline__ float rows4_max(float v) {
+    float x, y;
+    swap32(v, v, x, y);
+    v = fmaxf(x, y);
+    swap16(v, v, x, y);
+    return fmaxf(x, y);
+}
+__device__ __forceinline__ float rows4_sum(float v) {
+    float x, y;
+    swap32(v, v, x, y);
+    v = x + y;
+    swap16(v, v, x, y);
+    return x + y;
+}
+
+// Running softmax statistics: maximum m and z = sum exp(x - m).
+struct MZ {
+    float m, z;
+};
+__device__ __forceinline__ MZ mz_combine(MZ a, MZ b) {
+    const float M = fmaxf(a.m, b.m);
+    if (M == -INFINITY) return MZ{M, 0.f};
+    return MZ{M, a.z * __expf(a.m - M) + b.z * __expf(b.m - M)};
+}
 
 // ---- plan: tiles of the active rows ------------------------------------------
 constexpr int kPlanThreads = 1024;
@@ -113,6 +173,7 @@ constexpr int kPlanThreads = 1024;
 struct PlanRows {
     int n_rows;
     int g, dim;
+    int tile_blocks;
     int64_t n_uids, q_elems;
     const int32_t* row_ntok;
     const int64_t* row_off;
@@ -135,7 +196,7 @@ __device__ __forceinline__ bool row_scorable(const PlanRows& p, int r) {
 __device__ __forceinline__ uint32_t tiles_of_row(const PlanRows& p, int r) {
     if (!row_scorable(p, r)) return 0;
     const uint32_t nb = ((uint32_t)p.row_ntok[r] + 15u) >> 4;
-    return (nb + kTileBlocks - 1) / kTileBlocks;
+    return (nb + p.tile_blocks - 1) / p.tile_blocks;
 }
 
 // Exclusive scan of one value per thread over a workgroup of kPlanThreads; returns the
@@ -189,26 +250,42 @@ __global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, con
     uint32_t total;
     const uint32_t first = wg_base[blockIdx.x] + wg_exclusive_scan(nt, &total);
     if (r < p.n_rows) row_tile0[r] = first;
-    for (uint32_t i = 0; i < nt; ++i) tiles[first + i] = Tile{r, (int32_t)(i * kTileBlocks)};
+    for (uint32_t i = 0; i < nt; ++i) tiles[first + i] = Tile{r, (int32_t)(i * p.tile_blocks)};
 }
 
 // ---- shared pieces of the tile kernels ---------------------------------------------
-constexpr int kTileThreads = 256;
-constexpr int kEntriesPerThread = kTileBlocks / kTileThreads;
-static_assert(kTileBlocks % kTileThreads == 0, "whole table entries per thread");
 
-typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+// What every tile kernel derives from its tile.
+struct TileCtx {
+    int row, b0;
+    int ntok, nb, nbt;       // tokens and blocks of the row, blocks of this tile
+    int64_t uid0;            // uid of the tile's block 0
+};
+template <int T>
+__device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, const int32_t* row_ntok, const int64_t* row_off) {
+    const Tile tile = tiles[blockIdx.x];
+    TileCtx c;
+    c.row = tile.row;
+    c.b0 = tile.b0;
+    c.ntok = row_ntok[tile.row];
+    c.nb = (c.ntok + 15) >> 4;
+    c.nbt = min(T, c.nb - tile.b0);
+    c.uid0 = row_off[tile.row] + tile.b0;
+    return c;
+}
 
 // Resident units of a tile, compacted into LDS as (block index in tile, pool frame), in
-// block order: every thread looks at kEntriesPerThread table entries, a ballot + popcount
-// gives each resident entry its place.  Returns the list length.  Ends with a barrier.
+// block order: every thread looks at up to T/256 table entries, a ballot + popcount
+// gives each resident entry its place.  Returns the list length.  Contains two barriers.
+template <int T>
 __device__ __forceinline__ int build_unit_list(const int32_t* __restrict__ slot_tbl, int64_t uid0, int nbt,
-                                               uint32_t n_slots, int2* s_list, int* s_cnt /* [entries * 4] */) {
+                                               uint32_t n_slots, int2* s_list, int* s_cnt /* [E * 4] */) {
+    constexpr int E = (T + kThreads - 1) / kThreads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int slot[kEntriesPerThread], within[kEntriesPerThread];
+    int slot[E], within[E];
 #pragma unroll
-    for (int e = 0; e < kEntriesPerThread; ++e) {
-        const int b = e * kTileThreads + threadIdx.x;
+    for (int e = 0; e < E; ++e) {
+        const int b = e * kThreads + threadIdx.x;
         slot[e] = b < nbt ? slot_tbl[uid0 + b] : -1;
         if ((uint32_t)slot[e] >= n_slots) slot[e] = -1;
         const uint64_t bal = __ballot(slot[e] >= 0);
@@ -218,14 +295,14 @@ __device__ __forceinline__ int build_unit_list(const int32_t* __restrict__ slot_
     __syncthreads();
     int total = 0;
 #pragma unroll
-    for (int e = 0; e < kEntriesPerThread; ++e) {
+    for (int e = 0; e < E; ++e) {
         int base = total;
         for (int w = 0; w < 4; ++w) {
             const int c = s_cnt[e * 4 + w];
             if (w < wave) base += c;
             total += c;
         }
-        if (slot[e] >= 0) s_list[base + within[e]] = make_int2(e * kTileThreads + threadIdx.x, slot[e]);
+        if (slot[e] >= 0) s_list[base + within[e]] = make_int2(e * kThreads + threadIdx.x, slot[e]);
     }
     __syncthreads();
     return total;
@@ -248,43 +325,159 @@ __device__ __forceinline__ int2 list_entry(const int2* s_list, int idx) {      /
     return make_int2(__builtin_amdgcn_readfirstlane(e.x), __builtin_amdgcn_readfirstlane(e.y));
 }
 
-// Running softmax statistics: maximum m and z = sum exp(x - m).
-struct MZ {
-    float m, z;
-};
-__device__ __forceinline__ MZ mz_combine(MZ a, MZ b) {
-    const float M = fmaxf(a.m, b.m);
-    if (M == -INFINITY) return MZ{M, 0.f};
-    return MZ{M, a.z * __expf(a.m - M) + b.z * __expf(b.m - M)};
+// The unit loop shared by the tile kernels.  Wavefront w takes list entries w, w + 4, ...:
+// balanced whatever the residency pattern.  Two units are in flight per wavefront; the
+// loads of the following unit are issued unconditionally (past the end of the list they
+// re-read the last unit, a cache hit): a branch around them would make the compiler wait
+// for every outstanding load before the first use of the current unit, which serialises
+// load and compute.  `unit(cur, block index in tile)` consumes one unit.
+template <int NK, class UnitFn>
+__device__ __forceinline__ void for_each_unit(const int2* s_list, int n_res, const uint4* __restrict__ k_pool,
+                                              int unit_v4, UnitFn unit) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4 cur[NK], nxt[NK];
+    int idx = wave;
+    int i_cur = -1;
+    if (idx < n_res) {
+        const int2 e = list_entry(s_list, idx);
+        i_cur = e.x;
+        load_unit<NK>(cur, k_pool, (uint32_t)e.y, unit_v4, lane);
+    }
+    while (i_cur >= 0) {
+        idx += 4;
+        const int2 e_nxt = list_entry(s_list, idx < n_res ? idx : n_res - 1);
+        const int i_nxt = idx < n_res ? e_nxt.x : -1;
+        load_unit<NK>(nxt, k_pool, (uint32_t)e_nxt.y, unit_v4, lane);
+        unit(cur, i_cur);
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) cur[kk] = nxt[kk];
+        i_cur = i_nxt;
+    }
 }
 
-// ---- score_tile: g in {1, 2, 4, 8}, queries in registers ----------------------------
-template <int G, int DIM, int DT>
-__global__ __launch_bounds__(kTileThreads) void score_tile_kernel(
+// Where a tile kernel leaves its results.
+struct TileOut {
+    int agg;
+    float* mass;        // [n_uids]
+    float* part_r;      // [n_uids][g]: s * exp(m - M_tile), rows of more than one tile only
+    float2* tile_mz;    // [n_tiles][g]: (M_tile, Z_tile), same rows
+};
+
+// Group aggregation of v over the GP lanes / threads that hold the queries of one block.
+template <int GP>
+__device__ __forceinline__ float group_agg(float v, int agg, float* s_v) {
+    if constexpr (GP <= 64) {
+#pragma unroll
+        for (int d = GP / 2; d >= 1; d >>= 1) {
+            const float o = __shfl_xor(v, d);
+            v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
+        }
+    } else {
+        // 128 threads per block: through LDS; the result is valid in the thread with j == 0
+        __syncthreads();
+        s_v[threadIdx.x] = v;
+        __syncthreads();
+        if ((threadIdx.x & (GP - 1)) == 0) {
+            for (int i = 1; i < GP; ++i) {
+                const float o = s_v[threadIdx.x + i];
+                v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
+            }
+        }
+    }
+    return v;
+}
+
+// Per-query total of (m, z) over the whole workgroup; thread (bsub, j) = (tid / GP, tid % GP)
+// contributes `acc` for query j.  Contains one barrier.
+template <int GP>
+__device__ __forceinline__ MZ wg_total(MZ acc, float2* s_red /* [256] */) {
+    const int j = threadIdx.x & (GP - 1);
+#pragma unroll
+    for (int d = GP; d < 64; d <<= 1) acc = mz_combine(acc, MZ{__shfl_xor(acc.m, d), __shfl_xor(acc.z, d)});
+    s_red[threadIdx.x] = make_float2(acc.m, acc.z);
+    __syncthreads();
+    MZ tot{-INFINITY, 0.f};
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        if (GP <= 64 || (w & 1) == (j >> 6)) {
+            const float2 p = s_red[w * 64 + (GP <= 64 ? j : (j & 63))];
+            tot = mz_combine(tot, MZ{p.x, p.y});
+        }
+    return tot;
+}
+
+// Epilogue of a tile kernel: s_ms[b * g + j] holds (m, s) of block b, query j, or
+// (-inf, 0) where the block is not resident.  GP = smallest power of two >= g; thread
+// (bsub, j) sweeps blocks bsub, bsub + 256/GP, ...
+template <int GP, int T>
+__device__ __forceinline__ void tile_epilogue(const float2* s_ms, float2* s_red /* [256] */, float2* s_tot /* [GP] */,
+                                              float* s_v /* [256], GP > 64 only */, int g, const TileCtx& c,
+                                              const TileOut& o) {
+    constexpr int BS = kThreads / GP;
+    const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
+    const bool jv = j < g;
+    MZ acc{-INFINITY, 0.f};
+    if (jv)
+        for (int b = bsub; b < c.nbt; b += BS) {
+            const float2 p = s_ms[b * g + j];
+            acc = mz_combine(acc, MZ{p.x, p.y});
+        }
+    const MZ tot = wg_total<GP>(acc, s_red);
+
+    if (c.nb <= T) {
+        // the row is this tile: finish it here (the tile has resident units, so tot.z >= 1 for every query)
+        const float inv = jv ? 1.f / tot.z : 0.f;
+        for (int b0 = 0; b0 < c.nbt; b0 += BS) {
+            const int b = b0 + bsub;
+            const bool in = b < c.nbt;
+            const float2 p = (in && jv) ? s_ms[b * g + j] : make_float2(-INFINITY, 0.f);
+            float v = p.y * __expf(p.x - tot.m) * inv;     // p.y = 0 where the block is not resident
+            if (!(p.y > 0.f)) v = 0.f;
+            v = group_agg<GP>(v, o.agg, s_v);
+            if (in && j == 0 && p.y > 0.f) o.mass[c.uid0 + b] = o.agg == KVM_AGG_MAX ? v : v / (float)g;
+        }
+    } else {
+        if (bsub == 0 && jv) {
+            s_tot[j] = make_float2(tot.m, tot.z);
+            o.tile_mz[(size_t)blockIdx.x * g + j] = make_float2(tot.m, tot.z);
+        }
+        __syncthreads();
+        // s * exp(m - M_tile) per (unit, query), contiguous for the whole tile; 0 where not resident
+        for (int i = threadIdx.x; i < c.nbt * g; i += kThreads) {
+            const float2 p = s_ms[i];
+            o.part_r[c.uid0 * g + i] = p.y > 0.f ? p.y * __expf(p.x - s_tot[i % g].x) : 0.f;
+        }
+    }
+}
+
+// LDS a tile kernel needs besides its (m, s) array.
+template <int T, int GP>
+struct TileLds {
+    int2 list[T];
+    int cnt[((T + kThreads - 1) / kThreads) * 4];
+    float2 red[kThreads];
+    float2 tot[GP];
+    float v[GP > 64 ? kThreads : 1];
+};
+
+// ---- score_tile_dot2: g in {1, 2, 4, 8}, queries in registers ----------------------
+template <int G, int DIM, int DT, int T>
+__global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, const int32_t* __restrict__ row_ntok,
     const int64_t* __restrict__ row_off, const int64_t* __restrict__ row_q_off,
     const int32_t* __restrict__ slot_tbl, const uint4* __restrict__ k_pool, uint32_t n_slots,
-    const uint16_t* __restrict__ q, float scale, int agg, float* __restrict__ mass, float* __restrict__ part_r,
-    float2* __restrict__ tile_mz) {
+    const uint16_t* __restrict__ q, float scale, TileOut out) {
     static_assert(G == 1 || G == 2 || G == 4 || G == 8, "power-of-two group sizes only");
     constexpr int NK = DIM / 32;          // 16-byte loads per lane per unit
-    constexpr int UNIT_V4 = DIM * 2;      // 16-byte vectors per unit
     constexpr int QROW_V4 = DIM / 8;      // 16-byte vectors per query
-    constexpr int BS = kTileThreads / G;  // blocks per sweep of the epilogue
-    __shared__ float2 s_ms[kTileBlocks * G];   // (m, s) per (block, query); (-inf, 0) = not resident
-    __shared__ int2 s_list[kTileBlocks];
-    __shared__ int s_cnt[kEntriesPerThread * 4];
-    __shared__ float2 s_red[4][G];
+    __shared__ float2 s_ms[T * G];        // (m, s) per (block, query); (-inf, 0) = not resident
+    __shared__ TileLds<T, G> lds;
 
     if (blockIdx.x >= *n_tiles) return;
-    const Tile tile = tiles[blockIdx.x];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off);
+    const int lane = threadIdx.x & 63;
     const int t = lane & 15, cg = lane >> 4;
-    const int ntok = row_ntok[tile.row];
-    const int nb = (ntok + 15) >> 4;
-    const int nbt = min(kTileBlocks, nb - tile.b0);
-    const int64_t uid0 = row_off[tile.row] + tile.b0;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[tile.row]);
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
 
     uint4 qv[G][NK];
 #pragma unroll
@@ -292,31 +485,12 @@ __global__ __launch_bounds__(kTileThreads) void score_tile_kernel(
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) qv[j][kk] = qrow[j * QROW_V4 + 4 * kk + cg];
 
-    for (int i = threadIdx.x; i < nbt * G; i += kTileThreads) s_ms[i] = make_float2(-INFINITY, 0.f);
-    const int n_res = build_unit_list(slot_tbl, uid0, nbt, n_slots, s_list, s_cnt);
+    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_ms[i] = make_float2(-INFINITY, 0.f);
+    const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) return;                      // nothing resident in this tile (uniform)
 
-    // Wavefront w takes list entries w, w + 4, ...: balanced whatever the residency pattern.
-    // Two units in flight per wavefront.  The loads of the following unit are issued
-    // unconditionally (past the end of the list they re-read the last unit, a cache hit): a
-    // branch around them would make the compiler wait for every outstanding load before the
-    // first use of the current unit, which serialises load and compute.
-    uint4 cur[NK], nxt[NK];
-    int idx = wave;
-    int i_cur = -1;
-    if (idx < n_res) {
-        const int2 e = list_entry(s_list, idx);
-        i_cur = e.x;
-        load_unit<NK>(cur, k_pool, (uint32_t)e.y, UNIT_V4, lane);
-    }
-    while (i_cur >= 0) {
-        idx += 4;
-        const int2 e_nxt = list_entry(s_list, idx < n_res ? idx : n_res - 1);
-        const int i_nxt = idx < n_res ? e_nxt.x : -1;
-        load_unit<NK>(nxt, k_pool, (uint32_t)e_nxt.y, UNIT_V4, lane);
-
-        const int tok_in_block = min(16, ntok - 16 * (tile.b0 + i_cur));
-        const bool valid = t < tok_in_block;
+    for_each_unit<NK>(lds.list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
+        const bool valid = t < min(16, c.ntok - 16 * (c.b0 + i_cur));
         // four queries at a time: each 16-lane row ends up owning one of them
 #pragma unroll
         for (int j0 = 0; j0 < G; j0 += 4) {
@@ -335,146 +509,148 @@ __global__ __launch_bounds__(kTileThreads) void score_tile_kernel(
             const int jq = j0 + query_of_row(cg);
             if (t == 0 && jq < G) s_ms[i_cur * G + jq] = make_float2(mx, s);
         }
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) cur[kk] = nxt[kk];
-        i_cur = i_nxt;
-    }
+    });
     __syncthreads();
-
-    // Tile statistics per query: thread (bsub, j) sweeps blocks bsub, bsub + BS, ...
-    const int j = threadIdx.x & (G - 1), bsub = threadIdx.x / G;
-    MZ acc{-INFINITY, 0.f};
-    for (int b = bsub; b < nbt; b += BS) {
-        const float2 p = s_ms[b * G + j];
-        acc = mz_combine(acc, MZ{p.x, p.y});
-    }
-#pragma unroll
-    for (int d = G; d < 64; d <<= 1) acc = mz_combine(acc, MZ{__shfl_xor(acc.m, d), __shfl_xor(acc.z, d)});
-    if (lane < G) s_red[wave][lane] = make_float2(acc.m, acc.z);
-    __syncthreads();
-    MZ tot{s_red[0][j].x, s_red[0][j].y};
-#pragma unroll
-    for (int w = 1; w < 4; ++w) tot = mz_combine(tot, MZ{s_red[w][j].x, s_red[w][j].y});
-
-    if (nb <= kTileBlocks) {
-        // the row is this tile: finish it here
-        const float inv = 1.f / tot.z;                  // n_res > 0, so tot.z >= 1
-        for (int b0 = 0; b0 < nbt; b0 += BS) {
-            const int b = b0 + bsub;
-            const float2 p = b < nbt ? s_ms[b * G + j] : make_float2(-INFINITY, 0.f);
-            float v = p.y * __expf(p.x - tot.m) * inv;  // exp(-inf) = 0 for blocks that are not resident
-#pragma unroll
-            for (int d = G / 2; d >= 1; d >>= 1) {
-                const float o = __shfl_xor(v, d);
-                v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
-            }
-            if (j == 0 && p.y > 0.f) mass[uid0 + b] = agg == KVM_AGG_MAX ? v : v * (1.f / G);
-        }
-    } else {
-        // s * exp(m - M_tile) per (unit, query), contiguous for the whole tile; 0 where not resident
-        for (int i = threadIdx.x; i < nbt * G; i += kTileThreads) {
-            const float2 p = s_ms[i];
-            part_r[uid0 * G + i] = p.y * __expf(p.x - tot.m);
-        }
-        if (threadIdx.x < G) tile_mz[(size_t)blockIdx.x * G + threadIdx.x] = make_float2(tot.m, tot.z);
-    }
+    tile_epilogue<G, T>(s_ms, lds.red, lds.tot, lds.v, G, c, out);
 }
 
-// ---- score_rowmerge: rows of more than one tile, g in {1, 2, 4, 8} -------------------
+// ---- score_tile_mfma: any g <= 16 * NCT, queries as matrix-core operands -----------
+// Per unit the logits are the dense product [16 tokens x dim] . [dim x g].  The queries
+// are the B operands (column = query l%16 of a 16-query column tile, k = channel), loaded
+// once per workgroup.  Result layout: lane l holds tokens 4*(l/16) + 0..3 of query l%16.
+template <int NCT, int DIM, int DT, int T>
+__global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
+    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
+    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
+    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out) {
+    constexpr int NK = DIM / 32;
+    constexpr int QROW_V4 = DIM / 8;
+    constexpr int GP = NCT * 16;          // 16, 32, 64 or 128
+    __shared__ float2 s_ms[T * NCT * 16];
+    __shared__ TileLds<T, GP> lds;
+
+    if (blockIdx.x >= *n_tiles) return;
+    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off);
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, cg = lane >> 4;
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
+
+    uint4 qb[NCT][NK];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int j = ct * 16 + n;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk)
+            qb[ct][kk] = j < G ? qrow[j * QROW_V4 + 4 * kk + cg] : make_uint4(0, 0, 0, 0);
+    }
+    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_ms[i] = make_float2(-INFINITY, 0.f);
+    const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
+    if (n_res == 0) return;
+
+    for_each_unit<NK>(lds.list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
+        const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) acc = mfma16<DT>(cur[kk], qb[ct][kk], acc);
+            float z[4];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                z[r] = (4 * cg + r) < tok_in_block ? acc[r] * scale : -INFINITY;
+                mx = fmaxf(mx, z[r]);
+            }
+            mx = rows4_max(mx);                      // the block has at least one token, so mx is finite
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s += __expf(z[r] - mx);
+            s = rows4_sum(s);
+            const int j = ct * 16 + n;
+            if (cg == 0 && j < G) s_ms[i_cur * G + j] = make_float2(mx, s);
+        }
+    });
+    __syncthreads();
+    tile_epilogue<GP, T>(s_ms, lds.red, lds.tot, lds.v, G, c, out);
+}
+
+// ---- score_rowmerge: rows of more than one tile ---------------------------------------
 // One workgroup per tile again: it folds the (M, Z) of all tiles of its row (a few pairs,
 // read by every thread) and rescales its own tile's values into masses.
-template <int G>
-__global__ __launch_bounds__(kTileThreads) void score_rowmerge_kernel(
-    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, const int32_t* __restrict__ row_ntok,
-    const int64_t* __restrict__ row_off, const uint32_t* __restrict__ row_tile0,
-    const int32_t* __restrict__ slot_tbl, uint32_t n_slots, const float* __restrict__ part_r,
-    const float2* __restrict__ tile_mz, int agg, float* __restrict__ mass) {
-    constexpr int BS = kTileThreads / G;
+template <int GP, int T>
+__global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int g,
+    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
+    const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
+    constexpr int BS = kThreads / GP;
+    constexpr int SWEEPS = (T + BS - 1) / BS;
+    __shared__ float s_v[GP > 64 ? kThreads : 1];
     if (blockIdx.x >= *n_tiles) return;
-    const Tile tile = tiles[blockIdx.x];
-    const int nb = (row_ntok[tile.row] + 15) >> 4;
-    if (nb <= kTileBlocks) return;                   // finished by its tile
-    const int nbt = min(kTileBlocks, nb - tile.b0);
-    const int64_t uid0 = row_off[tile.row] + tile.b0;
-    const float2* tmz = tile_mz + (size_t)row_tile0[tile.row] * G;
-    const int n_t = (nb + kTileBlocks - 1) / kTileBlocks;
-    const int j = threadIdx.x & (G - 1), bsub = threadIdx.x / G;
+    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off);
+    if (c.nb <= T) return;                           // finished by its tile
+    const float2* tmz = o.tile_mz + (size_t)row_tile0[c.row] * g;
+    const int n_t = (c.nb + T - 1) / T;
+    const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
+    const bool jv = j < g;
     MZ tot{-INFINITY, 0.f};
-    for (int i = 0; i < n_t; ++i) {
-        const float2 p = tmz[i * G + j];
-        tot = mz_combine(tot, MZ{p.x, p.y});
-    }
+    if (jv)
+        for (int i = 0; i < n_t; ++i) {
+            const float2 p = tmz[i * g + j];
+            tot = mz_combine(tot, MZ{p.x, p.y});
+        }
     // this tile's factor exp(M_tile - M_row) / Z_row
-    const float f = tot.z > 0.f ? __expf(tile_mz[(size_t)blockIdx.x * G + j].x - tot.m) / tot.z : 0.f;
+    float f = 0.f;
+    if (jv && tot.z > 0.f) {
+        const float m_tile = o.tile_mz[(size_t)blockIdx.x * g + j].x;
+        f = m_tile > -INFINITY ? __expf(m_tile - tot.m) / tot.z : 0.f;
+    }
     // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
-    constexpr int SWEEPS = kTileBlocks / BS;
     float r[SWEEPS];
     int32_t slot[SWEEPS];
 #pragma unroll
     for (int k = 0; k < SWEEPS; ++k) {
         const int b = k * BS + bsub;
-        const int bc = b < nbt ? b : 0;
-        slot[k] = slot_tbl[uid0 + bc];
-        r[k] = part_r[(uid0 + bc) * G + j];
+        const int bc = b < c.nbt ? b : 0;
+        slot[k] = slot_tbl[c.uid0 + bc];
+        r[k] = o.part_r[(c.uid0 + bc) * g + (jv ? j : 0)];
     }
 #pragma unroll
     for (int k = 0; k < SWEEPS; ++k) {
         const int b = k * BS + bsub;
-        const bool res = b < nbt && (uint32_t)slot[k] < n_slots;
-        float v = res ? r[k] * f : 0.f;
-#pragma unroll
-        for (int d = G / 2; d >= 1; d >>= 1) {
-            const float o = __shfl_xor(v, d);
-            v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
-        }
-        if (res && j == 0) mass[uid0 + b] = agg == KVM_AGG_MAX ? v : v * (1.f / G);
+        const bool res = b < c.nbt && (uint32_t)slot[k] < n_slots;
+        float v = (res && jv) ? r[k] * f : 0.f;
+        v = group_agg<GP>(v, o.agg, s_v);
+        if (res && j == 0) o.mass[c.uid0 + b] = o.agg == KVM_AGG_MAX ? v : v / (float)g;
     }
 }
 
-// ---- score_partial_generic: any g, queries staged in LDS, (m, s) pairs to global -----
+// ---- score_partial_generic: any g and dim, queries staged in LDS, (m, s) pairs to global -----
+constexpr int kGenericTile = 256;
 template <int DIM, int DT>
-__global__ __launch_bounds__(kTileThreads) void score_partial_generic_kernel(
+__global__ __launch_bounds__(kThreads) void score_partial_generic_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
     const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
     const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
     const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale,
     float2* __restrict__ part) {
     constexpr int NK = DIM / 32;
-    constexpr int UNIT_V4 = DIM * 2;
     constexpr int QROW_V4 = DIM / 8;
     extern __shared__ uint4 q_lds[];      // [g][QROW_V4]
-    __shared__ int2 s_list[kTileBlocks];
-    __shared__ int s_cnt[kEntriesPerThread * 4];
+    __shared__ int2 s_list[kGenericTile];
+    __shared__ int s_cnt[4];
 
     if (blockIdx.x >= *n_tiles) return;
-    const Tile tile = tiles[blockIdx.x];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const TileCtx c = tile_ctx<kGenericTile>(tiles, row_ntok, row_off);
+    const int lane = threadIdx.x & 63;
     const int t = lane & 15, cg = lane >> 4;
-    const int ntok = row_ntok[tile.row];
-    const int nb = (ntok + 15) >> 4;
-    const int nbt = min(kTileBlocks, nb - tile.b0);
-    const int64_t uid0 = row_off[tile.row] + tile.b0;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[tile.row]);
-    for (int i = threadIdx.x; i < G * QROW_V4; i += kTileThreads) q_lds[i] = qrow[i];
-    const int n_res = build_unit_list(slot_tbl, uid0, nbt, n_slots, s_list, s_cnt);   // barriers cover q_lds too
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
+    for (int i = threadIdx.x; i < G * QROW_V4; i += kThreads) q_lds[i] = qrow[i];
+    const int n_res = build_unit_list<kGenericTile>(slot_tbl, c.uid0, c.nbt, n_slots, s_list, s_cnt);  // barriers cover q_lds
 
-    uint4 cur[NK], nxt[NK];
-    int idx = wave;
-    int i_cur = -1;
-    if (idx < n_res) {
-        const int2 e = list_entry(s_list, idx);
-        i_cur = e.x;
-        load_unit<NK>(cur, k_pool, (uint32_t)e.y, UNIT_V4, lane);
-    }
-    while (i_cur >= 0) {
-        idx += 4;
-        const int2 e_nxt = list_entry(s_list, idx < n_res ? idx : n_res - 1);
-        const int i_nxt = idx < n_res ? e_nxt.x : -1;
-        load_unit<NK>(nxt, k_pool, (uint32_t)e_nxt.y, UNIT_V4, lane);
-
-        const int tok_in_block = min(16, ntok - 16 * (tile.b0 + i_cur));
-        const bool valid = t < tok_in_block;
-        float2* out = part + (uid0 + i_cur) * G;
+    for_each_unit<NK>(s_list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
+        const bool valid = t < min(16, c.ntok - 16 * (c.b0 + i_cur));
+        float2* out = part + (c.uid0 + i_cur) * G;
         for (int j0 = 0; j0 < G; j0 += 4) {
             float a[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -492,52 +668,36 @@ __global__ __launch_bounds__(kTileThreads) void score_partial_generic_kernel(
             const int jq = j0 + query_of_row(cg);
             if (t == 0 && jq < G) out[jq] = make_float2(mx, s);
         }
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) cur[kk] = nxt[kk];
-        i_cur = i_nxt;
-    }
+    });
 }
 
-// ---- score_finalize -----------------------------------------------------------
+// ---- score_finalize (generic path) -----------------------------------------------------
 // GP = smallest power of two >= g.  Thread (bsub, j) = (tid / GP, tid % GP)
 // handles query j of blocks bsub, bsub + 256/GP, ...
 template <int GP>
-__global__ __launch_bounds__(256) void score_finalize_kernel(
+__global__ __launch_bounds__(kThreads) void score_finalize_kernel(
     PlanRows pr, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, const float2* __restrict__ part, int agg,
     float* __restrict__ mass) {
-    constexpr int BS = 256 / GP;
-    __shared__ float sM[256], sZ[256];
-    __shared__ float sV[256];
+    constexpr int BS = kThreads / GP;
+    __shared__ float2 s_red[kThreads];
+    __shared__ float s_v[GP > 64 ? kThreads : 1];
     const int row = blockIdx.x;
     if (!row_scorable(pr, row)) return;
     const int g = pr.g;
     const int nb = (pr.row_ntok[row] + 15) >> 4;
     const int64_t uid0 = pr.row_off[row];
-    const int j = threadIdx.x % GP, bsub = threadIdx.x / GP;
+    const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
     const bool jv = j < g;
 
-    float M = -INFINITY, Z = 0.f;
-    for (int b = bsub; b < nb; b += BS) {
-        if (!jv || (uint32_t)slot_tbl[uid0 + b] >= n_slots) continue;
-        const float2 p = part[(uid0 + b) * g + j];
-        if (p.x > M) {
-            Z = Z * __expf(M - p.x) + p.y;
-            M = p.x;
-        } else {
-            Z += p.y * __expf(p.x - M);
+    MZ acc{-INFINITY, 0.f};
+    if (jv)
+        for (int b = bsub; b < nb; b += BS) {
+            if ((uint32_t)slot_tbl[uid0 + b] >= n_slots) continue;
+            const float2 p = part[(uid0 + b) * g + j];
+            acc = mz_combine(acc, MZ{p.x, p.y});
         }
-    }
-    sM[threadIdx.x] = M;
-    sZ[threadIdx.x] = Z;
-    __syncthreads();
-    float Mj = -INFINITY;
-    for (int i = 0; i < BS; ++i) Mj = fmaxf(Mj, sM[i * GP + j]);
-    float Zj = 0.f;
-    for (int i = 0; i < BS; ++i) {
-        const float m = sM[i * GP + j];
-        if (m > -INFINITY) Zj += sZ[i * GP + j] * __expf(m - Mj);
-    }
-    const float inv = Zj > 0.f ? 1.f / Zj : 0.f;
+    const MZ tot = wg_total<GP>(acc, s_red);
+    const float inv = tot.z > 0.f ? 1.f / tot.z : 0.f;
 
     for (int b0 = 0; b0 < nb; b0 += BS) {
         const int b = b0 + bsub;
@@ -545,44 +705,52 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(
         float v = 0.f;
         if (res && jv) {
             const float2 p = part[(uid0 + b) * g + j];
-            v = p.y * __expf(p.x - Mj) * inv;
+            v = p.y * __expf(p.x - tot.m) * inv;
         }
-        // combine the GP queries of the block (masses are >= 0, so 0 is neutral for max too)
-        if constexpr (GP <= 64) {
-#pragma unroll
-            for (int d = GP / 2; d >= 1; d >>= 1) {
-                const float o = __shfl_xor(v, d);
-                v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
-            }
-        } else {
-            __syncthreads();
-            sV[threadIdx.x] = v;
-            __syncthreads();
-            if (j == 0) {
-                for (int i = 1; i < GP; ++i) {
-                    const float o = sV[bsub * GP + i];
-                    v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
-                }
-            }
-        }
+        v = group_agg<GP>(v, agg, s_v);
         if (res && j == 0) mass[uid0 + b] = agg == KVM_AGG_MAX ? v : v / (float)g;
     }
 }
 
 // ---- host side ----------------------------------------------------------------
+enum class Path { Dot2, Mfma, Generic };
+
+struct Choice {
+    Path path;
+    int tile_blocks;
+    int nct;        // Mfma: 16-query column tiles (1, 2, 4 or 8)
+};
+
+// Which kernel scores (g, dim), and with what tile size.  The (m, s) array in LDS takes
+// tile_blocks * (padded g) * 8 bytes: 32 KiB in every case.
+Choice choose(int g, int dim) {
+    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8)) return Choice{Path::Dot2, 512, 0};
+    if (dim <= 256) {
+        const int nct = (g + 15) / 16;
+        const int nct_p = nct <= 1 ? 1 : nct <= 2 ? 2 : nct <= 4 ? 4 : 8;
+        return Choice{Path::Mfma, 256 / nct_p, nct_p};
+    }
+    return Choice{Path::Generic, kGenericTile, 0};
+}
+
+inline int64_t max_tiles(int64_t n_uids, int64_t n_rows, int tile_blocks) {
+    // rows do not overlap in uid space, so sum(ceil(nb_r / T)) <= n_uids / T + n_rows
+    return n_uids / tile_blocks + n_rows;
+}
+
 struct ScoreWs {
     uint32_t* n_tiles;
     uint32_t* wg_sum;
     Tile* tiles;
     uint32_t* row_tile0;
     float2* tile_mz;
-    float2* part;       // (m, s) pairs [n_uids][g] (generic path) or floats [n_uids][g] (tile path)
+    float2* part;       // (m, s) pairs [n_uids][g] (generic path) or floats [n_uids][g] (tile paths)
     size_t bytes;
 };
 
-ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g) {
+ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, int tile_blocks) {
     const size_t n_wg = ((size_t)n_rows + kPlanThreads - 1) / kPlanThreads;
-    const size_t tiles_max = (size_t)max_tiles(n_uids, n_rows);
+    const size_t tiles_max = (size_t)max_tiles(n_uids, n_rows, tile_blocks);
     const size_t off_sum = 256;
     const size_t off_tiles = off_sum + align_up(n_wg * sizeof(uint32_t), 256);
     const size_t off_row0 = off_tiles + align_up(tiles_max * sizeof(Tile), 256);
@@ -605,34 +773,50 @@ struct ScoreArgs {
     const kvm_rows_t* rows;
     const void* q;
     float scale;
-    int agg;
-    float* mass;
     PlanRows pr;
     ScoreWs w;
+    TileOut out;
     unsigned grid;
     hipStream_t st;
 };
 
-// g in {1, 2, 4, 8} with the queries small enough for registers: tile kernel + row merge.
-template <int G, int DIM, int DT>
-int launch_tile_path(const ScoreArgs& a) {
-    const uint4* kp = static_cast<const uint4*>(a.pool->k_pool);
-    const uint32_t ns = (uint32_t)a.pool->n_slots;
-    {
-        TimedLaunch tl("score_partial", a.st);
-        score_tile_kernel<G, DIM, DT><<<a.grid, kTileThreads, 0, a.st>>>(
-            a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off, a.rows->slot_tbl, kp, ns,
-            static_cast<const uint16_t*>(a.q), a.scale, a.agg, a.mass, reinterpret_cast<float*>(a.w.part),
-            a.w.tile_mz);
-        if (int rc = launch_status("score_tile")) return rc;
-    }
+template <int GP, int T>
+int launch_rowmerge(const ScoreArgs& a) {
     TimedLaunch tl("score_finalize", a.st);
-    score_rowmerge_kernel<G><<<a.grid, kTileThreads, 0, a.st>>>(
-        a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl, ns,
-        reinterpret_cast<const float*>(a.w.part), a.w.tile_mz, a.agg, a.mass);
+    score_rowmerge_kernel<GP, T><<<a.grid, kThreads, 0, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok,
+                                                               a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
+                                                               (uint32_t)a.pool->n_slots, a.out);
     return launch_status("score_rowmerge");
 }
 
+template <int G, int DIM, int DT>
+int launch_dot2_path(const ScoreArgs& a) {
+    {
+        TimedLaunch tl("score_partial", a.st);
+        score_tile_dot2_kernel<G, DIM, DT, 512><<<a.grid, kThreads, 0, a.st>>>(
+            a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off, a.rows->slot_tbl,
+            static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots, static_cast<const uint16_t*>(a.q),
+            a.scale, a.out);
+        if (int rc = launch_status("score_tile_dot2")) return rc;
+    }
+    return launch_rowmerge<G, 512>(a);
+}
+
+template <int NCT, int DIM, int DT>
+int launch_mfma_path(const ScoreArgs& a) {
+    constexpr int T = 256 / NCT;
+    {
+        TimedLaunch tl("score_partial", a.st);
+        score_tile_mfma_kernel<NCT, DIM, DT, T><<<a.grid, kThreads, 0, a.st>>>(
+            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off,
+            a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
+            static_cast<const uint16_t*>(a.q), a.scale, a.out);
+        if (int rc = launch_status("score_tile_mfma")) return rc;
+    }
+    return launch_rowmerge<NCT * 16, T>(a);
+}
+
+// Any g and dim: queries staged in LDS, vector dot products, (m, s) pairs through global memory.
 template <int DIM, int DT>
 int launch_generic_path(const ScoreArgs& a) {
     const int g = a.rows->g;
@@ -646,19 +830,19 @@ int launch_generic_path(const ScoreArgs& a) {
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     {
         TimedLaunch tl("score_partial", a.st);
-        kern<<<a.grid, kTileThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, g, a.rows->row_ntok, a.rows->row_off,
-                                                  a.rows->row_q_off, a.rows->slot_tbl,
-                                                  static_cast<const uint4*>(a.pool->k_pool), ns,
-                                                  static_cast<const uint16_t*>(a.q), a.scale, a.w.part);
+        kern<<<a.grid, kThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, g, a.rows->row_ntok, a.rows->row_off,
+                                              a.rows->row_q_off, a.rows->slot_tbl,
+                                              static_cast<const uint4*>(a.pool->k_pool), ns,
+                                              static_cast<const uint16_t*>(a.q), a.scale, a.w.part);
         if (int rc = launch_status("score_partial_generic")) return rc;
     }
     TimedLaunch tl("score_finalize", a.st);
     int gp = 1;
     while (gp < g) gp <<= 1;
-#define KVM_FIN(GP)                                                                                             \
-    case GP:                                                                                                    \
-        score_finalize_kernel<GP><<<a.rows->n_rows, 256, 0, a.st>>>(a.pr, a.rows->slot_tbl, ns, a.w.part, a.agg, \
-                                                                    a.mass);                                    \
+#define KVM_FIN(GP)                                                                                               \
+    case GP:                                                                                                      \
+        score_finalize_kernel<GP><<<a.rows->n_rows, kThreads, 0, a.st>>>(a.pr, a.rows->slot_tbl, ns, a.w.part,    \
+                                                                         a.out.agg, a.out.mass);                  \
         break;
     switch (gp) {
         KVM_FIN(1) KVM_FIN(2) KVM_FIN(4) KVM_FIN(8) KVM_FIN(16) KVM_FIN(32) KVM_FIN(64) KVM_FIN(128)
@@ -669,37 +853,48 @@ int launch_generic_path(const ScoreArgs& a) {
 }
 
 template <int DIM, int DT>
-int launch_dim(const ScoreArgs& a) {
+int launch_dim(const ScoreArgs& a, const Choice& ch) {
     if constexpr (DIM <= 128) {
-        switch (a.rows->g) {
-            case 1: return launch_tile_path<1, DIM, DT>(a);
-            case 2: return launch_tile_path<2, DIM, DT>(a);
-            case 4: return launch_tile_path<4, DIM, DT>(a);
-            case 8: return launch_tile_path<8, DIM, DT>(a);
-            default: break;
+        if (ch.path == Path::Dot2) {
+            switch (a.rows->g) {
+                case 1: return launch_dot2_path<1, DIM, DT>(a);
+                case 2: return launch_dot2_path<2, DIM, DT>(a);
+                case 4: return launch_dot2_path<4, DIM, DT>(a);
+                default: return launch_dot2_path<8, DIM, DT>(a);
+            }
+        }
+    }
+    if constexpr (DIM <= 256) {
+        if (ch.path == Path::Mfma) {
+            switch (ch.nct) {
+                case 1: return launch_mfma_path<1, DIM, DT>(a);
+                case 2: return launch_mfma_path<2, DIM, DT>(a);
+                case 4: return launch_mfma_path<4, DIM, DT>(a);
+                default: return launch_mfma_path<8, DIM, DT>(a);
+            }
         }
     }
     return launch_generic_path<DIM, DT>(a);
 }
 
 template <int DT>
-int launch_dtype(const ScoreArgs& a) {
+int launch_dtype(const ScoreArgs& a, const Choice& ch) {
     switch (a.pool->dim) {
-        case 32: return launch_dim<32, DT>(a);
-        case 64: return launch_dim<64, DT>(a);
-        case 96: return launch_dim<96, DT>(a);
-        case 128: return launch_dim<128, DT>(a);
-        case 192: return launch_dim<192, DT>(a);
-        case 256: return launch_dim<256, DT>(a);
-        case 576: return launch_dim<576, DT>(a);
+        case 32: return launch_dim<32, DT>(a, ch);
+        case 64: return launch_dim<64, DT>(a, ch);
+        case 96: return launch_dim<96, DT>(a, ch);
+        case 128: return launch_dim<128, DT>(a, ch);
+        case 192: return launch_dim<192, DT>(a, ch);
+        case 256: return launch_dim<256, DT>(a, ch);
+        case 576: return launch_dim<576, DT>(a, ch);
         default: return fail(KVM_ESHAPE, "kvm_score_step: no kernel for dim %d", a.pool->dim);
     }
 }
 
 }  // namespace
 
-size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g) {
-    return carve(nullptr, n_uids, n_rows, g).bytes;
+size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim) {
+    return carve(nullptr, n_uids, n_rows, g, choose(g, dim).tile_blocks).bytes;
 }
 
 }  // namespace kvm
@@ -728,21 +923,21 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
     KVM_REQUIRE(reinterpret_cast<uintptr_t>(ws) % 256 == 0, KVM_EINVAL, "kvm_score_step: ws not 256-byte aligned");
     KVM_REQUIRE(reinterpret_cast<uintptr_t>(q) % 16 == 0 && reinterpret_cast<uintptr_t>(pool->k_pool) % 16 == 0,
                 KVM_EINVAL, "kvm_score_step: q and k_pool must be 16-byte aligned");
+    const Choice ch = choose(rows->g, pool->dim);
     ScoreArgs a;
     a.pool = pool;
     a.rows = rows;
     a.q = q;
     a.scale = softmax_scale;
-    a.agg = agg;
-    a.mass = mass;
-    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g);
+    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g, ch.tile_blocks);
     KVM_REQUIRE(ws_bytes >= a.w.bytes, KVM_ENOSPC, "kvm_score_step: workspace %zu < %zu bytes", ws_bytes, a.w.bytes);
-    const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows);
+    const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows, ch.tile_blocks);
     KVM_REQUIRE(tiles_max <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: too many tiles");
+    a.out = TileOut{agg, mass, reinterpret_cast<float*>(a.w.part), a.w.tile_mz};
     a.grid = (unsigned)tiles_max;
     a.st = static_cast<hipStream_t>(stream);
-    a.pr = PlanRows{rows->n_rows, rows->g,        pool->dim,       rows->n_uids,    rows->q_elems,
-                    rows->row_ntok, rows->row_off, rows->row_q_off, rows->row_active};
+    a.pr = PlanRows{rows->n_rows, rows->g,        pool->dim,     ch.tile_blocks,  rows->n_uids,
+                    rows->q_elems, rows->row_ntok, rows->row_off, rows->row_q_off, rows->row_active};
     const int n_wg = (rows->n_rows + kPlanThreads - 1) / kPlanThreads;
     {
         TimedLaunch tl("score_plan", a.st);
@@ -751,5 +946,5 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
         plan_emit_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum, a.w.tiles, a.w.row_tile0);
         if (int rc = launch_status("score_plan")) return rc;
     }
-    return pool->dtype == KVM_BF16 ? launch_dtype<KVM_BF16>(a) : launch_dtype<KVM_FP16>(a);
+    return pool->dtype == KVM_BF16 ? launch_dtype<KVM_BF16>(a, ch) : launch_dtype<KVM_FP16>(a, ch);
 }

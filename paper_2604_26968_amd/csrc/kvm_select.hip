@@ -334,9 +334,8 @@ size_t select_workspace_bytes(int64_t n_uids) { return carve(nullptr, n_uids).by
 }  // namespace kvm
 
 extern "C" size_t kvm_workspace_bytes(int op, int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim) {
-    (void)dim;
     if (n_uids < 0 || n_rows < 0) return 0;
-    if (op == KVM_OP_SCORE) return kvm::score_workspace_bytes(n_uids, n_rows, g < 1 ? 1 : g);
+    if (op == KVM_OP_SCORE) return kvm::score_workspace_bytes(n_uids, n_rows, g < 1 ? 1 : g, dim);
     if (op == KVM_OP_SELECT) return kvm::select_workspace_bytes(n_uids);
     return 0;
 }

@@ -58,6 +58,10 @@ def test_score_tiny_gqa_fp16(oracle):
     (16, 1, 64, synth.BF16),     # g = 16
     (5, 1, 96, synth.FP16),      # odd g, dim 96
     (2, 1, 256, synth.BF16),     # dim 256
+    (12, 1, 128, synth.FP16),    # g = 12: one 16-query column tile on the matrix cores
+    (24, 1, 256, synth.BF16),    # g = 24, dim 256: two column tiles
+    (40, 1, 64, synth.BF16),     # g = 40: three column tiles (padded to four)
+    (128, 1, 128, synth.FP16),   # g = 128, dim 128: eight column tiles
 ])
 def test_score_shapes_ragged_rows(oracle, hq, hkv, dim, dtype):
     """Rows of 1 .. 200 blocks with ragged tails, gaps in uid space, spare pool frames,
