@@ -7,18 +7,23 @@
 // Structure (all kernels in this file):
 //   plan_*          build the list of tiles = (row, first block) of at most T blocks for the
 //                   active rows, on the device, so the scorer's grid has no idle workgroups
-//                   whatever the spread of row lengths.  T depends on the kernel (32 .. 512).
-//   score_tile_*    one workgroup per tile, one wavefront per unit at a time.  Per
-//                   (unit, query) the block maximum m and s = sum exp(z - m) stay in LDS;
-//                   the workgroup reduces them to the tile's (M, Z) per query.  A row that
-//                   fits one tile is finished on the spot (only its masses are written);
-//                   otherwise the tile writes s * exp(m - M) per (unit, query), coalesced,
-//                   plus its (M, Z), and score_rowmerge combines the tiles of the row.
-//       _dot2       g in {1, 2, 4, 8}: queries in registers, v_dot2 with fp32 accumulate
-//       _mfma       any g <= 128, dim <= 256: queries as matrix-core operands in registers
+//                   whatever the spread of row lengths.  T depends on the kernel (64 .. 512).
+//   score_tile_*    one workgroup per tile.  Per (unit, query) the kernel keeps
+//                   lse = log sum_t exp(z_t) over the block's tokens in LDS (the block's
+//                   softmax mass is exp(lse - row lse)); the workgroup reduces them to the
+//                   tile's lse per query.  A row that fits one tile is finished on the spot
+//                   (only its masses are written); otherwise the tile writes its block
+//                   values, coalesced, plus the tile value, and score_rowmerge combines the
+//                   tiles of the row.
+//       _dot2       g in {1, 2, 4, 8}, dim <= 128: queries in registers, v_dot2 with fp32
+//                   accumulate, one wavefront per unit
+//       _mfma       any other g <= 128, dim <= 256: queries as matrix-core operands in
+//                   registers, one wavefront per unit
+//       _wide       dim 576 (MLA latent): the four wavefronts split up to 128 queries and
+//                   share each unit through LDS
 //   score_partial_generic / score_finalize
-//                   any g and dim up to 576: queries staged in LDS, (m, s) pairs through
-//                   global memory, one workgroup per row to finish
+//                   fallback for any other (g, dim): queries staged in LDS, (m, s) pairs
+//                   through global memory, one workgroup per row to finish
 //
 // The tile kernels are the only ones that touch K; they read every resident unit
 // exactly once with non-temporal 16-byte loads that cover 1 KiB contiguous per
@@ -359,32 +364,35 @@ __device__ __forceinline__ void for_each_unit(const int2* s_list, int n_res, con
 struct TileOut {
     int agg;
     float* mass;        // [n_uids]
-    float* part_r;      // [n_uids][g]: s * exp(m - M_tile), rows of more than one tile only
-    float2* tile_mz;    // [n_tiles][g]: (M_tile, Z_tile), same rows
+    float* part_lse;    // [n_uids][g]: log sum exp of the block's logits, rows of more than one tile only
+    float* tile_lse;    // [n_tiles][g]: log sum exp over the tile, same rows
 };
 
-// Group aggregation of v over the GP lanes / threads that hold the queries of one block.
-template <int GP>
-__device__ __forceinline__ float group_agg(float v, int agg, float* s_v) {
-    if constexpr (GP <= 64) {
+// Group aggregation of N values per thread over the GP lanes / threads that hold the
+// queries of one block.  For GP = 128 (two wavefronts per block) the wavefront results meet
+// in LDS: s_v holds 4 * N floats and the call contains one barrier.
+template <int GP, int N>
+__device__ __forceinline__ void group_agg(float (&v)[N], int agg, float* s_v) {
+    constexpr int IN_WAVE = GP <= 64 ? GP : 64;
 #pragma unroll
-        for (int d = GP / 2; d >= 1; d >>= 1) {
-            const float o = __shfl_xor(v, d);
-            v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
+    for (int k = 0; k < N; ++k)
+#pragma unroll
+        for (int d = IN_WAVE / 2; d >= 1; d >>= 1) {
+            const float o = __shfl_xor(v[k], d);
+            v[k] = agg == KVM_AGG_MAX ? fmaxf(v[k], o) : v[k] + o;
         }
-    } else {
-        // 128 threads per block: through LDS; the result is valid in the thread with j == 0
+    if constexpr (GP > 64) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        if (lane == 0)
+#pragma unroll
+            for (int k = 0; k < N; ++k) s_v[k * 4 + wave] = v[k];
         __syncthreads();
-        s_v[threadIdx.x] = v;
-        __syncthreads();
-        if ((threadIdx.x & (GP - 1)) == 0) {
-            for (int i = 1; i < GP; ++i) {
-                const float o = s_v[threadIdx.x + i];
-                v = agg == KVM_AGG_MAX ? fmaxf(v, o) : v + o;
-            }
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const float x = s_v[k * 4 + (wave & ~1)], y = s_v[k * 4 + (wave | 1)];
+            v[k] = agg == KVM_AGG_MAX ? fmaxf(x, y) : x + y;
         }
     }
-    return v;
 }
 
 // Per-query total of (m, z) over the whole workgroup; thread (bsub, j) = (tid / GP, tid % GP)
@@ -406,58 +414,60 @@ __device__ __forceinline__ MZ wg_total(MZ acc, float2* s_red /* [256] */) {
     return tot;
 }
 
-// Epilogue of a tile kernel: s_ms[b * g + j] holds (m, s) of block b, query j, or
-// (-inf, 0) where the block is not resident.  GP = smallest power of two >= g; thread
-// (bsub, j) sweeps blocks bsub, bsub + 256/GP, ...
+// log(sum exp) of what an MZ has seen; -inf for nothing.
+__device__ __forceinline__ float mz_lse(MZ a) { return a.z > 0.f ? a.m + __logf(a.z) : -INFINITY; }
+
+// Epilogue of a tile kernel.  s_lse[b * g + j] = log sum_t exp(z_t) over the tokens of block b
+// for query j (the block's softmax mass is exp(s_lse - row lse)), or -inf where the block is
+// not resident.  GP = smallest power of two >= g; thread (bsub, j) sweeps blocks bsub,
+// bsub + 256/GP, ...
 template <int GP, int T>
-__device__ __forceinline__ void tile_epilogue(const float2* s_ms, float2* s_red /* [256] */, float2* s_tot /* [GP] */,
-                                              float* s_v /* [256], GP > 64 only */, int g, const TileCtx& c,
-                                              const TileOut& o) {
+__device__ __forceinline__ void tile_epilogue(const float* s_lse, float2* s_red /* [256] */, float* s_v, int g,
+                                              const TileCtx& c, size_t tile_index, const TileOut& o) {
     constexpr int BS = kThreads / GP;
+    constexpr int SWEEPS = (T + BS - 1) / BS;
     const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
     const bool jv = j < g;
     MZ acc{-INFINITY, 0.f};
     if (jv)
-        for (int b = bsub; b < c.nbt; b += BS) {
-            const float2 p = s_ms[b * g + j];
-            acc = mz_combine(acc, MZ{p.x, p.y});
-        }
-    const MZ tot = wg_total<GP>(acc, s_red);
+        for (int b = bsub; b < c.nbt; b += BS) acc = mz_combine(acc, MZ{s_lse[b * g + j], 1.f});
+    const float tile_lse = mz_lse(wg_total<GP>(acc, s_red));
 
     if (c.nb <= T) {
-        // the row is this tile: finish it here (the tile has resident units, so tot.z >= 1 for every query)
-        const float inv = jv ? 1.f / tot.z : 0.f;
-        for (int b0 = 0; b0 < c.nbt; b0 += BS) {
-            const int b = b0 + bsub;
-            const bool in = b < c.nbt;
-            const float2 p = (in && jv) ? s_ms[b * g + j] : make_float2(-INFINITY, 0.f);
-            float v = p.y * __expf(p.x - tot.m) * inv;     // p.y = 0 where the block is not resident
-            if (!(p.y > 0.f)) v = 0.f;
-            v = group_agg<GP>(v, o.agg, s_v);
-            if (in && j == 0 && p.y > 0.f) o.mass[c.uid0 + b] = o.agg == KVM_AGG_MAX ? v : v / (float)g;
+        // the row is this tile: finish it here, a few sweeps at a time to keep registers low
+        constexpr int CH = SWEEPS < 8 ? SWEEPS : 8;
+        for (int k0 = 0; k0 < SWEEPS; k0 += CH) {
+            float v[CH];
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                const int b = (k0 + k) * BS + bsub;
+                const float l = (b < c.nbt && jv) ? s_lse[b * g + j] : -INFINITY;
+                v[k] = l > -INFINITY ? __expf(l - tile_lse) : 0.f;
+            }
+            if (GP > 64 && k0 > 0) __syncthreads();       // s_v of the previous chunk has been read
+            group_agg<GP, CH>(v, o.agg, s_v);
+#pragma unroll
+            for (int k = 0; k < CH; ++k) {
+                const int b = (k0 + k) * BS + bsub;
+                // query 0 tells whether the block is resident
+                if (j == 0 && b < c.nbt && s_lse[b * g] > -INFINITY)
+                    o.mass[c.uid0 + b] = o.agg == KVM_AGG_MAX ? v[k] : v[k] / (float)g;
+            }
         }
     } else {
-        if (bsub == 0 && jv) {
-            s_tot[j] = make_float2(tot.m, tot.z);
-            o.tile_mz[(size_t)blockIdx.x * g + j] = make_float2(tot.m, tot.z);
-        }
-        __syncthreads();
-        // s * exp(m - M_tile) per (unit, query), contiguous for the whole tile; 0 where not resident
-        for (int i = threadIdx.x; i < c.nbt * g; i += kThreads) {
-            const float2 p = s_ms[i];
-            o.part_r[c.uid0 * g + i] = p.y > 0.f ? p.y * __expf(p.x - s_tot[i % g].x) : 0.f;
-        }
+        if (bsub == 0 && jv) o.tile_lse[tile_index * g + j] = tile_lse;
+        // the tile's block values, contiguous; -inf where not resident
+        for (int i = threadIdx.x; i < c.nbt * g; i += kThreads) o.part_lse[c.uid0 * g + i] = s_lse[i];
     }
 }
 
-// LDS a tile kernel needs besides its (m, s) array.
+// LDS a tile kernel needs besides its block-value array.
 template <int T, int GP>
 struct TileLds {
     int2 list[T];
     int cnt[((T + kThreads - 1) / kThreads) * 4];
     float2 red[kThreads];
-    float2 tot[GP];
-    float v[GP > 64 ? kThreads : 1];
+    float v[GP > 64 ? 4 * ((T + kThreads / GP - 1) / (kThreads / GP)) : 1];
 };
 
 // ---- score_tile_dot2: g in {1, 2, 4, 8}, queries in registers ----------------------
@@ -470,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
     static_assert(G == 1 || G == 2 || G == 4 || G == 8, "power-of-two group sizes only");
     constexpr int NK = DIM / 32;          // 16-byte loads per lane per unit
     constexpr int QROW_V4 = DIM / 8;      // 16-byte vectors per query
-    __shared__ float2 s_ms[T * G];        // (m, s) per (block, query); (-inf, 0) = not resident
+    __shared__ float s_lse[T * G];        // log sum exp per (block, query); -inf = not resident
     __shared__ TileLds<T, G> lds;
 
     if (blockIdx.x >= *n_tiles) return;
@@ -485,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) qv[j][kk] = qrow[j * QROW_V4 + 4 * kk + cg];
 
-    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_ms[i] = make_float2(-INFINITY, 0.f);
+    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_lse[i] = -INFINITY;
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) return;                      // nothing resident in this tile (uniform)
 
@@ -507,11 +517,11 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
             const float e = valid ? __expf(zz - mx) : 0.f;
             const float s = row16_sum(e);
             const int jq = j0 + query_of_row(cg);
-            if (t == 0 && jq < G) s_ms[i_cur * G + jq] = make_float2(mx, s);
+            if (t == 0 && jq < G) s_lse[i_cur * G + jq] = mx + __logf(s);
         }
     });
     __syncthreads();
-    tile_epilogue<G, T>(s_ms, lds.red, lds.tot, lds.v, G, c, out);
+    tile_epilogue<G, T>(s_lse, lds.red, lds.v, G, c, blockIdx.x, out);
 }
 
 // ---- score_tile_mfma: any g <= 16 * NCT, queries as matrix-core operands -----------
@@ -527,7 +537,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     constexpr int NK = DIM / 32;
     constexpr int QROW_V4 = DIM / 8;
     constexpr int GP = NCT * 16;          // 16, 32, 64 or 128
-    __shared__ float2 s_ms[T * NCT * 16];
+    __shared__ float s_lse[T * NCT * 16];
     __shared__ TileLds<T, GP> lds;
 
     if (blockIdx.x >= *n_tiles) return;
@@ -544,7 +554,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
         for (int kk = 0; kk < NK; ++kk)
             qb[ct][kk] = j < G ? qrow[j * QROW_V4 + 4 * kk + cg] : make_uint4(0, 0, 0, 0);
     }
-    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_ms[i] = make_float2(-INFINITY, 0.f);
+    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_lse[i] = -INFINITY;
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) return;
 
@@ -568,60 +578,170 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
             for (int r = 0; r < 4; ++r) s += __expf(z[r] - mx);
             s = rows4_sum(s);
             const int j = ct * 16 + n;
-            if (cg == 0 && j < G) s_ms[i_cur * G + j] = make_float2(mx, s);
+            if (cg == 0 && j < G) s_lse[i_cur * G + j] = mx + __logf(s);
         }
     });
     __syncthreads();
-    tile_epilogue<GP, T>(s_ms, lds.red, lds.tot, lds.v, G, c, out);
+    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, blockIdx.x, out);
+}
+
+// ---- score_tile_wide: wide frames (MLA latent, dim 576) scored by up to 128 queries ---
+// The 128 x dim query operands do not fit one wavefront's registers, so the four
+// wavefronts of the workgroup split the queries (32 each, two column tiles) and share the
+// unit: its frame is staged in LDS once (global -> registers -> LDS, double buffered, the
+// next unit's loads in flight while the current one is multiplied) and every wavefront
+// reads its A operands from there.  One barrier per unit.  A workgroup takes SUB consecutive
+// tiles of T blocks of its row, one after the other, so the 147 KB of query operands are
+// loaded once per SUB * T blocks.
+template <int DIM, int DT, int T, int SUB>
+__global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
+    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
+    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
+    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out) {
+    constexpr int NK = DIM / 32;
+    constexpr int UNIT_V4 = DIM * 2;
+    constexpr int QROW_V4 = DIM / 8;
+    constexpr int V4_PT = (UNIT_V4 + kThreads - 1) / kThreads;    // 16-byte vectors staged per thread
+    constexpr int GP = 128;
+    extern __shared__ uint4 dyn_lds[];
+    uint4* kbuf = dyn_lds;                                         // [2][UNIT_V4]
+    float* s_lse = reinterpret_cast<float*>(kbuf + 2 * UNIT_V4);  // [T * 128]
+    TileLds<T, GP>& lds = *reinterpret_cast<TileLds<T, GP>*>(s_lse + T * GP);
+
+    if (blockIdx.x >= *n_tiles) return;
+    const TileCtx plan = tile_ctx<T * SUB>(tiles, row_ntok, row_off);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, cg = lane >> 4;
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[plan.row]);
+    const bool wave_has_queries = 32 * wave < G;
+
+    uint4 qb[2][NK];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+        const int j = 32 * wave + ct * 16 + n;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk)
+            qb[ct][kk] = j < G ? qrow[j * QROW_V4 + 4 * kk + cg] : make_uint4(0, 0, 0, 0);
+    }
+    for (int sub = 0; sub < SUB && sub * T < plan.nbt; ++sub) {
+    TileCtx c = plan;
+    c.b0 = plan.b0 + sub * T;
+    c.nbt = min(T, plan.nbt - sub * T);
+    c.uid0 = plan.uid0 + sub * T;
+    __syncthreads();                                  // the previous sub-tile's epilogue is done with s_lse
+    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_lse[i] = -INFINITY;
+    const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
+    if (n_res == 0) continue;                         // uniform
+
+    uint4 st[V4_PT];
+    auto fetch = [&](int idx) {           // unconditional: past the list end it re-reads the last unit
+        const int2 e = list_entry(lds.list, idx < n_res ? idx : n_res - 1);
+        const v4u_t* p = reinterpret_cast<const v4u_t*>(k_pool + (size_t)(uint32_t)e.y * UNIT_V4);
+#pragma unroll
+        for (int i = 0; i < V4_PT; ++i) {
+            const int v = min((int)threadIdx.x + kThreads * i, UNIT_V4 - 1);
+            const v4u_t x = __builtin_nontemporal_load(p + v);
+            st[i] = make_uint4(x.x, x.y, x.z, x.w);
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < V4_PT; ++i) {
+            const int v = threadIdx.x + kThreads * i;
+            if (v < UNIT_V4) kbuf[buf * UNIT_V4 + v] = st[i];
+        }
+    };
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int idx = 0; idx < n_res; ++idx) {
+        const int i_cur = list_entry(lds.list, idx).x;
+        fetch(idx + 1);
+        if (wave_has_queries) {
+            const uint4* kb = kbuf + (idx & 1) * UNIT_V4 + lane;
+            f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) {
+                const uint4 a = kb[kk * 64];
+                acc[0] = mfma16<DT>(a, qb[0][kk], acc[0]);
+                acc[1] = mfma16<DT>(a, qb[1][kk], acc[1]);
+            }
+            const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
+                float z[4];
+                float mx = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    z[r] = (4 * cg + r) < tok_in_block ? acc[ct][r] * scale : -INFINITY;
+                    mx = fmaxf(mx, z[r]);
+                }
+                mx = rows4_max(mx);
+                float s = 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s += __expf(z[r] - mx);
+                s = rows4_sum(s);
+                const int j = 32 * wave + ct * 16 + n;
+                if (cg == 0 && j < G) s_lse[i_cur * G + j] = mx + __logf(s);
+            }
+        }
+        // buffer (idx + 1) & 1 was last read in iteration idx - 1, which every wavefront has left
+        stage((idx + 1) & 1);
+        __syncthreads();
+    }
+    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, (size_t)blockIdx.x * SUB + sub, out);
+    }
 }
 
 // ---- score_rowmerge: rows of more than one tile ---------------------------------------
-// One workgroup per tile again: it folds the (M, Z) of all tiles of its row (a few pairs,
-// read by every thread) and rescales its own tile's values into masses.
-template <int GP, int T>
+// One workgroup per tile again: it folds the tile values of its row into the row's log sum
+// exp (a few numbers, read by every thread) and turns its own tile's block values into masses.
+template <int GP, int T, int SUB>
 __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int g,
     const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
     const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
     constexpr int BS = kThreads / GP;
     constexpr int SWEEPS = (T + BS - 1) / BS;
-    __shared__ float s_v[GP > 64 ? kThreads : 1];
+    __shared__ float s_v[GP > 64 ? 4 * SWEEPS : 1];
     if (blockIdx.x >= *n_tiles) return;
-    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off);
-    if (c.nb <= T) return;                           // finished by its tile
-    const float2* tmz = o.tile_mz + (size_t)row_tile0[c.row] * g;
-    const int n_t = (c.nb + T - 1) / T;
+    const TileCtx plan = tile_ctx<T * SUB>(tiles, row_ntok, row_off);
+    if (plan.nb <= T) return;                        // finished by its tile
+    const float* tl = o.tile_lse + (size_t)row_tile0[plan.row] * SUB * g;
+    const int n_t = (plan.nb + T - 1) / T;
     const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
     const bool jv = j < g;
     MZ tot{-INFINITY, 0.f};
     if (jv)
-        for (int i = 0; i < n_t; ++i) {
-            const float2 p = tmz[i * g + j];
-            tot = mz_combine(tot, MZ{p.x, p.y});
+        for (int i = 0; i < n_t; ++i) tot = mz_combine(tot, MZ{tl[i * g + j], 1.f});
+    const float row_lse = mz_lse(tot);
+    for (int sub = 0; sub < SUB && sub * T < plan.nbt; ++sub) {
+        const int nbt = min(T, plan.nbt - sub * T);
+        const int64_t uid0 = plan.uid0 + sub * T;
+        // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
+        float v[SWEEPS];
+        int32_t slot[SWEEPS];
+#pragma unroll
+        for (int k = 0; k < SWEEPS; ++k) {
+            const int b = k * BS + bsub;
+            const int bc = b < nbt ? b : 0;
+            slot[k] = slot_tbl[uid0 + bc];
+            v[k] = o.part_lse[(uid0 + bc) * g + (jv ? j : 0)];
         }
-    // this tile's factor exp(M_tile - M_row) / Z_row
-    float f = 0.f;
-    if (jv && tot.z > 0.f) {
-        const float m_tile = o.tile_mz[(size_t)blockIdx.x * g + j].x;
-        f = m_tile > -INFINITY ? __expf(m_tile - tot.m) / tot.z : 0.f;
-    }
-    // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
-    float r[SWEEPS];
-    int32_t slot[SWEEPS];
 #pragma unroll
-    for (int k = 0; k < SWEEPS; ++k) {
-        const int b = k * BS + bsub;
-        const int bc = b < c.nbt ? b : 0;
-        slot[k] = slot_tbl[c.uid0 + bc];
-        r[k] = o.part_r[(c.uid0 + bc) * g + (jv ? j : 0)];
-    }
+        for (int k = 0; k < SWEEPS; ++k) {
+            const bool res = k * BS + bsub < nbt && (uint32_t)slot[k] < n_slots;
+            v[k] = (res && jv && v[k] > -INFINITY) ? __expf(v[k] - row_lse) : 0.f;
+        }
+        if (GP > 64 && sub > 0) __syncthreads();     // s_v of the previous sub-tile has been read
+        group_agg<GP, SWEEPS>(v, o.agg, s_v);
 #pragma unroll
-    for (int k = 0; k < SWEEPS; ++k) {
-        const int b = k * BS + bsub;
-        const bool res = b < c.nbt && (uint32_t)slot[k] < n_slots;
-        float v = (res && jv) ? r[k] * f : 0.f;
-        v = group_agg<GP>(v, o.agg, s_v);
-        if (res && j == 0) o.mass[c.uid0 + b] = o.agg == KVM_AGG_MAX ? v : v / (float)g;
+        for (int k = 0; k < SWEEPS; ++k) {
+            const int b = k * BS + bsub;
+            if (j == 0 && b < nbt && (uint32_t)slot[k] < n_slots)
+                o.mass[uid0 + b] = o.agg == KVM_AGG_MAX ? v[k] : v[k] / (float)g;
+        }
     }
 }
 
@@ -680,7 +800,7 @@ __global__ __launch_bounds__(kThreads) void score_finalize_kernel(
     float* __restrict__ mass) {
     constexpr int BS = kThreads / GP;
     __shared__ float2 s_red[kThreads];
-    __shared__ float s_v[GP > 64 ? kThreads : 1];
+    __shared__ float s_v[4];
     const int row = blockIdx.x;
     if (!row_scorable(pr, row)) return;
     const int g = pr.g;
@@ -707,30 +827,36 @@ __global__ __launch_bounds__(kThreads) void score_finalize_kernel(
             const float2 p = part[(uid0 + b) * g + j];
             v = p.y * __expf(p.x - tot.m) * inv;
         }
-        v = group_agg<GP>(v, agg, s_v);
-        if (res && j == 0) mass[uid0 + b] = agg == KVM_AGG_MAX ? v : v / (float)g;
+        float vv[1] = {v};
+        if (GP > 64) __syncthreads();
+        group_agg<GP, 1>(vv, agg, s_v);
+        if (res && j == 0) mass[uid0 + b] = agg == KVM_AGG_MAX ? vv[0] : vv[0] / (float)g;
     }
 }
 
 // ---- host side ----------------------------------------------------------------
-enum class Path { Dot2, Mfma, Generic };
+constexpr int kWideTile = 64;
+constexpr int kWideSub = 4;
+enum class Path { Dot2, Mfma, Wide, Generic };
 
 struct Choice {
     Path path;
-    int tile_blocks;
-    int nct;        // Mfma: 16-query column tiles (1, 2, 4 or 8)
+    int tile_blocks;   // blocks per workgroup (what the plan cuts rows into)
+    int sub;           // statistic tiles per workgroup
+    int nct;           // Mfma: 16-query column tiles (1, 2, 4 or 8)
 };
 
-// Which kernel scores (g, dim), and with what tile size.  The (m, s) array in LDS takes
-// tile_blocks * (padded g) * 8 bytes: 32 KiB in every case.
+// Which kernel scores (g, dim), and with what tile size.  The block-value array in LDS takes
+// tile_blocks * (padded g) * 4 bytes: at most 32 KiB.
 Choice choose(int g, int dim) {
-    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8)) return Choice{Path::Dot2, 512, 0};
+    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8)) return Choice{Path::Dot2, 512, 1, 0};
     if (dim <= 256) {
         const int nct = (g + 15) / 16;
         const int nct_p = nct <= 1 ? 1 : nct <= 2 ? 2 : nct <= 4 ? 4 : 8;
-        return Choice{Path::Mfma, 256 / nct_p, nct_p};
+        return Choice{Path::Mfma, 512 / nct_p, 1, nct_p};
     }
-    return Choice{Path::Generic, kGenericTile, 0};
+    if (dim == 576) return Choice{Path::Wide, kWideTile * kWideSub, kWideSub, 0};
+    return Choice{Path::Generic, kGenericTile, 1, 0};
 }
 
 inline int64_t max_tiles(int64_t n_uids, int64_t n_rows, int tile_blocks) {
@@ -743,26 +869,26 @@ struct ScoreWs {
     uint32_t* wg_sum;
     Tile* tiles;
     uint32_t* row_tile0;
-    float2* tile_mz;
+    float* tile_lse;    // [tiles][g]
     float2* part;       // (m, s) pairs [n_uids][g] (generic path) or floats [n_uids][g] (tile paths)
     size_t bytes;
 };
 
-ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, int tile_blocks) {
+ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, int tile_blocks, int sub) {
     const size_t n_wg = ((size_t)n_rows + kPlanThreads - 1) / kPlanThreads;
     const size_t tiles_max = (size_t)max_tiles(n_uids, n_rows, tile_blocks);
     const size_t off_sum = 256;
     const size_t off_tiles = off_sum + align_up(n_wg * sizeof(uint32_t), 256);
     const size_t off_row0 = off_tiles + align_up(tiles_max * sizeof(Tile), 256);
     const size_t off_tmz = off_row0 + align_up((size_t)n_rows * sizeof(uint32_t), 256);
-    const size_t off_part = off_tmz + align_up(tiles_max * (size_t)g * sizeof(float2), 256);
+    const size_t off_part = off_tmz + align_up(tiles_max * (size_t)sub * (size_t)g * sizeof(float), 256);
     const uintptr_t base = reinterpret_cast<uintptr_t>(ws);
     ScoreWs w;
     w.n_tiles = reinterpret_cast<uint32_t*>(base);
     w.wg_sum = reinterpret_cast<uint32_t*>(base + off_sum);
     w.tiles = reinterpret_cast<Tile*>(base + off_tiles);
     w.row_tile0 = reinterpret_cast<uint32_t*>(base + off_row0);
-    w.tile_mz = reinterpret_cast<float2*>(base + off_tmz);
+    w.tile_lse = reinterpret_cast<float*>(base + off_tmz);
     w.part = reinterpret_cast<float2*>(base + off_part);
     w.bytes = off_part + align_up((size_t)n_uids * (size_t)g * sizeof(float2), 256);
     return w;
@@ -780,10 +906,10 @@ struct ScoreArgs {
     hipStream_t st;
 };
 
-template <int GP, int T>
+template <int GP, int T, int SUB = 1>
 int launch_rowmerge(const ScoreArgs& a) {
     TimedLaunch tl("score_finalize", a.st);
-    score_rowmerge_kernel<GP, T><<<a.grid, kThreads, 0, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok,
+    score_rowmerge_kernel<GP, T, SUB><<<a.grid, kThreads, 0, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok,
                                                                a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
                                                                (uint32_t)a.pool->n_slots, a.out);
     return launch_status("score_rowmerge");
@@ -804,7 +930,7 @@ int launch_dot2_path(const ScoreArgs& a) {
 
 template <int NCT, int DIM, int DT>
 int launch_mfma_path(const ScoreArgs& a) {
-    constexpr int T = 256 / NCT;
+    constexpr int T = 512 / NCT;
     {
         TimedLaunch tl("score_partial", a.st);
         score_tile_mfma_kernel<NCT, DIM, DT, T><<<a.grid, kThreads, 0, a.st>>>(
@@ -814,6 +940,25 @@ int launch_mfma_path(const ScoreArgs& a) {
         if (int rc = launch_status("score_tile_mfma")) return rc;
     }
     return launch_rowmerge<NCT * 16, T>(a);
+}
+
+// Wide frames (dim 576): workgroup-cooperative matrix-core kernel.
+template <int DIM, int DT>
+int launch_wide_path(const ScoreArgs& a) {
+    constexpr int T = kWideTile;
+    const size_t lds = 2 * (size_t)DIM * 2 * sizeof(uint4) + (size_t)T * 128 * sizeof(float) + sizeof(TileLds<T, 128>);
+    auto kern = score_tile_wide_kernel<DIM, DT, T, kWideSub>;
+    KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+    {
+        TimedLaunch tl("score_partial", a.st);
+        kern<<<a.grid, kThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off,
+                                              a.rows->row_q_off, a.rows->slot_tbl,
+                                              static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
+                                              static_cast<const uint16_t*>(a.q), a.scale, a.out);
+        if (int rc = launch_status("score_tile_wide")) return rc;
+    }
+    return launch_rowmerge<128, T, kWideSub>(a);
 }
 
 // Any g and dim: queries staged in LDS, vector dot products, (m, s) pairs through global memory.
@@ -874,6 +1019,9 @@ int launch_dim(const ScoreArgs& a, const Choice& ch) {
             }
         }
     }
+    if constexpr (DIM == 576) {
+        if (ch.path == Path::Wide) return launch_wide_path<DIM, DT>(a);
+    }
     return launch_generic_path<DIM, DT>(a);
 }
 
@@ -894,7 +1042,8 @@ int launch_dtype(const ScoreArgs& a, const Choice& ch) {
 }  // namespace
 
 size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim) {
-    return carve(nullptr, n_uids, n_rows, g, choose(g, dim).tile_blocks).bytes;
+    const Choice ch = choose(g, dim);
+    return carve(nullptr, n_uids, n_rows, g, ch.tile_blocks, ch.sub).bytes;
 }
 
 }  // namespace kvm
@@ -929,11 +1078,11 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
     a.rows = rows;
     a.q = q;
     a.scale = softmax_scale;
-    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g, ch.tile_blocks);
+    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g, ch.tile_blocks, ch.sub);
     KVM_REQUIRE(ws_bytes >= a.w.bytes, KVM_ENOSPC, "kvm_score_step: workspace %zu < %zu bytes", ws_bytes, a.w.bytes);
     const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows, ch.tile_blocks);
     KVM_REQUIRE(tiles_max <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: too many tiles");
-    a.out = TileOut{agg, mass, reinterpret_cast<float*>(a.w.part), a.w.tile_mz};
+    a.out = TileOut{agg, mass, reinterpret_cast<float*>(a.w.part), a.w.tile_lse};
     a.grid = (unsigned)tiles_max;
     a.st = static_cast<hipStream_t>(stream);
     a.pr = PlanRows{rows->n_rows, rows->g,        pool->dim,     ch.tile_blocks,  rows->n_uids,
