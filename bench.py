@@ -3,8 +3,9 @@
 
 One step = beta update -> scoring of every resident unit -> EMA + priority ->
 budget victim selection -> pack of the victims to pinned host -> unpack of an
-equal number of host units into the freed frames, all through the C ABI on one
-stream.  Workload: the Llama-3-8B-shaped configuration (32 layers, 32 q / 8 KV
+equal number of host units into the freed frames, all through the C ABI.  The
+kernels run on one stream; the host-link copies of the swapped records run on a
+side stream and overlap the scoring of the same / the following step.  Workload: the Llama-3-8B-shaped configuration (32 layers, 32 q / 8 KV
 heads, d 128, bf16, 64 sequences of uniform [2048, 8192] tokens, block 16,
 EMA decay 0.95, budget = 60 % of the initially resident units, 4096 reuse
 events per step).  Prints one JSON line.
@@ -31,6 +32,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--n-seq", type=int, default=64, help="sequences in the batch (64 = the named workload)")
     ap.add_argument("--swap-units", type=int, default=1024, help="units evicted and prefetched per step")
+    ap.add_argument("--overlap-swap", action="store_true",
+                    help="move the swapped records over the host link on a side stream instead of in line")
+    ap.add_argument("--direct-swap", action="store_true",
+                    help="in-line swap without device staging: the pack / unpack kernels access pinned host memory themselves")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
@@ -127,23 +132,65 @@ def main():
 
     step_victims = torch.zeros(swap, dtype=torch.int64, device=dev)
     step_freed = torch.full((swap,), -1, dtype=torch.int32, device=dev)
+    # Per-step swap traffic goes over a side stream: the prefetch records of step i travel host -> device
+    # while step i is being scored, the victims' records device -> host while step i + 1 is being scored.
+    # Two staging buffers per direction alternate between steps; events order the buffer reuse.
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    out_dev = [torch.empty(swap * rec, dtype=torch.uint8, device=dev) for _ in range(2)]
+    in_dev = [torch.empty(swap * rec, dtype=torch.uint8, device=dev) for _ in range(2)]
+    ev_gathered = [torch.cuda.Event() for _ in range(2)]
+    ev_d2h = [torch.cuda.Event() for _ in range(2)]
+    ev_h2d = [torch.cuda.Event() for _ in range(2)]
+    ev_scattered = [torch.cuda.Event() for _ in range(2)]
+    for e in ev_d2h + ev_scattered:
+        e.record(main)
 
-    def step(i):
-        """One full pass.  Resident units at entry: budget + swap."""
+    def step_serial(i):
+        """One full pass, everything in line on one stream.  Resident units at entry: budget + swap."""
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
         kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
         kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         lo = i * swap
-        seg_host = host_tier[lo * rec:(lo + swap) * rec]
         # the segment's old records were prefetched by the previous step, so it is free to take the victims
+        sd = None if args.direct_swap else staging_dev
         kvm.kvm_pack(pool, wl.slot_tbl, wl.state, step_victims, swap, host_slots[lo:lo + swap], step_freed,
-                     staging_dev, seg_host, n_bad=n_bad, n_dev=n_victims)
+                     sd, host_tier[lo * rec:(lo + swap) * rec], n_bad=n_bad, n_dev=n_victims)
         nxt = (i + 1) * swap
-        kvm.kvm_unpack(pool, wl.slot_tbl, wl.state, host_uids[nxt:nxt + swap], swap, step_freed, staging_dev,
+        kvm.kvm_unpack(pool, wl.slot_tbl, wl.state, host_uids[nxt:nxt + swap], swap, step_freed, sd,
                        host_tier[nxt * rec:(nxt + swap) * rec], n_bad=n_bad, n_dev=n_victims)
 
+    def step_overlapped(i):
+        """Same pass with the host-link copies on the side stream."""
+        b = i & 1
+        nxt = (i + 1) * swap
+        with torch.cuda.stream(side):
+            side.wait_event(ev_scattered[b])                         # in_dev[b] was last read two steps ago
+            in_dev[b].copy_(host_tier[nxt * rec:(nxt + swap) * rec], non_blocking=True)
+            ev_h2d[b].record(side)
+        ev = evs[i % n_q_sets]
+        kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
+        kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
+        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
+        lo = i * swap
+        main.wait_event(ev_d2h[b])                                   # out_dev[b] has left for the host
+        kvm.kvm_pack(pool, wl.slot_tbl, wl.state, step_victims, swap, host_slots[lo:lo + swap], step_freed,
+                     out_dev[b], None, n_bad=n_bad, n_dev=n_victims)
+        ev_gathered[b].record(main)
+        with torch.cuda.stream(side):
+            side.wait_event(ev_gathered[b])
+            # the segment's old records were prefetched by the previous step, so it is free to take the victims
+            host_tier[lo * rec:(lo + swap) * rec].copy_(out_dev[b], non_blocking=True)
+            ev_d2h[b].record(side)
+        main.wait_event(ev_h2d[b])
+        kvm.kvm_unpack(pool, wl.slot_tbl, wl.state, host_uids[nxt:nxt + swap], swap, step_freed, in_dev[b], None,
+                       n_bad=n_bad, n_dev=n_victims)
+        ev_scattered[b].record(main)
+
+    step = step_overlapped if args.overlap_swap else step_serial
     prefetch(0)
     # the frames of segment 0 came from the bulk list; from now on each step reuses the frames it frees
     torch.cuda.synchronize()
@@ -160,7 +207,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.warmup, total_steps):
         step(i)
-    torch.cuda.synchronize()
+    torch.cuda.synchronize()                      # both streams: the last victims have reached the host
     elapsed = time.perf_counter() - t0
     kvm.kvm_timing_enable(False)
     assert int(n_bad.item()) == 0, int(n_bad.item())
@@ -200,7 +247,9 @@ def main():
         "config": {"workload": "llama3-8b-shaped GQA: 32 layers, 32q/8kv heads, d128, bf16, %d seqs U[2048,8192] tok, "
                                "block 16, decay 0.95, budget 60%%, 4096 events/step" % args.n_seq,
                    "units_total": n, "units_scored_per_step": scored_units, "rows": n_rows,
-                   "swap_units_per_step": swap, "resident_fraction": round(scored_units / n, 4)},
+                   "swap_units_per_step": swap, "resident_fraction": round(scored_units / n, 4),
+                   "swap_copies": "side stream" if args.overlap_swap else ("in line, zero-copy kernels" if args.direct_swap
+                                                                            else "in line")},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "evicted_units_per_s": round(swap / (elapsed / args.steps), 1),
         "prefetched_units_per_s": round(swap / (elapsed / args.steps), 1),

@@ -249,6 +249,11 @@ int kvm_select_victims(const float* prio /* dev [n_uids] */, const uint8_t* stat
  * gather kernel writes the pinned host buffer directly.
  * staging_host must hold n * (unit_k_bytes + unit_v_bytes) bytes;
  * staging_dev_bytes must hold at least one record.
+ * When staging_host is NULL the call only gathers: the n records stay in
+ * staging_dev (which must hold them all) and the caller moves them, e.g. with
+ * hipMemcpyAsync on a side stream so that the copy overlaps the next step's
+ * scoring.  kvm_unpack with staging_host NULL likewise only scatters records
+ * that the caller has already brought into staging_dev.
  *
  * kvm_unpack is the inverse: record i of staging_host goes to pool frame
  * dst_slots[i]; slot_tbl[uid] = dst_slots[i]; state: set RESIDENT, clear

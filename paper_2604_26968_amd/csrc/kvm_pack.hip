@@ -97,11 +97,14 @@ int check_common(const char* who, const kvm_pool_t* pool, const void* slot_tbl, 
     KVM_REQUIRE(pool->n_slots <= 0x7fffffffull, KVM_EINVAL, "%s: n_slots exceeds int32 slot ids", who);
     if (n == 0) return KVM_OK;
     KVM_REQUIRE(pool->k_pool && (pool->v_pool || pool->unit_v_bytes == 0), KVM_EINVAL, "%s: null pool memory", who);
-    KVM_REQUIRE(slot_tbl && state && uids && slots && staging_host, KVM_EINVAL, "%s: null buffer", who);
+    KVM_REQUIRE(slot_tbl && state && uids && slots, KVM_EINVAL, "%s: null buffer", who);
+    KVM_REQUIRE(staging_host || staging_dev, KVM_EINVAL, "%s: no staging buffer at all", who);
     const size_t rec = (size_t)pool->unit_k_bytes + pool->unit_v_bytes;
-    KVM_REQUIRE(staging_host_bytes / rec >= (size_t)n, KVM_ENOSPC, "%s: host staging %zu bytes < %lld records of %zu",
-                who, staging_host_bytes, (long long)n, rec);
+    KVM_REQUIRE(!staging_host || staging_host_bytes / rec >= (size_t)n, KVM_ENOSPC,
+                "%s: host staging %zu bytes < %lld records of %zu", who, staging_host_bytes, (long long)n, rec);
     KVM_REQUIRE(!staging_dev || staging_dev_bytes >= rec, KVM_ENOSPC, "%s: device staging smaller than one record", who);
+    KVM_REQUIRE(staging_host || staging_dev_bytes / rec >= (size_t)n, KVM_ENOSPC,
+                "%s: without a host buffer the device staging must hold all %lld records", who, (long long)n);
     KVM_REQUIRE(reinterpret_cast<uintptr_t>(staging_host) % 16 == 0 && reinterpret_cast<uintptr_t>(staging_dev) % 16 == 0,
                 KVM_EINVAL, "%s: staging buffers must be 16-byte aligned", who);
     return KVM_OK;
@@ -145,8 +148,9 @@ extern "C" int kvm_pack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* stat
                                                        n_uids, uids, host_slots, freed_slots, first, n_dev,
                                                        static_cast<uint4*>(staging_dev), n_bad);
         if (int rc = launch_status("pack")) return rc;
-        KVM_HIP_TRY(hipMemcpyAsync(static_cast<char*>(staging_host) + first * rec, staging_dev, (size_t)cnt * rec,
-                                   hipMemcpyDeviceToHost, st));
+        if (staging_host)
+            KVM_HIP_TRY(hipMemcpyAsync(static_cast<char*>(staging_host) + first * rec, staging_dev, (size_t)cnt * rec,
+                                       hipMemcpyDeviceToHost, st));
     }
     return KVM_OK;
 }
@@ -181,8 +185,9 @@ extern "C" int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* st
     if (per_chunk > 0x40000000ll) per_chunk = 0x40000000ll;
     for (int64_t first = 0; first < n; first += per_chunk) {
         const int64_t cnt = n - first < per_chunk ? n - first : per_chunk;
-        KVM_HIP_TRY(hipMemcpyAsync(staging_dev, static_cast<const char*>(staging_host) + first * rec, (size_t)cnt * rec,
-                                   hipMemcpyHostToDevice, st));
+        if (staging_host)
+            KVM_HIP_TRY(hipMemcpyAsync(staging_dev, static_cast<const char*>(staging_host) + first * rec,
+                                       (size_t)cnt * rec, hipMemcpyHostToDevice, st));
         unpack_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(kp, vp, (uint32_t)pool->n_slots, k_v4, v_v4, slot_tbl, state,
                                                          n_uids, uids, dst_slots, first, n_dev,
                                                          static_cast<const uint4*>(staging_dev), n_bad);

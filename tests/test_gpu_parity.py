@@ -288,6 +288,57 @@ def test_pack_unpack_bytes_and_tables(oracle, shape, direct):
     np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
 
 
+def test_pack_unpack_split_phases_with_caller_copies(oracle):
+    """Gather-only pack (records stay in device staging) + the caller's own copy on a side stream,
+    then the caller's copy back + scatter-only unpack: same bytes and tables as the oracle."""
+    from paper_2604_26968_amd import kvm
+    shape = synth.Shape(2, 8, 2, 128, synth.BF16, True, [400, 90])
+    case = synth.make_case(shape, seed=17, spare_slots=3)
+    dev = DeviceCase(case)
+    k8, v8 = host_pools(case)
+    rng = np.random.default_rng(5)
+    uids = rng.choice(np.nonzero(case.state & RES)[0], size=50, replace=False).astype(np.int64)
+    hs = np.arange(50, dtype=np.int32)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    want, want_freed = oracle.pack(k8, v8, shape.unit_k_bytes, shape.unit_v_bytes, tbl, st, uids, hs)
+    rec = dev.rec
+    d_uids, d_hs = torch.from_numpy(uids).cuda(), torch.from_numpy(hs).cuda()
+    freed = torch.full((50,), -1, dtype=torch.int32, device="cuda")
+    sdev = torch.zeros(50 * rec, dtype=torch.uint8, device="cuda")
+    host = torch.zeros(50 * rec, dtype=torch.uint8, pin_memory=True)
+    side = torch.cuda.Stream()
+    done = torch.cuda.Event()
+    kvm.kvm_pack(dev.pool, dev.slot_tbl, dev.state, d_uids, 50, d_hs, freed, sdev, None, n_bad=dev.n_bad)
+    done.record()
+    with torch.cuda.stream(side):
+        side.wait_event(done)
+        host.copy_(sdev, non_blocking=True)
+    side.synchronize()
+    np.testing.assert_array_equal(host.numpy().reshape(50, rec), want)
+    np.testing.assert_array_equal(freed.cpu().numpy(), want_freed)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    # too small a device staging buffer is refused when there is no host buffer
+    with pytest.raises(kvm.KvmError) as e:
+        kvm.kvm_pack(dev.pool, dev.slot_tbl, dev.state, d_uids, 50, d_hs, freed, sdev[:10 * rec], None)
+    assert e.value.code == kvm.ENOSPC
+    # back: caller copies host -> device staging, library scatters
+    dst = np.roll(want_freed, 7).astype(np.int32)
+    sdev.zero_()
+    with torch.cuda.stream(side):
+        sdev.copy_(host, non_blocking=True)
+        done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    kvm.kvm_unpack(dev.pool, dev.slot_tbl, dev.state, d_uids, 50, torch.from_numpy(dst).cuda(), sdev, None,
+                   n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    oracle.unpack(k8, v8, shape.unit_k_bytes, shape.unit_v_bytes, tbl, st, uids, dst, want)
+    gk, gv = dev.pools_host()
+    np.testing.assert_array_equal(gk, k8)
+    np.testing.assert_array_equal(gv, v8)
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    assert int(dev.n_bad.item()) == 0
+
+
 def test_pack_unpack_round_trip_is_identity():
     case = synth.make_case(synth.Shape(2, 8, 2, 128, synth.BF16, True, [1000]), seed=2)
     dev = DeviceCase(case)
