@@ -21,6 +21,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E published peak
+
+# name -> (description, shape builder, default sequences, budget fraction, EMA decay, swap units per step,
+#          rows sampled for the CPU baseline (None = all rows of `sample_seqs` sequences), sample_seqs)
+WORKLOADS = {
+    "llama8b": ("llama3-8b-shaped GQA: 32 layers, 32q/8kv heads, d128, bf16, %d seqs U[2048,8192] tok",
+                lambda synth, n: synth.llama8b_shape(n, seed=2), 64, 0.60, 0.95, 1024, None, 32),
+    "llama70b": ("llama3-70b-shaped GQA (one GPU's share): 80 layers, 64q/8kv heads, d128, bf16, %d x 131072 tok",
+                 lambda synth, n: synth.llama70b_shape(n), 4, 0.50, 0.95, 4096, 8, 0),
+    "mla": ("deepseek-v3-shaped MLA: 61 layers, 576-channel latent, 128 absorbed queries, bf16, %d x 32768 tok",
+            lambda synth, n: synth.mla_shape(n), 32, 0.40, 0.90, 1024, 2, 0),
+}
 # FETCH_SIZE 6,609,933 x 2 KiB + WRITE_SIZE 21,527.7 x 1 KiB per launch of score_tile_kernel<4, 128, bf16>
 SCORE_TILE_TRAFFIC_BYTES = int(6609933 * 2048 + 21527.7 * 1024)
 
@@ -30,8 +41,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--n-seq", type=int, default=64, help="sequences in the batch (64 = the named workload)")
-    ap.add_argument("--swap-units", type=int, default=1024, help="units evicted and prefetched per step")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="llama8b",
+                    help="llama8b is the named benchmark workload; the others are the larger configurations")
+    ap.add_argument("--n-seq", type=int, default=0, help="sequences in the batch (0 = the workload's own number)")
+    ap.add_argument("--swap-units", type=int, default=0, help="units evicted and prefetched per step (0 = workload default)")
     ap.add_argument("--overlap-swap", action="store_true",
                     help="move the swapped records over the host link on a side stream instead of in line")
     ap.add_argument("--direct-swap", action="store_true",
@@ -53,16 +66,18 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda"
     t_setup = time.time()
-    shape = synth.llama8b_shape(args.n_seq, seed=2)
+    wdesc, wshape, w_nseq, w_budget, decay, w_swap, w_sample_rows, w_sample_seqs = WORKLOADS[args.workload]
+    n_seq = args.n_seq or w_nseq
+    shape = wshape(synth, n_seq)
     pair_w = synth.categorical_weights(3)
     reuse_p = np.linspace(0.15, 0.95, 16)
     wl = synth.DeviceWorkload(shape, seed=1, pair_weights=pair_w)
     n, n_rows, g, dim = wl.n_uids, wl.n_rows, shape.g, shape.dim
     rec = shape.unit_k_bytes + shape.unit_v_bytes
-    pool = kvm.make_pool(wl.k_pool.view(torch.int16), wl.v_pool.view(torch.int16), dim, shape.dtype)
+    pool = kvm.make_pool(wl.k_pool.view(torch.int16), None if wl.v_pool is None else wl.v_pool.view(torch.int16), dim,
+                         shape.dtype)
     rows = kvm.make_rows(wl.row_ntok, wl.row_off, wl.row_q_off, wl.slot_tbl, g, wl.q_elems)
     scale = 1.0 / float(np.sqrt(dim))
-    decay = 0.95
 
     mass = torch.zeros(n, dtype=torch.float32, device=dev)
     S = torch.zeros(n, dtype=torch.float32, device=dev)
@@ -84,17 +99,22 @@ def main():
         evs.append((torch.from_numpy(p).to(dev), torch.from_numpy(o).to(dev)))
 
     n_res0 = int((wl.state & 1).sum().item())
-    budget = int(0.6 * n_res0)
+    budget = int(w_budget * n_res0)
     k0 = n_res0 - budget
-    swap = args.swap_units
+    swap = args.swap_units or w_swap
     total_steps = args.warmup + args.steps
-    assert swap * (total_steps + 1) <= k0, "not enough host-resident units for this many steps"
+    assert swap * (total_steps + 2) <= k0, "not enough host-resident units for this many steps"
+    # Tier 1 keeps the records the later steps prefetch (all of them when they fit 24 GiB of pinned memory);
+    # the rest of the bulk eviction goes through a scratch buffer and is dropped, as if demoted further down.
+    chunk = min(k0, 32768)
+    keep = k0 if k0 * rec <= 24 * 2**30 else ((swap * (total_steps + 2) + chunk - 1) // chunk) * chunk
 
     victims = torch.zeros(k0, dtype=torch.int64, device=dev)
     freed = torch.full((k0,), -1, dtype=torch.int32, device=dev)
     host_slots = torch.arange(k0, dtype=torch.int32, device=dev)
-    host_tier = torch.empty(k0 * rec, dtype=torch.uint8, pin_memory=True)    # tier 1
-    staging_dev = torch.empty(min(k0, 32768) * rec, dtype=torch.uint8, device=dev)
+    host_tier = torch.empty(keep * rec, dtype=torch.uint8, pin_memory=True)    # tier 1
+    host_scratch = torch.empty(chunk * rec, dtype=torch.uint8, pin_memory=True) if keep < k0 else None
+    staging_dev = torch.empty(chunk * rec, dtype=torch.uint8, device=dev)
 
     def management_pass(i, k_arg, budget_arg):
         ev = evs[i % n_q_sets]
@@ -116,7 +136,11 @@ def main():
     victims.copy_(victims[perm])
     torch.cuda.synchronize()
     t0 = time.time()
-    kvm.kvm_pack(pool, wl.slot_tbl, wl.state, victims, k0, host_slots, freed, staging_dev, host_tier, n_bad=n_bad)
+    for lo in range(0, k0, chunk):
+        cnt = min(chunk, k0 - lo)
+        dst = host_tier[lo * rec:(lo + cnt) * rec] if lo + cnt <= keep else host_scratch
+        kvm.kvm_pack(pool, wl.slot_tbl, wl.state, victims[lo:lo + cnt], cnt, host_slots[lo:lo + cnt],
+                     freed[lo:lo + cnt], staging_dev, dst, n_bad=n_bad)
     torch.cuda.synchronize()
     t_bulk_pack = time.time() - t0
     host_uids = victims.clone()                 # uid stored in host record i
@@ -227,14 +251,24 @@ def main():
     kvm.kvm_timing_reset()
     # Dominant kernel: score_partial (the tile kernel).  Algorithmic bytes per launch: per resident unit its
     # K frame (16 * dim * 2) and its mass (4); per block of an active row its table entry (4); per row its
-    # g queries.  Every row of this workload fits one 512-block tile, so no partials go through HBM.
+    # g queries; per block of a row that spans several tiles one float per query (the block's log-sum-exp,
+    # which the row merge reads back).  Rows of the llama8b workload all fit one 512-block tile.
     n_blocks_active = n
-    algo_bytes = scored_units * (shape.unit_k_bytes + 4) + n_blocks_active * 4 + n_rows * g * dim * 2
+    if dim <= 128 and g in (1, 2, 4, 8):
+        tile_blocks = 512
+    elif dim <= 256:
+        nct = (g + 15) // 16
+        tile_blocks = 512 // (1 if nct <= 1 else 2 if nct <= 2 else 4 if nct <= 4 else 8)
+    else:
+        tile_blocks = 64
+    multi_tile_blocks = int(wl.nb[wl.nb > tile_blocks].sum())
+    algo_bytes = (scored_units * (shape.unit_k_bytes + 4) + n_blocks_active * 4 + n_rows * g * dim * 2
+                  + multi_tile_blocks * g * 4)
     sp = kernels["score_partial"]["avg_ms"]
     achieved = algo_bytes / (sp * 1e-3) / 1e9
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload
     # (profiles/score_tile_llama8b_pmc.md); valid for the default workload only.
-    traffic = SCORE_TILE_TRAFFIC_BYTES if (args.n_seq == 64 and swap == 1024) else None
+    traffic = SCORE_TILE_TRAFFIC_BYTES if (args.workload == "llama8b" and n_seq == 64 and swap == 1024) else None
     roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}
@@ -244,8 +278,8 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "llama3-8b-shaped GQA: 32 layers, 32q/8kv heads, d128, bf16, %d seqs U[2048,8192] tok, "
-                               "block 16, decay 0.95, budget 60%%, 4096 events/step" % args.n_seq,
+        "config": {"workload": (wdesc % n_seq) + ", block 16, decay %g, budget %d%%, 4096 events/step"
+                               % (decay, round(100 * w_budget)),
                    "units_total": n, "units_scored_per_step": scored_units, "rows": n_rows,
                    "swap_units_per_step": swap, "resident_fraction": round(scored_units / n, 4),
                    "swap_copies": "side stream" if args.overlap_swap else ("in line, zero-copy kernels" if args.direct_swap
@@ -290,11 +324,14 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        sample_seqs = list(range(min(32, args.n_seq)))
         # score once more (untimed) so that the masses belong to the table as it stands now
         kvm.kvm_score_step(pool, rows, qs[0], scale, mass, ws)
         torch.cuda.synchronize()
-        case = wl.host_sample(sample_seqs)
+        if w_sample_rows is None:
+            case = wl.host_sample(seq_ids=list(range(min(w_sample_seqs, n_seq))))
+        else:
+            pick = np.random.default_rng(7).choice(n_rows, size=min(w_sample_rows, n_rows), replace=False)
+            case = wl.host_sample(rows=np.sort(pick))
         q_host = qs[0].view(torch.int16).cpu().numpy().view(np.uint16)
         q_rows = np.concatenate([q_host[r * g * dim:(r + 1) * g * dim] for r in case.sample_rows])
         ref_mass = np.zeros(case.n_uids, np.float32)
@@ -307,7 +344,7 @@ def main():
         ph = p_hat.cpu().numpy()
         oracle.ema_update(case.row_ntok, case.row_off, ref_mass, decay, case.row_weight, case.pair, ph, st_ref, S_ref,
                           prio_ref)
-        oracle.select_victims(prio_ref, st_ref, k=-1, budget_units=int(0.6 * case.n_uids))
+        oracle.select_victims(prio_ref, st_ref, k=-1, budget_units=int(w_budget * case.n_uids))
         t_cpu = time.perf_counter() - t0
         res = case.slot_tbl >= 0
         cpu_bytes = int(res.sum()) * shape.unit_k_bytes
@@ -315,9 +352,8 @@ def main():
         rel = np.abs(gpu_mass[res] - ref_mass[res]) / np.maximum(np.abs(ref_mass[res]), 1e-9)
         out["cpu_baseline"] = {"value": round(cpu_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(),
                                "kind": "oracle",
-                               "sample": "all %d rows of sequences %s (%d resident units, %.2f GB of K): score + ema + "
-                                         "select, %.1f s" % (case.n_rows, sample_seqs, int(res.sum()), cpu_bytes / 1e9,
-                                                            t_cpu)}
+                               "sample": "%d of %d rows (%d resident units, %.2f GB of K): score + ema + select, "
+                                         "%.1f s" % (case.n_rows, n_rows, int(res.sum()), cpu_bytes / 1e9, t_cpu)}
         out["parity_sample_max_rel_err"] = float(rel.max())
     print(json.dumps(out))
 

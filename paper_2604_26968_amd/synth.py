@@ -305,11 +305,14 @@ class DeviceWorkload:
         return torch.randn(self.q_elems, generator=gen, device=self.k_pool.device,
                            dtype=torch.float32).to(self.tdtype)
 
-    def host_sample(self, seq_ids) -> "Case":
-        """Host copy of the rows of the given sequences with their units compacted into a
-        small pool (slot ids renumbered), for the CPU oracle."""
+    def host_sample(self, seq_ids=None, rows=None) -> "Case":
+        """Host copy of some rows (all rows of the given sequences, or the given row indices) with
+        their units compacted into a small pool (slot ids renumbered), for the CPU oracle."""
         torch = self.torch
-        rows = np.nonzero(np.isin(self.row_seq, np.asarray(seq_ids)))[0]
+        if rows is None:
+            rows = np.nonzero(np.isin(self.row_seq, np.asarray(seq_ids)))[0]
+        rows = np.asarray(rows, np.int64)
+        seq_ids = sorted(set(int(s) for s in self.row_seq[rows]))
         nb = self.nb[rows]
         new_off = np.zeros(len(rows), np.int64)
         new_off[1:] = np.cumsum(nb[:-1])
@@ -339,3 +342,13 @@ class DeviceWorkload:
 def llama8b_shape(n_seq: int = 64, seed: int = 2) -> Shape:
     """32 layers, 32 q / 8 KV heads, d 128, bf16, n_seq sequences of uniform [2048, 8192] tokens."""
     return Shape(32, 32, 8, 128, BF16, True, uniform_lengths(n_seq, 2048, 8192, seed))
+
+
+def llama70b_shape(n_seq: int = 4, n_tok: int = 131072) -> Shape:
+    """One GPU's share of the Llama-3-70B-shaped workload: 80 layers, 64 q / 8 KV heads, d 128, bf16."""
+    return Shape(80, 64, 8, 128, BF16, True, [n_tok] * n_seq)
+
+
+def mla_shape(n_seq: int = 32, n_tok: int = 32768) -> Shape:
+    """DeepSeek-V3-shaped MLA: 61 layers, one 576-channel latent head scored by 128 queries, no V."""
+    return Shape(61, 128, 1, 576, BF16, False, [n_tok] * n_seq)
