@@ -456,8 +456,10 @@ __device__ __forceinline__ void tile_epilogue(const float* s_lse, float2* s_red 
         }
     } else {
         if (bsub == 0 && jv) o.tile_lse[tile_index * g + j] = tile_lse;
-        // the tile's block values, contiguous; -inf where not resident
-        for (int i = threadIdx.x; i < c.nbt * g; i += kThreads) o.part_lse[c.uid0 * g + i] = s_lse[i];
+        // the block values of the resident blocks (query 0 tells), g contiguous floats per block
+        if (jv)
+            for (int b = bsub; b < c.nbt; b += BS)
+                if (s_lse[b * g] > -INFINITY) o.part_lse[(c.uid0 + b) * g + j] = s_lse[b * g + j];
     }
 }
 
@@ -620,9 +622,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
         const int j = 32 * wave + ct * 16 + n;
+        const uint4* qj = qrow + (j < G ? j : 0) * QROW_V4 + cg;       // queries past g are never written out
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk)
-            qb[ct][kk] = j < G ? qrow[j * QROW_V4 + 4 * kk + cg] : make_uint4(0, 0, 0, 0);
+        for (int kk = 0; kk < NK; ++kk) qb[ct][kk] = qj[4 * kk];
     }
     for (int sub = 0; sub < SUB && sub * T < plan.nbt; ++sub) {
     TileCtx c = plan;
@@ -634,8 +636,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) continue;                         // uniform
 
+    // One unit in flight per workgroup besides the one being multiplied.  The fetch is
+    // unconditional (past the list end it re-reads the last unit) so that no branch surrounds it.
+    // (A second register set for a deeper prefetch measured no faster: the kernel is at its
+    // register limit with the 144 query-operand registers.)
     uint4 st[V4_PT];
-    auto fetch = [&](int idx) {           // unconditional: past the list end it re-reads the last unit
+    auto fetch = [&](int idx) {
         const int2 e = list_entry(lds.list, idx < n_res ? idx : n_res - 1);
         const v4u_t* p = reinterpret_cast<const v4u_t*>(k_pool + (size_t)(uint32_t)e.y * UNIT_V4);
 #pragma unroll
@@ -661,11 +667,17 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
         if (wave_has_queries) {
             const uint4* kb = kbuf + (idx & 1) * UNIT_V4 + lane;
             f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+            // A operands come from LDS a few k-steps ahead of their use, so that the LDS latency
+            // is paid once per unit and not once per k-step
+            constexpr int AHEAD = 4;
+            uint4 a[AHEAD];
+#pragma unroll
+            for (int p = 0; p < AHEAD - 1; ++p) a[p] = kb[p * 64];
 #pragma unroll
             for (int kk = 0; kk < NK; ++kk) {
-                const uint4 a = kb[kk * 64];
-                acc[0] = mfma16<DT>(a, qb[0][kk], acc[0]);
-                acc[1] = mfma16<DT>(a, qb[1][kk], acc[1]);
+                if (kk + AHEAD - 1 < NK) a[(kk + AHEAD - 1) % AHEAD] = kb[(kk + AHEAD - 1) * 64];
+                acc[0] = mfma16<DT>(a[kk % AHEAD], qb[0][kk], acc[0]);
+                acc[1] = mfma16<DT>(a[kk % AHEAD], qb[1][kk], acc[1]);
             }
             const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));
 #pragma unroll
@@ -720,6 +732,7 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
         const int nbt = min(T, plan.nbt - sub * T);
         const int64_t uid0 = plan.uid0 + sub * T;
         // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
+        // Entries of blocks that are not resident were never written and are masked out.
         float v[SWEEPS];
         int32_t slot[SWEEPS];
 #pragma unroll
@@ -732,7 +745,7 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
 #pragma unroll
         for (int k = 0; k < SWEEPS; ++k) {
             const bool res = k * BS + bsub < nbt && (uint32_t)slot[k] < n_slots;
-            v[k] = (res && jv && v[k] > -INFINITY) ? __expf(v[k] - row_lse) : 0.f;
+            v[k] = (res && jv) ? __expf(v[k] - row_lse) : 0.f;
         }
         if (GP > 64 && sub > 0) __syncthreads();     // s_v of the previous sub-tile has been read
         group_agg<GP, SWEEPS>(v, o.agg, s_v);
