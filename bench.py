@@ -32,8 +32,8 @@ WORKLOADS = {
     "mla": ("deepseek-v3-shaped MLA: 61 layers, 576-channel latent, 128 absorbed queries, bf16, %d x 32768 tok",
             lambda synth, n: synth.mla_shape(n), 32, 0.40, 0.90, 1024, 2, 0),
 }
-# FETCH_SIZE 6,609,933 x 2 KiB + WRITE_SIZE 21,527.7 x 1 KiB per launch of score_tile_kernel<4, 128, bf16>
-SCORE_TILE_TRAFFIC_BYTES = int(6609933 * 2048 + 21527.7 * 1024)
+# FETCH_SIZE 6,609,384.6 x 2 KiB + WRITE_SIZE 21,526.6 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
+SCORE_TILE_TRAFFIC_BYTES = int(6609384.6 * 2048 + 21526.6 * 1024)
 
 
 def main():
@@ -45,10 +45,11 @@ def main():
                     help="llama8b is the named benchmark workload; the others are the larger configurations")
     ap.add_argument("--n-seq", type=int, default=0, help="sequences in the batch (0 = the workload's own number)")
     ap.add_argument("--swap-units", type=int, default=0, help="units evicted and prefetched per step (0 = workload default)")
-    ap.add_argument("--overlap-swap", action="store_true",
-                    help="move the swapped records over the host link on a side stream instead of in line")
-    ap.add_argument("--direct-swap", action="store_true",
-                    help="in-line swap without device staging: the pack / unpack kernels access pinned host memory themselves")
+    ap.add_argument("--swap-mode", choices=["fused", "staged", "direct", "side-stream"], default="fused",
+                    help="how the per-step victims / prefetch records cross the host link: one fused two-way "
+                         "zero-copy kernel (kvm_swap); kvm_pack then kvm_unpack through device staging and "
+                         "hipMemcpyAsync; the same with zero-copy kernels; or gather / scatter in line with the "
+                         "copies on a side stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
@@ -179,7 +180,13 @@ def main():
         kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         lo = i * swap
         # the segment's old records were prefetched by the previous step, so it is free to take the victims
-        sd = None if args.direct_swap else staging_dev
+        if args.swap_mode == "fused":
+            nxt = (i + 1) * swap
+            kvm.kvm_swap(pool, wl.slot_tbl, wl.state, step_victims, host_uids[nxt:nxt + swap], swap,
+                         host_slots[lo:lo + swap], step_freed, host_tier[lo * rec:(lo + swap) * rec],
+                         host_tier[nxt * rec:(nxt + swap) * rec], n_bad=n_bad, n_dev=n_victims)
+            return
+        sd = None if args.swap_mode == "direct" else staging_dev
         kvm.kvm_pack(pool, wl.slot_tbl, wl.state, step_victims, swap, host_slots[lo:lo + swap], step_freed,
                      sd, host_tier[lo * rec:(lo + swap) * rec], n_bad=n_bad, n_dev=n_victims)
         nxt = (i + 1) * swap
@@ -214,7 +221,7 @@ def main():
                        n_bad=n_bad, n_dev=n_victims)
         ev_scattered[b].record(main)
 
-    step = step_overlapped if args.overlap_swap else step_serial
+    step = step_overlapped if args.swap_mode == "side-stream" else step_serial
     prefetch(0)
     # the frames of segment 0 came from the bulk list; from now on each step reuses the frames it frees
     torch.cuda.synchronize()
@@ -245,7 +252,7 @@ def main():
 
     kernels = {}
     for name in ("score_plan", "score_partial", "score_finalize", "ema_prio", "beta", "select_hist", "select_emit",
-                 "pack", "unpack"):
+                 "pack", "unpack", "swap"):
         cnt, ms = kvm.kvm_timing_read(name)
         kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
     kvm.kvm_timing_reset()
@@ -267,7 +274,7 @@ def main():
     sp = kernels["score_partial"]["avg_ms"]
     achieved = algo_bytes / (sp * 1e-3) / 1e9
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload
-    # (profiles/score_tile_llama8b_pmc.md); valid for the default workload only.
+    # (profiles/score_tile_dot2_llama8b_pmc.md); valid for the default workload only.
     traffic = SCORE_TILE_TRAFFIC_BYTES if (args.workload == "llama8b" and n_seq == 64 and swap == 1024) else None
     roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -282,8 +289,7 @@ def main():
                                % (decay, round(100 * w_budget)),
                    "units_total": n, "units_scored_per_step": scored_units, "rows": n_rows,
                    "swap_units_per_step": swap, "resident_fraction": round(scored_units / n, 4),
-                   "swap_copies": "side stream" if args.overlap_swap else ("in line, zero-copy kernels" if args.direct_swap
-                                                                            else "in line")},
+                   "swap_mode": args.swap_mode},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "evicted_units_per_s": round(swap / (elapsed / args.steps), 1),
         "prefetched_units_per_s": round(swap / (elapsed / args.steps), 1),

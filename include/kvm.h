@@ -276,6 +276,23 @@ int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8
                const void* staging_host /* pinned */, size_t staging_host_bytes,
                uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
+/* kvm_swap = kvm_pack(out_uids) followed by kvm_unpack(in_uids) into the frames just
+ * freed (entry i of in_uids takes the frame of entry i of out_uids), in one pass
+ * with no device staging: the kernel writes record i to host_out and reads record
+ * i from host_in directly, so both directions of the host link work at once
+ * (sections 3.2: demotion and promotion are asynchronous and independent).
+ * freed_slots[i] is the frame entry i of out_uids left (as kvm_pack, -1 if that
+ * entry was skipped); an in entry whose out entry was skipped, whose uid is out
+ * of range or which is already resident is skipped too, and its frame stays free.
+ * Every skipped half-entry counts once in *n_bad.  n_dev as for kvm_pack.
+ * Errors: as kvm_pack.                                                         */
+int kvm_swap(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+             int64_t n_uids, const int64_t* out_uids /* dev [n] */, const int64_t* in_uids /* dev [n] */, int64_t n,
+             const int64_t* n_dev /* dev [1] or NULL */, const int32_t* host_slots /* dev [n] */,
+             int32_t* freed_slots /* dev [n] out */, void* host_out /* pinned */, size_t host_out_bytes,
+             const void* host_in /* pinned */, size_t host_in_bytes, uint32_t* n_bad /* dev [1] in/out, or NULL */,
+             void* stream);
+
 /* ======================================================================== *
  * Helpers
  * ======================================================================== */
@@ -296,7 +313,7 @@ const char* kvm_version(void);
  * launch of the kernel called `name` since the last kvm_timing_reset, and
  * returns the launch count (0 if the name is unknown); *total_ms gets the sum.
  * Names: "score_partial", "score_finalize", "score_plan", "ema_prio",
- * "beta", "select_hist", "select_scan", "select_emit", "pack", "unpack".    */
+ * "beta", "select_hist", "select_emit", "pack", "unpack", "swap".            */
 int  kvm_timing_enable(int on);
 void kvm_timing_reset(void);
 int  kvm_timing_read(const char* name, double* total_ms);

@@ -87,6 +87,71 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(uint4* __restrict__ k_
     }
 }
 
+// pack + unpack in one pass over the list: record i of host_out receives the frame of
+// out_uids[i], the same frame is then refilled from record i of host_in for in_uids[i].
+// Both directions of the host link are busy at once; there is no device staging.
+__global__ __launch_bounds__(kThreads) void swap_kernel(uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
+                                                        uint32_t n_slots, uint32_t k_v4, uint32_t v_v4,
+                                                        int32_t* __restrict__ slot_tbl, uint8_t* __restrict__ state,
+                                                        int64_t n_uids, const int64_t* __restrict__ out_uids,
+                                                        const int64_t* __restrict__ in_uids,
+                                                        const int32_t* __restrict__ host_slots,
+                                                        int32_t* __restrict__ freed_slots, int64_t first,
+                                                        const int64_t* __restrict__ n_dev, uint4* __restrict__ host_out,
+                                                        const uint4* __restrict__ host_in, uint32_t* n_bad) {
+    __shared__ int32_t s_slot;
+    __shared__ int s_refill;
+    const int64_t i = first + blockIdx.x;
+    if (n_dev && i >= *n_dev) return;
+    if (threadIdx.x == 0) {
+        const int64_t uo = out_uids[i], ui = in_uids[i];
+        int32_t slot = -1;
+        if (uo >= 0 && uo < n_uids && (state[uo] & KVM_ST_RESIDENT)) slot = slot_tbl[uo];
+        if ((uint32_t)slot >= n_slots) slot = -1;
+        freed_slots[i] = slot;
+        int refill = 0;
+        uint32_t bad = 0;
+        if (slot >= 0) {
+            slot_tbl[uo] = -1 - host_slots[i];
+            state[uo] = (uint8_t)((state[uo] & ~KVM_ST_RESIDENT) | KVM_ST_ON_HOST);
+        } else {
+            ++bad;
+        }
+        // the unpack half sees the table as the pack half left it
+        if (slot >= 0 && ui >= 0 && ui < n_uids && !(state[ui] & KVM_ST_RESIDENT)) {
+            refill = 1;
+            slot_tbl[ui] = slot;
+            state[ui] = (uint8_t)((state[ui] & ~KVM_ST_ON_HOST) | KVM_ST_RESIDENT);
+        } else {
+            ++bad;
+        }
+        if (bad && n_bad) atomicAdd(n_bad, bad);
+        s_slot = slot;
+        s_refill = refill;
+    }
+    __syncthreads();
+    const int32_t slot = s_slot;
+    if (slot < 0) return;
+    const bool refill = s_refill != 0;
+    const size_t rec_v4 = (size_t)k_v4 + v_v4;
+    uint4* out = host_out + (size_t)blockIdx.x * rec_v4;
+    const uint4* in = host_in + (size_t)blockIdx.x * rec_v4;
+    uint4* kf = k_pool + (size_t)slot * k_v4;
+    for (uint32_t v = threadIdx.x; v < k_v4; v += kThreads) {
+        const uint4 x = kf[v];
+        out[v] = x;
+        if (refill) kf[v] = in[v];
+    }
+    if (v_v4) {
+        uint4* vf = v_pool + (size_t)slot * v_v4;
+        for (uint32_t v = threadIdx.x; v < v_v4; v += kThreads) {
+            const uint4 x = vf[v];
+            out[k_v4 + v] = x;
+            if (refill) vf[v] = in[k_v4 + v];
+        }
+    }
+}
+
 int check_common(const char* who, const kvm_pool_t* pool, const void* slot_tbl, const void* state, int64_t n_uids,
                  const void* uids, int64_t n, const void* slots, const void* staging_dev, size_t staging_dev_bytes,
                  const void* staging_host, size_t staging_host_bytes) {
@@ -194,4 +259,33 @@ extern "C" int kvm_unpack(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* st
         if (int rc = launch_status("unpack")) return rc;
     }
     return KVM_OK;
+}
+
+extern "C" int kvm_swap(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                        const int64_t* out_uids, const int64_t* in_uids, int64_t n, const int64_t* n_dev,
+                        const int32_t* host_slots, int32_t* freed_slots, void* host_out, size_t host_out_bytes,
+                        const void* host_in, size_t host_in_bytes, uint32_t* n_bad, void* stream) {
+    using namespace kvm;
+    clear_error();
+    if (int rc = check_common("kvm_swap", pool, slot_tbl, state, n_uids, out_uids, n, host_slots, nullptr, 0, host_out,
+                              host_out_bytes))
+        return rc;
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(in_uids && freed_slots && host_in && host_out, KVM_EINVAL, "kvm_swap: null buffer");
+    const size_t rec = (size_t)pool->unit_k_bytes + pool->unit_v_bytes;
+    KVM_REQUIRE(host_in_bytes / rec >= (size_t)n, KVM_ENOSPC, "kvm_swap: host_in %zu bytes < %lld records of %zu",
+                host_in_bytes, (long long)n, rec);
+    KVM_REQUIRE(reinterpret_cast<uintptr_t>(host_in) % 16 == 0, KVM_EINVAL, "kvm_swap: host_in must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t k_v4 = pool->unit_k_bytes / 16, v_v4 = pool->unit_v_bytes / 16;
+    TimedLaunch tl("swap", st);
+    for (int64_t first = 0; first < n; first += 0x40000000ll) {
+        const int64_t cnt = n - first < 0x40000000ll ? n - first : 0x40000000ll;
+        swap_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(
+            static_cast<uint4*>(pool->k_pool), static_cast<uint4*>(pool->v_pool), (uint32_t)pool->n_slots, k_v4, v_v4,
+            slot_tbl, state, n_uids, out_uids, in_uids, host_slots, freed_slots, first, n_dev,
+            reinterpret_cast<uint4*>(static_cast<char*>(host_out) + first * rec),
+            reinterpret_cast<const uint4*>(static_cast<const char*>(host_in) + first * rec), n_bad);
+    }
+    return launch_status("swap");
 }

@@ -50,7 +50,9 @@ __global__ void beta_mean_kernel(const uint32_t* hits, const uint32_t* misses, f
 }
 
 // ---- ema + priority -------------------------------------------------------------
-// One wavefront per row; lanes stride over the row's blocks.
+// LANES threads per row (64 = one wavefront per row, for fleets of short rows; 256 = one
+// workgroup per row, for long rows); they stride over the row's blocks.
+template <int LANES>
 __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uids, const int32_t* __restrict__ row_ntok,
                                                        const int64_t* __restrict__ row_off,
                                                        const uint8_t* __restrict__ row_active,
@@ -62,7 +64,8 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
     __shared__ float ph[KVM_N_PAIRS];
     if (threadIdx.x < KVM_N_PAIRS) ph[threadIdx.x] = p_hat[threadIdx.x];
     __syncthreads();
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    constexpr int ROWS_PER_WG = 256 / LANES;
+    const int row = blockIdx.x * ROWS_PER_WG + threadIdx.x / LANES;
     if (row >= n_rows) return;
     const int n = row_ntok[row];
     if (n <= 0) return;
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
     const bool active = row_active ? row_active[row] != 0 : true;
     const float w = row_weight[row];
     const float keep = decay, take = 1.0f - decay;
-    for (int64_t b = threadIdx.x & 63; b < nb; b += 64) {
+    for (int64_t b = threadIdx.x % LANES; b < nb; b += LANES) {
         const int64_t uid = off + b;
         uint8_t st = state[uid];
         float s = S[uid];
@@ -130,8 +133,14 @@ extern "C" int kvm_ema_update(const kvm_rows_t* rows, const float* mass, float e
                 "kvm_ema_update: null buffer");
     hipStream_t st = static_cast<hipStream_t>(stream);
     TimedLaunch tl("ema_prio", st);
-    const unsigned grid = (unsigned)((rows->n_rows + 3) / 4);
-    ema_prio_kernel<<<grid, 256, 0, st>>>(rows->n_rows, rows->n_uids, rows->row_ntok, rows->row_off, rows->row_active,
-                                          mass, ema_decay, row_weight, pair, p_hat, state, S, prio);
+    if (rows->n_uids / rows->n_rows >= 192) {
+        ema_prio_kernel<256><<<(unsigned)rows->n_rows, 256, 0, st>>>(rows->n_rows, rows->n_uids, rows->row_ntok,
+                                                                    rows->row_off, rows->row_active, mass, ema_decay,
+                                                                    row_weight, pair, p_hat, state, S, prio);
+    } else {
+        ema_prio_kernel<64><<<(unsigned)((rows->n_rows + 3) / 4), 256, 0, st>>>(
+            rows->n_rows, rows->n_uids, rows->row_ntok, rows->row_off, rows->row_active, mass, ema_decay, row_weight,
+            pair, p_hat, state, S, prio);
+    }
     return launch_status("ema_prio");
 }

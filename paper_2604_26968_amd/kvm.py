@@ -24,7 +24,7 @@ AGG_MAX, AGG_MEAN = 0, 1
 OP_SCORE, OP_SELECT = 0, 1
 
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_beta_update", "kvm_ema_update", "kvm_select_victims",
-           "kvm_pack", "kvm_unpack", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
+           "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
            "kvm_timing_enable", "kvm_timing_reset", "kvm_timing_read"]
 
 
@@ -83,6 +83,9 @@ def _load() -> C.CDLL:
     lib.kvm_unpack.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                                C.c_void_p, C.c_void_p]
+    lib.kvm_swap.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
+                             C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
     return lib
 
@@ -195,6 +198,15 @@ def kvm_unpack(pool: Pool, slot_tbl, state, uids, n: int, dst_slots, staging_dev
                           _ptr(staging_dev), _nbytes(staging_dev),
                           _ptr(staging_host, None, "cpu"), _nbytes(staging_host),
                           _ptr(n_bad, torch.int32), _stream(stream)))
+
+
+def kvm_swap(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, host_slots, freed_slots, host_out, host_in,
+             n_bad=None, n_dev=None, stream=None):
+    _check(lib.kvm_swap(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                        _ptr(out_uids, torch.int64), _ptr(in_uids, torch.int64), n, _ptr(n_dev, torch.int64),
+                        _ptr(host_slots, torch.int32), _ptr(freed_slots, torch.int32),
+                        _ptr(host_out, None, "cpu"), _nbytes(host_out), _ptr(host_in, None, "cpu"), _nbytes(host_in),
+                        _ptr(n_bad, torch.int32), _stream(stream)))
 
 
 def kvm_last_error() -> str:

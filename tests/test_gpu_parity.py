@@ -339,6 +339,50 @@ def test_pack_unpack_split_phases_with_caller_copies(oracle):
     assert int(dev.n_bad.item()) == 0
 
 
+@pytest.mark.parametrize("shape", [
+    synth.Shape(2, 8, 2, 128, synth.BF16, True, [300, 77]),
+    synth.Shape(4, 16, 1, 576, synth.BF16, False, [400]),
+])
+def test_swap_equals_pack_then_unpack(oracle, shape):
+    """The fused call leaves tables, pools and host records exactly as the oracle's pack followed
+    by unpack into the freed frames, including skipped entries."""
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(shape, seed=23)
+    out_first = evict_some(case, 0.3, 4)                        # these live on the host already
+    dev = DeviceCase(case)
+    k8, v8 = host_pools(case)
+    rng = np.random.default_rng(6)
+    n = 20
+    res = np.nonzero(case.state & RES)[0]
+    out_uids = rng.choice(res, size=n, replace=False).astype(np.int64)
+    in_uids = rng.choice(out_first, size=n, replace=False).astype(np.int64)
+    out_uids[3] = -1                     # malformed victim: its partner cannot come in either
+    in_uids[7] = res[0] if res[0] not in out_uids else res[1]   # already resident: frame 7 stays free
+    hs = (900 + np.arange(n)).astype(np.int32)
+    rec = dev.rec
+    host_in = rng.integers(0, 256, size=(n, rec), dtype=np.uint8)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    bad = np.zeros(1, np.uint32)
+    want_out, want_freed = oracle.pack(k8, v8, shape.unit_k_bytes, shape.unit_v_bytes, tbl, st, out_uids, hs, n_bad=bad)
+    oracle.unpack(k8, v8, shape.unit_k_bytes, shape.unit_v_bytes, tbl, st, in_uids, want_freed, host_in, n_bad=bad)
+    h_out = torch.zeros(n * rec, dtype=torch.uint8, pin_memory=True)
+    h_in = torch.from_numpy(host_in.reshape(-1).copy()).pin_memory()
+    freed = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    kvm.kvm_swap(dev.pool, dev.slot_tbl, dev.state, torch.from_numpy(out_uids).cuda(), torch.from_numpy(in_uids).cuda(),
+                 n, torch.from_numpy(hs).cuda(), freed, h_out, h_in, n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(freed.cpu().numpy(), want_freed)
+    ok = want_freed >= 0
+    np.testing.assert_array_equal(h_out.numpy().reshape(n, rec)[ok], want_out[ok])
+    gk, gv = dev.pools_host()
+    np.testing.assert_array_equal(gk, k8)
+    if v8 is not None:
+        np.testing.assert_array_equal(gv, v8)
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    assert int(dev.n_bad.item()) == int(bad[0]) == 3
+
+
 def test_pack_unpack_round_trip_is_identity():
     case = synth.make_case(synth.Shape(2, 8, 2, 128, synth.BF16, True, [1000]), seed=2)
     dev = DeviceCase(case)
