@@ -28,7 +28,7 @@ WORKLOADS = {
     "llama8b": ("llama3-8b-shaped GQA: 32 layers, 32q/8kv heads, d128, bf16, %d seqs U[2048,8192] tok",
                 lambda synth, n: synth.llama8b_shape(n, seed=2), 64, 0.60, 0.95, 1024, None, 32),
     "llama70b": ("llama3-70b-shaped GQA (one GPU's share): 80 layers, 64q/8kv heads, d128, bf16, %d x 131072 tok",
-                 lambda synth, n: synth.llama70b_shape(n), 4, 0.50, 0.95, 4096, 8, 0),
+                 lambda synth, n: synth.llama70b_shape(n), 4, 0.50, 0.95, 4096, 64, 0),
     "mla": ("deepseek-v3-shaped MLA: 61 layers, 576-channel latent, 128 absorbed queries, bf16, %d x 32768 tok",
             lambda synth, n: synth.mla_shape(n), 32, 0.40, 0.90, 1024, 2, 0),
 }
