@@ -116,6 +116,19 @@ def beta_update(ev_pair, ev_outcome, hits, misses, alpha0=1.0, beta0=1.0, p_hat=
     return p_hat
 
 
+def beta_blend_update(ev_pair, ev_outcome, hits, misses, win, win_head, kappa, alpha0=1.0, beta0=1.0, n_bad=None):
+    """Returns (p_hat, conf, p_blend); win is uint8 [16, window] (255 = never written)."""
+    window = win.shape[1]
+    p_hat, conf, p_blend = (np.zeros(16, np.float32) for _ in range(3))
+    rc = lib().kvm_ref_beta_blend_update(
+        _p(ev_pair, np.uint8), _p(ev_outcome, np.uint8), C.c_int64(len(ev_pair)),
+        _p(hits, np.uint32), _p(misses, np.uint32), C.c_double(alpha0), C.c_double(beta0),
+        _p(win, np.uint8), _p(win_head, np.uint32), C.c_int(window), C.c_double(kappa),
+        _p(p_hat, np.float32), _p(conf, np.float32), _p(p_blend, np.float32), _p(n_bad, np.uint32))
+    _check(rc, "kvm_ref_beta_blend_update")
+    return p_hat, conf, p_blend
+
+
 def ema_update(row_ntok, row_off, mass, decay, row_weight, pair, p_hat, state, S, prio,
                row_active=None, block_tokens=16):
     rc = lib().kvm_ref_ema_update(

@@ -18,6 +18,10 @@
  *   kvm_ref_ema_update      section 3.4 (EMA importance, head weights) times the
  *                           posterior mean of Eq. 5
  *   kvm_ref_beta_update     section 3.3, Eq. 5 and the update rule after it
+ *   kvm_ref_beta_blend_update
+ *                           section 3.3, last two paragraphs: confidence that saturates
+ *                           with the number of observations, empirical frequency over a
+ *                           sliding window, blend weighted by the confidence
  *   kvm_ref_select_victims  section 3.4 ("lowest weighted aggregate importance"),
  *                           as a full sort
  *   kvm_ref_pack / unpack   section 3.2 (tier 0 <-> tier 1 moves), as memcpy
@@ -229,6 +233,54 @@ int kvm_ref_beta_update(const uint8_t* ev_pair, const uint8_t* ev_outcome, int64
         const double a = alpha0 + (double)hits[i];
         const double b = beta0 + (double)misses[i];
         p_hat[i] = (float)(a / (a + b));
+    }
+    return REF_OK;
+}
+
+/* Section 3.3, after Eq. 5: the estimate used for decisions blends the posterior
+ * mean with the hit frequency among the last `window` observations of the pair;
+ * the weight of the posterior is a confidence that grows towards 1 with the
+ * number of observations.  The paper gives neither formula; the reading taken:
+ *   n      = hits + misses of the pair (all observations so far)
+ *   conf   = n / (n + kappa)                  (0 when n + kappa == 0)
+ *   f      = (1-outcomes among the last min(n_pushed, window) observations) / their number,
+ *            or the posterior mean when the window holds nothing yet
+ *   blend  = conf * posterior + (1 - conf) * f
+ * The window is a ring per pair: win[pair * window + i] holds 0 or 1, any other value
+ * marks a place never written; win_head[pair] is the next place to write.
+ * Events are taken in array order; malformed events are skipped as in
+ * kvm_ref_beta_update and touch neither the counters nor the window. */
+int kvm_ref_beta_blend_update(const uint8_t* ev_pair, const uint8_t* ev_outcome, int64_t n_events,
+                              uint32_t* hits, uint32_t* misses, double alpha0, double beta0,
+                              uint8_t* win, uint32_t* win_head, int window, double kappa,
+                              float* p_hat, float* conf, float* p_blend, uint32_t* n_bad) {
+    if (n_events < 0 || !hits || !misses || !p_hat || !conf || !p_blend || !win || !win_head) return REF_EINVAL;
+    if (n_events > 0 && (!ev_pair || !ev_outcome)) return REF_EINVAL;
+    if (!(alpha0 > 0.0) || !(beta0 > 0.0) || window <= 0 || !(kappa >= 0.0)) return REF_EINVAL;
+    for (int i = 0; i < 16; ++i)
+        if (win_head[i] >= (uint32_t)window) return REF_EINVAL;
+    for (int64_t e = 0; e < n_events; ++e) {
+        const int p = ev_pair[e], o = ev_outcome[e];
+        if (p >= 16 || o > 1) { if (n_bad) ++*n_bad; continue; }
+        if (o) hits[p] += 1; else misses[p] += 1;
+        win[(size_t)p * window + win_head[p]] = (uint8_t)o;
+        win_head[p] = (win_head[p] + 1) % (uint32_t)window;
+    }
+    for (int i = 0; i < 16; ++i) {
+        const double a = alpha0 + (double)hits[i];
+        const double b = beta0 + (double)misses[i];
+        const double post = a / (a + b);
+        const double n = (double)hits[i] + (double)misses[i];
+        const double c = (n + kappa > 0.0) ? n / (n + kappa) : 0.0;
+        long ones = 0, seen = 0;
+        for (int j = 0; j < window; ++j) {
+            const uint8_t v = win[(size_t)i * window + j];
+            if (v <= 1) { ++seen; ones += v; }
+        }
+        const double f = seen ? (double)ones / (double)seen : post;
+        p_hat[i] = (float)post;
+        conf[i] = (float)c;
+        p_blend[i] = (float)(c * post + (1.0 - c) * f);
     }
     return REF_OK;
 }
