@@ -139,6 +139,22 @@ def ema_update(row_ntok, row_off, mass, decay, row_weight, pair, p_hat, state, S
     _check(rc, "kvm_ref_ema_update")
 
 
+def ema_update_ex(row_ntok, row_off, mass, decay, pos_decay, row_weight, pair, p_hat, state, S, prio,
+                  row_seq=None, row_head=None, seq_transition=None, head_mult=None,
+                  row_active=None, block_tokens=16):
+    """head_mult: float32 [4, n_heads] or None."""
+    n_seq = 0 if seq_transition is None else len(seq_transition)
+    n_heads = 0 if head_mult is None else head_mult.shape[1]
+    rc = lib().kvm_ref_ema_update_ex(
+        C.c_int(len(row_ntok)), C.c_int(block_tokens), C.c_int64(len(state)),
+        _p(row_ntok, np.int32), _p(row_off, np.int64), _p(row_active, np.uint8),
+        _p(mass, np.float32), C.c_double(decay), C.c_double(pos_decay), _p(row_weight, np.float32),
+        _p(row_seq, np.int32), _p(row_head, np.int32), _p(seq_transition, np.uint8), C.c_int(n_seq),
+        _p(head_mult, np.float32), C.c_int(n_heads),
+        _p(pair, np.uint8), _p(p_hat, np.float32), _p(state, np.uint8), _p(S, np.float32), _p(prio, np.float32))
+    _check(rc, "kvm_ref_ema_update_ex")
+
+
 def select_victims(prio, state, k=-1, budget_units=0, victims_cap=None):
     n = len(prio)
     cap = n if victims_cap is None else victims_cap

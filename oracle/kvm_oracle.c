@@ -17,6 +17,9 @@
  *                           group maximum of section 3.4
  *   kvm_ref_ema_update      section 3.4 (EMA importance, head weights) times the
  *                           posterior mean of Eq. 5
+ *   kvm_ref_ema_update_ex   the same with the two refinements section 3.4 names: the
+ *                           importance decays with positional distance, and per-head
+ *                           multipliers chosen by the transition type (sections 3.4, 3.7)
  *   kvm_ref_beta_update     section 3.3, Eq. 5 and the update rule after it
  *   kvm_ref_beta_blend_update
  *                           section 3.3, last two paragraphs: confidence that saturates
@@ -313,6 +316,60 @@ int kvm_ref_ema_update(int n_rows, int block_tokens, int64_t n_uids,
             }
             if (state[uid] & ST_SCORED)
                 prio[uid] = (float)((double)row_weight[r] * (double)S[uid] * (double)p_hat[pair[uid] & 15]);
+            else
+                prio[uid] = INFINITY;
+        }
+    }
+    return REF_OK;
+}
+
+/* Section 3.4 says the EMA "incorporates positional distance decay" and that per-head
+ * multipliers are applied during task transitions (section 3.7, item 2) without giving
+ * either formula.  The reading taken:
+ *   distance d of block b in a row of nb blocks = nb - 1 - b (blocks behind the decode
+ *   position, which lies in the row's last block);
+ *   the observation fed to the EMA is x = pos_decay^d * mass            (pos_decay in (0, 1]);
+ *   multiplier of row r = head_mult[t * n_heads + row_head[r]] where t = seq_transition[row_seq[r]]
+ *   is the transition type (0..3) its sequence is going through, or 1 when t > 3 (no
+ *   transition) or when head_mult is NULL;
+ *   prio = row_weight * multiplier * S * p_hat[pair].
+ * With pos_decay = 1 and no multipliers this is kvm_ref_ema_update. */
+int kvm_ref_ema_update_ex(int n_rows, int block_tokens, int64_t n_uids,
+                          const int32_t* row_ntok, const int64_t* row_off, const uint8_t* row_active,
+                          const float* mass, double decay, double pos_decay, const float* row_weight,
+                          const int32_t* row_seq, const int32_t* row_head, const uint8_t* seq_transition,
+                          int n_seq, const float* head_mult, int n_heads,
+                          const uint8_t* pair, const float* p_hat,
+                          uint8_t* state, float* S, float* prio) {
+    if (!row_ntok || !row_off || !mass || !row_weight || !pair || !p_hat || !state || !S || !prio)
+        return REF_EINVAL;
+    if (!(decay >= 0.0 && decay <= 1.0) || !(pos_decay > 0.0 && pos_decay <= 1.0) || block_tokens <= 0)
+        return REF_EINVAL;
+    if (head_mult && (!row_seq || !row_head || !seq_transition || n_seq <= 0 || n_heads <= 0)) return REF_EINVAL;
+    for (int r = 0; r < n_rows; ++r) {
+        const int n = row_ntok[r];
+        const int nb = n > 0 ? (n + block_tokens - 1) / block_tokens : 0;
+        if (nb && (row_off[r] < 0 || row_off[r] + nb > n_uids)) return REF_EINVAL;
+        const int active = row_active ? row_active[r] != 0 : 1;
+        double mult = 1.0;
+        if (head_mult) {
+            if (row_seq[r] < 0 || row_seq[r] >= n_seq || row_head[r] < 0 || row_head[r] >= n_heads) return REF_EINVAL;
+            const int t = seq_transition[row_seq[r]];
+            if (t <= 3) mult = (double)head_mult[(size_t)t * n_heads + row_head[r]];
+        }
+        for (int b = 0; b < nb; ++b) {
+            const int64_t uid = row_off[r] + b;
+            if (active && (state[uid] & ST_RESIDENT)) {
+                const double x = pow(pos_decay, (double)(nb - 1 - b)) * (double)mass[uid];
+                if (!(state[uid] & ST_SCORED)) {
+                    S[uid] = (float)x;
+                    state[uid] |= ST_SCORED;
+                } else {
+                    S[uid] = (float)(decay * (double)S[uid] + (1.0 - decay) * x);
+                }
+            }
+            if (state[uid] & ST_SCORED)
+                prio[uid] = (float)((double)row_weight[r] * mult * (double)S[uid] * (double)p_hat[pair[uid] & 15]);
             else
                 prio[uid] = INFINITY;
         }

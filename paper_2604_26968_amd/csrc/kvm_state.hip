@@ -49,6 +49,109 @@ __global__ void beta_mean_kernel(const uint32_t* hits, const uint32_t* misses, f
     }
 }
 
+// ---- sliding window + blended estimate (section 3.3, after Eq. 5) ------------------------
+// Ring of the last `window` outcomes per pair.  The order of events matters here (only the
+// newest `window` of a pair survive), so one workgroup walks the event array in chunks of
+// 1024 and gives every valid event its rank among the events of its pair: rank inside the
+// wavefront from ballots, plus the counts of earlier wavefronts and earlier chunks.  An event
+// is written iff it is among the last `window` of its pair in this call, at ring place
+// (head + rank) mod window: distinct places, no write race.
+constexpr int kWinThreads = 1024;
+constexpr int kWinWaves = kWinThreads / kWave;
+
+__global__ __launch_bounds__(kWinThreads) void beta_window_kernel(const uint8_t* __restrict__ ev_pair,
+                                                                  const uint8_t* __restrict__ ev_outcome, int64_t n,
+                                                                  uint8_t* __restrict__ win,
+                                                                  uint32_t* __restrict__ win_head, uint32_t window) {
+    __shared__ uint32_t tot[KVM_N_PAIRS];    // valid events of each pair in this call
+    __shared__ uint32_t run[KVM_N_PAIRS];    // ... of which in earlier chunks
+    __shared__ uint32_t head0[KVM_N_PAIRS];
+    __shared__ uint32_t wcnt[kWinWaves][KVM_N_PAIRS];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    if (tid < KVM_N_PAIRS) {
+        tot[tid] = 0;
+        run[tid] = 0;
+        head0[tid] = win_head[tid] % window;
+    }
+    if (tid < kWinWaves * KVM_N_PAIRS) (&wcnt[0][0])[tid] = 0;
+    __syncthreads();
+    for (int64_t e = tid; e < n; e += kWinThreads) {
+        const uint32_t p = ev_pair[e], o = ev_outcome[e];
+        if (p < KVM_N_PAIRS && o <= 1) atomicAdd(&tot[p], 1u);
+    }
+    __syncthreads();
+    for (int64_t base = 0; base < n; base += kWinThreads) {
+        const int64_t e = base + tid;
+        uint32_t p = 0, o = 0;
+        bool valid = false;
+        if (e < n) {
+            p = ev_pair[e];
+            o = ev_outcome[e];
+            valid = p < KVM_N_PAIRS && o <= 1;
+        }
+        // lanes of this wavefront that hold a valid event of the same pair
+        uint64_t same = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 4; ++bit) {
+            const uint64_t b = __ballot((p >> bit) & 1);
+            same &= ((p >> bit) & 1) ? b : ~b;
+        }
+        const uint32_t rank_in_wave = __popcll(same & ((1ull << lane) - 1));
+        if (valid && rank_in_wave == 0) wcnt[wave][p] = __popcll(same);
+        __syncthreads();
+        if (valid) {
+            uint32_t rank = run[p] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) rank += wcnt[w][p];
+            if ((uint64_t)rank + window >= tot[p])
+                win[(size_t)p * window + (head0[p] + rank) % window] = (uint8_t)o;
+        }
+        __syncthreads();
+        if (tid < KVM_N_PAIRS) {
+            uint32_t c = 0;
+            for (int w = 0; w < kWinWaves; ++w) c += wcnt[w][tid];
+            run[tid] += c;
+        }
+        __syncthreads();
+        if (tid < kWinWaves * KVM_N_PAIRS) (&wcnt[0][0])[tid] = 0;
+        __syncthreads();
+    }
+    if (tid < KVM_N_PAIRS) win_head[tid] = (uint32_t)(((uint64_t)head0[tid] + tot[tid]) % window);
+}
+
+// One workgroup per pair: window frequency, posterior mean, confidence, blend.
+__global__ __launch_bounds__(256) void beta_blend_kernel(const uint32_t* __restrict__ hits,
+                                                         const uint32_t* __restrict__ misses, float alpha0,
+                                                         float beta0, const uint8_t* __restrict__ win,
+                                                         uint32_t window, float kappa, float* __restrict__ p_hat,
+                                                         float* __restrict__ conf, float* __restrict__ p_blend) {
+    __shared__ uint32_t s_ones, s_seen;
+    const int i = blockIdx.x;
+    if (threadIdx.x == 0) s_ones = s_seen = 0;
+    __syncthreads();
+    uint32_t ones = 0, seen = 0;
+    for (uint32_t j = threadIdx.x; j < window; j += 256) {
+        const uint32_t v = win[(size_t)i * window + j];
+        seen += v <= 1;
+        ones += v == 1;
+    }
+    if (seen) {
+        atomicAdd(&s_seen, seen);
+        atomicAdd(&s_ones, ones);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float a = alpha0 + (float)hits[i];
+        const float b = beta0 + (float)misses[i];
+        const float post = a / (a + b);
+        const float n = (float)hits[i] + (float)misses[i];
+        const float c = (n + kappa > 0.f) ? n / (n + kappa) : 0.f;
+        const float f = s_seen ? (float)s_ones / (float)s_seen : post;
+        p_hat[i] = post;
+        conf[i] = c;
+        p_blend[i] = c * post + (1.f - c) * f;
+    }
+}
+
 // ---- ema + priority -------------------------------------------------------------
 // LANES threads per row (64 = one wavefront per row, for fleets of short rows; 256 = one
 // workgroup per row, for long rows); they stride over the row's blocks.
@@ -116,6 +219,34 @@ extern "C" int kvm_beta_update(const uint8_t* ev_pair, const uint8_t* ev_outcome
     }
     beta_mean_kernel<<<1, 64, 0, st>>>(hits, misses, alpha0, beta0, p_hat);
     return launch_status("beta");
+}
+
+extern "C" int kvm_beta_blend_update(const uint8_t* ev_pair, const uint8_t* ev_outcome, int64_t n_events,
+                                     uint32_t* hits, uint32_t* misses, float alpha0, float beta0, uint8_t* win,
+                                     uint32_t* win_head, int32_t window, float kappa, float* p_hat, float* conf,
+                                     float* p_blend, uint32_t* n_bad, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(n_events >= 0, KVM_EINVAL, "kvm_beta_blend_update: n_events %lld < 0", (long long)n_events);
+    KVM_REQUIRE(hits && misses && p_hat && conf && p_blend && win && win_head, KVM_EINVAL,
+                "kvm_beta_blend_update: null counter, window or output");
+    KVM_REQUIRE(n_events == 0 || (ev_pair && ev_outcome), KVM_EINVAL, "kvm_beta_blend_update: null event array");
+    KVM_REQUIRE(alpha0 > 0.f && beta0 > 0.f, KVM_EINVAL, "kvm_beta_blend_update: prior (%g, %g) must be positive",
+                (double)alpha0, (double)beta0);
+    KVM_REQUIRE(window >= 1 && window <= KVM_MAX_WINDOW, KVM_EINVAL,
+                "kvm_beta_blend_update: window %d outside [1, %d]", window, KVM_MAX_WINDOW);
+    KVM_REQUIRE(kappa >= 0.f, KVM_EINVAL, "kvm_beta_blend_update: kappa %g < 0", (double)kappa);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("beta", st);
+    if (n_events > 0) {
+        beta_window_kernel<<<1, kWinThreads, 0, st>>>(ev_pair, ev_outcome, n_events, win, win_head, (uint32_t)window);
+        int64_t grid = (n_events + kBetaThreads * 16 - 1) / (kBetaThreads * 16);
+        if (grid > kBetaMaxGrid) grid = kBetaMaxGrid;
+        beta_count_kernel<<<(unsigned)grid, kBetaThreads, 0, st>>>(ev_pair, ev_outcome, n_events, hits, misses, n_bad);
+    }
+    beta_blend_kernel<<<KVM_N_PAIRS, 256, 0, st>>>(hits, misses, alpha0, beta0, win, (uint32_t)window, kappa, p_hat,
+                                                   conf, p_blend);
+    return launch_status("beta_blend");
 }
 
 extern "C" int kvm_ema_update(const kvm_rows_t* rows, const float* mass, float ema_decay, const float* row_weight,
