@@ -155,6 +155,27 @@ def ema_update_ex(row_ntok, row_off, mass, decay, pos_decay, row_weight, pair, p
     _check(rc, "kvm_ref_ema_update_ex")
 
 
+def span_update(row_ntok, row_off, row_layer, mass, state, theta_num, theta_den, span_sum, span_cnt,
+                w_min, w_max, layer_window, row_active=None, block_tokens=16):
+    rc = lib().kvm_ref_span_update(
+        C.c_int(len(row_ntok)), C.c_int(block_tokens), C.c_int64(len(state)),
+        _p(row_ntok, np.int32), _p(row_off, np.int64), _p(row_active, np.uint8), _p(row_layer, np.int32),
+        C.c_int(len(layer_window)), _p(mass, np.float32), _p(state, np.uint8),
+        C.c_uint32(theta_num), C.c_uint32(theta_den), _p(span_sum, np.uint64), _p(span_cnt, np.uint32),
+        C.c_int32(w_min), C.c_int32(w_max), _p(layer_window, np.int32))
+    _check(rc, "kvm_ref_span_update")
+
+
+def prefetch_keys(row_ntok, row_off, row_layer, row_pos, layer_window, state, pair, p_est, pos_decay,
+                  key, cand, block_tokens=16):
+    rc = lib().kvm_ref_prefetch_keys(
+        C.c_int(len(row_ntok)), C.c_int(block_tokens), C.c_int64(len(state)),
+        _p(row_ntok, np.int32), _p(row_off, np.int64), _p(row_layer, np.int32), _p(row_pos, np.int32),
+        _p(layer_window, np.int32), C.c_int(len(layer_window)), _p(state, np.uint8), _p(pair, np.uint8),
+        _p(p_est, np.float32), C.c_double(pos_decay), _p(key, np.float32), _p(cand, np.uint8))
+    _check(rc, "kvm_ref_prefetch_keys")
+
+
 def select_victims(prio, state, k=-1, budget_units=0, victims_cap=None):
     n = len(prio)
     cap = n if victims_cap is None else victims_cap

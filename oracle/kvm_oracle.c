@@ -27,6 +27,10 @@
  *                           sliding window, blend weighted by the confidence
  *   kvm_ref_select_victims  section 3.4 ("lowest weighted aggregate importance"),
  *                           as a full sort
+ *   kvm_ref_span_update     section 3.5: per-layer prefetch window from the observed
+ *                           attention span
+ *   kvm_ref_prefetch_keys   section 3.5: candidates inside the positional window around the
+ *                           decode position, ranked with the reuse estimate of section 3.3
  *   kvm_ref_pack / unpack   section 3.2 (tier 0 <-> tier 1 moves), as memcpy
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
@@ -420,6 +424,111 @@ int kvm_ref_select_victims(const float* prio, const uint8_t* state, int64_t n_ui
     qsort(victims, (size_t)k, sizeof(int64_t), i64_cmp);
     *n_victims = k;
     free(c);
+    return REF_OK;
+}
+
+/* ---------------------------------------------- position-aware prefetching */
+
+/* Section 3.5: the prefetch window "adapts based on observed attention patterns",
+ * narrow for layers that attend locally, wide for layers that attend globally.  No
+ * formula is given.  The reading taken: the attention span of a row is the smallest
+ * number s >= 1 of trailing blocks (counted back from the row's last block, blocks not
+ * in HBM counting as distance but contributing nothing) whose masses hold at least
+ * theta = theta_num / theta_den of the row's total mass this step; a layer's window is
+ * block_tokens * ceil(mean span of its rows), clamped to [w_min, w_max] tokens.
+ * So that the integer decision is the same on every implementation, masses enter as
+ * fixed point: Q(m) = floor(m * 2^32) for m in (0, 256], 0 for anything else (NaN
+ * included), clamped at 256; all sums are exact 64-bit integers.
+ * span_sum / span_cnt accumulate over calls (the caller resets or ages them);
+ * layer_window[l] is rewritten for layers with span_cnt > 0 and left alone otherwise. */
+int kvm_ref_span_update(int n_rows, int block_tokens, int64_t n_uids,
+                        const int32_t* row_ntok, const int64_t* row_off, const uint8_t* row_active,
+                        const int32_t* row_layer, int n_layers, const float* mass, const uint8_t* state,
+                        uint32_t theta_num, uint32_t theta_den, uint64_t* span_sum, uint32_t* span_cnt,
+                        int32_t w_min, int32_t w_max, int32_t* layer_window) {
+    if (!row_ntok || !row_off || !row_layer || !mass || !state || !span_sum || !span_cnt || !layer_window)
+        return REF_EINVAL;
+    if (block_tokens <= 0 || n_layers <= 0 || theta_den == 0 || theta_num > theta_den || theta_den > 65536 ||
+        w_min < 0 || w_max < w_min)
+        return REF_EINVAL;
+    for (int r = 0; r < n_rows; ++r) {
+        const int n = row_ntok[r];
+        const int nb = n > 0 ? (n + block_tokens - 1) / block_tokens : 0;
+        if (nb && (row_off[r] < 0 || row_off[r] + nb > n_uids)) return REF_EINVAL;
+        if (row_layer[r] < 0 || row_layer[r] >= n_layers) return REF_EINVAL;
+        if (row_active && !row_active[r]) continue;
+        uint64_t total = 0;
+        for (int b = 0; b < nb; ++b) {
+            const int64_t uid = row_off[r] + b;
+            const float m = mass[uid];
+            uint64_t qv = 0;
+            if ((state[uid] & ST_RESIDENT) && m > 0.0f) qv = (uint64_t)((double)(m < 256.0f ? m : 256.0f) * 4294967296.0);
+            total += qv;
+        }
+        if (total == 0) continue;
+        uint64_t acc = 0;
+        int span = nb;
+        for (int s = 1; s <= nb; ++s) {
+            const int64_t uid = row_off[r] + (nb - s);
+            const float m = mass[uid];
+            if ((state[uid] & ST_RESIDENT) && m > 0.0f) acc += (uint64_t)((double)(m < 256.0f ? m : 256.0f) * 4294967296.0);
+            if (acc * (uint64_t)theta_den >= (uint64_t)theta_num * total) { span = s; break; }
+        }
+        span_sum[row_layer[r]] += (uint64_t)span;
+        span_cnt[row_layer[r]] += 1;
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        if (!span_cnt[l]) continue;
+        const uint64_t mean_up = (span_sum[l] + span_cnt[l] - 1) / span_cnt[l];
+        uint64_t w = mean_up * (uint64_t)block_tokens;
+        if (w < (uint64_t)w_min) w = (uint64_t)w_min;
+        if (w > (uint64_t)w_max) w = (uint64_t)w_max;
+        layer_window[l] = (int32_t)w;
+    }
+    return REF_OK;
+}
+
+/* Section 3.5: while a request decodes at position n, the blocks most likely to be
+ * needed next are those within a window w of n; they are promoted from the lower tier
+ * ahead of use, "combined with" the reuse estimate of section 3.3.  The text gives the
+ * window once as [n - w, n] and once as [n, n + w]; positions after n hold no keys yet
+ * during decoding, so the reading taken is [n - w, n].  For row r with decode position
+ * n = row_pos[r] (tokens; negative = the row asks for nothing) and w = layer_window[row_layer[r]]:
+ *   block b is a candidate iff it is on the host and not in HBM and its tokens
+ *   [B b, B b + B - 1] meet [n - w, n]  (B = block_tokens);
+ *   key = 1 - p_est[pair] * pos_decay^(floor(n / B) - b)      (lower = fetch sooner);
+ *   cand = RESIDENT | SCORED for candidates (the pattern kvm_ref_select_victims admits), 0
+ *   otherwise, and key = +inf for non-candidates.
+ * The list itself is then the k lowest (key, uid) by kvm_ref_select_victims(key, cand, k). */
+int kvm_ref_prefetch_keys(int n_rows, int block_tokens, int64_t n_uids,
+                          const int32_t* row_ntok, const int64_t* row_off, const int32_t* row_layer,
+                          const int32_t* row_pos, const int32_t* layer_window, int n_layers,
+                          const uint8_t* state, const uint8_t* pair, const float* p_est, double pos_decay,
+                          float* key, uint8_t* cand) {
+    if (!row_ntok || !row_off || !row_layer || !row_pos || !layer_window || !state || !pair || !p_est || !key || !cand)
+        return REF_EINVAL;
+    if (block_tokens <= 0 || n_layers <= 0 || !(pos_decay > 0.0 && pos_decay <= 1.0)) return REF_EINVAL;
+    for (int r = 0; r < n_rows; ++r) {
+        const int nt = row_ntok[r];
+        const int nb = nt > 0 ? (nt + block_tokens - 1) / block_tokens : 0;
+        if (nb && (row_off[r] < 0 || row_off[r] + nb > n_uids)) return REF_EINVAL;
+        if (row_layer[r] < 0 || row_layer[r] >= n_layers) return REF_EINVAL;
+        const int64_t n = row_pos[r];
+        const int64_t w = layer_window[row_layer[r]];
+        for (int b = 0; b < nb; ++b) {
+            const int64_t uid = row_off[r] + b;
+            const int64_t first = (int64_t)b * block_tokens, last = first + block_tokens - 1;
+            const int on_host = (state[uid] & ST_ON_HOST) && !(state[uid] & ST_RESIDENT);
+            if (n >= 0 && w >= 0 && on_host && last >= n - w && first <= n) {
+                const double dist = (double)(n / block_tokens - b);
+                key[uid] = (float)(1.0 - (double)p_est[pair[uid] & 15] * pow(pos_decay, dist));
+                cand[uid] = ST_RESIDENT | ST_SCORED;
+            } else {
+                key[uid] = INFINITY;
+                cand[uid] = 0;
+            }
+        }
+    }
     return REF_OK;
 }
 
