@@ -197,6 +197,37 @@ int kvm_beta_update(const uint8_t* ev_pair /* dev [n_events] */,
                     float alpha0, float beta0, float* p_hat /* dev [16] out */,
                     uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
+/* Blended reuse estimate — section 3.3, the two paragraphs after Eq. 5.
+ *
+ * Does everything kvm_beta_update does and, with the same events taken in
+ * array order, keeps per pair a ring of its last `window` outcomes:
+ *   win[pair * window + i] is 0 or 1; any other value marks a place never
+ *   written (the caller fills the array with 0xFF before first use);
+ *   win_head[pair] < window is the next place to write.
+ * Then, per pair, with n = hits + misses:
+ *   conf    = n / (n + kappa)                       (0 when n + kappa == 0)
+ *   f       = share of 1s among the written places of the ring, or p_hat when none
+ *   p_blend = conf * p_hat + (1 - conf) * f
+ * so a pair with few observations follows its recent frequency and a well
+ * observed pair its posterior mean.  The paper gives neither the saturation
+ * function nor the window; kappa and window are the caller's.
+ * The ring update runs in one workgroup (the order of events matters):
+ * meant for the thousands of lookups of a decode step, ~1 us per 1024 events.
+ * Malformed events touch neither counters nor ring.  A win_head entry >=
+ * window is taken modulo window.
+ * Errors: KVM_EINVAL (as kvm_beta_update; window outside [1, KVM_MAX_WINDOW];
+ * kappa < 0; null win / win_head / conf / p_blend).                         */
+#define KVM_MAX_WINDOW 65536
+int kvm_beta_blend_update(const uint8_t* ev_pair /* dev [n_events] */,
+                          const uint8_t* ev_outcome /* dev [n_events] */, int64_t n_events,
+                          uint32_t* hits /* dev [16] in/out */, uint32_t* misses /* dev [16] in/out */,
+                          float alpha0, float beta0,
+                          uint8_t* win /* dev [16 * window] in/out */, uint32_t* win_head /* dev [16] in/out */,
+                          int32_t window, float kappa,
+                          float* p_hat /* dev [16] out */, float* conf /* dev [16] out */,
+                          float* p_blend /* dev [16] out */,
+                          uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
 /* ======================================================================== *
  * 3. EMA of the masses and eviction priority — section 3.4.
  *
@@ -212,6 +243,34 @@ int kvm_ema_update(const kvm_rows_t* rows, const float* mass /* dev [n_uids] */,
                    const float* row_weight /* dev [n_rows] */, const uint8_t* pair /* dev [n_uids], < 16 */,
                    const float* p_hat /* dev [16] */, uint8_t* state /* dev [n_uids] in/out */,
                    float* S /* dev [n_uids] in/out */, float* prio /* dev [n_uids] out */, void* stream);
+
+/* The same with the two refinements section 3.4 names without formulas (the
+ * importance "incorporates positional distance decay"; per-head multipliers
+ * are applied during a task transition, section 3.7 item 2):
+ *   the observation fed to the EMA is pos_decay^d * mass[uid], d = nb - 1 - b
+ *   blocks behind the row's last block (where the decode position lies);
+ *   prio = row_weight[r] * mult_r * S * p_hat[pair], mult_r =
+ *   head_mult[t * n_heads + row_head[r]] with t = seq_transition[row_seq[r]]
+ *   when t <= 3 (a transition of type t is in progress), else 1.
+ * head_mult NULL = no multipliers (row_seq, row_head, seq_transition unused).
+ * A row whose row_seq / row_head lies outside [0, n_seq) / [0, n_heads) keeps
+ * multiplier 1.  pos_decay = 1 and head_mult NULL give kvm_ema_update bit for bit.
+ * Errors: as kvm_ema_update; KVM_EINVAL for pos_decay outside (0, 1] or
+ * head_mult without the three index arrays.                                 */
+typedef struct {
+    float          pos_decay;       /* (0, 1]; 1 = no positional decay                   */
+    int32_t        n_seq;           /* entries of seq_transition                         */
+    int32_t        n_heads;         /* entries of one row of head_mult                   */
+    const int32_t* row_seq;         /* dev [n_rows] sequence of each row                 */
+    const int32_t* row_head;        /* dev [n_rows] head index, e.g. layer * H + head    */
+    const uint8_t* seq_transition;  /* dev [n_seq] 0..3 = transition type, > 3 = none    */
+    const float*   head_mult;       /* dev [4][n_heads], or NULL                         */
+} kvm_ema_ex_t;
+int kvm_ema_update_ex(const kvm_rows_t* rows, const float* mass /* dev [n_uids] */, float ema_decay,
+                      const kvm_ema_ex_t* ex /* host */,
+                      const float* row_weight /* dev [n_rows] */, const uint8_t* pair /* dev [n_uids], < 16 */,
+                      const float* p_hat /* dev [16] */, uint8_t* state /* dev [n_uids] in/out */,
+                      float* S /* dev [n_uids] in/out */, float* prio /* dev [n_uids] out */, void* stream);
 
 /* ======================================================================== *
  * 4. Victim selection — "lowest weighted aggregate importance", section 3.4,
@@ -293,6 +352,70 @@ int kvm_swap(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t
              const void* host_in /* pinned */, size_t host_in_bytes, uint32_t* n_bad /* dev [1] in/out, or NULL */,
              void* stream);
 
+/* kvm_exchange: the same trade against a host tier that is addressed by slot
+ * (record of host slot h at host_tier + h * (unit_k_bytes + unit_v_bytes)), as
+ * the table describes it: for i < n (and < *n_out_dev, < *n_in_dev when given)
+ * the unit out_uids[i], resident in frame f, and the unit in_uids[i], on the
+ * host in slot h = -1 - slot_tbl[in_uids[i]], change places in place: frame f
+ * receives the record of slot h, slot h the old contents of frame f;
+ * slot_tbl[out] = -1 - h, slot_tbl[in] = f, RESIDENT / ON_HOST flip on both.
+ * No spare frame or host slot is used, so a prefetch list produced on the
+ * device (kvm_prefetch_keys + kvm_select_victims) can be served without the
+ * host gathering records first.  A pair is skipped and counted in *n_bad when
+ * out is not resident, in is not on the host (or equals out), or a frame / slot
+ * id is out of range.  Units must not repeat within or across the lists.
+ * Errors: KVM_EINVAL, KVM_ESHAPE as kvm_pack.                               */
+int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+                 int64_t n_uids, const int64_t* out_uids /* dev [n] */, const int64_t* in_uids /* dev [n] */, int64_t n,
+                 const int64_t* n_out_dev /* dev [1] or NULL */, const int64_t* n_in_dev /* dev [1] or NULL */,
+                 void* host_tier /* pinned, tier_slots records */, uint64_t tier_slots,
+                 uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+/* ======================================================================== *
+ * 6. Position-aware prefetching — section 3.5.
+ *
+ * kvm_span_update: the prefetch window "adapts based on observed attention
+ * patterns", narrow for layers that attend locally, wide for layers that
+ * attend globally (no formula given).  Reading: the span of an active row is
+ * the smallest s >= 1 such that its last s blocks hold at least theta_num /
+ * theta_den of the row's total mass this step (blocks not in HBM count as
+ * distance and contribute nothing; rows with no mass are skipped);
+ * span_sum[layer] += s, span_cnt[layer] += 1 (both accumulate over calls; the
+ * caller resets or ages them); then for every layer with span_cnt > 0
+ *   layer_window[l] = clamp(16 * ceil(span_sum[l] / span_cnt[l]), w_min, w_max)
+ * in tokens; other layers keep their window.  Masses enter as fixed point,
+ * floor(min(m, 1) * 2^32) (0 for m <= 0 or NaN), sums and comparisons are exact
+ * integers: the result does not depend on summation order.
+ * Errors: KVM_EINVAL (null pointers, n_layers <= 0, theta outside [0, 1] or
+ * theta_den > 65536, w_min < 0, w_max < w_min).  Rows with row_layer outside
+ * [0, n_layers) are skipped.                                                */
+int kvm_span_update(const kvm_rows_t* rows, const int32_t* row_layer /* dev [n_rows] */, int32_t n_layers,
+                    const float* mass /* dev [n_uids] */, const uint8_t* state /* dev [n_uids] */,
+                    uint32_t theta_num, uint32_t theta_den,
+                    uint64_t* span_sum /* dev [n_layers] in/out */, uint32_t* span_cnt /* dev [n_layers] in/out */,
+                    int32_t w_min, int32_t w_max, int32_t* layer_window /* dev [n_layers] in/out */, void* stream);
+
+/* kvm_prefetch_keys: which host-resident units to promote ahead of use.  While
+ * a request decodes at position n the blocks within a window w of n are the
+ * likeliest to be needed next; the text gives the window once as [n - w, n] and
+ * once as [n, n + w]; positions after n hold no keys yet, so [n - w, n] is used.
+ * For row r, n = row_pos[r] (tokens; negative = the row asks for nothing),
+ * w = layer_window[row_layer[r]]: block b is a candidate iff state has ON_HOST
+ * and not RESIDENT and its tokens [16 b, 16 b + 15] meet [n - w, n].  Then
+ *   key[uid]  = 1 - p_est[pair[uid]] * pos_decay^(floor(n / 16) - b)   (lower = sooner)
+ *   cand[uid] = KVM_ST_RESIDENT | KVM_ST_SCORED
+ * and key = +inf, cand = 0 for every other block of the row.  cand has the
+ * form kvm_select_victims admits, so the prefetch list (uid ascending) is
+ *   kvm_select_victims(key, cand, n_uids, k, 0, list, ...)
+ * with k = the number of free frames, and kvm_unpack / kvm_swap move it.
+ * p_est: posterior means or the blended estimates of kvm_beta_blend_update.
+ * Errors: KVM_EINVAL (null pointers, n_layers <= 0, pos_decay outside (0, 1]). */
+int kvm_prefetch_keys(const kvm_rows_t* rows, const int32_t* row_layer /* dev [n_rows] */,
+                      const int32_t* row_pos /* dev [n_rows] */, const int32_t* layer_window /* dev [n_layers] */,
+                      int32_t n_layers, const uint8_t* state /* dev [n_uids] */, const uint8_t* pair /* dev [n_uids] */,
+                      const float* p_est /* dev [16] */, float pos_decay,
+                      float* key /* dev [n_uids] out */, uint8_t* cand /* dev [n_uids] out */, void* stream);
+
 /* ======================================================================== *
  * Helpers
  * ======================================================================== */
@@ -313,7 +436,8 @@ const char* kvm_version(void);
  * launch of the kernel called `name` since the last kvm_timing_reset, and
  * returns the launch count (0 if the name is unknown); *total_ms gets the sum.
  * Names: "score_partial", "score_finalize", "score_plan", "ema_prio",
- * "beta", "select_hist", "select_emit", "pack", "unpack", "swap".            */
+ * "beta", "select_hist", "select_emit", "pack", "unpack", "swap", "span",
+ * "prefetch_keys".                                                          */
 int  kvm_timing_enable(int on);
 void kvm_timing_reset(void);
 int  kvm_timing_read(const char* name, double* total_ms);

@@ -218,6 +218,18 @@ def unpack(k_pool, v_pool, unit_k_bytes, unit_v_bytes, slot_tbl, state, uids, ds
     _check(rc, "kvm_ref_unpack")
 
 
+def exchange(k_pool, v_pool, unit_k_bytes, unit_v_bytes, slot_tbl, state, out_uids, in_uids, tier, n_bad=None):
+    """tier: uint8 [tier_slots, rec], modified in place like the pools and tables."""
+    n_slots = k_pool.size // unit_k_bytes
+    rc = lib().kvm_ref_exchange(
+        _p(k_pool.reshape(-1), np.uint8), _p(None if v_pool is None else v_pool.reshape(-1), np.uint8),
+        C.c_uint64(n_slots), C.c_uint32(unit_k_bytes), C.c_uint32(unit_v_bytes),
+        _p(slot_tbl, np.int32), _p(state, np.uint8), C.c_int64(len(state)),
+        _p(out_uids, np.int64), _p(in_uids, np.int64), C.c_int64(len(out_uids)),
+        _p(tier.reshape(-1), np.uint8), C.c_uint64(tier.shape[0]), _p(n_bad, np.uint32))
+    _check(rc, "kvm_ref_exchange")
+
+
 def decode(bits: int, dtype: int) -> float:
     f = lib().kvm_ref_decode
     f.restype = C.c_double

@@ -32,6 +32,7 @@
  *   kvm_ref_prefetch_keys   section 3.5: candidates inside the positional window around the
  *                           decode position, ranked with the reuse estimate of section 3.3
  *   kvm_ref_pack / unpack   section 3.2 (tier 0 <-> tier 1 moves), as memcpy
+ *   kvm_ref_exchange        the same as an in-place trade with a slot-addressed host tier
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (paper tables, closed forms, library routines, brute force); none is
@@ -437,8 +438,10 @@ int kvm_ref_select_victims(const float* prio, const uint8_t* state, int64_t n_ui
  * theta = theta_num / theta_den of the row's total mass this step; a layer's window is
  * block_tokens * ceil(mean span of its rows), clamped to [w_min, w_max] tokens.
  * So that the integer decision is the same on every implementation, masses enter as
- * fixed point: Q(m) = floor(m * 2^32) for m in (0, 256], 0 for anything else (NaN
- * included), clamped at 256; all sums are exact 64-bit integers.
+ * fixed point: Q(m) = floor(m * 2^32) for m in (0, 1], 0 for anything else (NaN
+ * included), clamped at 1 (a unit's mass is a softmax share, so it cannot exceed 1; the
+ * clamp keeps the 64-bit sums exact for any row length); the comparison with theta is
+ * made on exact 128-bit products.
  * span_sum / span_cnt accumulate over calls (the caller resets or ages them);
  * layer_window[l] is rewritten for layers with span_cnt > 0 and left alone otherwise. */
 int kvm_ref_span_update(int n_rows, int block_tokens, int64_t n_uids,
@@ -462,7 +465,7 @@ int kvm_ref_span_update(int n_rows, int block_tokens, int64_t n_uids,
             const int64_t uid = row_off[r] + b;
             const float m = mass[uid];
             uint64_t qv = 0;
-            if ((state[uid] & ST_RESIDENT) && m > 0.0f) qv = (uint64_t)((double)(m < 256.0f ? m : 256.0f) * 4294967296.0);
+            if ((state[uid] & ST_RESIDENT) && m > 0.0f) qv = (uint64_t)((double)(m < 1.0f ? m : 1.0f) * 4294967296.0);
             total += qv;
         }
         if (total == 0) continue;
@@ -471,8 +474,8 @@ int kvm_ref_span_update(int n_rows, int block_tokens, int64_t n_uids,
         for (int s = 1; s <= nb; ++s) {
             const int64_t uid = row_off[r] + (nb - s);
             const float m = mass[uid];
-            if ((state[uid] & ST_RESIDENT) && m > 0.0f) acc += (uint64_t)((double)(m < 256.0f ? m : 256.0f) * 4294967296.0);
-            if (acc * (uint64_t)theta_den >= (uint64_t)theta_num * total) { span = s; break; }
+            if ((state[uid] & ST_RESIDENT) && m > 0.0f) acc += (uint64_t)((double)(m < 1.0f ? m : 1.0f) * 4294967296.0);
+            if ((unsigned __int128)acc * theta_den >= (unsigned __int128)theta_num * total) { span = s; break; }
         }
         span_sum[row_layer[r]] += (uint64_t)span;
         span_cnt[row_layer[r]] += 1;
@@ -585,6 +588,43 @@ int kvm_ref_unpack(uint8_t* k_pool, uint8_t* v_pool, uint64_t n_slots,
         slot_tbl[uid] = slot;
         state[uid] = (uint8_t)((state[uid] & ~ST_ON_HOST) | ST_RESIDENT);
     }
+    return REF_OK;
+}
+
+/* The trade of section 3.2 (demote one unit, promote another) against a host tier that is
+ * addressed by slot: the frame of out_uids[i] and the tier record of in_uids[i] swap
+ * contents, the table entries and state bits follow.  Written with a temporary copy. */
+int kvm_ref_exchange(uint8_t* k_pool, uint8_t* v_pool, uint64_t n_slots,
+                     uint32_t unit_k_bytes, uint32_t unit_v_bytes,
+                     int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                     const int64_t* out_uids, const int64_t* in_uids, int64_t n,
+                     uint8_t* tier, uint64_t tier_slots, uint32_t* n_bad) {
+    if (!k_pool || (unit_v_bytes && !v_pool) || !slot_tbl || !state || n < 0) return REF_EINVAL;
+    if (n > 0 && (!out_uids || !in_uids || !tier)) return REF_EINVAL;
+    const size_t rec = (size_t)unit_k_bytes + unit_v_bytes;
+    uint8_t* tmp = (uint8_t*)malloc(rec ? rec : 1);
+    if (!tmp) return REF_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t uo = out_uids[i], ui = in_uids[i];
+        int ok = uo >= 0 && uo < n_uids && ui >= 0 && ui < n_uids && uo != ui;
+        ok = ok && (state[uo] & ST_RESIDENT) && slot_tbl[uo] >= 0 && (uint64_t)slot_tbl[uo] < n_slots;
+        ok = ok && (state[ui] & ST_ON_HOST) && !(state[ui] & ST_RESIDENT) && slot_tbl[ui] < 0 &&
+             (uint64_t)(-1 - (int64_t)slot_tbl[ui]) < tier_slots;
+        if (!ok) { if (n_bad) ++*n_bad; continue; }
+        const int32_t frame = slot_tbl[uo];
+        const int64_t host = -1 - (int64_t)slot_tbl[ui];
+        uint8_t* r = tier + (size_t)host * rec;
+        memcpy(tmp, r, rec);                                               /* record coming in  */
+        memcpy(r, k_pool + (size_t)frame * unit_k_bytes, unit_k_bytes);    /* frame going out   */
+        if (unit_v_bytes) memcpy(r + unit_k_bytes, v_pool + (size_t)frame * unit_v_bytes, unit_v_bytes);
+        memcpy(k_pool + (size_t)frame * unit_k_bytes, tmp, unit_k_bytes);
+        if (unit_v_bytes) memcpy(v_pool + (size_t)frame * unit_v_bytes, tmp + unit_k_bytes, unit_v_bytes);
+        slot_tbl[uo] = (int32_t)(-1 - host);
+        state[uo] = (uint8_t)((state[uo] & ~ST_RESIDENT) | ST_ON_HOST);
+        slot_tbl[ui] = frame;
+        state[ui] = (uint8_t)((state[ui] & ~ST_ON_HOST) | ST_RESIDENT);
+    }
+    free(tmp);
     return REF_OK;
 }
 

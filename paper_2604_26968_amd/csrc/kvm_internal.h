@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -51,6 +52,18 @@ inline int launch_status(const char* what) {
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- device arithmetic -----------------------------------------------------
+// decay^d for an integer distance d >= 0, given lg = log2(decay) <= 0 in double.  The
+// exponent d * lg is formed in double and split into its nearest integer and a fraction in
+// [-0.5, 0.5]: the fraction goes through the fp32 exp2, the integer part is applied as an
+// exact scaling, so the relative error stays at the level of one fp32 exp2 (~1e-7) however
+// large d is.  Underflows to 0 (through denormals) like the exact value.
+__device__ inline float pow_by_distance(double lg, int64_t d) {
+    const double e = fmax((double)d * lg, -320.0);
+    const double ei = rint(e);
+    return ldexpf(exp2f((float)(e - ei)), (int)ei);
+}
 
 // ---- shapes ----------------------------------------------------------------
 constexpr int kWave = 64;

@@ -152,6 +152,67 @@ __global__ __launch_bounds__(kThreads) void swap_kernel(uint4* __restrict__ k_po
     }
 }
 
+// In-place exchange with a host tier addressed by slot: the frame of out_uids[i] and the tier
+// record of in_uids[i] trade contents.  Every thread swaps its own 16-byte pieces (load both,
+// store both), so no piece is overwritten before it has been read and neither a spare frame nor
+// a spare tier slot is needed.
+__global__ __launch_bounds__(kThreads) void exchange_kernel(uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
+                                                            uint32_t n_slots, uint32_t k_v4, uint32_t v_v4,
+                                                            int32_t* __restrict__ slot_tbl,
+                                                            uint8_t* __restrict__ state, int64_t n_uids,
+                                                            const int64_t* __restrict__ out_uids,
+                                                            const int64_t* __restrict__ in_uids, int64_t first,
+                                                            const int64_t* __restrict__ n_out_dev,
+                                                            const int64_t* __restrict__ n_in_dev,
+                                                            uint4* __restrict__ tier, uint64_t tier_slots,
+                                                            uint32_t* n_bad) {
+    __shared__ int32_t s_slot;
+    __shared__ int64_t s_host;
+    const int64_t i = first + blockIdx.x;
+    if ((n_out_dev && i >= *n_out_dev) || (n_in_dev && i >= *n_in_dev)) return;
+    if (threadIdx.x == 0) {
+        const int64_t uo = out_uids[i], ui = in_uids[i];
+        int32_t slot = -1;
+        int64_t host = -1;
+        if (uo >= 0 && uo < n_uids && (state[uo] & KVM_ST_RESIDENT)) slot = slot_tbl[uo];
+        if ((uint32_t)slot >= n_slots) slot = -1;
+        if (ui >= 0 && ui < n_uids && ui != uo && (state[ui] & KVM_ST_ON_HOST) && !(state[ui] & KVM_ST_RESIDENT) &&
+            slot_tbl[ui] < 0)
+            host = -1 - (int64_t)slot_tbl[ui];
+        if ((uint64_t)host >= tier_slots) host = -1;
+        if (slot >= 0 && host >= 0) {
+            slot_tbl[uo] = (int32_t)(-1 - host);
+            state[uo] = (uint8_t)((state[uo] & ~KVM_ST_RESIDENT) | KVM_ST_ON_HOST);
+            slot_tbl[ui] = slot;
+            state[ui] = (uint8_t)((state[ui] & ~KVM_ST_ON_HOST) | KVM_ST_RESIDENT);
+        } else {
+            slot = -1;
+            if (n_bad) atomicAdd(n_bad, 1u);
+        }
+        s_slot = slot;
+        s_host = host;
+    }
+    __syncthreads();
+    const int32_t slot = s_slot;
+    if (slot < 0) return;
+    const size_t rec_v4 = (size_t)k_v4 + v_v4;
+    uint4* rec = tier + (size_t)s_host * rec_v4;
+    uint4* kf = k_pool + (size_t)slot * k_v4;
+    for (uint32_t v = threadIdx.x; v < k_v4; v += kThreads) {
+        const uint4 a = kf[v], b = rec[v];
+        kf[v] = b;
+        rec[v] = a;
+    }
+    if (v_v4) {
+        uint4* vf = v_pool + (size_t)slot * v_v4;
+        for (uint32_t v = threadIdx.x; v < v_v4; v += kThreads) {
+            const uint4 a = vf[v], b = rec[k_v4 + v];
+            vf[v] = b;
+            rec[k_v4 + v] = a;
+        }
+    }
+}
+
 int check_common(const char* who, const kvm_pool_t* pool, const void* slot_tbl, const void* state, int64_t n_uids,
                  const void* uids, int64_t n, const void* slots, const void* staging_dev, size_t staging_dev_bytes,
                  const void* staging_host, size_t staging_host_bytes) {
@@ -288,4 +349,34 @@ extern "C" int kvm_swap(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* stat
             reinterpret_cast<const uint4*>(static_cast<const char*>(host_in) + first * rec), n_bad);
     }
     return launch_status("swap");
+}
+
+extern "C" int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                            const int64_t* out_uids, const int64_t* in_uids, int64_t n, const int64_t* n_out_dev,
+                            const int64_t* n_in_dev, void* host_tier, uint64_t tier_slots, uint32_t* n_bad,
+                            void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(pool, KVM_EINVAL, "kvm_exchange: null pool");
+    KVM_REQUIRE(n >= 0 && n_uids >= 0, KVM_EINVAL, "kvm_exchange: negative count");
+    KVM_REQUIRE(pool->unit_k_bytes > 0 && pool->unit_k_bytes % 16 == 0 && pool->unit_v_bytes % 16 == 0, KVM_ESHAPE,
+                "kvm_exchange: unit sizes (%u, %u) must be multiples of 16", pool->unit_k_bytes, pool->unit_v_bytes);
+    KVM_REQUIRE(pool->n_slots <= 0x7fffffffull && tier_slots <= 0x7fffffffull, KVM_EINVAL,
+                "kvm_exchange: slot counts exceed int32 ids");
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(pool->k_pool && (pool->v_pool || pool->unit_v_bytes == 0), KVM_EINVAL, "kvm_exchange: null pool memory");
+    KVM_REQUIRE(slot_tbl && state && out_uids && in_uids && host_tier, KVM_EINVAL, "kvm_exchange: null buffer");
+    KVM_REQUIRE(reinterpret_cast<uintptr_t>(host_tier) % 16 == 0, KVM_EINVAL,
+                "kvm_exchange: host tier must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t k_v4 = pool->unit_k_bytes / 16, v_v4 = pool->unit_v_bytes / 16;
+    TimedLaunch tl("swap", st);
+    for (int64_t first = 0; first < n; first += 0x40000000ll) {
+        const int64_t cnt = n - first < 0x40000000ll ? n - first : 0x40000000ll;
+        exchange_kernel<<<(unsigned)cnt, kThreads, 0, st>>>(
+            static_cast<uint4*>(pool->k_pool), static_cast<uint4*>(pool->v_pool), (uint32_t)pool->n_slots, k_v4, v_v4,
+            slot_tbl, state, n_uids, out_uids, in_uids, first, n_out_dev, n_in_dev, static_cast<uint4*>(host_tier),
+            tier_slots, n_bad);
+    }
+    return launch_status("exchange");
 }

@@ -1,0 +1,215 @@
+// kvm_span_update and kvm_prefetch_keys: position-aware prefetching (section 3.5).
+//
+// span  : per row, the smallest number of trailing blocks that hold a fraction theta of the
+//         row's mass; per layer, the prefetch window = 16 * ceil(mean span).  Exact integer
+//         arithmetic on fixed-point masses, so the result does not depend on summation order.
+// keys  : per unit, whether it is a prefetch candidate (on the host, inside the window around
+//         the decode position) and its rank key 1 - reuse estimate x decay^distance.  The list
+//         itself is kvm_select_victims(key, cand, k): the k lowest keys.
+#include "kvm_internal.h"
+
+namespace kvm {
+namespace {
+
+// floor(m * 2^32) for m in (0, 1], 0 for anything else (NaN included), clamped at 1 (a mass
+// is a softmax share); a row's total then fits 64 bits for any row length.
+__device__ inline uint64_t fixed_mass(float m, uint8_t st) {
+    if (!(st & KVM_ST_RESIDENT) || !(m > 0.0f)) return 0;
+    return (uint64_t)(fminf(m, 1.0f) * 4294967296.0f);
+}
+
+__device__ inline uint64_t shfl_u64(uint64_t v, int src) {
+    const uint32_t lo = __shfl((uint32_t)v, src), hi = __shfl((uint32_t)(v >> 32), src);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ inline uint64_t shfl_up_u64(uint64_t v, int delta) {
+    const uint32_t lo = __shfl_up((uint32_t)v, delta), hi = __shfl_up((uint32_t)(v >> 32), delta);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ inline uint64_t shfl_xor_u64(uint64_t v, int mask) {
+    const uint32_t lo = __shfl_xor((uint32_t)v, mask), hi = __shfl_xor((uint32_t)(v >> 32), mask);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// One wavefront per row.  Pass 1: the row's total.  Pass 2: walk back from the last block in
+// chunks of 64 blocks, inclusive prefix sums inside the chunk, first lane whose running sum
+// reaches theta * total gives the span.
+__global__ __launch_bounds__(256) void span_rows_kernel(int n_rows, int64_t n_uids, int n_layers,
+                                                        const int32_t* __restrict__ row_ntok,
+                                                        const int64_t* __restrict__ row_off,
+                                                        const uint8_t* __restrict__ row_active,
+                                                        const int32_t* __restrict__ row_layer,
+                                                        const float* __restrict__ mass,
+                                                        const uint8_t* __restrict__ state, uint32_t theta_num,
+                                                        uint32_t theta_den, unsigned long long* span_sum,
+                                                        uint32_t* span_cnt) {
+    const int row = blockIdx.x * 4 + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (row >= n_rows) return;
+    const int n = row_ntok[row];
+    if (n <= 0) return;
+    const int64_t nb = ((int64_t)n + 15) >> 4;
+    const int64_t off = row_off[row];
+    if (off < 0 || off + nb > n_uids) return;
+    if (row_active && !row_active[row]) return;
+    const int layer = row_layer[row];
+    if (layer < 0 || layer >= n_layers) return;
+
+    uint64_t total = 0;
+    for (int64_t b = lane; b < nb; b += kWave) total += fixed_mass(mass[off + b], state[off + b]);
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) total += shfl_xor_u64(total, m);
+    if (total == 0) return;
+    const unsigned __int128 need = (unsigned __int128)theta_num * total;
+
+    uint64_t before = 0;   // sum over earlier chunks
+    int64_t span = nb;
+    for (int64_t base = 0; base < nb; base += kWave) {
+        const int64_t s1 = base + lane;                  // this lane looks at distance s1 (span s1 + 1)
+        uint64_t v = 0;
+        if (s1 < nb) {
+            const int64_t uid = off + (nb - 1 - s1);
+            v = fixed_mass(mass[uid], state[uid]);
+        }
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const uint64_t up = shfl_up_u64(v, d);
+            if (lane >= d) v += up;
+        }
+        const uint64_t acc = before + v;
+        const uint64_t hit = __ballot(s1 < nb && (unsigned __int128)acc * theta_den >= need);
+        if (hit) {
+            span = base + __ffsll((unsigned long long)hit);   // first lane + 1
+            break;
+        }
+        before += shfl_u64(v, kWave - 1);
+    }
+    if (lane == 0) {
+        atomicAdd(&span_sum[layer], (unsigned long long)span);
+        atomicAdd(&span_cnt[layer], 1u);
+    }
+}
+
+__global__ void span_window_kernel(int n_layers, const unsigned long long* span_sum, const uint32_t* span_cnt,
+                                   int32_t w_min, int32_t w_max, int32_t* layer_window) {
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= n_layers || span_cnt[l] == 0) return;
+    const unsigned long long mean_up = (span_sum[l] + span_cnt[l] - 1) / span_cnt[l];
+    unsigned long long w = mean_up * 16ull;
+    if (w < (unsigned long long)w_min) w = (unsigned long long)w_min;
+    if (w > (unsigned long long)w_max) w = (unsigned long long)w_max;
+    layer_window[l] = (int32_t)w;
+}
+
+// LANES threads per row, striding over its blocks.
+template <int LANES>
+__global__ __launch_bounds__(256) void prefetch_keys_kernel(int n_rows, int64_t n_uids, int n_layers,
+                                                            const int32_t* __restrict__ row_ntok,
+                                                            const int64_t* __restrict__ row_off,
+                                                            const int32_t* __restrict__ row_layer,
+                                                            const int32_t* __restrict__ row_pos,
+                                                            const int32_t* __restrict__ layer_window,
+                                                            const uint8_t* __restrict__ state,
+                                                            const uint8_t* __restrict__ pair,
+                                                            const float* __restrict__ p_est, double lg_pos_decay,
+                                                            float* __restrict__ key, uint8_t* __restrict__ cand) {
+    __shared__ float pe[KVM_N_PAIRS];
+    if (threadIdx.x < KVM_N_PAIRS) pe[threadIdx.x] = p_est[threadIdx.x];
+    __syncthreads();
+    constexpr int ROWS_PER_WG = 256 / LANES;
+    const int row = blockIdx.x * ROWS_PER_WG + threadIdx.x / LANES;
+    if (row >= n_rows) return;
+    const int nt = row_ntok[row];
+    if (nt <= 0) return;
+    const int64_t nb = ((int64_t)nt + 15) >> 4;
+    const int64_t off = row_off[row];
+    if (off < 0 || off + nb > n_uids) return;
+    const int layer = row_layer[row];
+    const bool layer_ok = layer >= 0 && layer < n_layers;
+    const int64_t n = row_pos[row];
+    const int64_t w = layer_ok ? layer_window[layer] : -1;
+    const bool row_asks = n >= 0 && w >= 0;
+    const int64_t nblk = n >> 4;
+    for (int64_t b = threadIdx.x % LANES; b < nb; b += LANES) {
+        const int64_t uid = off + b;
+        const uint8_t st = state[uid];
+        const int64_t first = b * 16, last = first + 15;
+        const bool on_host = (st & KVM_ST_ON_HOST) && !(st & KVM_ST_RESIDENT);
+        const bool ok = row_asks && on_host && last >= n - w && first <= n;
+        float k = INFINITY;
+        if (ok) k = 1.0f - pe[pair[uid] & 15] * pow_by_distance(lg_pos_decay, nblk - b);
+        key[uid] = k;
+        cand[uid] = ok ? (uint8_t)(KVM_ST_RESIDENT | KVM_ST_SCORED) : (uint8_t)0;
+    }
+}
+
+int check_rows(const char* who, const kvm_rows_t* rows, bool* nothing) {
+    *nothing = false;
+    KVM_REQUIRE(rows, KVM_EINVAL, "%s: null rows", who);
+    KVM_REQUIRE(rows->n_rows >= 0 && rows->n_uids >= 0, KVM_EINVAL, "%s: negative size", who);
+    if (rows->n_rows == 0 || rows->n_uids == 0) {
+        *nothing = true;
+        return KVM_OK;
+    }
+    KVM_REQUIRE(rows->row_ntok && rows->row_off, KVM_EINVAL, "%s: null row array", who);
+    return KVM_OK;
+}
+
+}  // namespace
+}  // namespace kvm
+
+extern "C" int kvm_span_update(const kvm_rows_t* rows, const int32_t* row_layer, int32_t n_layers, const float* mass,
+                               const uint8_t* state, uint32_t theta_num, uint32_t theta_den, uint64_t* span_sum,
+                               uint32_t* span_cnt, int32_t w_min, int32_t w_max, int32_t* layer_window,
+                               void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(n_layers > 0, KVM_EINVAL, "kvm_span_update: n_layers %d <= 0", n_layers);
+    KVM_REQUIRE(theta_den > 0 && theta_den <= 65536 && theta_num <= theta_den, KVM_EINVAL,
+                "kvm_span_update: theta %u / %u must lie in [0, 1] with a denominator of at most 65536", theta_num,
+                theta_den);
+    KVM_REQUIRE(w_min >= 0 && w_max >= w_min, KVM_EINVAL, "kvm_span_update: window bounds [%d, %d]", w_min, w_max);
+    KVM_REQUIRE(span_sum && span_cnt && layer_window, KVM_EINVAL, "kvm_span_update: null accumulator or output");
+    bool nothing;
+    if (int rc = check_rows("kvm_span_update", rows, &nothing)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("span", st);
+    if (!nothing) {
+        KVM_REQUIRE(row_layer && mass && state, KVM_EINVAL, "kvm_span_update: null buffer");
+        span_rows_kernel<<<(unsigned)((rows->n_rows + 3) / 4), 256, 0, st>>>(
+            rows->n_rows, rows->n_uids, n_layers, rows->row_ntok, rows->row_off, rows->row_active, row_layer, mass,
+            state, theta_num, theta_den, reinterpret_cast<unsigned long long*>(span_sum), span_cnt);
+    }
+    span_window_kernel<<<(unsigned)((n_layers + 255) / 256), 256, 0, st>>>(
+        n_layers, reinterpret_cast<const unsigned long long*>(span_sum), span_cnt, w_min, w_max, layer_window);
+    return launch_status("span");
+}
+
+extern "C" int kvm_prefetch_keys(const kvm_rows_t* rows, const int32_t* row_layer, const int32_t* row_pos,
+                                 const int32_t* layer_window, int32_t n_layers, const uint8_t* state,
+                                 const uint8_t* pair, const float* p_est, float pos_decay, float* key, uint8_t* cand,
+                                 void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(n_layers > 0, KVM_EINVAL, "kvm_prefetch_keys: n_layers %d <= 0", n_layers);
+    KVM_REQUIRE(pos_decay > 0.f && pos_decay <= 1.f, KVM_EINVAL,
+                "kvm_prefetch_keys: positional decay %g outside (0, 1]", (double)pos_decay);
+    bool nothing;
+    if (int rc = check_rows("kvm_prefetch_keys", rows, &nothing)) return rc;
+    if (nothing) return KVM_OK;
+    KVM_REQUIRE(row_layer && row_pos && layer_window && state && pair && p_est && key && cand, KVM_EINVAL,
+                "kvm_prefetch_keys: null buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("prefetch_keys", st);
+    const double lg = std::log2((double)pos_decay);
+    if (rows->n_uids / rows->n_rows >= 192) {
+        prefetch_keys_kernel<256><<<(unsigned)rows->n_rows, 256, 0, st>>>(
+            rows->n_rows, rows->n_uids, n_layers, rows->row_ntok, rows->row_off, row_layer, row_pos, layer_window,
+            state, pair, p_est, lg, key, cand);
+    } else {
+        prefetch_keys_kernel<64><<<(unsigned)((rows->n_rows + 3) / 4), 256, 0, st>>>(
+            rows->n_rows, rows->n_uids, n_layers, rows->row_ntok, rows->row_off, row_layer, row_pos, layer_window,
+            state, pair, p_est, lg, key, cand);
+    }
+    return launch_status("prefetch_keys");
+}

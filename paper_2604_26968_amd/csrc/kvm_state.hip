@@ -153,9 +153,20 @@ __global__ __launch_bounds__(256) void beta_blend_kernel(const uint32_t* __restr
 }
 
 // ---- ema + priority -------------------------------------------------------------
+// Optional refinements of section 3.4 (positional distance decay) and sections 3.4 / 3.7
+// (per-head multipliers during a task transition); all pointers device.
+struct EmaEx {
+    double lg_pos_decay;   // log2 of the positional decay
+    int n_seq, n_heads;
+    const int32_t* row_seq;
+    const int32_t* row_head;
+    const uint8_t* seq_transition;
+    const float* head_mult;
+};
+
 // LANES threads per row (64 = one wavefront per row, for fleets of short rows; 256 = one
 // workgroup per row, for long rows); they stride over the row's blocks.
-template <int LANES>
+template <int LANES, bool EX>
 __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uids, const int32_t* __restrict__ row_ntok,
                                                        const int64_t* __restrict__ row_off,
                                                        const uint8_t* __restrict__ row_active,
@@ -163,7 +174,7 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
                                                        const float* __restrict__ row_weight,
                                                        const uint8_t* __restrict__ pair,
                                                        const float* __restrict__ p_hat, uint8_t* __restrict__ state,
-                                                       float* __restrict__ S, float* __restrict__ prio) {
+                                                       float* __restrict__ S, float* __restrict__ prio, EmaEx ex) {
     __shared__ float ph[KVM_N_PAIRS];
     if (threadIdx.x < KVM_N_PAIRS) ph[threadIdx.x] = p_hat[threadIdx.x];
     __syncthreads();
@@ -176,14 +187,23 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
     const int64_t off = row_off[row];
     if (off < 0 || off + nb > n_uids) return;
     const bool active = row_active ? row_active[row] != 0 : true;
-    const float w = row_weight[row];
+    float w = row_weight[row];
+    if (EX && ex.head_mult) {
+        // Out-of-range indices cannot be reported from here: such a row keeps multiplier 1.
+        const int sq = ex.row_seq[row], hd = ex.row_head[row];
+        if (sq >= 0 && sq < ex.n_seq && hd >= 0 && hd < ex.n_heads) {
+            const uint32_t t = ex.seq_transition[sq];
+            if (t <= 3) w *= ex.head_mult[(size_t)t * ex.n_heads + hd];
+        }
+    }
     const float keep = decay, take = 1.0f - decay;
     for (int64_t b = threadIdx.x % LANES; b < nb; b += LANES) {
         const int64_t uid = off + b;
         uint8_t st = state[uid];
         float s = S[uid];
         if (active && (st & KVM_ST_RESIDENT)) {
-            const float x = mass[uid];
+            float x = mass[uid];
+            if (EX) x *= pow_by_distance(ex.lg_pos_decay, nb - 1 - b);
             if (!(st & KVM_ST_SCORED)) {
                 s = x;
                 st |= KVM_ST_SCORED;
@@ -195,6 +215,37 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
         }
         prio[uid] = (st & KVM_ST_SCORED) ? w * s * ph[pair[uid] & 15] : INFINITY;
     }
+}
+
+template <bool EX>
+void launch_ema(const kvm_rows_t* rows, const float* mass, float ema_decay, const float* row_weight,
+                const uint8_t* pair, const float* p_hat, uint8_t* state, float* S, float* prio, const EmaEx& ex,
+                hipStream_t st) {
+    if (rows->n_uids / rows->n_rows >= 192) {
+        ema_prio_kernel<256, EX><<<(unsigned)rows->n_rows, 256, 0, st>>>(
+            rows->n_rows, rows->n_uids, rows->row_ntok, rows->row_off, rows->row_active, mass, ema_decay, row_weight,
+            pair, p_hat, state, S, prio, ex);
+    } else {
+        ema_prio_kernel<64, EX><<<(unsigned)((rows->n_rows + 3) / 4), 256, 0, st>>>(
+            rows->n_rows, rows->n_uids, rows->row_ntok, rows->row_off, rows->row_active, mass, ema_decay, row_weight,
+            pair, p_hat, state, S, prio, ex);
+    }
+}
+
+int check_ema(const char* who, const kvm_rows_t* rows, const float* mass, float ema_decay, const float* row_weight,
+              const uint8_t* pair, const float* p_hat, uint8_t* state, float* S, float* prio, bool* nothing) {
+    *nothing = false;
+    KVM_REQUIRE(rows, KVM_EINVAL, "%s: null rows", who);
+    KVM_REQUIRE(rows->n_rows >= 0 && rows->n_uids >= 0, KVM_EINVAL, "%s: negative size", who);
+    KVM_REQUIRE(ema_decay >= 0.f && ema_decay <= 1.f, KVM_EINVAL, "%s: decay %g outside [0, 1]", who,
+                (double)ema_decay);
+    if (rows->n_rows == 0 || rows->n_uids == 0) {
+        *nothing = true;
+        return KVM_OK;
+    }
+    KVM_REQUIRE(rows->row_ntok && rows->row_off, KVM_EINVAL, "%s: null row array", who);
+    KVM_REQUIRE(mass && row_weight && pair && p_hat && state && S && prio, KVM_EINVAL, "%s: null buffer", who);
+    return KVM_OK;
 }
 
 }  // namespace
@@ -254,24 +305,36 @@ extern "C" int kvm_ema_update(const kvm_rows_t* rows, const float* mass, float e
                               void* stream) {
     using namespace kvm;
     clear_error();
-    KVM_REQUIRE(rows, KVM_EINVAL, "kvm_ema_update: null rows");
-    KVM_REQUIRE(rows->n_rows >= 0 && rows->n_uids >= 0, KVM_EINVAL, "kvm_ema_update: negative size");
-    KVM_REQUIRE(ema_decay >= 0.f && ema_decay <= 1.f, KVM_EINVAL, "kvm_ema_update: decay %g outside [0, 1]",
-                (double)ema_decay);
-    if (rows->n_rows == 0 || rows->n_uids == 0) return KVM_OK;
-    KVM_REQUIRE(rows->row_ntok && rows->row_off, KVM_EINVAL, "kvm_ema_update: null row array");
-    KVM_REQUIRE(mass && row_weight && pair && p_hat && state && S && prio, KVM_EINVAL,
-                "kvm_ema_update: null buffer");
+    bool nothing;
+    if (int rc = check_ema("kvm_ema_update", rows, mass, ema_decay, row_weight, pair, p_hat, state, S, prio, &nothing))
+        return rc;
+    if (nothing) return KVM_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     TimedLaunch tl("ema_prio", st);
-    if (rows->n_uids / rows->n_rows >= 192) {
-        ema_prio_kernel<256><<<(unsigned)rows->n_rows, 256, 0, st>>>(rows->n_rows, rows->n_uids, rows->row_ntok,
-                                                                    rows->row_off, rows->row_active, mass, ema_decay,
-                                                                    row_weight, pair, p_hat, state, S, prio);
-    } else {
-        ema_prio_kernel<64><<<(unsigned)((rows->n_rows + 3) / 4), 256, 0, st>>>(
-            rows->n_rows, rows->n_uids, rows->row_ntok, rows->row_off, rows->row_active, mass, ema_decay, row_weight,
-            pair, p_hat, state, S, prio);
-    }
+    launch_ema<false>(rows, mass, ema_decay, row_weight, pair, p_hat, state, S, prio, EmaEx{}, st);
     return launch_status("ema_prio");
+}
+
+extern "C" int kvm_ema_update_ex(const kvm_rows_t* rows, const float* mass, float ema_decay, const kvm_ema_ex_t* ex,
+                                 const float* row_weight, const uint8_t* pair, const float* p_hat, uint8_t* state,
+                                 float* S, float* prio, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(ex, KVM_EINVAL, "kvm_ema_update_ex: null options");
+    KVM_REQUIRE(ex->pos_decay > 0.f && ex->pos_decay <= 1.f, KVM_EINVAL,
+                "kvm_ema_update_ex: positional decay %g outside (0, 1]", (double)ex->pos_decay);
+    KVM_REQUIRE(!ex->head_mult ||
+                    (ex->row_seq && ex->row_head && ex->seq_transition && ex->n_seq > 0 && ex->n_heads > 0),
+                KVM_EINVAL, "kvm_ema_update_ex: head multipliers given without row_seq / row_head / seq_transition");
+    bool nothing;
+    if (int rc = check_ema("kvm_ema_update_ex", rows, mass, ema_decay, row_weight, pair, p_hat, state, S, prio,
+                           &nothing))
+        return rc;
+    if (nothing) return KVM_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("ema_prio", st);
+    EmaEx e{std::log2((double)ex->pos_decay), ex->n_seq, ex->n_heads, ex->row_seq, ex->row_head, ex->seq_transition,
+            ex->head_mult};
+    launch_ema<true>(rows, mass, ema_decay, row_weight, pair, p_hat, state, S, prio, e, st);
+    return launch_status("ema_prio_ex");
 }

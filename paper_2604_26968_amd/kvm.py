@@ -23,8 +23,9 @@ ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
 AGG_MAX, AGG_MEAN = 0, 1
 OP_SCORE, OP_SELECT = 0, 1
 
-EXPORTS = ["kvm_size", "kvm_score_step", "kvm_beta_update", "kvm_ema_update", "kvm_select_victims",
-           "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
+EXPORTS = ["kvm_size", "kvm_score_step", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
+           "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
+           "kvm_prefetch_keys", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
            "kvm_timing_enable", "kvm_timing_reset", "kvm_timing_read"]
 
 
@@ -60,6 +61,12 @@ class Rows(C.Structure):
                 ("row_active", C.c_void_p), ("slot_tbl", C.c_void_p)]
 
 
+class EmaEx(C.Structure):
+    _fields_ = [("pos_decay", C.c_float), ("n_seq", C.c_int32), ("n_heads", C.c_int32),
+                ("row_seq", C.c_void_p), ("row_head", C.c_void_p), ("seq_transition", C.c_void_p),
+                ("head_mult", C.c_void_p)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run __graft_entry__.build() (hipcc) first")
@@ -86,6 +93,17 @@ def _load() -> C.CDLL:
     lib.kvm_swap.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                              C.c_void_p, C.c_void_p]
+    lib.kvm_beta_blend_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_float,
+                                          C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvm_ema_update_ex.argtypes = [C.POINTER(Rows), C.c_void_p, C.c_float, C.POINTER(EmaEx), C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvm_span_update.argtypes = [C.POINTER(Rows), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                    C.c_uint32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.kvm_prefetch_keys.argtypes = [C.POINTER(Rows), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvm_exchange.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
     return lib
 
@@ -164,6 +182,52 @@ def kvm_beta_update(ev_pair, ev_outcome, hits, misses, p_hat, alpha0: float = 1.
                                _ptr(p_hat, torch.float32), _ptr(n_bad, torch.int32), _stream(stream)))
 
 
+def kvm_beta_blend_update(ev_pair, ev_outcome, hits, misses, win, win_head, kappa: float, p_hat, conf, p_blend,
+                          alpha0: float = 1.0, beta0: float = 1.0, n_bad=None, stream=None):
+    """win: uint8 device tensor [16, window], filled with 255 before first use; win_head: int32 [16]."""
+    n = 0 if ev_pair is None else ev_pair.numel()
+    _check(lib.kvm_beta_blend_update(_ptr(ev_pair, torch.uint8), _ptr(ev_outcome, torch.uint8), n,
+                                     _ptr(hits, torch.int32), _ptr(misses, torch.int32), alpha0, beta0,
+                                     _ptr(win, torch.uint8), _ptr(win_head, torch.int32), win.shape[1], kappa,
+                                     _ptr(p_hat, torch.float32), _ptr(conf, torch.float32),
+                                     _ptr(p_blend, torch.float32), _ptr(n_bad, torch.int32), _stream(stream)))
+
+
+def make_ema_ex(pos_decay: float = 1.0, row_seq=None, row_head=None, seq_transition=None, head_mult=None) -> EmaEx:
+    """head_mult: float32 device tensor [4, n_heads] or None."""
+    e = EmaEx(pos_decay, 0 if seq_transition is None else seq_transition.numel(),
+              0 if head_mult is None else head_mult.shape[1],
+              _ptr(row_seq, torch.int32), _ptr(row_head, torch.int32), _ptr(seq_transition, torch.uint8),
+              _ptr(head_mult, torch.float32))
+    e._keep = (row_seq, row_head, seq_transition, head_mult)
+    return e
+
+
+def kvm_ema_update_ex(rows: Rows, mass, ema_decay: float, ex: EmaEx, row_weight, pair, p_hat, state, S, prio,
+                      stream=None):
+    _check(lib.kvm_ema_update_ex(C.byref(rows), _ptr(mass, torch.float32), ema_decay, C.byref(ex),
+                                 _ptr(row_weight, torch.float32), _ptr(pair, torch.uint8),
+                                 _ptr(p_hat, torch.float32), _ptr(state, torch.uint8),
+                                 _ptr(S, torch.float32), _ptr(prio, torch.float32), _stream(stream)))
+
+
+def kvm_span_update(rows: Rows, row_layer, mass, state, theta_num: int, theta_den: int, span_sum, span_cnt,
+                    w_min: int, w_max: int, layer_window, stream=None):
+    """span_sum: int64 [n_layers] (read as unsigned), span_cnt / layer_window: int32 [n_layers]."""
+    _check(lib.kvm_span_update(C.byref(rows), _ptr(row_layer, torch.int32), layer_window.numel(),
+                               _ptr(mass, torch.float32), _ptr(state, torch.uint8), theta_num, theta_den,
+                               _ptr(span_sum, torch.int64), _ptr(span_cnt, torch.int32), w_min, w_max,
+                               _ptr(layer_window, torch.int32), _stream(stream)))
+
+
+def kvm_prefetch_keys(rows: Rows, row_layer, row_pos, layer_window, state, pair, p_est, pos_decay: float, key, cand,
+                      stream=None):
+    _check(lib.kvm_prefetch_keys(C.byref(rows), _ptr(row_layer, torch.int32), _ptr(row_pos, torch.int32),
+                                 _ptr(layer_window, torch.int32), layer_window.numel(), _ptr(state, torch.uint8),
+                                 _ptr(pair, torch.uint8), _ptr(p_est, torch.float32), pos_decay,
+                                 _ptr(key, torch.float32), _ptr(cand, torch.uint8), _stream(stream)))
+
+
 def kvm_ema_update(rows: Rows, mass, ema_decay: float, row_weight, pair, p_hat, state, S, prio, stream=None):
     _check(lib.kvm_ema_update(C.byref(rows), _ptr(mass, torch.float32), ema_decay,
                               _ptr(row_weight, torch.float32), _ptr(pair, torch.uint8),
@@ -207,6 +271,16 @@ def kvm_swap(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, host_slots,
                         _ptr(host_slots, torch.int32), _ptr(freed_slots, torch.int32),
                         _ptr(host_out, None, "cpu"), _nbytes(host_out), _ptr(host_in, None, "cpu"), _nbytes(host_in),
                         _ptr(n_bad, torch.int32), _stream(stream)))
+
+
+def kvm_exchange(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, host_tier, n_out_dev=None, n_in_dev=None,
+                 n_bad=None, stream=None):
+    """host_tier: pinned uint8 tensor holding whole records, record of host slot h at h * record bytes."""
+    rec = pool.unit_k_bytes + pool.unit_v_bytes
+    _check(lib.kvm_exchange(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                            _ptr(out_uids, torch.int64), _ptr(in_uids, torch.int64), n, _ptr(n_out_dev, torch.int64),
+                            _ptr(n_in_dev, torch.int64), _ptr(host_tier, None, "cpu"), _nbytes(host_tier) // rec,
+                            _ptr(n_bad, torch.int32), _stream(stream)))
 
 
 def kvm_last_error() -> str:

@@ -170,6 +170,16 @@ def make_case(shape: Shape, seed: int, spare_slots: int = 0, uid_gap: int = 0,
                 state, pair, row_weight, n_uids)
 
 
+def row_head_index(case: Case) -> np.ndarray:
+    """layer * n_kv_heads + head of every row (rows are ordered sequence, layer, head)."""
+    lh = case.shape.n_layers * case.shape.n_kv_heads
+    return (np.arange(case.n_rows) % lh).astype(np.int32)
+
+
+def row_layer_index(case: Case) -> np.ndarray:
+    return (row_head_index(case) // case.shape.n_kv_heads).astype(np.int32)
+
+
 def make_queries(case: Case, seed: int, scale: float = 1.0) -> np.ndarray:
     """Fresh N(0, scale^2) queries for every row: uint16 [n_rows * g * dim]."""
     rng = np.random.default_rng(seed)

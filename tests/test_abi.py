@@ -33,6 +33,7 @@ def test_struct_layouts_match_header(kvm):
     assert C.sizeof(kvm.Sizing) == 64
     assert C.sizeof(kvm.Pool) == 40
     assert C.sizeof(kvm.Rows) == 64
+    assert C.sizeof(kvm.EmaEx) == 48
 
 
 @pytest.mark.parametrize("name", list(G["table3"]))
@@ -92,6 +93,34 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_beta_update(None, None, 0, None, None, 1.0, 1.0, None, None, None) == kvm.EINVAL
     assert lib.kvm_ema_update(None, None, 0.9, None, None, None, None, None, None, None) == kvm.EINVAL
     assert lib.kvm_ema_update(C.byref(rows), None, 1.5, None, None, None, None, None, None, None) == kvm.EINVAL
+    ex = kvm.EmaEx(0.0, 0, 0, None, None, None, None)
+    assert lib.kvm_ema_update_ex(C.byref(rows), None, 0.9, None, None, None, None, None, None, None, None) == kvm.EINVAL
+    assert lib.kvm_ema_update_ex(C.byref(rows), None, 0.9, C.byref(ex), None, None, None, None, None, None, None) \
+        == kvm.EINVAL
+    assert "positional decay" in kvm.kvm_last_error()
+    ex = kvm.EmaEx(0.5, 0, 0, None, None, None, 1)          # multipliers without the index arrays
+    assert lib.kvm_ema_update_ex(C.byref(rows), None, 0.9, C.byref(ex), None, None, None, None, None, None, None) \
+        == kvm.EINVAL
+    blend = lambda n, window, kappa, ptr: lib.kvm_beta_blend_update(
+        None, None, n, ptr, ptr, 1.0, 1.0, ptr, ptr, window, kappa, ptr, ptr, ptr, None, None)
+    assert blend(0, 8, 1.0, None) == kvm.EINVAL             # null counters
+    assert blend(0, 0, 1.0, 1) == kvm.EINVAL and "window" in kvm.kvm_last_error()
+    assert blend(0, 1 << 20, 1.0, 1) == kvm.EINVAL
+    assert blend(0, 8, -1.0, 1) == kvm.EINVAL and "kappa" in kvm.kvm_last_error()
+    assert blend(5, 8, 1.0, 1) == kvm.EINVAL                # events without arrays
+    span = lambda n_layers, num, den, w_min, w_max, ptr: lib.kvm_span_update(
+        C.byref(rows), None, n_layers, None, None, num, den, ptr, ptr, w_min, w_max, ptr, None)
+    assert span(0, 9, 10, 0, 100, 1) == kvm.EINVAL
+    assert span(4, 11, 10, 0, 100, 1) == kvm.EINVAL and "theta" in kvm.kvm_last_error()
+    assert span(4, 9, 0, 0, 100, 1) == kvm.EINVAL
+    assert span(4, 9, 10, 50, 10, 1) == kvm.EINVAL
+    assert span(4, 9, 10, 0, 100, None) == kvm.EINVAL
+    assert span(4, 9, 10, 0, 100, 1) == kvm.EINVAL and "null row array" in kvm.kvm_last_error()
+    keys = lambda n_layers, decay: lib.kvm_prefetch_keys(
+        C.byref(rows), None, None, None, n_layers, None, None, None, decay, None, None, None)
+    assert keys(0, 0.9) == kvm.EINVAL
+    assert keys(4, 0.0) == kvm.EINVAL and keys(4, 1.5) == kvm.EINVAL
+    assert keys(4, 0.9) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, -1, 0, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, 10, -2, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_pack(None, None, None, 0, None, 0, None, None, None, None, 0, None, 0, None, None) == kvm.EINVAL

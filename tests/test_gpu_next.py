@@ -1,0 +1,393 @@
+"""GPU parity for the refinements beyond the base pass: blended reuse estimate (section 3.3),
+EMA with positional decay and transition multipliers (sections 3.4, 3.7), attention-span windows
+and position-window prefetch lists (section 3.5).  Every call goes through the C ABI; expected
+values come from the oracle only."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_26968_amd import synth
+from tests.harness import DeviceCase, host_pools
+
+pytestmark = pytest.mark.gpu
+
+RES, HOST, PROT, SCORED = 1, 2, 4, 8
+
+
+def dev_of(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ------------------------------------------------------------------ blended estimate
+@pytest.mark.parametrize("window,kappa", [(1, 3.0), (7, 0.0), (64, 16.0), (1000, 250.0), (65536, 1e6)])
+def test_blend_counters_ring_and_estimates(oracle, window, kappa):
+    """Counters, ring contents and ring heads bit-exact; estimates within 1e-6 relative (a handful
+    of fp32 roundings against fp64).  Several calls so that the ring wraps and chunks of 1024 events
+    are crossed; one call is longer than the ring for every pair, one holds malformed events."""
+    from paper_2604_26968_amd import kvm
+    hits, misses = np.zeros(16, np.uint32), np.zeros(16, np.uint32)
+    win, head = np.full((16, window), 255, np.uint8), np.zeros(16, np.uint32)
+    d_hits, d_misses = torch.zeros(16, dtype=torch.int32, device="cuda"), torch.zeros(16, dtype=torch.int32, device="cuda")
+    d_win = torch.full((16, window), 255, dtype=torch.uint8, device="cuda")
+    d_head = torch.zeros(16, dtype=torch.int32, device="cuda")
+    d_out = [torch.zeros(16, dtype=torch.float32, device="cuda") for _ in range(3)]
+    d_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    bad = np.zeros(1, np.uint32)
+    w = synth.categorical_weights(9)
+    for call, n in enumerate([0, 1, 63, 1024, 1025, 5000, 40000, 3]):
+        ev_p, ev_o = synth.make_events(n, 70 + call, pair_weights=w, reuse_prob=np.linspace(0.05, 0.95, 16))
+        if n >= 1024:
+            ev_p, ev_o = ev_p.copy(), ev_o.copy()
+            ev_p[5::97] = 16 + (np.arange(len(ev_p[5::97])) % 100)
+            ev_o[11::131] = 2 + (np.arange(len(ev_o[11::131])) % 50)
+        want = oracle.beta_blend_update(ev_p, ev_o, hits, misses, win, head, kappa, alpha0=1.0, beta0=1.0, n_bad=bad)
+        kvm.kvm_beta_blend_update(dev_of(ev_p) if n else None, dev_of(ev_o) if n else None, d_hits, d_misses, d_win,
+                                  d_head, kappa, *d_out, n_bad=d_bad)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_hits.cpu().numpy().view(np.uint32), hits)
+        np.testing.assert_array_equal(d_misses.cpu().numpy().view(np.uint32), misses)
+        np.testing.assert_array_equal(d_win.cpu().numpy(), win)
+        np.testing.assert_array_equal(d_head.cpu().numpy().view(np.uint32), head)
+        assert int(d_bad.item()) == int(bad[0])
+        for got, ref in zip(d_out, want):
+            np.testing.assert_allclose(got.cpu().numpy(), ref, rtol=1e-6, atol=1e-12)
+
+
+def test_blend_single_pair_burst_longer_than_the_ring(oracle):
+    """All events on one pair: only the last `window` survive, wherever the head stood."""
+    from paper_2604_26968_amd import kvm
+    window = 100
+    rng = np.random.default_rng(1)
+    hits, misses = np.zeros(16, np.uint32), np.zeros(16, np.uint32)
+    win, head = np.full((16, window), 255, np.uint8), np.zeros(16, np.uint32)
+    d_hits, d_misses = torch.zeros(16, dtype=torch.int32, device="cuda"), torch.zeros(16, dtype=torch.int32, device="cuda")
+    d_win = torch.full((16, window), 255, dtype=torch.uint8, device="cuda")
+    d_head = torch.zeros(16, dtype=torch.int32, device="cuda")
+    d_out = [torch.zeros(16, dtype=torch.float32, device="cuda") for _ in range(3)]
+    for n in (37, 4099, 100, 2048):
+        ev_p = np.full(n, 13, np.uint8)
+        ev_o = (rng.random(n) < 0.3).astype(np.uint8)
+        want = oracle.beta_blend_update(ev_p, ev_o, hits, misses, win, head, 50.0)
+        kvm.kvm_beta_blend_update(dev_of(ev_p), dev_of(ev_o), d_hits, d_misses, d_win, d_head, 50.0, *d_out)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_win.cpu().numpy(), win)
+        np.testing.assert_array_equal(d_head.cpu().numpy().view(np.uint32), head)
+        np.testing.assert_allclose(d_out[2].cpu().numpy(), want[2], rtol=1e-6)
+
+
+# ------------------------------------------------------------------ EMA refinements
+def ema_case():
+    case = synth.make_case(synth.Shape(3, 8, 2, 64, synth.BF16, True, [100, 3300, 33, 700]), seed=16, uid_gap=2,
+                           pair_weights=synth.categorical_weights(1))
+    rng = np.random.default_rng(3)
+    res = np.flatnonzero(case.state & RES)
+    gone = rng.choice(res, size=len(res) // 5, replace=False)
+    case.state[gone] = (case.state[gone] & ~np.uint8(RES)) | HOST
+    return case
+
+
+@pytest.mark.parametrize("pos_decay,with_mult", [(1.0, False), (0.97, False), (1.0, True), (0.999, True), (0.5, True)])
+def test_ema_ex_multi_step(oracle, pos_decay, with_mult):
+    """S within 2e-6 relative per step (the positional factor is one fp32 exp2 of an exactly reduced
+    argument plus one product; the rest as in the plain update), abs floor for values that underflow;
+    state bits exact."""
+    from paper_2604_26968_amd import kvm
+    case = ema_case()
+    dev = DeviceCase(case)
+    rng = np.random.default_rng(0)
+    n_seq = len(case.shape.seq_lens)
+    n_heads = case.shape.n_layers * case.shape.n_kv_heads
+    row_head = synth.row_head_index(case)
+    mult = (0.25 + 2 * rng.random((4, n_heads))).astype(np.float32) if with_mult else None
+    S, prio = np.zeros(case.n_uids, np.float32), np.full(case.n_uids, -3.0, np.float32)
+    dev.prio.fill_(-3.0)
+    state = case.state.copy()
+    d_seq, d_head = dev_of(case.row_seq), dev_of(row_head)
+    d_mult = dev_of(mult) if with_mult else None
+    for step in range(5):
+        mass = rng.random(case.n_uids).astype(np.float32)
+        p_hat = rng.random(16).astype(np.float32)
+        trans = rng.choice(np.array([0, 1, 2, 3, 255, 4], np.uint8), n_seq).astype(np.uint8)
+        active = (rng.random(case.n_rows) < 0.8).astype(np.uint8) if step else None
+        dev.mass.copy_(torch.from_numpy(mass))
+        dev.p_hat.copy_(torch.from_numpy(p_hat))
+        ex = kvm.make_ema_ex(pos_decay, d_seq if with_mult else None, d_head if with_mult else None,
+                             dev_of(trans) if with_mult else None, d_mult)
+        kvm.kvm_ema_update_ex(dev.rows(active), dev.mass, 0.9, ex, dev.row_weight, dev.pair, dev.p_hat, dev.state,
+                              dev.S, dev.prio)
+        torch.cuda.synchronize()
+        oracle.ema_update_ex(case.row_ntok, case.row_off, mass, 0.9, pos_decay, case.row_weight, case.pair, p_hat,
+                             state, S, prio, row_seq=case.row_seq if with_mult else None,
+                             row_head=row_head if with_mult else None, seq_transition=trans if with_mult else None,
+                             head_mult=mult, row_active=active)
+        gS, gprio = dev.S.cpu().numpy(), dev.prio.cpu().numpy()
+        np.testing.assert_array_equal(dev.state.cpu().numpy(), state)
+        np.testing.assert_allclose(gS, S, rtol=2e-6, atol=1e-37)
+        fin = np.isfinite(prio)
+        np.testing.assert_array_equal(np.isposinf(gprio), np.isposinf(prio))
+        np.testing.assert_allclose(gprio[fin], prio[fin], rtol=2e-6, atol=1e-37)
+        dev.S.copy_(torch.from_numpy(S))        # identical inputs for the next step
+
+
+def test_ema_ex_without_refinements_equals_plain_kernel_bit_for_bit():
+    from paper_2604_26968_amd import kvm
+    case = ema_case()
+    rng = np.random.default_rng(5)
+    mass = dev_of(rng.random(case.n_uids).astype(np.float32))
+    S0 = rng.random(case.n_uids).astype(np.float32)
+    out = []
+    for ex in (False, True):
+        dev = DeviceCase(case)
+        dev.mass.copy_(mass)
+        dev.S.copy_(torch.from_numpy(S0))
+        dev.p_hat.copy_(torch.linspace(0.1, 0.9, 16))
+        if ex:
+            kvm.kvm_ema_update_ex(dev.rows(), dev.mass, 0.95, kvm.make_ema_ex(1.0), dev.row_weight, dev.pair,
+                                  dev.p_hat, dev.state, dev.S, dev.prio)
+        else:
+            kvm.kvm_ema_update(dev.rows(), dev.mass, 0.95, dev.row_weight, dev.pair, dev.p_hat, dev.state, dev.S,
+                               dev.prio)
+        torch.cuda.synchronize()
+        out.append((dev.S.cpu().numpy(), dev.prio.cpu().numpy(), dev.state.cpu().numpy()))
+    for a, b in zip(*out):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_ema_ex_long_row_positional_factor(oracle):
+    """8,192-block rows: the factor spans 0.9995^8191 = 0.017 .. 1 and, for 0.9, underflows to 0."""
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(synth.Shape(1, 8, 1, 64, synth.BF16, True, [131072]), seed=2)
+    for pos_decay in (0.9995, 0.9):
+        dev = DeviceCase(case)
+        dev.mass.fill_(1.0)
+        dev.p_hat.fill_(1.0)
+        kvm.kvm_ema_update_ex(dev.rows(), dev.mass, 0.9, kvm.make_ema_ex(pos_decay), dev.row_weight, dev.pair,
+                              dev.p_hat, dev.state, dev.S, dev.prio)
+        torch.cuda.synchronize()
+        S, prio, state = (np.zeros(case.n_uids, np.float32), np.zeros(case.n_uids, np.float32), case.state.copy())
+        oracle.ema_update_ex(case.row_ntok, case.row_off, np.ones(case.n_uids, np.float32), 0.9, pos_decay,
+                             case.row_weight, case.pair, np.ones(16, np.float32), state, S, prio)
+        np.testing.assert_allclose(dev.S.cpu().numpy(), S, rtol=1e-6, atol=1e-37)
+
+
+# ------------------------------------------------------------------ prefetching
+def prefetch_case(seed=4):
+    case = synth.make_case(synth.Shape(4, 8, 2, 64, synth.BF16, True, [100, 2500, 33, 900, 16]), seed=seed, uid_gap=1,
+                           pair_weights=synth.categorical_weights(2))
+    rng = np.random.default_rng(seed)
+    res = np.flatnonzero(case.state & RES)
+    gone = rng.choice(res, size=len(res) // 2, replace=False)
+    case.state[gone] = (case.state[gone] & ~np.uint8(RES)) | HOST
+    return case
+
+
+@pytest.mark.parametrize("theta", [(9, 10), (1, 2), (1, 1), (0, 1), (65535, 65536)])
+def test_span_update_exact(oracle, theta):
+    """Integer results: span sums, counts and windows are bit-exact."""
+    from paper_2604_26968_amd import kvm
+    case = prefetch_case()
+    dev = DeviceCase(case)
+    L = case.shape.n_layers
+    rng = np.random.default_rng(8)
+    row_layer = synth.row_layer_index(case)
+    s_sum, s_cnt, win = np.zeros(L + 1, np.uint64), np.zeros(L + 1, np.uint32), np.full(L + 1, -7, np.int32)
+    d_sum = torch.zeros(L + 1, dtype=torch.int64, device="cuda")
+    d_cnt = torch.zeros(L + 1, dtype=torch.int32, device="cuda")
+    d_win = torch.full((L + 1,), -7, dtype=torch.int32, device="cuda")
+    d_layer = dev_of(row_layer)
+    for step in range(3):
+        # masses concentrated near the end, more sharply in the early layers; a few odd values
+        mass = np.zeros(case.n_uids, np.float32)
+        for r in range(case.n_rows):
+            nb = (case.row_ntok[r] + 15) // 16
+            sharp = 0.5 + 0.1 * row_layer[r] + 0.3 * rng.random()
+            m = (sharp ** np.arange(nb)[::-1]) * rng.random(nb)
+            mass[case.row_off[r]:case.row_off[r] + nb] = m / max(m.sum(), 1e-30)
+        mass[rng.random(case.n_uids) < 0.01] = np.nan
+        mass[rng.random(case.n_uids) < 0.01] = -0.5
+        mass[rng.random(case.n_uids) < 0.005] = 3.0
+        active = (rng.random(case.n_rows) < 0.8).astype(np.uint8) if step else None
+        oracle.span_update(case.row_ntok, case.row_off, row_layer, mass, case.state, theta[0], theta[1], s_sum, s_cnt,
+                           32, 2000, win, row_active=active)
+        dev.mass.copy_(torch.from_numpy(mass))
+        kvm.kvm_span_update(dev.rows(active), d_layer, dev.mass, dev.state, theta[0], theta[1], d_sum, d_cnt, 32, 2000,
+                            d_win)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_sum.cpu().numpy().view(np.uint64), s_sum)
+        np.testing.assert_array_equal(d_cnt.cpu().numpy().view(np.uint32), s_cnt)
+        np.testing.assert_array_equal(d_win.cpu().numpy(), win)
+    assert win[L] == -7 and s_cnt[:L].min() > 0
+
+
+def test_span_long_rows(oracle):
+    """8,192-block rows cross many 64-block chunks; uniform masses give ceil(theta nb) exactly."""
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(synth.Shape(2, 8, 1, 64, synth.BF16, True, [131072, 70000]), seed=2)
+    dev = DeviceCase(case)
+    row_layer = synth.row_layer_index(case)
+    rng = np.random.default_rng(1)
+    for kind in ("uniform", "random"):
+        mass = np.full(case.n_uids, 2.0 ** -13, np.float32) if kind == "uniform" else \
+            (rng.random(case.n_uids) ** 8).astype(np.float32)
+        s_sum, s_cnt, win = np.zeros(2, np.uint64), np.zeros(2, np.uint32), np.zeros(2, np.int32)
+        oracle.span_update(case.row_ntok, case.row_off, row_layer, mass, case.state, 9, 10, s_sum, s_cnt, 0, 1 << 30, win)
+        d_sum = torch.zeros(2, dtype=torch.int64, device="cuda")
+        d_cnt = torch.zeros(2, dtype=torch.int32, device="cuda")
+        d_win = torch.zeros(2, dtype=torch.int32, device="cuda")
+        dev.mass.copy_(torch.from_numpy(mass))
+        kvm.kvm_span_update(dev.rows(), dev_of(row_layer), dev.mass, dev.state, 9, 10, d_sum, d_cnt, 0, 1 << 30, d_win)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(d_sum.cpu().numpy().view(np.uint64), s_sum)
+        np.testing.assert_array_equal(d_win.cpu().numpy(), win)
+        if kind == "uniform":
+            assert s_sum[0] == -(-9 * 8192 // 10) + -(-9 * 4375 // 10)
+
+
+@pytest.mark.parametrize("pos_decay", [1.0, 0.98, 0.5])
+def test_prefetch_keys_and_list(oracle, pos_decay):
+    """Candidate flags exact; keys within 2e-7 absolute (keys are 1 - y with y in [0, 1] known to
+    ~1e-7 relative); the list built by the selector from the library's own keys equals the oracle's
+    selection on those same keys, and differs from the oracle's end-to-end list only at the cutoff."""
+    from paper_2604_26968_amd import kvm
+    case = prefetch_case(seed=9)
+    dev = DeviceCase(case)
+    rng = np.random.default_rng(2)
+    L = case.shape.n_layers
+    row_layer = synth.row_layer_index(case)
+    row_pos = np.where(rng.random(case.n_rows) < 0.1, -1, case.row_ntok - rng.integers(0, 20, case.n_rows)).astype(np.int32)
+    window = np.array([0, 48, 400, 100000], np.int32)[:L]
+    p_est = rng.random(16).astype(np.float32)
+    key, cand = np.full(case.n_uids, -2.0, np.float32), np.full(case.n_uids, 99, np.uint8)
+    oracle.prefetch_keys(case.row_ntok, case.row_off, row_layer, row_pos, window, case.state, case.pair, p_est,
+                         pos_decay, key, cand)
+    d_key = torch.full((case.n_uids,), -2.0, dtype=torch.float32, device="cuda")
+    d_cand = torch.full((case.n_uids,), 99, dtype=torch.uint8, device="cuda")
+    kvm.kvm_prefetch_keys(dev.rows(), dev_of(row_layer), dev_of(row_pos), dev_of(window), dev.state, dev.pair,
+                          dev_of(p_est), pos_decay, d_key, d_cand)
+    torch.cuda.synchronize()
+    gkey, gcand = d_key.cpu().numpy(), d_cand.cpu().numpy()
+    np.testing.assert_array_equal(gcand, cand)
+    isc = cand == (RES | SCORED)
+    assert isc.sum() > 100
+    np.testing.assert_array_equal(np.isposinf(gkey), np.isposinf(key))
+    np.testing.assert_allclose(gkey[isc], key[isc], rtol=0, atol=2e-7)
+    assert np.all(gkey[~isc & (cand == 99)] == -2.0)          # gaps between rows are not written
+    k = int(isc.sum()) // 3
+    kvm.kvm_select_victims(d_key, d_cand, dev.victims, dev.n_victims, dev.ws, k=k)
+    torch.cuda.synchronize()
+    got = dev.victims[: int(dev.n_victims.item())].cpu().numpy()
+    np.testing.assert_array_equal(got, oracle.select_victims(gkey, gcand, k=k))       # identical keys: exact
+    want = oracle.select_victims(key, cand, k=k)
+    assert len(got) == len(want) == k
+    diff = np.setxor1d(got, want)
+    cutoff = np.max(key[want])
+    assert np.all(np.abs(key[diff] - cutoff) <= 4e-7)
+
+
+def test_prefetch_list_feeds_unpack(oracle):
+    """The whole chain on the device: keys -> select -> unpack with the device-side count; the pool,
+    table and state afterwards equal the oracle's chain."""
+    from paper_2604_26968_amd import kvm
+
+    case = synth.make_case(synth.Shape(2, 4, 2, 64, synth.BF16, True, [600, 200]), seed=12, spare_slots=0)
+    dev = DeviceCase(case)
+    k8, v8 = host_pools(case)
+    rng = np.random.default_rng(3)
+    sh = case.shape
+    rec = sh.unit_k_bytes + sh.unit_v_bytes
+    # evict a third of the units to the host through the library's own pack (oracle mirrors it)
+    res = np.flatnonzero((case.state & RES) & ~((case.state & PROT) >> 2))
+    out = np.sort(rng.choice(res, size=len(res) // 3, replace=False)).astype(np.int64)
+    hs = np.arange(len(out), dtype=np.int32)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    staging, freed = oracle.pack(k8, v8, sh.unit_k_bytes, sh.unit_v_bytes, tbl, st, out, hs)
+    g_staging, g_freed = dev.pack(out, hs)
+    np.testing.assert_array_equal(g_staging, staging)
+    # prefetch list: the blocks near the decode positions
+    row_layer = synth.row_layer_index(case)
+    row_pos = case.row_ntok.copy()
+    window = np.array([64, 256], np.int32)
+    p_est = np.linspace(0.2, 0.9, 16).astype(np.float32)
+    key, cand = np.zeros(case.n_uids, np.float32), np.zeros(case.n_uids, np.uint8)
+    oracle.prefetch_keys(case.row_ntok, case.row_off, row_layer, row_pos, window, st, case.pair, p_est, 1.0, key, cand)
+    k = 10
+    want = oracle.select_victims(key, cand, k=k)
+    assert len(want) == k
+    d_key = torch.zeros(case.n_uids, dtype=torch.float32, device="cuda")
+    d_cand = torch.zeros(case.n_uids, dtype=torch.uint8, device="cuda")
+    kvm.kvm_prefetch_keys(dev.rows(), dev_of(row_layer), dev_of(row_pos), dev_of(window), dev.state, dev.pair,
+                          dev_of(p_est), 1.0, d_key, d_cand)
+    kvm.kvm_select_victims(d_key, d_cand, dev.victims, dev.n_victims, dev.ws, k=k)
+    torch.cuda.synchronize()
+    got = dev.victims[:k].cpu().numpy()
+    np.testing.assert_array_equal(got, want)         # pos_decay 1: keys are 1 - p_est exactly on both sides
+    # records of the chosen units, in list order, as they sit on the host; frames = the first k freed
+    host_slot = -1 - tbl[want]
+    recs = np.ascontiguousarray(staging.reshape(-1, rec)[host_slot])
+    dst = freed[:k].astype(np.int32)
+    oracle.unpack(k8, v8, sh.unit_k_bytes, sh.unit_v_bytes, tbl, st, want, dst, recs)
+    h_in = torch.from_numpy(recs.reshape(-1)).pin_memory()
+    kvm.kvm_unpack(dev.pool, dev.slot_tbl, dev.state, dev.victims, k, dev_of(dst), None, h_in, n_dev=dev.n_victims,
+                   n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    gk, gv = dev.pools_host()
+    np.testing.assert_array_equal(gk, k8)
+    np.testing.assert_array_equal(gv, v8)
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    assert int(dev.n_bad.item()) == 0
+
+
+# ------------------------------------------------------------------ in-place exchange
+@pytest.mark.parametrize("shape", [
+    synth.Shape(2, 8, 2, 128, synth.BF16, True, [300, 77]),
+    synth.Shape(4, 16, 1, 576, synth.BF16, False, [400]),
+])
+def test_exchange_in_place_with_slot_addressed_tier(oracle, shape):
+    """Pools, tier, tables and state after the call equal the oracle's, byte for byte, including
+    skipped pairs and lists cut short by the device-side counts."""
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(shape, seed=31)
+    k8, v8 = host_pools(case)
+    rng = np.random.default_rng(8)
+    uk, uv = shape.unit_k_bytes, shape.unit_v_bytes
+    rec = uk + uv
+    res = np.flatnonzero(case.state & RES)
+    first_out = np.sort(rng.choice(res, size=len(res) // 3, replace=False)).astype(np.int64)
+    n_tier = len(first_out) + 7
+    hs = rng.permutation(n_tier)[:len(first_out)].astype(np.int32)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    staging, _ = oracle.pack(k8, v8, uk, uv, tbl, st, first_out, hs)
+    tier = rng.integers(0, 256, size=(n_tier, rec), dtype=np.uint8)
+    tier[hs] = staging
+    # device side starts from the same situation
+    case.slot_tbl[:], case.state[:] = tbl, st
+    dev = DeviceCase(case)
+    d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
+    n = 40
+    res_now = np.flatnonzero(st & RES)
+    outs = rng.choice(res_now, size=n, replace=False).astype(np.int64)
+    ins = rng.choice(first_out, size=n, replace=False).astype(np.int64)
+    outs[3] = -1
+    ins[9] = res_now[0] if res_now[0] not in outs else res_now[1]       # already resident
+    outs[20] = np.setdiff1d(first_out, ins)[0]                          # not resident (and in neither list otherwise)
+    bad = np.zeros(1, np.uint32)
+    for n_out_dev, n_in_dev in ((None, None), (25, 30)):
+        lim = n if n_out_dev is None else min(n_out_dev, n_in_dev)
+        oracle.exchange(k8, v8, uk, uv, tbl, st, outs[:lim], ins[:lim], tier, n_bad=bad)
+        kvm.kvm_exchange(dev.pool, dev.slot_tbl, dev.state, dev_of(outs), dev_of(ins), n, d_tier,
+                         n_out_dev=None if n_out_dev is None else torch.tensor([n_out_dev], device="cuda"),
+                         n_in_dev=None if n_in_dev is None else torch.tensor([n_in_dev], device="cuda"),
+                         n_bad=dev.n_bad)
+        torch.cuda.synchronize()
+        gk, gv = dev.pools_host()
+        np.testing.assert_array_equal(gk, k8)
+        if v8 is not None:
+            np.testing.assert_array_equal(gv, v8)
+        np.testing.assert_array_equal(d_tier.numpy().reshape(n_tier, rec), tier)
+        np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+        np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+        assert int(dev.n_bad.item()) == int(bad[0])
+        # second round: the same lists reversed bring everything back except the skipped pairs
+        outs, ins = ins.copy(), outs.copy()
+    assert bad[0] >= 3

@@ -87,3 +87,86 @@ def test_bad_entries_are_skipped_and_counted(oracle):
                   np.array([0, case.n_slots], np.int32), staging[:2], n_bad=bad)
     assert bad[0] == 2
     np.testing.assert_array_equal(k8, k_before)
+
+
+# ---- in-place exchange with a slot-addressed host tier -----------------------------------------
+def tiered_case(oracle, seed=7, latent=False):
+    """A case with a third of its units demoted to a host tier (through the pinned pack oracle)."""
+    shape = synth.Shape(2, 4, 1, 576, synth.BF16, False, [260]) if latent else \
+        synth.Shape(2, 4, 2, 32, synth.BF16, True, [150, 90])
+    case = synth.make_case(shape, seed)
+    k8, v8 = pools(case)
+    rng = np.random.default_rng(seed)
+    res = np.flatnonzero(case.state & RES)
+    out = np.sort(rng.choice(res, size=len(res) // 3, replace=False)).astype(np.int64)
+    host = rng.permutation(len(out) + 5)[:len(out)].astype(np.int32)          # scattered host slots, 5 unused
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    uk, uv = shape.unit_k_bytes, shape.unit_v_bytes
+    staging, _ = oracle.pack(k8, v8, uk, uv, tbl, st, out, host)
+    tier = rng.integers(0, 256, size=(len(out) + 5, uk + uv), dtype=np.uint8)
+    tier[host] = staging
+    return case, k8, v8, tbl, st, tier, out
+
+
+def test_exchange_equals_numpy_swap_and_pack_unpack_composition(oracle):
+    for latent in (False, True):
+        case, k8, v8, tbl, st, tier, on_host = tiered_case(oracle, latent=latent)
+        uk, uv = case.shape.unit_k_bytes, case.shape.unit_v_bytes
+        rng = np.random.default_rng(1)
+        n = 9
+        outs = rng.choice(np.flatnonzero(st & RES), size=n, replace=False).astype(np.int64)
+        ins = rng.choice(on_host, size=n, replace=False).astype(np.int64)
+        # (a) numpy: swap rows
+        frames, hslots = tbl[outs].copy(), (-1 - tbl[ins]).copy()
+        k_want, tier_want = k8.copy(), tier.copy()
+        v_want = v8.copy() if v8 is not None else None
+        tier_want[hslots, :uk] = k8[frames]
+        k_want[frames] = tier[hslots, :uk]
+        if v8 is not None:
+            tier_want[hslots, uk:] = v8[frames]
+            v_want[frames] = tier[hslots, uk:]
+        # (b) composition of the pinned pack and unpack
+        k_c, v_c, tbl_c, st_c = k8.copy(), (v8.copy() if v8 is not None else None), tbl.copy(), st.copy()
+        incoming = tier[hslots].copy()
+        staging, freed = oracle.pack(k_c, v_c, uk, uv, tbl_c, st_c, outs, hslots.astype(np.int32))
+        oracle.unpack(k_c, v_c, uk, uv, tbl_c, st_c, ins, freed, incoming)
+        tier_c = tier.copy()
+        tier_c[hslots] = staging
+        bad = np.zeros(1, np.uint32)
+        oracle.exchange(k8, v8, uk, uv, tbl, st, outs, ins, tier, n_bad=bad)
+        assert bad[0] == 0
+        for got, a, b in ((k8, k_want, k_c), (tier, tier_want, tier_c), (tbl, tbl_c, tbl_c), (st, st_c, st_c)):
+            np.testing.assert_array_equal(got, a)
+            np.testing.assert_array_equal(got, b)
+        if v8 is not None:
+            np.testing.assert_array_equal(v8, v_want)
+            np.testing.assert_array_equal(v8, v_c)
+        np.testing.assert_array_equal(tbl[outs], -1 - hslots)
+        np.testing.assert_array_equal(tbl[ins], frames)
+
+
+def test_exchange_twice_is_identity_and_bad_pairs_are_skipped(oracle):
+    case, k8, v8, tbl, st, tier, on_host = tiered_case(oracle, seed=11)
+    uk, uv = case.shape.unit_k_bytes, case.shape.unit_v_bytes
+    k0, v0, tbl0, st0, tier0 = k8.copy(), v8.copy(), tbl.copy(), st.copy(), tier.copy()
+    res = np.flatnonzero(st & RES)
+    outs, ins = res[:6].astype(np.int64), on_host[:6].astype(np.int64)
+    oracle.exchange(k8, v8, uk, uv, tbl, st, outs, ins, tier)
+    assert not np.array_equal(k8, k0)
+    oracle.exchange(k8, v8, uk, uv, tbl, st, ins, outs, tier)       # roles reversed: back where they were
+    for a, b in ((k8, k0), (v8, v0), (tbl, tbl0), (st, st0), (tier, tier0)):
+        np.testing.assert_array_equal(a, b)
+    # malformed pairs change nothing and are counted
+    bad = np.zeros(1, np.uint32)
+    outs_bad = np.array([on_host[0], res[0], -1, res[1], res[2]], np.int64)     # not resident / ok / invalid / ok / ok
+    ins_bad = np.array([on_host[1], res[3], on_host[2], case.n_uids, on_host[3]], np.int64)   # ok / resident / ok / invalid / ok
+    oracle.exchange(k8, v8, uk, uv, tbl, st, outs_bad, ins_bad, tier, n_bad=bad)
+    assert bad[0] == 4
+    assert tbl[res[2]] < 0 and tbl[on_host[3]] >= 0
+    changed = np.flatnonzero(tbl != tbl0)
+    np.testing.assert_array_equal(np.sort(changed), np.sort([res[2], on_host[3]]))
+    # a host slot beyond the tier is refused
+    far = [u for u in on_host[4:] if -1 - tbl[u] >= 1][0]
+    bad[0] = 0
+    oracle.exchange(k8, v8, uk, uv, tbl, st, res[4:5].astype(np.int64), np.array([far], np.int64), tier[:1], n_bad=bad)
+    assert bad[0] == 1 and tbl[far] < 0

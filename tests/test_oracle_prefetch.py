@@ -15,7 +15,7 @@ def span_brute(masses, resident, theta):
     q = []
     for m, r in zip(masses, resident):
         m = float(np.float32(m))
-        q.append(int(Fraction(min(m, 256.0)) * 2 ** 32) if (r and m > 0) else 0)   # floor of an exact product
+        q.append(int(Fraction(min(m, 1.0)) * 2 ** 32) if (r and m > 0) else 0)   # floor of an exact product
     total = sum(q)
     if total == 0:
         return None
@@ -66,7 +66,7 @@ def test_random_rows_against_fraction_brute_force_and_layer_mean(oracle):
     mass = (rng.random(n) ** 4).astype(np.float32)
     mass[rng.random(n) < 0.05] = np.nan
     mass[rng.random(n) < 0.05] = -1.0
-    mass[rng.random(n) < 0.02] = 1000.0                     # clamps to 256
+    mass[rng.random(n) < 0.02] = 1000.0                     # clamps to 1
     st = np.where(rng.random(n) < 0.7, RES, HOST).astype(np.uint8)
     layer = rng.integers(0, n_layers, n_rows).astype(np.int32)
     active = (rng.random(n_rows) < 0.8).astype(np.uint8)
