@@ -50,6 +50,11 @@ def main():
                          "zero-copy kernel (kvm_swap); kvm_pack then kvm_unpack through device staging and "
                          "hipMemcpyAsync; the same with zero-copy kernels; or gather / scatter in line with the "
                          "copies on a side stream")
+    ap.add_argument("--refined", action="store_true",
+                    help="run the pass with the refinements switched on: blended reuse estimate, EMA with "
+                         "positional decay and transition multipliers, attention-span windows, and a prefetch list "
+                         "chosen on the device (keys + select) and served by the in-place exchange with a "
+                         "slot-addressed host tier")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
@@ -117,6 +122,26 @@ def main():
     host_scratch = torch.empty(chunk * rec, dtype=torch.uint8, pin_memory=True) if keep < k0 else None
     staging_dev = torch.empty(chunk * rec, dtype=torch.uint8, device=dev)
 
+    if args.refined:
+        L, lh = shape.n_layers, shape.n_layers * shape.n_kv_heads
+        rng = np.random.default_rng(17)
+        head_idx = (np.arange(n_rows) % lh).astype(np.int32)
+        row_layer = torch.from_numpy(head_idx // shape.n_kv_heads).to(dev)
+        n_seqs = len(shape.seq_lens)
+        ex = kvm.make_ema_ex(0.9995, torch.from_numpy(wl.row_seq).to(dev), torch.from_numpy(head_idx).to(dev),
+                             torch.from_numpy(rng.choice(np.array([0, 1, 2, 3, 255], np.uint8), n_seqs)).to(dev),
+                             torch.from_numpy((0.5 + rng.random((4, lh))).astype(np.float32)).to(dev))
+        win = torch.full((16, 256), 255, dtype=torch.uint8, device=dev)
+        win_head = torch.zeros(16, dtype=torch.int32, device=dev)
+        conf = torch.zeros(16, dtype=torch.float32, device=dev)
+        p_blend = torch.zeros(16, dtype=torch.float32, device=dev)
+        span_sum = torch.zeros(L, dtype=torch.int64, device=dev)
+        span_cnt = torch.zeros(L, dtype=torch.int32, device=dev)
+        layer_window = torch.full((L,), 1 << 30, dtype=torch.int32, device=dev)
+        pf_key = torch.zeros(n, dtype=torch.float32, device=dev)
+        pf_cand = torch.zeros(n, dtype=torch.uint8, device=dev)
+        n_pf = torch.zeros(1, dtype=torch.int64, device=dev)
+
     def management_pass(i, k_arg, budget_arg):
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
@@ -171,6 +196,24 @@ def main():
     for e in ev_d2h + ev_scattered:
         e.record(main)
 
+    pf_list = torch.zeros(swap, dtype=torch.int64, device=dev)
+
+    def step_refined(i):
+        """The pass with every refinement on.  The prefetch list comes from the device (candidates inside the
+        per-layer window behind the decode position, ranked by blended reuse estimate x positional decay) and
+        is served, together with the victims, by the in-place exchange against the slot-addressed tier."""
+        ev = evs[i % n_q_sets]
+        kvm.kvm_beta_blend_update(ev[0], ev[1], hits, misses, win, win_head, 64.0, p_hat, conf, p_blend, n_bad=n_bad)
+        kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
+        kvm.kvm_ema_update_ex(rows, mass, decay, ex, wl.row_weight, wl.pair, p_blend, wl.state, S, prio)
+        kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window)
+        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
+        kvm.kvm_prefetch_keys(rows, row_layer, wl.row_ntok, layer_window, wl.state, wl.pair, p_blend, 0.9995,
+                              pf_key, pf_cand)
+        kvm.kvm_select_victims(pf_key, pf_cand, pf_list, n_pf, ws, k=swap)
+        kvm.kvm_exchange(pool, wl.slot_tbl, wl.state, step_victims, pf_list, swap, host_tier, n_out_dev=n_victims,
+                         n_in_dev=n_pf, n_bad=n_bad)
+
     def step_serial(i):
         """One full pass, everything in line on one stream.  Resident units at entry: budget + swap."""
         ev = evs[i % n_q_sets]
@@ -222,6 +265,9 @@ def main():
         ev_scattered[b].record(main)
 
     step = step_overlapped if args.swap_mode == "side-stream" else step_serial
+    if args.refined:
+        assert keep == k0, "the refined pass addresses the whole host tier by slot"
+        step = step_refined
     prefetch(0)
     # the frames of segment 0 came from the bulk list; from now on each step reuses the frames it frees
     torch.cuda.synchronize()
@@ -252,7 +298,7 @@ def main():
 
     kernels = {}
     for name in ("score_plan", "score_partial", "score_finalize", "ema_prio", "beta", "select_hist", "select_emit",
-                 "pack", "unpack", "swap"):
+                 "pack", "unpack", "swap", "span", "prefetch_keys"):
         cnt, ms = kvm.kvm_timing_read(name)
         kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
     kvm.kvm_timing_reset()
@@ -289,7 +335,7 @@ def main():
                                % (decay, round(100 * w_budget)),
                    "units_total": n, "units_scored_per_step": scored_units, "rows": n_rows,
                    "swap_units_per_step": swap, "resident_fraction": round(scored_units / n, 4),
-                   "swap_mode": args.swap_mode},
+                   "swap_mode": "exchange" if args.refined else args.swap_mode, "refined": bool(args.refined)},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "evicted_units_per_s": round(swap / (elapsed / args.steps), 1),
         "prefetched_units_per_s": round(swap / (elapsed / args.steps), 1),

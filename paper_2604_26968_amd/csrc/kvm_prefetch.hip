@@ -32,8 +32,81 @@ __device__ inline uint64_t shfl_xor_u64(uint64_t v, int mask) {
 }
 
 // One wavefront per row.  Pass 1: the row's total.  Pass 2: walk back from the last block in
-// chunks of 64 blocks, inclusive prefix sums inside the chunk, first lane whose running sum
-// reaches theta * total gives the span.
+// chunks of 64 x kSeg blocks; lane l holds kSeg consecutive distances (so a wavefront load covers
+// contiguous memory), one prefix scan over the lane sums per chunk finds the lane in which the
+// running sum reaches theta * total, and that lane walks its kSeg values to the exact block.
+constexpr int kSeg = 8;
+// Consecutive rows one wavefront handles, one after the other.  Rows next to each other usually
+// belong to the same layer, so the wavefront adds their spans up in registers and touches the
+// per-layer accumulators (32 hot addresses for a 32-layer model) once per run of equal layers.
+constexpr int kSpanRowsPerWave = 8;
+
+// Span of one row (0 = the row does not count: inactive, empty, out of range, no mass).
+__device__ inline int64_t row_span(int row, int lane, int64_t n_uids, int n_layers,
+                                   const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
+                                   const uint8_t* __restrict__ row_active, const int32_t* __restrict__ row_layer,
+                                   const float* __restrict__ mass, const uint8_t* __restrict__ state,
+                                   uint32_t theta_num, uint32_t theta_den) {
+    const int n = row_ntok[row];
+    if (n <= 0) return 0;
+    const int64_t nb = ((int64_t)n + 15) >> 4;
+    const int64_t off = row_off[row];
+    if (off < 0 || off + nb > n_uids) return 0;
+    if (row_active && !row_active[row]) return 0;
+    const int layer = row_layer[row];
+    if (layer < 0 || layer >= n_layers) return 0;
+
+    uint64_t total = 0;
+    for (int64_t b = lane; b < nb; b += kWave) total += fixed_mass(mass[off + b], state[off + b]);
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) total += shfl_xor_u64(total, m);
+    if (total == 0) return 0;
+    const unsigned __int128 need = (unsigned __int128)theta_num * total;
+
+    uint64_t before = 0;   // sum over earlier chunks
+    for (int64_t base = 0; base < nb; base += kWave * kSeg) {
+        uint64_t q[kSeg];
+        uint64_t v = 0;
+        const int64_t s0 = base + (int64_t)lane * kSeg;      // this lane's first distance
+#pragma unroll
+        for (int j = 0; j < kSeg; ++j) {
+            const int64_t s1 = s0 + j;
+            q[j] = 0;
+            if (s1 < nb) {
+                const int64_t uid = off + (nb - 1 - s1);
+                q[j] = fixed_mass(mass[uid], state[uid]);
+            }
+            v += q[j];
+        }
+        uint64_t incl = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const uint64_t up = shfl_up_u64(incl, d);
+            if (lane >= d) incl += up;
+        }
+        const uint64_t hit = __ballot(s0 < nb && (unsigned __int128)(before + incl) * theta_den >= need);
+        if (hit) {
+            const int first = __ffsll((unsigned long long)hit) - 1;
+            int64_t mine = s0 + kSeg;
+            if (lane == first) {                             // the crossing lies among this lane's values
+                uint64_t acc = before + incl - v;
+                bool found = false;
+#pragma unroll
+                for (int j = 0; j < kSeg; ++j) {
+                    acc += q[j];
+                    if (!found && (unsigned __int128)acc * theta_den >= need) {
+                        found = true;
+                        mine = s0 + j + 1;
+                    }
+                }
+            }
+            return (int64_t)shfl_u64((uint64_t)mine, first);
+        }
+        before += shfl_u64(incl, kWave - 1);
+    }
+    return nb;
+}
+
 __global__ __launch_bounds__(256) void span_rows_kernel(int n_rows, int64_t n_uids, int n_layers,
                                                         const int32_t* __restrict__ row_ntok,
                                                         const int64_t* __restrict__ row_off,
@@ -43,50 +116,33 @@ __global__ __launch_bounds__(256) void span_rows_kernel(int n_rows, int64_t n_ui
                                                         const uint8_t* __restrict__ state, uint32_t theta_num,
                                                         uint32_t theta_den, unsigned long long* span_sum,
                                                         uint32_t* span_cnt) {
-    const int row = blockIdx.x * 4 + threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
-    if (row >= n_rows) return;
-    const int n = row_ntok[row];
-    if (n <= 0) return;
-    const int64_t nb = ((int64_t)n + 15) >> 4;
-    const int64_t off = row_off[row];
-    if (off < 0 || off + nb > n_uids) return;
-    if (row_active && !row_active[row]) return;
-    const int layer = row_layer[row];
-    if (layer < 0 || layer >= n_layers) return;
-
-    uint64_t total = 0;
-    for (int64_t b = lane; b < nb; b += kWave) total += fixed_mass(mass[off + b], state[off + b]);
-#pragma unroll
-    for (int m = 1; m < kWave; m <<= 1) total += shfl_xor_u64(total, m);
-    if (total == 0) return;
-    const unsigned __int128 need = (unsigned __int128)theta_num * total;
-
-    uint64_t before = 0;   // sum over earlier chunks
-    int64_t span = nb;
-    for (int64_t base = 0; base < nb; base += kWave) {
-        const int64_t s1 = base + lane;                  // this lane looks at distance s1 (span s1 + 1)
-        uint64_t v = 0;
-        if (s1 < nb) {
-            const int64_t uid = off + (nb - 1 - s1);
-            v = fixed_mass(mass[uid], state[uid]);
+    const int64_t row0 = ((int64_t)blockIdx.x * 4 + threadIdx.x / kWave) * kSpanRowsPerWave;
+    int cur_layer = -1;
+    unsigned long long sum = 0;
+    uint32_t cnt = 0;
+    for (int i = 0; i < kSpanRowsPerWave; ++i) {
+        const int64_t row = row0 + i;
+        if (row >= n_rows) break;
+        const int64_t span = row_span((int)row, lane, n_uids, n_layers, row_ntok, row_off, row_active, row_layer, mass,
+                                      state, theta_num, theta_den);
+        if (span == 0) continue;
+        const int layer = row_layer[row];
+        if (layer != cur_layer) {
+            if (cnt && lane == 0) {
+                atomicAdd(&span_sum[cur_layer], sum);
+                atomicAdd(&span_cnt[cur_layer], cnt);
+            }
+            cur_layer = layer;
+            sum = 0;
+            cnt = 0;
         }
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint64_t up = shfl_up_u64(v, d);
-            if (lane >= d) v += up;
-        }
-        const uint64_t acc = before + v;
-        const uint64_t hit = __ballot(s1 < nb && (unsigned __int128)acc * theta_den >= need);
-        if (hit) {
-            span = base + __ffsll((unsigned long long)hit);   // first lane + 1
-            break;
-        }
-        before += shfl_u64(v, kWave - 1);
+        sum += (unsigned long long)span;
+        cnt += 1;
     }
-    if (lane == 0) {
-        atomicAdd(&span_sum[layer], (unsigned long long)span);
-        atomicAdd(&span_cnt[layer], 1u);
+    if (cnt && lane == 0) {
+        atomicAdd(&span_sum[cur_layer], sum);
+        atomicAdd(&span_cnt[cur_layer], cnt);
     }
 }
 
@@ -176,7 +232,8 @@ extern "C" int kvm_span_update(const kvm_rows_t* rows, const int32_t* row_layer,
     TimedLaunch tl("span", st);
     if (!nothing) {
         KVM_REQUIRE(row_layer && mass && state, KVM_EINVAL, "kvm_span_update: null buffer");
-        span_rows_kernel<<<(unsigned)((rows->n_rows + 3) / 4), 256, 0, st>>>(
+        const int64_t rows_per_wg = 4 * kSpanRowsPerWave;
+        span_rows_kernel<<<(unsigned)((rows->n_rows + rows_per_wg - 1) / rows_per_wg), 256, 0, st>>>(
             rows->n_rows, rows->n_uids, n_layers, rows->row_ntok, rows->row_off, rows->row_active, row_layer, mass,
             state, theta_num, theta_den, reinterpret_cast<unsigned long long*>(span_sum), span_cnt);
     }

@@ -92,6 +92,7 @@ def test_ema_ex_multi_step(oracle, pos_decay, with_mult):
     argument plus one product; the rest as in the plain update), abs floor for values that underflow;
     state bits exact."""
     from paper_2604_26968_amd import kvm
+    pos_decay = float(np.float32(pos_decay))       # the value the C ABI's float argument carries
     case = ema_case()
     dev = DeviceCase(case)
     rng = np.random.default_rng(0)
@@ -157,7 +158,7 @@ def test_ema_ex_long_row_positional_factor(oracle):
     """8,192-block rows: the factor spans 0.9995^8191 = 0.017 .. 1 and, for 0.9, underflows to 0."""
     from paper_2604_26968_amd import kvm
     case = synth.make_case(synth.Shape(1, 8, 1, 64, synth.BF16, True, [131072]), seed=2)
-    for pos_decay in (0.9995, 0.9):
+    for pos_decay in (float(np.float32(0.9995)), float(np.float32(0.9))):
         dev = DeviceCase(case)
         dev.mass.fill_(1.0)
         dev.p_hat.fill_(1.0)
@@ -249,6 +250,7 @@ def test_prefetch_keys_and_list(oracle, pos_decay):
     ~1e-7 relative); the list built by the selector from the library's own keys equals the oracle's
     selection on those same keys, and differs from the oracle's end-to-end list only at the cutoff."""
     from paper_2604_26968_amd import kvm
+    pos_decay = float(np.float32(pos_decay))
     case = prefetch_case(seed=9)
     dev = DeviceCase(case)
     rng = np.random.default_rng(2)
@@ -364,15 +366,15 @@ def test_exchange_in_place_with_slot_addressed_tier(oracle, shape):
     case.slot_tbl[:], case.state[:] = tbl, st
     dev = DeviceCase(case)
     d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
-    n = 40
+    n = 24
     res_now = np.flatnonzero(st & RES)
     outs = rng.choice(res_now, size=n, replace=False).astype(np.int64)
     ins = rng.choice(first_out, size=n, replace=False).astype(np.int64)
     outs[3] = -1
-    ins[9] = res_now[0] if res_now[0] not in outs else res_now[1]       # already resident
-    outs[20] = np.setdiff1d(first_out, ins)[0]                          # not resident (and in neither list otherwise)
+    ins[9] = np.setdiff1d(res_now, outs)[0]                              # already resident
+    outs[12] = np.setdiff1d(first_out, ins)[0]                          # not resident (and in neither list otherwise)
     bad = np.zeros(1, np.uint32)
-    for n_out_dev, n_in_dev in ((None, None), (25, 30)):
+    for n_out_dev, n_in_dev in ((None, None), (15, 22)):
         lim = n if n_out_dev is None else min(n_out_dev, n_in_dev)
         oracle.exchange(k8, v8, uk, uv, tbl, st, outs[:lim], ins[:lim], tier, n_bad=bad)
         kvm.kvm_exchange(dev.pool, dev.slot_tbl, dev.state, dev_of(outs), dev_of(ins), n, d_tier,
