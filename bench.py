@@ -302,21 +302,12 @@ def main():
         cnt, ms = kvm.kvm_timing_read(name)
         kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
     kvm.kvm_timing_reset()
-    # Dominant kernel: score_partial (the tile kernel).  Algorithmic bytes per launch: per resident unit its
-    # K frame (16 * dim * 2) and its mass (4); per block of an active row its table entry (4); per row its
-    # g queries; per block of a row that spans several tiles one float per query (the block's log-sum-exp,
-    # which the row merge reads back).  Rows of the llama8b workload all fit one 512-block tile.
+    # Dominant kernel: score_partial (the tile kernel).  Algorithmic bytes per launch = what the method has to
+    # move whatever the kernel design: per resident unit its K frame (16 * dim * 2) and its mass (4); per block
+    # of an active row its table entry (4); per row its g queries.  The per-block partial values that long rows
+    # pass from the tile kernel to the row merge are the design's own traffic and are not counted.
     n_blocks_active = n
-    if dim <= 128 and g in (1, 2, 4, 8):
-        tile_blocks = 512
-    elif dim <= 256:
-        nct = (g + 15) // 16
-        tile_blocks = 512 // (1 if nct <= 1 else 2 if nct <= 2 else 4 if nct <= 4 else 8)
-    else:
-        tile_blocks = 64
-    multi_tile_blocks = int(wl.nb[wl.nb > tile_blocks].sum())
-    algo_bytes = (scored_units * (shape.unit_k_bytes + 4) + n_blocks_active * 4 + n_rows * g * dim * 2
-                  + multi_tile_blocks * g * 4)
+    algo_bytes = scored_units * (shape.unit_k_bytes + 4) + n_blocks_active * 4 + n_rows * g * dim * 2
     sp = kernels["score_partial"]["avg_ms"]
     achieved = algo_bytes / (sp * 1e-3) / 1e9
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload

@@ -15,7 +15,7 @@ def build(verbose: bool = False) -> str:
     """Run hipcc over every source, always (no staleness check); returns the library path."""
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-pass-failed", "-I", _INCLUDE, "-I", _CSRC]
+           "-Wno-pass-failed", "-Wno-inline-asm", "-I", _INCLUDE, "-I", _CSRC]
     cmd += [os.path.join(_CSRC, s) for s in SOURCES]
     cmd += ["-o", LIB_PATH]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -590,12 +590,19 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
 // ---- score_tile_wide: wide frames (MLA latent, dim 576) scored by up to 128 queries ---
 // The 128 x dim query operands do not fit one wavefront's registers, so the four
 // wavefronts of the workgroup split the queries (32 each, two column tiles) and share the
-// unit: its frame is staged in LDS once (global -> registers -> LDS, double buffered, the
-// next unit's loads in flight while the current one is multiplied) and every wavefront
-// reads its A operands from there.  One barrier per unit.  A workgroup takes SUB consecutive
-// tiles of T blocks of its row, one after the other, so the 147 KB of query operands are
-// loaded once per SUB * T blocks.
-template <int DIM, int DT, int T, int SUB>
+// unit through LDS.  Frames travel global -> LDS directly (global_load_lds, 16 bytes per
+// lane, no staging registers) into a ring of kWideBufs buffers: while one unit is being
+// multiplied the next kWideBufs - 1 are in flight, which is what the memory latency asks for
+// at 18 KiB per unit and two workgroups per compute unit.  One barrier per unit.
+// Every wavefront issues exactly kWideDma loads and 2 stores per unit, all unconditional, so
+// that "at most N vector memory operations outstanding" identifies which frames have landed.
+// Block values go straight to part_lse (row stride 128 floats, padded queries land in the
+// padding), the tile's own log-sum-exp per query is carried in registers; score_rowmerge_big
+// finishes every row.
+constexpr int kWideBufs = 4;
+constexpr int kWideTileBlocks = 256;
+
+template <int DIM, int DT, int TB>
 __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
     const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
@@ -604,71 +611,56 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     constexpr int NK = DIM / 32;
     constexpr int UNIT_V4 = DIM * 2;
     constexpr int QROW_V4 = DIM / 8;
-    constexpr int V4_PT = (UNIT_V4 + kThreads - 1) / kThreads;    // 16-byte vectors staged per thread
-    constexpr int GP = 128;
-    extern __shared__ uint4 dyn_lds[];
-    uint4* kbuf = dyn_lds;                                         // [2][UNIT_V4]
-    float* s_lse = reinterpret_cast<float*>(kbuf + 2 * UNIT_V4);  // [T * 128]
-    TileLds<T, GP>& lds = *reinterpret_cast<TileLds<T, GP>*>(s_lse + T * GP);
+    constexpr int PER_WAVE = UNIT_V4 / 4;          // 16-byte vectors each wavefront moves per unit
+    constexpr int FULL = PER_WAVE / 64, REM = PER_WAVE % 64;
+    constexpr int DMA = FULL + (REM ? 1 : 0);      // loads per wavefront per unit
+    constexpr int OPS = DMA + 2;                   // vector memory operations per wavefront per unit
+    static_assert(UNIT_V4 % 4 == 0, "unit must split over four wavefronts");
+    __shared__ uint4 kb0[UNIT_V4];
+    __shared__ uint4 kb1[UNIT_V4];
+    __shared__ uint4 kb2[UNIT_V4];
+    __shared__ uint4 kb3[UNIT_V4];
+    __shared__ int2 s_list[TB];
+    __shared__ int s_cnt[((TB + kThreads - 1) / kThreads) * 4];
 
     if (blockIdx.x >= *n_tiles) return;
-    const TileCtx plan = tile_ctx<T * SUB>(tiles, row_ntok, row_off);
+    const TileCtx c = tile_ctx<TB>(tiles, row_ntok, row_off);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, cg = lane >> 4;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[plan.row]);
-    const bool wave_has_queries = 32 * wave < G;
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
 
     uint4 qb[2][NK];
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
         const int j = 32 * wave + ct * 16 + n;
-        const uint4* qj = qrow + (j < G ? j : 0) * QROW_V4 + cg;       // queries past g are never written out
+        const uint4* qj = qrow + (j < G ? j : 0) * QROW_V4 + cg;       // padded queries repeat query 0
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) qb[ct][kk] = qj[4 * kk];
     }
-    for (int sub = 0; sub < SUB && sub * T < plan.nbt; ++sub) {
-    TileCtx c = plan;
-    c.b0 = plan.b0 + sub * T;
-    c.nbt = min(T, plan.nbt - sub * T);
-    c.uid0 = plan.uid0 + sub * T;
-    __syncthreads();                                  // the previous sub-tile's epilogue is done with s_lse
-    for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_lse[i] = -INFINITY;
-    const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
-    if (n_res == 0) continue;                         // uniform
-
-    // One unit in flight per workgroup besides the one being multiplied.  The fetch is
-    // unconditional (past the list end it re-reads the last unit) so that no branch surrounds it.
-    // (A second register set for a deeper prefetch measured no faster: the kernel is at its
-    // register limit with the 144 query-operand registers.)
-    uint4 st[V4_PT];
-    auto fetch = [&](int idx) {
-        const int2 e = list_entry(lds.list, idx < n_res ? idx : n_res - 1);
-        const v4u_t* p = reinterpret_cast<const v4u_t*>(k_pool + (size_t)(uint32_t)e.y * UNIT_V4);
+    const int n_res = build_unit_list<TB>(slot_tbl, c.uid0, c.nbt, n_slots, s_list, s_cnt);
+    MZ run[2] = {{-INFINITY, 0.f}, {-INFINITY, 0.f}};
+    if (n_res > 0) {                                  // uniform
+        // global -> LDS, 16 bytes per lane, LDS destination = m0 + 16 * lane.  Written as asm so that
+        // the waits stay under this kernel's control (see the wait counts below).
+        auto dma_op = [&](const uint4* src, uint4* dst) {
+            const uint32_t lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4*)dst;
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt"
+                         :
+                         : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds))
+                         : "memory", "m0");
+        };
+        auto dma = [&](uint4* buf, int idx) {
+            const int2 e = list_entry(s_list, idx < n_res ? idx : n_res - 1);
+            const uint4* src = k_pool + (size_t)(uint32_t)e.y * UNIT_V4 + wave * PER_WAVE + lane;
+            uint4* dst = buf + wave * PER_WAVE;
 #pragma unroll
-        for (int i = 0; i < V4_PT; ++i) {
-            const int v = min((int)threadIdx.x + kThreads * i, UNIT_V4 - 1);
-            const v4u_t x = __builtin_nontemporal_load(p + v);
-            st[i] = make_uint4(x.x, x.y, x.z, x.w);
-        }
-    };
-    auto stage = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < V4_PT; ++i) {
-            const int v = threadIdx.x + kThreads * i;
-            if (v < UNIT_V4) kbuf[buf * UNIT_V4 + v] = st[i];
-        }
-    };
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    for (int idx = 0; idx < n_res; ++idx) {
-        const int i_cur = list_entry(lds.list, idx).x;
-        fetch(idx + 1);
-        if (wave_has_queries) {
-            const uint4* kb = kbuf + (idx & 1) * UNIT_V4 + lane;
+            for (int i = 0; i < FULL; ++i) dma_op(src + 64 * i, dst + 64 * i);
+            if (REM && lane < REM) dma_op(src + 64 * FULL, dst + 64 * FULL);
+        };
+        auto compute = [&](const uint4* buf, int idx) {
+            const int i_cur = list_entry(s_list, idx).x;
+            const uint4* kb = buf + lane;
             f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-            // A operands come from LDS a few k-steps ahead of their use, so that the LDS latency
-            // is paid once per unit and not once per k-step
             constexpr int AHEAD = 4;
             uint4 a[AHEAD];
 #pragma unroll
@@ -680,6 +672,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
                 acc[1] = mfma16<DT>(a[kk % AHEAD], qb[1][kk], acc[1]);
             }
             const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));
+            float* pl = out.part_lse + (size_t)(c.uid0 + i_cur) * 128 + 32 * wave + n;
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
                 float z[4];
@@ -690,19 +683,53 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
                     mx = fmaxf(mx, z[r]);
                 }
                 mx = rows4_max(mx);
-                float s = 0.f;
+                float sm = 0.f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) s += __expf(z[r] - mx);
-                s = rows4_sum(s);
-                const int j = 32 * wave + ct * 16 + n;
-                if (cg == 0 && j < G) s_lse[i_cur * G + j] = mx + __logf(s);
+                for (int r = 0; r < 4; ++r) sm += __expf(z[r] - mx);
+                sm = rows4_sum(sm);
+                if (cg == 0) pl[ct * 16] = mx + __logf(sm);
+                run[ct] = mz_combine(run[ct], MZ{mx, sm});
             }
-        }
-        // buffer (idx + 1) & 1 was last read in iteration idx - 1, which every wavefront has left
-        stage((idx + 1) & 1);
-        __syncthreads();
+        };
+        // vmcnt(N): at most N vector memory operations of this wavefront still outstanding.  Behind
+        // the loads of unit idx sit, in issue order, the rest of iteration idx - 3 (2 stores) and the
+        // whole of iterations idx - 2 and idx - 1: 2 + 2 * OPS operations.
+        constexpr int LAG = 2 + 2 * OPS;
+        static_assert(kWideBufs == 4 && LAG < 64, "wait count assumes three units in flight");
+        dma(kb0, 0);
+        dma(kb1, 1);
+        dma(kb2, 2);
+        // the first three iterations have fewer operations behind the loads they wait for
+        constexpr int W0 = 2 * DMA, W1 = 2 * DMA + 2, W2 = 2 * DMA + 4;
+        int idx = 0;
+#define KVM_VMCNT(N) (((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
+#define KVM_WIDE_STEP(CUR, TGT, N)                       \
+    if (idx < n_res) {                                   \
+        __builtin_amdgcn_s_waitcnt(KVM_VMCNT(N));        \
+        __syncthreads();                                 \
+        dma(TGT, idx + 3);                               \
+        compute(CUR, idx);                               \
+        ++idx;                                           \
     }
-    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, (size_t)blockIdx.x * SUB + sub, out);
+        KVM_WIDE_STEP(kb0, kb3, W0)
+        KVM_WIDE_STEP(kb1, kb0, W1)
+        KVM_WIDE_STEP(kb2, kb1, W2)
+        KVM_WIDE_STEP(kb3, kb2, LAG)
+        while (idx < n_res) {
+            KVM_WIDE_STEP(kb0, kb3, LAG)
+            KVM_WIDE_STEP(kb1, kb0, LAG)
+            KVM_WIDE_STEP(kb2, kb1, LAG)
+            KVM_WIDE_STEP(kb3, kb2, LAG)
+        }
+#undef KVM_VMCNT
+#undef KVM_WIDE_STEP
+    }
+    if (cg == 0) {
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+            const int j = 32 * wave + ct * 16 + n;
+            if (j < G) out.tile_lse[(size_t)blockIdx.x * G + j] = mz_lse(run[ct]);
+        }
     }
 }
 
@@ -754,6 +781,73 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
             const int b = k * BS + bsub;
             if (j == 0 && b < nbt && (uint32_t)slot[k] < n_slots)
                 o.mass[uid0 + b] = o.agg == KVM_AGG_MAX ? v[k] : v[k] / (float)g;
+        }
+    }
+}
+
+// The same for groups of more than 64 queries (g <= 128).  There a block's values fill 512
+// bytes, so a wavefront takes a whole resident block (two coalesced loads, the group
+// aggregate is a plain wavefront reduction, no LDS exchange) and blocks that are not resident
+// are never read: the workgroup first compacts the resident blocks of its tile into a list.
+template <int TB /* blocks per workgroup = plan tile */, int T /* blocks per statistic tile */,
+          bool ALL /* also rows of a single tile; block values then have a row stride of 128 floats */>
+__global__ __launch_bounds__(kThreads) void score_rowmerge_big_kernel(
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int g,
+    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
+    const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
+    constexpr int SUB = TB / T;
+    __shared__ int2 s_list[TB];
+    __shared__ int s_cnt[((TB + kThreads - 1) / kThreads) * 4];
+    __shared__ float2 s_mz[kThreads];
+    __shared__ float s_rowlse[128];
+    if (blockIdx.x >= *n_tiles) return;
+    const TileCtx plan = tile_ctx<TB>(tiles, row_ntok, row_off);
+    if (!ALL && plan.nb <= T) return;                // finished by its tile
+    const int gs = ALL ? 128 : g;                    // row stride of the block values
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_res = build_unit_list<TB>(slot_tbl, plan.uid0, plan.nbt, n_slots, s_list, s_cnt);
+    // Row log-sum-exp per query, once per workgroup: thread (half, j) folds every second tile value
+    // of query j, the two halves meet in LDS; then every lane picks up its two queries (lane, lane + 64).
+    const float* tl = o.tile_lse + (size_t)row_tile0[plan.row] * SUB * g;
+    const int n_t = (plan.nb + T - 1) / T;
+    {
+        const int j = threadIdx.x & 127, half = threadIdx.x >> 7;
+        MZ t{-INFINITY, 0.f};
+        if (j < g)
+            for (int i = half; i < n_t; i += 2) t = mz_combine(t, MZ{tl[i * g + j], 1.f});
+        s_mz[threadIdx.x] = make_float2(t.m, t.z);
+        __syncthreads();
+        if (threadIdx.x < 128) {
+            const float2 x = s_mz[threadIdx.x], y = s_mz[threadIdx.x + 128];
+            s_rowlse[threadIdx.x] = mz_lse(mz_combine(MZ{x.x, x.y}, MZ{y.x, y.y}));
+        }
+        __syncthreads();
+    }
+    const bool v0 = lane < g, v1 = lane + 64 < g;
+    const float lse0 = s_rowlse[lane], lse1 = s_rowlse[lane + 64];
+    constexpr int U = 8;                             // resident blocks in flight per wavefront
+    for (int idx = wave; idx < n_res; idx += 4 * U) {
+        float a[U], b[U];
+        int blk[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = idx + 4 * u;
+            blk[u] = list_entry(s_list, i < n_res ? i : n_res - 1).x;
+            const float* pl = o.part_lse + (size_t)(plan.uid0 + blk[u]) * gs;
+            a[u] = pl[v0 ? lane : 0];
+            b[u] = pl[v1 ? lane + 64 : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float e0 = v0 ? __expf(a[u] - lse0) : 0.f, e1 = v1 ? __expf(b[u] - lse1) : 0.f;
+            float r = o.agg == KVM_AGG_MAX ? fmaxf(e0, e1) : e0 + e1;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const float x = __shfl_xor(r, d);
+                r = o.agg == KVM_AGG_MAX ? fmaxf(r, x) : r + x;
+            }
+            if (lane == 0 && idx + 4 * u < n_res)
+                o.mass[plan.uid0 + blk[u]] = o.agg == KVM_AGG_MAX ? r : r / (float)g;
         }
     }
 }
@@ -848,8 +942,6 @@ __global__ __launch_bounds__(kThreads) void score_finalize_kernel(
 }
 
 // ---- host side ----------------------------------------------------------------
-constexpr int kWideTile = 64;
-constexpr int kWideSub = 4;
 enum class Path { Dot2, Mfma, Wide, Generic };
 
 struct Choice {
@@ -868,7 +960,7 @@ Choice choose(int g, int dim) {
         const int nct_p = nct <= 1 ? 1 : nct <= 2 ? 2 : nct <= 4 ? 4 : 8;
         return Choice{Path::Mfma, 512 / nct_p, 1, nct_p};
     }
-    if (dim == 576) return Choice{Path::Wide, kWideTile * kWideSub, kWideSub, 0};
+    if (dim == 576) return Choice{Path::Wide, kWideTileBlocks, 1, 0};
     return Choice{Path::Generic, kGenericTile, 1, 0};
 }
 
@@ -903,7 +995,9 @@ ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, int tile_bloc
     w.row_tile0 = reinterpret_cast<uint32_t*>(base + off_row0);
     w.tile_lse = reinterpret_cast<float*>(base + off_tmz);
     w.part = reinterpret_cast<float2*>(base + off_part);
-    w.bytes = off_part + align_up((size_t)n_uids * (size_t)g * sizeof(float2), 256);
+    // (m, s) pairs per (unit, query) on the generic path; floats with a row stride of up to 128 on the tile paths
+    const size_t per_uid = (size_t)(g > 64 ? g : 64) * sizeof(float2);
+    w.bytes = off_part + align_up((size_t)n_uids * per_uid, 256);
     return w;
 }
 
@@ -922,6 +1016,12 @@ struct ScoreArgs {
 template <int GP, int T, int SUB = 1>
 int launch_rowmerge(const ScoreArgs& a) {
     TimedLaunch tl("score_finalize", a.st);
+    if constexpr (GP > 64) {
+        score_rowmerge_big_kernel<T * SUB, T, false><<<a.grid, kThreads, 0, a.st>>>(
+            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
+            (uint32_t)a.pool->n_slots, a.out);
+        return launch_status("score_rowmerge_big");
+    }
     score_rowmerge_kernel<GP, T, SUB><<<a.grid, kThreads, 0, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok,
                                                                a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
                                                                (uint32_t)a.pool->n_slots, a.out);
@@ -958,20 +1058,20 @@ int launch_mfma_path(const ScoreArgs& a) {
 // Wide frames (dim 576): workgroup-cooperative matrix-core kernel.
 template <int DIM, int DT>
 int launch_wide_path(const ScoreArgs& a) {
-    constexpr int T = kWideTile;
-    const size_t lds = 2 * (size_t)DIM * 2 * sizeof(uint4) + (size_t)T * 128 * sizeof(float) + sizeof(TileLds<T, 128>);
-    auto kern = score_tile_wide_kernel<DIM, DT, T, kWideSub>;
-    KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)lds));
+    constexpr int TB = kWideTileBlocks;
     {
         TimedLaunch tl("score_partial", a.st);
-        kern<<<a.grid, kThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off,
-                                              a.rows->row_q_off, a.rows->slot_tbl,
-                                              static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
-                                              static_cast<const uint16_t*>(a.q), a.scale, a.out);
+        score_tile_wide_kernel<DIM, DT, TB><<<a.grid, kThreads, 0, a.st>>>(
+            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off,
+            a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
+            static_cast<const uint16_t*>(a.q), a.scale, a.out);
         if (int rc = launch_status("score_tile_wide")) return rc;
     }
-    return launch_rowmerge<128, T, kWideSub>(a);
+    TimedLaunch tl("score_finalize", a.st);
+    score_rowmerge_big_kernel<TB, TB, true><<<a.grid, kThreads, 0, a.st>>>(
+        a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
+        (uint32_t)a.pool->n_slots, a.out);
+    return launch_status("score_rowmerge_big");
 }
 
 // Any g and dim: queries staged in LDS, vector dot products, (m, s) pairs through global memory.
