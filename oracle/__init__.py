@@ -230,6 +230,58 @@ def exchange(k_pool, v_pool, unit_k_bytes, unit_v_bytes, slot_tbl, state, out_ui
     _check(rc, "kvm_ref_exchange")
 
 
+def sha256(msg: bytes) -> bytes:
+    a = np.frombuffer(msg, np.uint8).copy() if len(msg) else np.zeros(1, np.uint8)
+    out = np.zeros(32, np.uint8)
+    _check(lib().kvm_ref_sha256(_p(a, np.uint8), C.c_uint64(len(msg)), _p(out, np.uint8)), "kvm_ref_sha256")
+    return out.tobytes()
+
+
+def hash_units(k_pool, v_pool, unit_k_bytes, unit_v_bytes, slot_tbl, state, uids, n_bad=None):
+    """Returns uint8 [n, 32]."""
+    n = len(uids)
+    digests = np.zeros((max(n, 1), 32), np.uint8)
+    n_slots = k_pool.size // unit_k_bytes
+    rc = lib().kvm_ref_hash_units(
+        _p(k_pool.reshape(-1), np.uint8), _p(None if v_pool is None else v_pool.reshape(-1), np.uint8),
+        C.c_uint64(n_slots), C.c_uint32(unit_k_bytes), C.c_uint32(unit_v_bytes),
+        _p(slot_tbl, np.int32), _p(state, np.uint8), C.c_int64(len(state)),
+        _p(uids, np.int64), C.c_int64(n), _p(digests.reshape(-1), np.uint8), _p(n_bad, np.uint32))
+    _check(rc, "kvm_ref_hash_units")
+    return digests[:n]
+
+
+class DedupStore:
+    """The oracle's store: a list of (digest, canonical uid, references)."""
+
+    def __init__(self, cap):
+        self.digest = np.zeros((cap, 32), np.uint8)
+        self.canon = np.full(cap, -1, np.int64)
+        self.refs = np.zeros(cap, np.uint32)
+        self.n = np.zeros(1, np.int64)
+        self.cap = cap
+
+    def insert(self, digests, uids):
+        n = len(uids)
+        out = np.zeros(max(n, 1), np.int64)
+        rc = lib().kvm_ref_dedup_insert(
+            _p(self.digest.reshape(-1), np.uint8), _p(self.canon, np.int64), _p(self.refs, np.uint32),
+            _p(self.n, np.int64), C.c_int64(self.cap), _p(np.ascontiguousarray(digests).reshape(-1), np.uint8),
+            _p(uids, np.int64), C.c_int64(n), _p(out, np.int64))
+        _check(rc, "kvm_ref_dedup_insert")
+        return out[:n]
+
+    def release(self, digests, n_bad=None):
+        rc = lib().kvm_ref_dedup_release(
+            _p(self.digest.reshape(-1), np.uint8), _p(self.refs, np.uint32), C.c_int64(int(self.n[0])),
+            _p(np.ascontiguousarray(digests).reshape(-1), np.uint8), C.c_int64(len(digests)), _p(n_bad, np.uint32))
+        _check(rc, "kvm_ref_dedup_release")
+
+    def as_dict(self):
+        """digest bytes -> (canonical uid, references)."""
+        return {self.digest[e].tobytes(): (int(self.canon[e]), int(self.refs[e])) for e in range(int(self.n[0]))}
+
+
 def decode(bits: int, dtype: int) -> float:
     f = lib().kvm_ref_decode
     f.restype = C.c_double

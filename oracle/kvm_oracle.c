@@ -33,6 +33,9 @@
  *                           decode position, ranked with the reuse estimate of section 3.3
  *   kvm_ref_pack / unpack   section 3.2 (tier 0 <-> tier 1 moves), as memcpy
  *   kvm_ref_exchange        the same as an in-place trade with a slot-addressed host tier
+ *   kvm_ref_sha256, kvm_ref_hash_units, kvm_ref_dedup_insert / release
+ *                           section 3.6: content addressing by SHA-256 (FIPS 180-4), store with
+ *                           reference counts
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * (paper tables, closed forms, library routines, brute force); none is
@@ -625,6 +628,163 @@ int kvm_ref_exchange(uint8_t* k_pool, uint8_t* v_pool, uint64_t n_slots,
         state[ui] = (uint8_t)((state[ui] & ~ST_ON_HOST) | ST_RESIDENT);
     }
     free(tmp);
+    return REF_OK;
+}
+
+/* --------------------------------------------- content-addressed dedup */
+
+/* SHA-256 as FIPS 180-4 defines it.  The round constants and the initial hash value are
+ * derived here from their definition (section 4.2.2: first 32 bits of the fractional parts
+ * of the cube roots of the first 64 primes; section 5.3.3: of the square roots of the first
+ * 8 primes) with exact integer arithmetic, not typed in. */
+static uint32_t sha_k[64], sha_h0[8];
+static int sha_ready = 0;
+
+static uint64_t int_root(unsigned __int128 x, int r) {      /* floor(x^(1/r)), r = 2 or 3 */
+    uint64_t lo = 0, hi = (uint64_t)1 << 40;
+    while (hi - lo > 1) {
+        const uint64_t mid = lo + (hi - lo) / 2;
+        unsigned __int128 p = (unsigned __int128)mid * mid;
+        if (r == 3) p *= mid;
+        if (p <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+static void sha_init(void) {
+    int found = 0;
+    for (int c = 2; found < 64; ++c) {
+        int prime = 1;
+        for (int d = 2; d * d <= c; ++d) if (c % d == 0) { prime = 0; break; }
+        if (!prime) continue;
+        /* floor(c^(1/3) * 2^32) = floor((c * 2^96)^(1/3)); its low 32 bits are the fraction's first 32 bits */
+        sha_k[found] = (uint32_t)int_root((unsigned __int128)c << 96, 3);
+        if (found < 8) sha_h0[found] = (uint32_t)int_root((unsigned __int128)c << 64, 2);
+        ++found;
+    }
+    sha_ready = 1;
+}
+
+static uint32_t rotr32(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
+
+static void sha_block(uint32_t h[8], const uint8_t* blk) {
+    uint32_t w[64];
+    for (int t = 0; t < 16; ++t)
+        w[t] = ((uint32_t)blk[4 * t] << 24) | ((uint32_t)blk[4 * t + 1] << 16) | ((uint32_t)blk[4 * t + 2] << 8) | blk[4 * t + 3];
+    for (int t = 16; t < 64; ++t) {
+        const uint32_t s0 = rotr32(w[t - 15], 7) ^ rotr32(w[t - 15], 18) ^ (w[t - 15] >> 3);
+        const uint32_t s1 = rotr32(w[t - 2], 17) ^ rotr32(w[t - 2], 19) ^ (w[t - 2] >> 10);
+        w[t] = s1 + w[t - 7] + s0 + w[t - 16];
+    }
+    uint32_t a = h[0], b = h[1], c = h[2], d = h[3], e = h[4], f = h[5], g = h[6], hh = h[7];
+    for (int t = 0; t < 64; ++t) {
+        const uint32_t S1 = rotr32(e, 6) ^ rotr32(e, 11) ^ rotr32(e, 25);
+        const uint32_t ch = (e & f) ^ (~e & g);
+        const uint32_t t1 = hh + S1 + ch + sha_k[t] + w[t];
+        const uint32_t S0 = rotr32(a, 2) ^ rotr32(a, 13) ^ rotr32(a, 22);
+        const uint32_t maj = (a & b) ^ (a & c) ^ (b & c);
+        const uint32_t t2 = S0 + maj;
+        hh = g; g = f; f = e; e = d + t1; d = c; c = b; b = a; a = t1 + t2;
+    }
+    h[0] += a; h[1] += b; h[2] += c; h[3] += d; h[4] += e; h[5] += f; h[6] += g; h[7] += hh;
+}
+
+/* Digest of msg_a followed by msg_b (either may be empty). */
+static void sha256_two(const uint8_t* a, size_t na, const uint8_t* b, size_t nb, uint8_t out[32]) {
+    if (!sha_ready) sha_init();
+    uint32_t h[8];
+    memcpy(h, sha_h0, sizeof h);
+    uint8_t buf[64];
+    size_t fill = 0;
+    const uint64_t total = (uint64_t)na + nb;
+    for (size_t i = 0; i < na + nb; ++i) {
+        buf[fill++] = i < na ? a[i] : b[i - na];
+        if (fill == 64) { sha_block(h, buf); fill = 0; }
+    }
+    buf[fill++] = 0x80;                                      /* padding: 1 bit, zeros, 64-bit length */
+    if (fill > 56) { while (fill < 64) buf[fill++] = 0; sha_block(h, buf); fill = 0; }
+    while (fill < 56) buf[fill++] = 0;
+    for (int i = 0; i < 8; ++i) buf[56 + i] = (uint8_t)((total * 8) >> (56 - 8 * i));
+    sha_block(h, buf);
+    for (int i = 0; i < 8; ++i) {
+        out[4 * i] = (uint8_t)(h[i] >> 24); out[4 * i + 1] = (uint8_t)(h[i] >> 16);
+        out[4 * i + 2] = (uint8_t)(h[i] >> 8); out[4 * i + 3] = (uint8_t)h[i];
+    }
+}
+
+int kvm_ref_sha256(const uint8_t* msg, uint64_t len, uint8_t* out) {
+    if ((!msg && len) || !out) return REF_EINVAL;
+    sha256_two(msg, (size_t)len, NULL, 0, out);
+    return REF_OK;
+}
+
+/* Section 3.6: blocks are indexed by the SHA-256 of their content.  The content of a unit is
+ * its record: K frame followed by V frame.  Units that are not in HBM (or malformed uids) get
+ * an all-zero digest and are counted in *n_bad. */
+int kvm_ref_hash_units(const uint8_t* k_pool, const uint8_t* v_pool, uint64_t n_slots,
+                       uint32_t unit_k_bytes, uint32_t unit_v_bytes,
+                       const int32_t* slot_tbl, const uint8_t* state, int64_t n_uids,
+                       const int64_t* uids, int64_t n, uint8_t* digests, uint32_t* n_bad) {
+    if (!k_pool || (unit_v_bytes && !v_pool) || !slot_tbl || !state || n < 0) return REF_EINVAL;
+    if (n > 0 && (!uids || !digests)) return REF_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t uid = uids[i];
+        if (uid < 0 || uid >= n_uids || !(state[uid] & ST_RESIDENT) || slot_tbl[uid] < 0 ||
+            (uint64_t)slot_tbl[uid] >= n_slots) {
+            memset(digests + 32 * i, 0, 32);
+            if (n_bad) ++*n_bad;
+            continue;
+        }
+        const size_t slot = (size_t)slot_tbl[uid];
+        sha256_two(k_pool + slot * unit_k_bytes, unit_k_bytes,
+                   unit_v_bytes ? v_pool + slot * unit_v_bytes : NULL, unit_v_bytes, digests + 32 * i);
+    }
+    return REF_OK;
+}
+
+/* Section 3.6: "its hash is checked against the store; on a match, a reference count is
+ * incremented instead of duplicating the block".  The store here is a plain list searched
+ * from the front: entry e holds a digest, the uid that first brought it (the canonical
+ * copy) and the number of references.  Items are taken in list order, so within one call
+ * the first occurrence of a new digest becomes canonical.  An entry whose count has dropped
+ * to zero (kvm_ref_dedup_release) is revived by the next insert of its digest, which becomes
+ * the new canonical copy.  canon_out[i] = canonical uid of item i (== uids[i] when item i is
+ * not a duplicate).  Returns REF_EINVAL when the list is full. */
+int kvm_ref_dedup_insert(uint8_t* st_digest, int64_t* st_canon, uint32_t* st_refs, int64_t* st_n, int64_t st_cap,
+                         const uint8_t* digests, const int64_t* uids, int64_t n, int64_t* canon_out) {
+    if (!st_digest || !st_canon || !st_refs || !st_n || n < 0 || (n > 0 && (!digests || !uids || !canon_out)))
+        return REF_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t e = 0;
+        while (e < *st_n && memcmp(st_digest + 32 * e, digests + 32 * i, 32) != 0) ++e;
+        if (e == *st_n) {
+            if (*st_n >= st_cap) return REF_EINVAL;
+            memcpy(st_digest + 32 * e, digests + 32 * i, 32);
+            st_canon[e] = uids[i];
+            st_refs[e] = 1;
+            ++*st_n;
+        } else if (st_refs[e] == 0) {
+            st_canon[e] = uids[i];
+            st_refs[e] = 1;
+        } else {
+            st_refs[e] += 1;
+        }
+        canon_out[i] = st_canon[e];
+    }
+    return REF_OK;
+}
+
+/* One reference less for each digest in the list (unknown digests and counts already at zero
+ * are counted in *n_bad). */
+int kvm_ref_dedup_release(const uint8_t* st_digest, uint32_t* st_refs, int64_t st_n,
+                          const uint8_t* digests, int64_t n, uint32_t* n_bad) {
+    if (!st_digest || !st_refs || n < 0 || (n > 0 && !digests)) return REF_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t e = 0;
+        while (e < st_n && memcmp(st_digest + 32 * e, digests + 32 * i, 32) != 0) ++e;
+        if (e == st_n || st_refs[e] == 0) { if (n_bad) ++*n_bad; continue; }
+        st_refs[e] -= 1;
+    }
     return REF_OK;
 }
 

@@ -360,6 +360,38 @@ __device__ __forceinline__ void for_each_unit(const int2* s_list, int n_res, con
     }
 }
 
+// The same with two units in flight per wavefront besides the one being consumed (three
+// register sets, the loop unrolled three times so that no set is ever copied).  More bytes in
+// flight per compute unit for kernels whose register budget allows it.
+template <int NK, class UnitFn>
+__device__ __forceinline__ void for_each_unit_deep(const int2* s_list, int n_res, const uint4* __restrict__ k_pool,
+                                                   int unit_v4, UnitFn unit) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint4 b0[NK], b1[NK], b2[NK];
+    int i0, i1, i2;
+    auto fetch = [&](uint4 (&dst)[NK], int idx) -> int {
+        const int2 e = list_entry(s_list, idx < n_res ? idx : n_res - 1);
+        load_unit<NK>(dst, k_pool, (uint32_t)e.y, unit_v4, lane);
+        return idx < n_res ? e.x : -1;
+    };
+    int idx = wave;
+    if (idx >= n_res) return;
+    i0 = fetch(b0, idx);
+    i1 = fetch(b1, idx + 4);
+    while (true) {
+        i2 = fetch(b2, idx + 8);
+        unit(b0, i0);
+        if (i1 < 0) break;
+        i0 = fetch(b0, idx + 12);
+        unit(b1, i1);
+        if (i2 < 0) break;
+        i1 = fetch(b1, idx + 16);
+        unit(b2, i2);
+        if (i0 < 0) break;
+        idx += 12;
+    }
+}
+
 // Where a tile kernel leaves its results.
 struct TileOut {
     int agg;
@@ -501,7 +533,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) return;                      // nothing resident in this tile (uniform)
 
-    for_each_unit<NK>(lds.list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
+    for_each_unit_deep<NK>(lds.list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
         const bool valid = t < min(16, c.ntok - 16 * (c.b0 + i_cur));
         // four queries at a time: each 16-lane row ends up owning one of them
 #pragma unroll
