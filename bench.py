@@ -141,6 +141,11 @@ def main():
         pf_key = torch.zeros(n, dtype=torch.float32, device=dev)
         pf_cand = torch.zeros(n, dtype=torch.uint8, device=dev)
         n_pf = torch.zeros(1, dtype=torch.int64, device=dev)
+        swap_units = args.swap_units or w_swap
+        store = kvm.make_store(1 << 22)
+        digests = torch.zeros((swap_units, 32), dtype=torch.uint8, device=dev)
+        canon = torch.zeros(swap_units, dtype=torch.int64, device=dev)
+        dedup_ws = torch.zeros(swap_units, dtype=torch.int64, device=dev)
 
     def management_pass(i, k_arg, budget_arg):
         ev = evs[i % n_q_sets]
@@ -213,6 +218,9 @@ def main():
         kvm.kvm_select_victims(pf_key, pf_cand, pf_list, n_pf, ws, k=swap)
         kvm.kvm_exchange(pool, wl.slot_tbl, wl.state, step_victims, pf_list, swap, host_tier, n_out_dev=n_victims,
                          n_in_dev=n_pf, n_bad=n_bad)
+        # content addressing of the units that just entered HBM (stands in for newly allocated blocks)
+        kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, pf_list, swap, digests)
+        kvm.kvm_dedup_insert(store, digests, pf_list, swap, canon, dedup_ws)
 
     def step_serial(i):
         """One full pass, everything in line on one stream.  Resident units at entry: budget + swap."""
@@ -298,7 +306,7 @@ def main():
 
     kernels = {}
     for name in ("score_plan", "score_partial", "score_finalize", "ema_prio", "beta", "select_hist", "select_emit",
-                 "pack", "unpack", "swap", "span", "prefetch_keys"):
+                 "pack", "unpack", "swap", "span", "prefetch_keys", "hash", "dedup"):
         cnt, ms = kvm.kvm_timing_read(name)
         kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
     kvm.kvm_timing_reset()
@@ -339,6 +347,21 @@ def main():
                   "bulk_pack_units_per_s": round(k0 / t_bulk_pack, 1)},
         "setup_s": round(setup_s, 1),
     }
+
+    if args.refined:
+        # bulk hashing rate (checkpoint-style pass over many units): integer-ALU bound, one lane per unit
+        n_bulk = min(1 << 18, budget)
+        bulk_uids = torch.nonzero(wl.state & 1).flatten()[:n_bulk].contiguous()
+        bulk_digests = torch.zeros((n_bulk, 32), dtype=torch.uint8, device=dev)
+        kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, bulk_uids, n_bulk, bulk_digests)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, bulk_uids, n_bulk, bulk_digests)
+        torch.cuda.synchronize()
+        t_hash = time.perf_counter() - t0
+        out["hash_bulk"] = {"units": n_bulk, "ms": round(t_hash * 1e3, 3),
+                            "GBps": round(n_bulk * rec / t_hash / 1e9, 1)}
+        del bulk_uids, bulk_digests
 
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)

@@ -417,6 +417,59 @@ int kvm_prefetch_keys(const kvm_rows_t* rows, const int32_t* row_layer /* dev [n
                       float* key /* dev [n_uids] out */, uint8_t* cand /* dev [n_uids] out */, void* stream);
 
 /* ======================================================================== *
+ * 7. Content addressing — section 3.6.
+ *
+ * kvm_hash_units: digests[i] = SHA-256 (FIPS 180-4) of the record of uids[i],
+ * i.e. of its K frame followed by its V frame, 32 bytes in the standard's byte
+ * order.  A uid that is out of range or not RESIDENT gets an all-zero digest
+ * and is counted in *n_bad.  One lane hashes one unit (the hash is a serial
+ * chain over the record), so the call wants thousands of units to fill the
+ * chip; it is bound by integer ALU work (about 30 operations per byte).
+ * Errors: KVM_EINVAL, KVM_ESHAPE (unit sizes not multiples of 64).           */
+int kvm_hash_units(const kvm_pool_t* pool, const int32_t* slot_tbl /* dev */, const uint8_t* state /* dev */,
+                   int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n,
+                   uint8_t* digests /* dev [n][32] out, 4-byte aligned */,
+                   uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+/* The store: "its hash is checked against the store; on a match, a reference
+ * count is incremented instead of duplicating the block".  An open-addressing
+ * table in device memory, all arrays caller-allocated with `cap` entries (cap a
+ * power of two, kept at most half full by the caller) and initialised once to
+ * tag = 0, canon = -1, refs = 0, pending = 0xFFFFFFFF.  It is keyed by the first
+ * 64 bits of the digest; every match is confirmed on all 256 bits.
+ *
+ * kvm_dedup_insert, items taken as if one after the other in list order:
+ *   digest not in the store (or its count is 0): the item becomes the canonical
+ *   copy, count = 1;  otherwise count += 1.
+ *   canon_out[i] = uid of the canonical copy (== uids[i]: item i is not a duplicate).
+ * So within one call the first occurrence of a new digest is the canonical one.
+ * All-zero digests are skipped (canon_out = own uid).  *n_full counts items
+ * that found no place (table too full: they stay unique and uncounted),
+ * *n_collide items whose 64-bit key met a different digest (they stay unique);
+ * with either non-zero the outcome depends on arrival order, otherwise it is
+ * the sequential definition exactly.  Entries are never removed; a count that
+ * kvm_dedup_release brought to 0 is revived by the next insert of its digest.
+ * ws: dev scratch, 8 * n bytes, 8-byte aligned.
+ * kvm_dedup_release: count -= 1 for each digest; unknown digests and counts
+ * already at 0 are counted in *n_bad.
+ * Errors: KVM_EINVAL (null pointers, cap not a power of two, n out of range),
+ * KVM_ENOSPC (ws).                                                          */
+typedef struct {
+    uint64_t* tag;       /* dev [cap]      first 8 digest bytes, 0 = empty              */
+    uint8_t*  digest;    /* dev [cap][32]  digest of the canonical copy                 */
+    int64_t*  canon;     /* dev [cap]      uid of the canonical copy, -1 = none yet     */
+    uint32_t* refs;      /* dev [cap]      reference count                              */
+    uint32_t* pending;   /* dev [cap]      scratch between the passes of one insert     */
+    uint64_t  cap;
+} kvm_store_t;
+int kvm_dedup_insert(const kvm_store_t* store /* host struct of dev pointers */,
+                     const uint8_t* digests /* dev [n][32] */, const int64_t* uids /* dev [n] */, int64_t n,
+                     int64_t* canon_out /* dev [n] out */, uint32_t* n_full /* dev [1] in/out, or NULL */,
+                     uint32_t* n_collide /* dev [1] in/out, or NULL */, void* ws, size_t ws_bytes, void* stream);
+int kvm_dedup_release(const kvm_store_t* store, const uint8_t* digests /* dev [n][32] */, int64_t n,
+                      uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+/* ======================================================================== *
  * Helpers
  * ======================================================================== */
 #define KVM_OP_SCORE  0
@@ -437,7 +490,7 @@ const char* kvm_version(void);
  * returns the launch count (0 if the name is unknown); *total_ms gets the sum.
  * Names: "score_partial", "score_finalize", "score_plan", "ema_prio",
  * "beta", "select_hist", "select_emit", "pack", "unpack", "swap", "span",
- * "prefetch_keys".                                                          */
+ * "prefetch_keys", "hash", "dedup".                                         */
 int  kvm_timing_enable(int on);
 void kvm_timing_reset(void);
 int  kvm_timing_read(const char* name, double* total_ms);

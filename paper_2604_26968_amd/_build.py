@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libkvm.so")
-SOURCES = ["kvm_util.hip", "kvm_score.hip", "kvm_state.hip", "kvm_select.hip", "kvm_pack.hip", "kvm_prefetch.hip"]
+SOURCES = ["kvm_util.hip", "kvm_score.hip", "kvm_state.hip", "kvm_select.hip", "kvm_pack.hip", "kvm_prefetch.hip", "kvm_dedup.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -25,7 +25,7 @@ OP_SCORE, OP_SELECT = 0, 1
 
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
-           "kvm_prefetch_keys", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
+           "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
            "kvm_timing_enable", "kvm_timing_reset", "kvm_timing_read"]
 
 
@@ -67,6 +67,11 @@ class EmaEx(C.Structure):
                 ("head_mult", C.c_void_p)]
 
 
+class Store(C.Structure):
+    _fields_ = [("tag", C.c_void_p), ("digest", C.c_void_p), ("canon", C.c_void_p), ("refs", C.c_void_p),
+                ("pending", C.c_void_p), ("cap", C.c_uint64)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run __graft_entry__.build() (hipcc) first")
@@ -104,6 +109,11 @@ def _load() -> C.CDLL:
                                       C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_exchange.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+    lib.kvm_hash_units.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                   C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvm_dedup_insert.argtypes = [C.POINTER(Store), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.kvm_dedup_release.argtypes = [C.POINTER(Store), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
     return lib
 
@@ -281,6 +291,37 @@ def kvm_exchange(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, host_ti
                             _ptr(out_uids, torch.int64), _ptr(in_uids, torch.int64), n, _ptr(n_out_dev, torch.int64),
                             _ptr(n_in_dev, torch.int64), _ptr(host_tier, None, "cpu"), _nbytes(host_tier) // rec,
                             _ptr(n_bad, torch.int32), _stream(stream)))
+
+
+def kvm_hash_units(pool: Pool, slot_tbl, state, uids, n: int, digests, n_bad=None, stream=None):
+    """digests: uint8 device tensor [n, 32]."""
+    _check(lib.kvm_hash_units(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                              _ptr(uids, torch.int64), n, _ptr(digests, torch.uint8), _ptr(n_bad, torch.int32),
+                              _stream(stream)))
+
+
+def make_store(cap: int, device="cuda") -> Store:
+    """An empty content store with `cap` places (a power of two)."""
+    t = dict(tag=torch.zeros(cap, dtype=torch.int64, device=device),
+             digest=torch.zeros((cap, 32), dtype=torch.uint8, device=device),
+             canon=torch.full((cap,), -1, dtype=torch.int64, device=device),
+             refs=torch.zeros(cap, dtype=torch.int32, device=device),
+             pending=torch.full((cap,), -1, dtype=torch.int32, device=device))
+    s = Store(t["tag"].data_ptr(), t["digest"].data_ptr(), t["canon"].data_ptr(), t["refs"].data_ptr(),
+              t["pending"].data_ptr(), cap)
+    s.tensors = t
+    return s
+
+
+def kvm_dedup_insert(store: Store, digests, uids, n: int, canon_out, ws, n_full=None, n_collide=None, stream=None):
+    _check(lib.kvm_dedup_insert(C.byref(store), _ptr(digests, torch.uint8), _ptr(uids, torch.int64), n,
+                                _ptr(canon_out, torch.int64), _ptr(n_full, torch.int32), _ptr(n_collide, torch.int32),
+                                _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def kvm_dedup_release(store: Store, digests, n: int, n_bad=None, stream=None):
+    _check(lib.kvm_dedup_release(C.byref(store), _ptr(digests, torch.uint8), n, _ptr(n_bad, torch.int32),
+                                 _stream(stream)))
 
 
 def kvm_last_error() -> str:

@@ -34,6 +34,7 @@ def test_struct_layouts_match_header(kvm):
     assert C.sizeof(kvm.Pool) == 40
     assert C.sizeof(kvm.Rows) == 64
     assert C.sizeof(kvm.EmaEx) == 48
+    assert C.sizeof(kvm.Store) == 48
 
 
 @pytest.mark.parametrize("name", list(G["table3"]))
@@ -121,6 +122,19 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert keys(0, 0.9) == kvm.EINVAL
     assert keys(4, 0.0) == kvm.EINVAL and keys(4, 1.5) == kvm.EINVAL
     assert keys(4, 0.9) == kvm.EINVAL
+    assert lib.kvm_hash_units(None, None, None, 8, None, 1, None, None, None) == kvm.EINVAL
+    odd = kvm.Pool(1, 1, 4, 128, kvm.BF16, 4096, 4000)
+    assert lib.kvm_hash_units(C.byref(odd), None, None, 8, None, 1, None, None, None) == kvm.ESHAPE
+    assert lib.kvm_hash_units(C.byref(pool), None, None, 8, None, 0, None, None, None) == kvm.OK
+    assert lib.kvm_hash_units(C.byref(pool), None, None, 8, None, 1, None, None, None) == kvm.EINVAL
+    st = kvm.Store(1, 1, 1, 1, 1, 12)
+    assert lib.kvm_dedup_insert(C.byref(st), None, None, 1, None, None, None, None, 0, None) == kvm.EINVAL
+    assert "power of two" in kvm.kvm_last_error()
+    st = kvm.Store(1, 1, 1, 1, 1, 16)
+    assert lib.kvm_dedup_insert(C.byref(st), None, None, 0, None, None, None, None, 0, None) == kvm.OK
+    assert lib.kvm_dedup_insert(C.byref(st), 4, 8, 5, 8, None, None, 8, 16, None) == kvm.ENOSPC
+    assert lib.kvm_dedup_release(None, None, 1, None, None) == kvm.EINVAL
+    assert lib.kvm_dedup_release(C.byref(st), None, 1, None, None) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, -1, 0, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, 10, -2, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_pack(None, None, None, 0, None, 0, None, None, None, None, 0, None, 0, None, None) == kvm.EINVAL

@@ -393,3 +393,135 @@ def test_exchange_in_place_with_slot_addressed_tier(oracle, shape):
         # second round: the same lists reversed bring everything back except the skipped pairs
         outs, ins = ins.copy(), outs.copy()
     assert bad[0] >= 3
+
+
+# ------------------------------------------------------------------ content addressing
+def duplicate_some_frames(case, rng, n_groups, group_size):
+    """Copy the K and V frames of a few units over others: groups of identical content."""
+    res = np.flatnonzero(case.state & RES)
+    pick = rng.choice(res, size=n_groups * group_size, replace=False).reshape(n_groups, group_size)
+    for grp in pick:
+        src = case.slot_tbl[grp[0]]
+        for u in grp[1:]:
+            case.k_pool[case.slot_tbl[u]] = case.k_pool[src]
+            if case.v_pool is not None:
+                case.v_pool[case.slot_tbl[u]] = case.v_pool[src]
+    return pick
+
+
+@pytest.mark.parametrize("shape", [
+    synth.Shape(2, 8, 2, 128, synth.BF16, True, [300, 77]),
+    synth.Shape(1, 4, 2, 64, synth.FP16, True, [512]),
+    synth.Shape(3, 16, 1, 576, synth.BF16, False, [400]),
+])
+def test_unit_digests_bit_exact(oracle, shape):
+    """Digests are bytes: exact.  Units that are not in HBM and malformed uids give zero digests."""
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(shape, seed=41)
+    rng = np.random.default_rng(4)
+    duplicate_some_frames(case, rng, 3, 4)
+    res = np.flatnonzero(case.state & RES)
+    gone = rng.choice(res, size=5, replace=False)
+    case.state[gone] = (case.state[gone] & ~np.uint8(RES)) | HOST
+    dev = DeviceCase(case)
+    k8, v8 = host_pools(case)
+    uids = np.r_[np.arange(case.n_uids), [-1, case.n_uids, 2 ** 40]].astype(np.int64)
+    rng.shuffle(uids)
+    bad = np.zeros(1, np.uint32)
+    want = oracle.hash_units(k8, v8, shape.unit_k_bytes, shape.unit_v_bytes, case.slot_tbl, case.state, uids, n_bad=bad)
+    d = torch.full((len(uids), 32), 7, dtype=torch.uint8, device="cuda")
+    kvm.kvm_hash_units(dev.pool, dev.slot_tbl, dev.state, dev_of(uids), len(uids), d, n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d.cpu().numpy(), want)
+    assert int(dev.n_bad.item()) == int(bad[0]) > 5
+
+
+def test_dedup_store_matches_the_sequential_definition(oracle):
+    """Several calls with repeated digests inside a call and across calls, releases in between;
+    canonical uids and the store's contents (digest -> canonical uid, count) are exact."""
+    from paper_2604_26968_amd import kvm
+    rng = np.random.default_rng(5)
+    catalogue = rng.integers(0, 256, size=(300, 32), dtype=np.uint8)
+    catalogue[0, :8] = 0                          # a digest whose first 8 bytes are zero is still a valid key
+    ref = oracle.DedupStore(1024)
+    store = kvm.make_store(1024)
+    n_full = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_col = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    bad = np.zeros(1, np.uint32)
+    next_uid = 1000
+
+    def store_dict():
+        t = {k: v.cpu().numpy() for k, v in store.tensors.items()}
+        out = {}
+        for e in np.flatnonzero(t["canon"] >= 0):
+            out[t["digest"][e].tobytes()] = (int(t["canon"][e]), int(t["refs"][e]))
+        assert np.all(t["pending"] == -1)
+        return out
+
+    for call, n in enumerate([1, 50, 700, 3, 2000]):
+        zipf = np.minimum(rng.zipf(1.3, n) - 1, 299)
+        digests = catalogue[zipf].copy()
+        if n >= 50:
+            digests[7] = 0                         # a failed hash: skipped
+        uids = (next_uid + rng.permutation(n)).astype(np.int64)
+        next_uid += n
+        keep = digests.any(axis=1)
+        want = uids.copy()
+        want[keep] = ref.insert(digests[keep], uids[keep])
+        canon = torch.zeros(n, dtype=torch.int64, device="cuda")
+        ws = torch.zeros(n, dtype=torch.int64, device="cuda")
+        kvm.kvm_dedup_insert(store, dev_of(digests), dev_of(uids), n, canon, ws, n_full=n_full, n_collide=n_col)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(canon.cpu().numpy(), want)
+        assert int(n_full.item()) == 0 and int(n_col.item()) == 0
+        assert store_dict() == ref.as_dict()
+        rel = catalogue[rng.integers(0, 300, 40)]
+        ref.release(rel, n_bad=bad)
+        kvm.kvm_dedup_release(store, dev_of(rel), len(rel), n_bad=d_bad)
+        torch.cuda.synchronize()
+        assert int(d_bad.item()) == int(bad[0])
+        assert store_dict() == ref.as_dict()
+
+
+def test_hash_then_dedup_finds_the_planted_duplicates(oracle):
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(synth.Shape(2, 8, 2, 128, synth.BF16, True, [1000, 400]), seed=43)
+    rng = np.random.default_rng(6)
+    groups = duplicate_some_frames(case, rng, 20, 5)
+    dev = DeviceCase(case)
+    uids = np.flatnonzero(case.state & RES).astype(np.int64)
+    n = len(uids)
+    d = torch.zeros((n, 32), dtype=torch.uint8, device="cuda")
+    kvm.kvm_hash_units(dev.pool, dev.slot_tbl, dev.state, dev_of(uids), n, d)
+    store = kvm.make_store(1 << 12)
+    canon = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ws = torch.zeros(n, dtype=torch.int64, device="cuda")
+    kvm.kvm_dedup_insert(store, d, dev_of(uids), n, canon, ws)
+    torch.cuda.synchronize()
+    canon = canon.cpu().numpy()
+    k8, v8 = host_pools(case)
+    ref = oracle.DedupStore(n)
+    want = ref.insert(oracle.hash_units(k8, v8, case.shape.unit_k_bytes, case.shape.unit_v_bytes, case.slot_tbl,
+                                        case.state, uids), uids)
+    np.testing.assert_array_equal(canon, want)
+    dup = uids[canon != uids]
+    assert len(dup) == 20 * 4
+    for grp in groups:
+        assert len(set(canon[np.searchsorted(uids, grp)])) == 1 and canon[np.searchsorted(uids, grp)][0] == grp.min()
+
+
+def test_dedup_table_too_small_reports_it():
+    from paper_2604_26968_amd import kvm
+    rng = np.random.default_rng(7)
+    digests = rng.integers(1, 256, size=(100, 32), dtype=np.uint8)
+    store = kvm.make_store(16)
+    n_full = torch.zeros(1, dtype=torch.int32, device="cuda")
+    canon = torch.zeros(100, dtype=torch.int64, device="cuda")
+    ws = torch.zeros(100, dtype=torch.int64, device="cuda")
+    uids = np.arange(100, dtype=np.int64)
+    kvm.kvm_dedup_insert(store, dev_of(digests), dev_of(uids), 100, canon, ws, n_full=n_full)
+    torch.cuda.synchronize()
+    assert int(n_full.item()) == 100 - 16
+    np.testing.assert_array_equal(canon.cpu().numpy(), uids)       # all distinct: every item is its own canonical copy
+    assert int((store.tensors["canon"] >= 0).sum().item()) == 16
