@@ -178,6 +178,21 @@ int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q
                    float softmax_scale, int agg, float* mass /* dev [n_uids] */,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* The same launch can carry the bytes of a deferred exchange (kvm_exchange_begin
+ * below): n_pairs extra workgroups at the front of the scorer's grid each swap
+ * one (pool frame, host tier record) pair in place while the rest of the grid
+ * scores, so the host link works during the scoring and not after it.
+ * xfer_frame[i] < 0 skips pair i.  The frames named belong to units the scorer
+ * cannot see (kvm_exchange_begin took them out of the table), so scoring and
+ * transfer never touch the same memory; results equal kvm_score_step followed
+ * by the same transfer.  n_pairs == 0 is kvm_score_step.
+ * Errors: as kvm_score_step; KVM_EINVAL for null transfer buffers.           */
+int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
+                        float softmax_scale, int agg, float* mass /* dev [n_uids] */,
+                        void* ws, size_t ws_bytes,
+                        const int32_t* xfer_frame /* dev [n_pairs] */, const int64_t* xfer_host /* dev [n_pairs] */,
+                        int64_t n_pairs, void* host_tier /* pinned */, void* stream);
+
 /* ======================================================================== *
  * 1. Beta posteriors — section 3.3, Eq. 5.
  *
@@ -371,6 +386,32 @@ int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uin
                  void* host_tier /* pinned, tier_slots records */, uint64_t tier_slots,
                  uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
+/* kvm_exchange in three parts, so that the bytes can move while the next step
+ * is being scored ("asynchronous" promotion and demotion, section 3.2):
+ *   kvm_exchange_begin  validates the pairs exactly as kvm_exchange does and, for
+ *       each valid pair, takes the out-unit out of HBM in the table (RESIDENT
+ *       off, ON_HOST on, slot_tbl = -1 - host slot of its partner) and notes
+ *       frame[i] = the frame it held, host[i] = that host slot; frame[i] = -1 for
+ *       a skipped pair (counted in *n_bad) and for i beyond the device-side
+ *       counts.  The in-unit's entries are left alone: it is still on the host.
+ *   kvm_score_step_xfer(frame, host, n)  moves the bytes during the next scoring.
+ *   kvm_exchange_end    gives each valid pair's in-unit the frame
+ *       (slot_tbl = frame[i], ON_HOST off, RESIDENT on).
+ * After the three calls tables, pools and tier equal what kvm_exchange leaves.
+ * Between begin and end neither unit of a pair is in HBM for the scorer, the
+ * EMA or the selector, and both table entries name the same host slot: the
+ * caller must not build another prefetch or victim list in between.
+ * Errors: as kvm_exchange; null frame / host.                                */
+int kvm_exchange_begin(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+                       int64_t n_uids, const int64_t* out_uids /* dev [n] */, const int64_t* in_uids /* dev [n] */,
+                       int64_t n, const int64_t* n_out_dev /* dev [1] or NULL */,
+                       const int64_t* n_in_dev /* dev [1] or NULL */, uint64_t tier_slots,
+                       int32_t* frame /* dev [n] out */, int64_t* host /* dev [n] out */,
+                       uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+int kvm_exchange_end(int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */, int64_t n_uids,
+                     const int64_t* in_uids /* dev [n] */, const int32_t* frame /* dev [n] */, int64_t n,
+                     void* stream);
+
 /* ======================================================================== *
  * 6. Position-aware prefetching — section 3.5.
  *
@@ -490,7 +531,7 @@ const char* kvm_version(void);
  * returns the launch count (0 if the name is unknown); *total_ms gets the sum.
  * Names: "score_partial", "score_finalize", "score_plan", "ema_prio",
  * "beta", "select_hist", "select_emit", "pack", "unpack", "swap", "span",
- * "prefetch_keys", "hash", "dedup".                                         */
+ * "prefetch_keys", "hash", "dedup", "exchange_flip".                        */
 int  kvm_timing_enable(int on);
 void kvm_timing_reset(void);
 int  kvm_timing_read(const char* name, double* total_ms);

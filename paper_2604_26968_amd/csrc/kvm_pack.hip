@@ -213,6 +213,53 @@ __global__ __launch_bounds__(kThreads) void exchange_kernel(uint4* __restrict__ 
     }
 }
 
+// First and last part of an exchange whose bytes move during the next scoring launch.
+__global__ __launch_bounds__(kThreads) void exchange_begin_kernel(uint32_t n_slots, int32_t* __restrict__ slot_tbl,
+                                                                  uint8_t* __restrict__ state, int64_t n_uids,
+                                                                  const int64_t* __restrict__ out_uids,
+                                                                  const int64_t* __restrict__ in_uids, int64_t n,
+                                                                  const int64_t* __restrict__ n_out_dev,
+                                                                  const int64_t* __restrict__ n_in_dev,
+                                                                  uint64_t tier_slots, int32_t* __restrict__ frame,
+                                                                  int64_t* __restrict__ host, uint32_t* n_bad) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    int32_t slot = -1;
+    int64_t h = -1;
+    if (!((n_out_dev && i >= *n_out_dev) || (n_in_dev && i >= *n_in_dev))) {
+        const int64_t uo = out_uids[i], ui = in_uids[i];
+        if (uo >= 0 && uo < n_uids && (state[uo] & KVM_ST_RESIDENT)) slot = slot_tbl[uo];
+        if ((uint32_t)slot >= n_slots) slot = -1;
+        if (ui >= 0 && ui < n_uids && ui != uo && (state[ui] & KVM_ST_ON_HOST) && !(state[ui] & KVM_ST_RESIDENT) &&
+            slot_tbl[ui] < 0)
+            h = -1 - (int64_t)slot_tbl[ui];
+        if ((uint64_t)h >= tier_slots) h = -1;
+        if (slot >= 0 && h >= 0) {
+            slot_tbl[uo] = (int32_t)(-1 - h);
+            state[uo] = (uint8_t)((state[uo] & ~KVM_ST_RESIDENT) | KVM_ST_ON_HOST);
+        } else {
+            slot = -1;
+            if (n_bad) atomicAdd(n_bad, 1u);
+        }
+    }
+    frame[i] = slot;
+    host[i] = slot >= 0 ? h : -1;
+}
+
+__global__ __launch_bounds__(kThreads) void exchange_end_kernel(int32_t* __restrict__ slot_tbl,
+                                                                uint8_t* __restrict__ state, int64_t n_uids,
+                                                                const int64_t* __restrict__ in_uids,
+                                                                const int32_t* __restrict__ frame, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    const int32_t f = frame[i];
+    if (f < 0) return;
+    const int64_t ui = in_uids[i];
+    if (ui < 0 || ui >= n_uids) return;       // cannot happen for a pair begin accepted
+    slot_tbl[ui] = f;
+    state[ui] = (uint8_t)((state[ui] & ~KVM_ST_ON_HOST) | KVM_ST_RESIDENT);
+}
+
 int check_common(const char* who, const kvm_pool_t* pool, const void* slot_tbl, const void* state, int64_t n_uids,
                  const void* uids, int64_t n, const void* slots, const void* staging_dev, size_t staging_dev_bytes,
                  const void* staging_host, size_t staging_host_bytes) {
@@ -379,4 +426,39 @@ extern "C" int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* 
             tier_slots, n_bad);
     }
     return launch_status("exchange");
+}
+
+extern "C" int kvm_exchange_begin(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                                  const int64_t* out_uids, const int64_t* in_uids, int64_t n,
+                                  const int64_t* n_out_dev, const int64_t* n_in_dev, uint64_t tier_slots,
+                                  int32_t* frame, int64_t* host, uint32_t* n_bad, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(pool, KVM_EINVAL, "kvm_exchange_begin: null pool");
+    KVM_REQUIRE(n >= 0 && n_uids >= 0, KVM_EINVAL, "kvm_exchange_begin: negative count");
+    KVM_REQUIRE(pool->n_slots <= 0x7fffffffull && tier_slots <= 0x7fffffffull, KVM_EINVAL,
+                "kvm_exchange_begin: slot counts exceed int32 ids");
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(slot_tbl && state && out_uids && in_uids && frame && host, KVM_EINVAL,
+                "kvm_exchange_begin: null buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("exchange_flip", st);
+    exchange_begin_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, st>>>(
+        (uint32_t)pool->n_slots, slot_tbl, state, n_uids, out_uids, in_uids, n, n_out_dev, n_in_dev, tier_slots, frame,
+        host, n_bad);
+    return launch_status("exchange_begin");
+}
+
+extern "C" int kvm_exchange_end(int32_t* slot_tbl, uint8_t* state, int64_t n_uids, const int64_t* in_uids,
+                                const int32_t* frame, int64_t n, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(n >= 0 && n_uids >= 0, KVM_EINVAL, "kvm_exchange_end: negative count");
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(slot_tbl && state && in_uids && frame, KVM_EINVAL, "kvm_exchange_end: null buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("exchange_flip", st);
+    exchange_end_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, st>>>(slot_tbl, state, n_uids,
+                                                                                       in_uids, frame, n);
+    return launch_status("exchange_end");
 }

@@ -258,6 +258,64 @@ __global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, con
     for (uint32_t i = 0; i < nt; ++i) tiles[first + i] = Tile{r, (int32_t)(i * p.tile_blocks)};
 }
 
+// ---- bytes of a deferred exchange riding along with a scoring launch ----------------------
+// `n` workgroups of a tile kernel's grid each swap one (frame, host tier record) pair in place
+// (what kvm_exchange_begin prepared) while the rest of the grid scores: the host link works
+// during the scoring instead of after it.  They are interleaved with the scoring workgroups at
+// the front of the grid (every stride-th one): all at the very front they would fill every
+// compute unit with waves that only wait for the link and scoring would start after them.  The frames involved belong to units the
+// scoring cannot see (kvm_exchange_begin has taken them out of the table), so the two kinds
+// of workgroup never touch the same memory.
+struct Xfer {
+    uint32_t n;
+    uint32_t stride;        // every stride-th workgroup of the first n * stride moves pair number (index / stride)
+    const int32_t* frame;   // [n] frame of pair i, -1 = skip
+    const int64_t* host;    // [n] host tier slot of pair i
+    uint4* k_pool;
+    uint4* v_pool;
+    uint4* tier;
+    uint32_t k_v4, v_v4;
+};
+
+__device__ __forceinline__ void xfer_pair(const Xfer& x, uint32_t i) {
+    const int32_t f = x.frame[i];
+    if (f < 0) return;
+    uint4* rec = x.tier + (size_t)x.host[i] * ((size_t)x.k_v4 + x.v_v4);
+    uint4* kf = x.k_pool + (size_t)f * x.k_v4;
+    for (uint32_t v = threadIdx.x; v < x.k_v4; v += kThreads) {
+        const uint4 a = kf[v], b = rec[v];
+        kf[v] = b;
+        rec[v] = a;
+    }
+    if (x.v_v4) {
+        uint4* vf = x.v_pool + (size_t)f * x.v_v4;
+        for (uint32_t v = threadIdx.x; v < x.v_v4; v += kThreads) {
+            const uint4 a = vf[v], b = rec[x.k_v4 + v];
+            vf[v] = b;
+            rec[x.k_v4 + v] = a;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void xfer_kernel(Xfer x) { xfer_pair(x, blockIdx.x); }
+
+// Which role workgroup `b` of a tile kernel's grid plays: returns true and the pair number for a
+// transfer workgroup, false and the tile number otherwise.
+__device__ __forceinline__ bool xfer_role(const Xfer& x, uint32_t b, uint32_t* index) {
+    const uint32_t region = x.n * x.stride;
+    if (b < region) {
+        const uint32_t q = b / x.stride;
+        if (b - q * x.stride == 0) {
+            *index = q;
+            return true;
+        }
+        *index = b - (q + 1);        // transfer workgroups before b: q + 1
+        return false;
+    }
+    *index = b - x.n;
+    return false;
+}
+
 // ---- shared pieces of the tile kernels ---------------------------------------------
 
 // What every tile kernel derives from its tile.
@@ -267,8 +325,9 @@ struct TileCtx {
     int64_t uid0;            // uid of the tile's block 0
 };
 template <int T>
-__device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, const int32_t* row_ntok, const int64_t* row_off) {
-    const Tile tile = tiles[blockIdx.x];
+__device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, const int32_t* row_ntok, const int64_t* row_off,
+                                            uint32_t tile_id) {
+    const Tile tile = tiles[tile_id];
     TileCtx c;
     c.row = tile.row;
     c.b0 = tile.b0;
@@ -510,15 +569,20 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, const int32_t* __restrict__ row_ntok,
     const int64_t* __restrict__ row_off, const int64_t* __restrict__ row_q_off,
     const int32_t* __restrict__ slot_tbl, const uint4* __restrict__ k_pool, uint32_t n_slots,
-    const uint16_t* __restrict__ q, float scale, TileOut out) {
+    const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
     static_assert(G == 1 || G == 2 || G == 4 || G == 8, "power-of-two group sizes only");
     constexpr int NK = DIM / 32;          // 16-byte loads per lane per unit
     constexpr int QROW_V4 = DIM / 8;      // 16-byte vectors per query
     __shared__ float s_lse[T * G];        // log sum exp per (block, query); -inf = not resident
     __shared__ TileLds<T, G> lds;
 
-    if (blockIdx.x >= *n_tiles) return;
-    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off);
+    uint32_t tile_id;
+    if (xfer_role(xf, blockIdx.x, &tile_id)) {     // this workgroup moves bytes instead of scoring
+        xfer_pair(xf, tile_id);
+        return;
+    }
+    if (tile_id >= *n_tiles) return;
+    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off, tile_id);
     const int lane = threadIdx.x & 63;
     const int t = lane & 15, cg = lane >> 4;
     const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
@@ -555,7 +619,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
         }
     });
     __syncthreads();
-    tile_epilogue<G, T>(s_lse, lds.red, lds.v, G, c, blockIdx.x, out);
+    tile_epilogue<G, T>(s_lse, lds.red, lds.v, G, c, tile_id, out);
 }
 
 // ---- score_tile_mfma: any g <= 16 * NCT, queries as matrix-core operands -----------
@@ -567,15 +631,20 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
     const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
     const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
-    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out) {
+    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
     constexpr int NK = DIM / 32;
     constexpr int QROW_V4 = DIM / 8;
     constexpr int GP = NCT * 16;          // 16, 32, 64 or 128
     __shared__ float s_lse[T * NCT * 16];
     __shared__ TileLds<T, GP> lds;
 
-    if (blockIdx.x >= *n_tiles) return;
-    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off);
+    uint32_t tile_id;
+    if (xfer_role(xf, blockIdx.x, &tile_id)) {     // this workgroup moves bytes instead of scoring
+        xfer_pair(xf, tile_id);
+        return;
+    }
+    if (tile_id >= *n_tiles) return;
+    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off, tile_id);
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, cg = lane >> 4;
     const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
@@ -616,7 +685,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
         }
     });
     __syncthreads();
-    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, blockIdx.x, out);
+    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, tile_id, out);
 }
 
 // ---- score_tile_wide: wide frames (MLA latent, dim 576) scored by up to 128 queries ---
@@ -639,7 +708,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
     const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
     const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
-    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out) {
+    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
     constexpr int NK = DIM / 32;
     constexpr int UNIT_V4 = DIM * 2;
     constexpr int QROW_V4 = DIM / 8;
@@ -655,8 +724,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     __shared__ int2 s_list[TB];
     __shared__ int s_cnt[((TB + kThreads - 1) / kThreads) * 4];
 
-    if (blockIdx.x >= *n_tiles) return;
-    const TileCtx c = tile_ctx<TB>(tiles, row_ntok, row_off);
+    uint32_t tile_id;
+    if (xfer_role(xf, blockIdx.x, &tile_id)) {     // this workgroup moves bytes instead of scoring
+        xfer_pair(xf, tile_id);
+        return;
+    }
+    if (tile_id >= *n_tiles) return;
+    const TileCtx c = tile_ctx<TB>(tiles, row_ntok, row_off, tile_id);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, cg = lane >> 4;
     const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
@@ -760,7 +834,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
             const int j = 32 * wave + ct * 16 + n;
-            if (j < G) out.tile_lse[(size_t)blockIdx.x * G + j] = mz_lse(run[ct]);
+            if (j < G) out.tile_lse[(size_t)tile_id * G + j] = mz_lse(run[ct]);
         }
     }
 }
@@ -777,7 +851,7 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
     constexpr int SWEEPS = (T + BS - 1) / BS;
     __shared__ float s_v[GP > 64 ? 4 * SWEEPS : 1];
     if (blockIdx.x >= *n_tiles) return;
-    const TileCtx plan = tile_ctx<T * SUB>(tiles, row_ntok, row_off);
+    const TileCtx plan = tile_ctx<T * SUB>(tiles, row_ntok, row_off, blockIdx.x);
     if (plan.nb <= T) return;                        // finished by its tile
     const float* tl = o.tile_lse + (size_t)row_tile0[plan.row] * SUB * g;
     const int n_t = (plan.nb + T - 1) / T;
@@ -833,7 +907,7 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_big_kernel(
     __shared__ float2 s_mz[kThreads];
     __shared__ float s_rowlse[128];
     if (blockIdx.x >= *n_tiles) return;
-    const TileCtx plan = tile_ctx<TB>(tiles, row_ntok, row_off);
+    const TileCtx plan = tile_ctx<TB>(tiles, row_ntok, row_off, blockIdx.x);
     if (!ALL && plan.nb <= T) return;                // finished by its tile
     const int gs = ALL ? 128 : g;                    // row stride of the block values
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -900,7 +974,7 @@ __global__ __launch_bounds__(kThreads) void score_partial_generic_kernel(
     __shared__ int s_cnt[4];
 
     if (blockIdx.x >= *n_tiles) return;
-    const TileCtx c = tile_ctx<kGenericTile>(tiles, row_ntok, row_off);
+    const TileCtx c = tile_ctx<kGenericTile>(tiles, row_ntok, row_off, blockIdx.x);
     const int lane = threadIdx.x & 63;
     const int t = lane & 15, cg = lane >> 4;
     const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
@@ -1041,7 +1115,8 @@ struct ScoreArgs {
     PlanRows pr;
     ScoreWs w;
     TileOut out;
-    unsigned grid;
+    Xfer xf;           // n == 0: nothing rides along
+    unsigned grid;     // scoring workgroups (upper bound on tiles); the tile kernels launch xf.n more
     hipStream_t st;
 };
 
@@ -1064,10 +1139,10 @@ template <int G, int DIM, int DT>
 int launch_dot2_path(const ScoreArgs& a) {
     {
         TimedLaunch tl("score_partial", a.st);
-        score_tile_dot2_kernel<G, DIM, DT, 512><<<a.grid, kThreads, 0, a.st>>>(
+        score_tile_dot2_kernel<G, DIM, DT, 512><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
             a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off, a.rows->slot_tbl,
             static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots, static_cast<const uint16_t*>(a.q),
-            a.scale, a.out);
+            a.scale, a.out, a.xf);
         if (int rc = launch_status("score_tile_dot2")) return rc;
     }
     return launch_rowmerge<G, 512>(a);
@@ -1078,10 +1153,10 @@ int launch_mfma_path(const ScoreArgs& a) {
     constexpr int T = 512 / NCT;
     {
         TimedLaunch tl("score_partial", a.st);
-        score_tile_mfma_kernel<NCT, DIM, DT, T><<<a.grid, kThreads, 0, a.st>>>(
+        score_tile_mfma_kernel<NCT, DIM, DT, T><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
             a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off,
             a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
-            static_cast<const uint16_t*>(a.q), a.scale, a.out);
+            static_cast<const uint16_t*>(a.q), a.scale, a.out, a.xf);
         if (int rc = launch_status("score_tile_mfma")) return rc;
     }
     return launch_rowmerge<NCT * 16, T>(a);
@@ -1093,10 +1168,10 @@ int launch_wide_path(const ScoreArgs& a) {
     constexpr int TB = kWideTileBlocks;
     {
         TimedLaunch tl("score_partial", a.st);
-        score_tile_wide_kernel<DIM, DT, TB><<<a.grid, kThreads, 0, a.st>>>(
+        score_tile_wide_kernel<DIM, DT, TB><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
             a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off,
             a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
-            static_cast<const uint16_t*>(a.q), a.scale, a.out);
+            static_cast<const uint16_t*>(a.q), a.scale, a.out, a.xf);
         if (int rc = launch_status("score_tile_wide")) return rc;
     }
     TimedLaunch tl("score_finalize", a.st);
@@ -1118,6 +1193,11 @@ int launch_generic_path(const ScoreArgs& a) {
     if (lds > 32 * 1024)
         KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    if (a.xf.n) {                                   // no room in this kernel: the bytes move first, on their own
+        TimedLaunch tl("swap", a.st);
+        xfer_kernel<<<a.xf.n, kThreads, 0, a.st>>>(a.xf);
+        if (int rc = launch_status("xfer")) return rc;
+    }
     {
         TimedLaunch tl("score_partial", a.st);
         kern<<<a.grid, kThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, g, a.rows->row_ntok, a.rows->row_off,
@@ -1193,11 +1273,10 @@ size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t 
 
 }  // namespace kvm
 
-extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
-                              float softmax_scale, int agg, float* mass, void* ws, size_t ws_bytes,
-                              void* stream) {
-    using namespace kvm;
-    clear_error();
+namespace kvm {
+namespace {
+int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, float softmax_scale, int agg,
+               float* mass, void* ws, size_t ws_bytes, const Xfer& xf, void* stream) {
     KVM_REQUIRE(pool && rows, KVM_EINVAL, "kvm_score_step: null descriptor");
     KVM_REQUIRE(rows->n_rows >= 0 && rows->n_uids >= 0 && rows->q_elems >= 0, KVM_EINVAL,
                 "kvm_score_step: negative size");
@@ -1228,6 +1307,13 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
     const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows, ch.tile_blocks);
     KVM_REQUIRE(tiles_max <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: too many tiles");
     a.out = TileOut{agg, mass, reinterpret_cast<float*>(a.w.part), a.w.tile_lse};
+    a.xf = xf;
+    KVM_REQUIRE(tiles_max + xf.n <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: grid too large");
+    if (xf.n) {
+        // spread the transfers over the first half of the tiles, at most one workgroup in eight
+        int64_t stride = tiles_max / (2 * (int64_t)xf.n);
+        a.xf.stride = (uint32_t)(stride < 1 ? 1 : stride > 8 ? 8 : stride);
+    }
     a.grid = (unsigned)tiles_max;
     a.st = static_cast<hipStream_t>(stream);
     a.pr = PlanRows{rows->n_rows, rows->g,        pool->dim,     ch.tile_blocks,  rows->n_uids,
@@ -1241,4 +1327,45 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
         if (int rc = launch_status("score_plan")) return rc;
     }
     return pool->dtype == KVM_BF16 ? launch_dtype<KVM_BF16>(a, ch) : launch_dtype<KVM_FP16>(a, ch);
+}
+}  // namespace
+}  // namespace kvm
+
+extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
+                              float softmax_scale, int agg, float* mass, void* ws, size_t ws_bytes,
+                              void* stream) {
+    kvm::clear_error();
+    return kvm::score_step(pool, rows, q, softmax_scale, agg, mass, ws, ws_bytes, kvm::Xfer{}, stream);
+}
+
+extern "C" int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
+                                   float softmax_scale, int agg, float* mass, void* ws, size_t ws_bytes,
+                                   const int32_t* xfer_frame, const int64_t* xfer_host, int64_t n_pairs,
+                                   void* host_tier, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(pool, KVM_EINVAL, "kvm_score_step_xfer: null pool");
+    KVM_REQUIRE(n_pairs >= 0 && n_pairs <= 0x3fffffffll, KVM_EINVAL, "kvm_score_step_xfer: n_pairs %lld out of range",
+                (long long)n_pairs);
+    Xfer xf{};
+    if (n_pairs > 0) {
+        KVM_REQUIRE(xfer_frame && xfer_host && host_tier, KVM_EINVAL, "kvm_score_step_xfer: null transfer buffer");
+        KVM_REQUIRE(pool->unit_k_bytes % 16 == 0 && pool->unit_v_bytes % 16 == 0, KVM_ESHAPE,
+                    "kvm_score_step_xfer: unit sizes must be multiples of 16");
+        KVM_REQUIRE(pool->k_pool && (pool->v_pool || pool->unit_v_bytes == 0), KVM_EINVAL,
+                    "kvm_score_step_xfer: null pool memory");
+        KVM_REQUIRE(reinterpret_cast<uintptr_t>(host_tier) % 16 == 0, KVM_EINVAL,
+                    "kvm_score_step_xfer: host tier must be 16-byte aligned");
+        xf = Xfer{(uint32_t)n_pairs, 1u, xfer_frame, xfer_host, static_cast<uint4*>(pool->k_pool),
+                  static_cast<uint4*>(pool->v_pool), static_cast<uint4*>(host_tier), pool->unit_k_bytes / 16,
+                  pool->unit_v_bytes / 16};
+    }
+    if (rows && (rows->n_rows == 0 || rows->n_uids == 0) && xf.n) {
+        // nothing to score: the bytes still have to move
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        TimedLaunch tl("swap", st);
+        xfer_kernel<<<xf.n, kThreads, 0, st>>>(xf);
+        return launch_status("xfer");
+    }
+    return score_step(pool, rows, q, softmax_scale, agg, mass, ws, ws_bytes, xf, stream);
 }

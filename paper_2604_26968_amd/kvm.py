@@ -23,7 +23,7 @@ ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
 AGG_MAX, AGG_MEAN = 0, 1
 OP_SCORE, OP_SELECT = 0, 1
 
-EXPORTS = ["kvm_size", "kvm_score_step", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
+EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
            "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
            "kvm_timing_enable", "kvm_timing_reset", "kvm_timing_read"]
@@ -114,6 +114,13 @@ def _load() -> C.CDLL:
     lib.kvm_dedup_insert.argtypes = [C.POINTER(Store), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.kvm_dedup_release.argtypes = [C.POINTER(Store), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    lib.kvm_score_step_xfer.argtypes = [C.POINTER(Pool), C.POINTER(Rows), C.c_void_p, C.c_float, C.c_int, C.c_void_p,
+                                        C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                        C.c_void_p]
+    lib.kvm_exchange_begin.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                       C.c_int64, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p]
+    lib.kvm_exchange_end.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
     return lib
 
@@ -322,6 +329,28 @@ def kvm_dedup_insert(store: Store, digests, uids, n: int, canon_out, ws, n_full=
 def kvm_dedup_release(store: Store, digests, n: int, n_bad=None, stream=None):
     _check(lib.kvm_dedup_release(C.byref(store), _ptr(digests, torch.uint8), n, _ptr(n_bad, torch.int32),
                                  _stream(stream)))
+
+
+def kvm_score_step_xfer(pool: Pool, rows: Rows, q, softmax_scale: float, mass, ws, xfer_frame, xfer_host, n_pairs: int,
+                        host_tier, agg: int = AGG_MAX, stream=None):
+    _check(lib.kvm_score_step_xfer(C.byref(pool), C.byref(rows), _ptr(q), softmax_scale, agg,
+                                   _ptr(mass, torch.float32), _ptr(ws), ws.numel() * ws.element_size(),
+                                   _ptr(xfer_frame, torch.int32), _ptr(xfer_host, torch.int64), n_pairs,
+                                   _ptr(host_tier, None, "cpu"), _stream(stream)))
+
+
+def kvm_exchange_begin(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, tier_slots: int, frame, host,
+                       n_out_dev=None, n_in_dev=None, n_bad=None, stream=None):
+    _check(lib.kvm_exchange_begin(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                                  _ptr(out_uids, torch.int64), _ptr(in_uids, torch.int64), n,
+                                  _ptr(n_out_dev, torch.int64), _ptr(n_in_dev, torch.int64), tier_slots,
+                                  _ptr(frame, torch.int32), _ptr(host, torch.int64), _ptr(n_bad, torch.int32),
+                                  _stream(stream)))
+
+
+def kvm_exchange_end(slot_tbl, state, in_uids, frame, n: int, stream=None):
+    _check(lib.kvm_exchange_end(_ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                                _ptr(in_uids, torch.int64), _ptr(frame, torch.int32), n, _stream(stream)))
 
 
 def kvm_last_error() -> str:

@@ -525,3 +525,80 @@ def test_dedup_table_too_small_reports_it():
     assert int(n_full.item()) == 100 - 16
     np.testing.assert_array_equal(canon.cpu().numpy(), uids)       # all distinct: every item is its own canonical copy
     assert int((store.tensors["canon"] >= 0).sum().item()) == 16
+
+
+# ------------------------------------------------------------------ exchange overlapped with scoring
+@pytest.mark.parametrize("shape,n_pairs", [
+    (synth.Shape(2, 8, 2, 128, synth.BF16, True, [700, 77, 1300]), 60),       # dot2 kernel, g = 4
+    (synth.Shape(2, 32, 1, 128, synth.FP16, True, [900]), 20),                # matrix-core kernel, g = 32
+    (synth.Shape(3, 128, 1, 576, synth.BF16, False, [4500, 300]), 30),        # wide kernel, rows of several tiles
+])
+def test_exchange_in_three_parts_rides_along_with_scoring(oracle, shape, n_pairs):
+    """begin -> score with the transfer in the same launch -> end.  Masses equal the oracle's scoring of
+    the table with the out-units taken out (neither unit of a pair is in HBM meanwhile); pools, tier,
+    tables and state afterwards equal the oracle's plain exchange, byte for byte."""
+    from paper_2604_26968_amd import kvm
+    from tests.harness import oracle_score
+    case = synth.make_case(shape, seed=51)
+    k8, v8 = host_pools(case)
+    rng = np.random.default_rng(9)
+    uk, uv = shape.unit_k_bytes, shape.unit_v_bytes
+    rec = uk + uv
+    res = np.flatnonzero(case.state & RES)
+    first_out = np.sort(rng.choice(res, size=len(res) // 3, replace=False)).astype(np.int64)
+    n_tier = len(first_out) + 3
+    hs = rng.permutation(n_tier)[:len(first_out)].astype(np.int32)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    staging, _ = oracle.pack(k8, v8, uk, uv, tbl, st, first_out, hs)
+    tier = rng.integers(0, 256, size=(n_tier, rec), dtype=np.uint8)
+    tier[hs] = staging
+    case.slot_tbl[:], case.state[:] = tbl, st
+    dev = DeviceCase(case)
+    d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
+    n = n_pairs
+    res_now = np.flatnonzero(st & RES)
+    outs = rng.choice(res_now, size=n, replace=False).astype(np.int64)
+    ins = rng.choice(first_out, size=n, replace=False).astype(np.int64)
+    outs[1] = -1
+    ins[4] = np.setdiff1d(res_now, outs)[0]
+    outs[6] = np.setdiff1d(first_out, ins)[0]
+    # oracle: the plain exchange gives the final state and tells which pairs were valid
+    tbl_f, st_f, k_f, tier_f = tbl.copy(), st.copy(), k8.copy(), tier.copy()
+    v_f = v8.copy() if v8 is not None else None
+    bad = np.zeros(1, np.uint32)
+    oracle.exchange(k_f, v_f, uk, uv, tbl_f, st_f, outs, ins, tier_f, n_bad=bad)
+    ok_out = np.array([0 <= u < case.n_uids and bool(st[u] & RES) and not bool(st_f[u] & RES) for u in outs])
+    assert ok_out.sum() == n - 3 and bad[0] == 3
+    tbl_mid = tbl.copy()
+    tbl_mid[outs[ok_out]] = -1                       # out of HBM for this scoring pass
+    q = synth.make_queries(case, 5)
+    scale = 1.0 / np.sqrt(shape.dim)
+    want_mass = oracle_score(oracle, case, q, scale, fill=-1.0, slot_tbl=tbl_mid)
+    # device
+    frame = torch.full((n,), -5, dtype=torch.int32, device="cuda")
+    host = torch.full((n,), -5, dtype=torch.int64, device="cuda")
+    d_outs, d_ins = dev_of(outs), dev_of(ins)
+    kvm.kvm_exchange_begin(dev.pool, dev.slot_tbl, dev.state, d_outs, d_ins, n, n_tier, frame, host, n_bad=dev.n_bad)
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step_xfer(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws, frame, host, n,
+                            d_tier)
+    torch.cuda.synchronize()
+    got_mass = dev.mass.cpu().numpy()
+    mid_state = dev.state.cpu().numpy()
+    assert not np.any(mid_state[outs[ok_out]] & RES) and not np.any(mid_state[ins[ok_out]] & RES)
+    kvm.kvm_exchange_end(dev.slot_tbl, dev.state, d_ins, frame, n)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(frame.cpu().numpy() >= 0, ok_out)
+    np.testing.assert_array_equal(frame.cpu().numpy()[ok_out], tbl[outs[ok_out]])
+    np.testing.assert_array_equal(host.cpu().numpy()[ok_out], -1 - tbl[ins[ok_out]])
+    assert int(dev.n_bad.item()) == 3
+    written = want_mass != -1.0
+    np.testing.assert_array_equal(got_mass != -1.0, written)
+    np.testing.assert_allclose(got_mass[written], want_mass[written], rtol=1e-3, atol=1e-9)
+    gk, gv = dev.pools_host()
+    np.testing.assert_array_equal(gk, k_f)
+    if v8 is not None:
+        np.testing.assert_array_equal(gv, v_f)
+    np.testing.assert_array_equal(d_tier.numpy().reshape(n_tier, rec), tier_f)
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl_f)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st_f)
