@@ -32,8 +32,9 @@ WORKLOADS = {
     "mla": ("deepseek-v3-shaped MLA: 61 layers, 576-channel latent, 128 absorbed queries, bf16, %d x 32768 tok",
             lambda synth, n: synth.mla_shape(n), 32, 0.40, 0.90, 1024, 2, 0),
 }
-# FETCH_SIZE 6,609,384.6 x 2 KiB + WRITE_SIZE 21,526.6 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
-SCORE_TILE_TRAFFIC_BYTES = int(6609384.6 * 2048 + 21526.6 * 1024)
+# FETCH_SIZE 6,626,252.2 x 2 KiB + WRITE_SIZE 37,911.3 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
+# with the 1,024 transfer workgroups of --swap-mode overlap riding along
+SCORE_TILE_TRAFFIC_BYTES = int(6626252.2 * 2048 + 37911.3 * 1024)
 
 
 def main():
@@ -362,7 +363,8 @@ def main():
     achieved = algo_bytes / (sp * 1e-3) / 1e9
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload
     # (profiles/score_tile_dot2_llama8b_pmc.md); valid for the default workload only.
-    traffic = SCORE_TILE_TRAFFIC_BYTES if (args.workload == "llama8b" and n_seq == 64 and swap == 1024) else None
+    traffic = SCORE_TILE_TRAFFIC_BYTES if (args.workload == "llama8b" and n_seq == 64 and swap == 1024
+                                           and args.swap_mode == "overlap" and not args.refined) else None
     roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}
