@@ -1345,7 +1345,7 @@ extern "C" int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* row
     using namespace kvm;
     clear_error();
     KVM_REQUIRE(pool, KVM_EINVAL, "kvm_score_step_xfer: null pool");
-    KVM_REQUIRE(n_pairs >= 0 && n_pairs <= 0x3fffffffll, KVM_EINVAL, "kvm_score_step_xfer: n_pairs %lld out of range",
+    KVM_REQUIRE(n_pairs >= 0 && n_pairs <= 0x7ffffffll, KVM_EINVAL, "kvm_score_step_xfer: n_pairs %lld out of range",
                 (long long)n_pairs);
     Xfer xf{};
     if (n_pairs > 0) {
