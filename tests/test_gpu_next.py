@@ -602,3 +602,112 @@ def test_exchange_in_three_parts_rides_along_with_scoring(oracle, shape, n_pairs
     np.testing.assert_array_equal(d_tier.numpy().reshape(n_tier, rec), tier_f)
     np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl_f)
     np.testing.assert_array_equal(dev.state.cpu().numpy(), st_f)
+
+
+def test_end_to_end_overlapped_exchange_dynamics(oracle):
+    """The pass as the bench runs it by default, five steps on a twin of the Llama-3-8B-shaped workload:
+    beta -> score (with the previous step's exchange bytes in the same launch) -> ema -> exchange_end ->
+    select to budget -> exchange_begin.  Masses, EMA state, victim sets, tables, pools and the host tier
+    follow the oracle step by step; each exchange as a whole equals the oracle's plain exchange."""
+    from paper_2604_26968_amd import kvm
+    from tests.harness import oracle_score
+    from tests.test_gpu_parity import victims_agree, MASS_RTOL, MASS_ATOL
+    shape = synth.Shape(2, 8, 2, 128, synth.BF16, True, [700, 2100, 333])
+    case = synth.make_case(shape, seed=61, pair_weights=synth.categorical_weights(3))
+    sh = case.shape
+    uk, uv = sh.unit_k_bytes, sh.unit_v_bytes
+    rec = uk + uv
+    rng = np.random.default_rng(2)
+    k8, v8 = host_pools(case)
+    # start: 40 % of the units on the host tier (slot-addressed), the rest in HBM
+    res = np.flatnonzero((case.state & RES) != 0)
+    res = res[(case.state[res] & PROT) == 0]
+    first_out = np.sort(rng.choice(res, size=int(0.4 * len(res)), replace=False)).astype(np.int64)
+    n_tier = len(first_out)
+    hs = rng.permutation(n_tier).astype(np.int32)
+    staging, _ = oracle.pack(k8, v8, uk, uv, case.slot_tbl, case.state, first_out, hs)
+    tier = np.zeros((n_tier, rec), np.uint8)
+    tier[hs] = staging
+    dev = DeviceCase(case)
+    d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
+    budget = int(np.sum((case.state & RES) != 0)) - 30           # 30 victims and 30 prefetches per step
+    n = 30
+    S, prio = np.zeros(case.n_uids, np.float32), np.zeros(case.n_uids, np.float32)
+    hits, misses = np.zeros(16, np.uint32), np.zeros(16, np.uint32)
+    frame = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    host = torch.full((n,), -1, dtype=torch.int64, device="cuda")
+    d_ins = torch.full((n,), -1, dtype=torch.int64, device="cuda")
+    pending = None                                               # (ins, frames, hosts, expected final state)
+    w = synth.categorical_weights(8)
+    scale = 1 / np.sqrt(128)
+    for step in range(5):
+        q = synth.make_queries(case, 80 + step)
+        ev = synth.make_events(512, 500 + step, pair_weights=w, reuse_prob=np.linspace(0.2, 0.95, 16))
+        gh, gm, gp = dev.beta(*ev)
+        p_hat = oracle.beta_update(ev[0], ev[1], hits, misses)
+        np.testing.assert_array_equal(gh, hits)
+        # score: the tables are as exchange_begin left them; the transfer of the previous step rides along
+        dev.mass.fill_(-1.0)
+        kvm.kvm_score_step_xfer(dev.pool, dev.rows(), torch.from_numpy(q.view(np.int16)).cuda(), scale, dev.mass,
+                                dev.ws, frame, host, n, d_tier)
+        torch.cuda.synchronize()
+        gmass = dev.mass.cpu().numpy()
+        omass = oracle_score(oracle, case, q, scale, fill=-1.0)
+        np.testing.assert_array_equal(gmass != -1.0, omass != -1.0)
+        wr = omass != -1.0
+        np.testing.assert_allclose(gmass[wr], omass[wr], rtol=MASS_RTOL, atol=MASS_ATOL)
+        gS, gprio, gstate = dev.ema(0.95)
+        oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, case.row_weight, case.pair, p_hat, case.state,
+                          S, prio)
+        np.testing.assert_array_equal(gstate, case.state)
+        resm = (case.state & RES) != 0
+        np.testing.assert_allclose(gS[resm], S[resm], rtol=MASS_RTOL)
+        # the previous exchange completes: incoming units get their frames
+        kvm.kvm_exchange_end(dev.slot_tbl, dev.state, d_ins, frame, n)
+        if pending is not None:
+            ins, frames, hosts, want = pending
+            k8[frames], tier[hosts, :uk] = tier[hosts, :uk].copy(), k8[frames].copy()
+            v8[frames], tier[hosts, uk:] = tier[hosts, uk:].copy(), v8[frames].copy()
+            case.slot_tbl[ins] = frames
+            case.state[ins] = (case.state[ins] & ~np.uint8(HOST)) | RES
+            case.k_pool[:] = k8.view(np.uint16).reshape(case.k_pool.shape)
+            # ... and the whole exchange equals the oracle's plain one (SCORED bits set meanwhile aside)
+            tbl_w, st_w, k_w, v_w, tier_w = want
+            np.testing.assert_array_equal(case.slot_tbl, tbl_w)
+            np.testing.assert_array_equal(case.state & ~np.uint8(SCORED), st_w & ~np.uint8(SCORED))
+            np.testing.assert_array_equal(k8, k_w)
+            np.testing.assert_array_equal(v8, v_w)
+            np.testing.assert_array_equal(tier, tier_w)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), case.slot_tbl)
+        np.testing.assert_array_equal(dev.state.cpu().numpy(), case.state)
+        gk, gvv = dev.pools_host()
+        np.testing.assert_array_equal(gk, k8)
+        np.testing.assert_array_equal(gvv, v8)
+        np.testing.assert_array_equal(d_tier.numpy().reshape(n_tier, rec), tier)
+        # victims down to the budget; both sides continue with the oracle's list
+        n_over = int(np.sum((case.state & RES) != 0)) - budget
+        gv = dev.select(k=-1, budget=budget)
+        ov = oracle.select_victims(prio, case.state, k=-1, budget_units=budget)
+        victims_agree(gv, ov, prio, case.state)
+        assert len(ov) == n_over == n
+        on_host = np.flatnonzero(((case.state & HOST) != 0) & ((case.state & RES) == 0))
+        ins = rng.choice(on_host, size=n, replace=False).astype(np.int64)
+        outs = ov.astype(np.int64)
+        # what the oracle's plain exchange makes of it (on copies)
+        want = (case.slot_tbl.copy(), case.state.copy(), k8.copy(), v8.copy(), tier.copy())
+        oracle.exchange(want[2], want[3], uk, uv, want[0], want[1], outs, ins, want[4])
+        # begin: the victims leave the table now
+        frames, hosts = case.slot_tbl[outs].copy(), (-1 - case.slot_tbl[ins]).astype(np.int64)
+        case.slot_tbl[outs] = (-1 - hosts).astype(np.int32)
+        case.state[outs] = (case.state[outs] & ~np.uint8(RES)) | HOST
+        d_ins = dev_of(ins)
+        kvm.kvm_exchange_begin(dev.pool, dev.slot_tbl, dev.state, dev_of(outs), d_ins, n, n_tier, frame, host,
+                               n_bad=dev.n_bad)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(frame.cpu().numpy(), frames)
+        np.testing.assert_array_equal(host.cpu().numpy(), hosts)
+        np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), case.slot_tbl)
+        np.testing.assert_array_equal(dev.state.cpu().numpy(), case.state)
+        pending = (ins, frames, hosts, want)
+    assert int(dev.n_bad.item()) == 0
