@@ -1085,7 +1085,8 @@ struct ScoreWs {
     size_t bytes;
 };
 
-ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, int tile_blocks, int sub) {
+ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, const Choice& ch) {
+    const int tile_blocks = ch.tile_blocks, sub = ch.sub;
     const size_t n_wg = ((size_t)n_rows + kPlanThreads - 1) / kPlanThreads;
     const size_t tiles_max = (size_t)max_tiles(n_uids, n_rows, tile_blocks);
     const size_t off_sum = 256;
@@ -1101,8 +1102,11 @@ ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, int tile_bloc
     w.row_tile0 = reinterpret_cast<uint32_t*>(base + off_row0);
     w.tile_lse = reinterpret_cast<float*>(base + off_tmz);
     w.part = reinterpret_cast<float2*>(base + off_part);
-    // (m, s) pairs per (unit, query) on the generic path; floats with a row stride of up to 128 on the tile paths
-    const size_t per_uid = (size_t)(g > 64 ? g : 64) * sizeof(float2);
+    // per unit: g floats on the tile paths (128 on the wide path, whose rows are padded), g (m, s) pairs on
+    // the generic path
+    const size_t per_uid = ch.path == Path::Wide      ? 128 * sizeof(float)
+                           : ch.path == Path::Generic ? (size_t)g * sizeof(float2)
+                                                      : (size_t)g * sizeof(float);
     w.bytes = off_part + align_up((size_t)n_uids * per_uid, 256);
     return w;
 }
@@ -1268,7 +1272,7 @@ int launch_dtype(const ScoreArgs& a, const Choice& ch) {
 
 size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim) {
     const Choice ch = choose(g, dim);
-    return carve(nullptr, n_uids, n_rows, g, ch.tile_blocks, ch.sub).bytes;
+    return carve(nullptr, n_uids, n_rows, g, ch).bytes;
 }
 
 }  // namespace kvm
@@ -1302,7 +1306,7 @@ int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, fl
     a.rows = rows;
     a.q = q;
     a.scale = softmax_scale;
-    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g, ch.tile_blocks, ch.sub);
+    a.w = carve(ws, rows->n_uids, rows->n_rows, rows->g, ch);
     KVM_REQUIRE(ws_bytes >= a.w.bytes, KVM_ENOSPC, "kvm_score_step: workspace %zu < %zu bytes", ws_bytes, a.w.bytes);
     const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows, ch.tile_blocks);
     KVM_REQUIRE(tiles_max <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: too many tiles");

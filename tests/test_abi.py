@@ -141,6 +141,6 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_pack(C.byref(pool), None, None, 0, None, 0, None, None, None, None, 0, None, 0, None, None) == kvm.OK
     assert lib.kvm_pack(C.byref(pool), None, None, 8, None, 3, None, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
     assert lib.kvm_unpack(C.byref(pool), None, None, 8, None, -3, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
-    assert kvm.kvm_workspace_bytes(kvm.OP_SCORE, 1000, 10, 4, 128) >= 1000 * 4 * 8
+    assert kvm.kvm_workspace_bytes(kvm.OP_SCORE, 1000, 10, 4, 128) >= 1000 * 4 * 4
     assert kvm.kvm_workspace_bytes(kvm.OP_SELECT, 1000) > 0
     assert kvm.kvm_workspace_bytes(99, 1000) == 0

@@ -15,6 +15,9 @@ RES, HOST, PROT, SCORED = 1, 2, 4, 8
 
 def test_llama8b_shaped_full_size(oracle):
     from paper_2604_26968_amd import kvm
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < 60 * 2**30:
         pytest.skip("needs 60 GiB of free HBM")
@@ -141,3 +144,93 @@ def test_llama8b_shaped_full_size(oracle):
     row_id = torch.repeat_interleave(torch.arange(n_rows, device=dev), torch.from_numpy(wl.nb).to(dev))
     row_sum.index_add_(0, row_id[resident], mass[resident].double())
     assert float(row_sum.min()) > 1.0 - 1e-4 and float(row_sum.max()) < g + 1e-4
+
+    # ---- the same with an exchange riding along, as the benchmark's default mode launches it -------
+    host_tier = torch.empty(2048 * rec, dtype=torch.uint8, pin_memory=True)
+    # 1,024 resident units go to host slots 0..1023 first; then they trade places with 1,024 others
+    res_ids = torch.nonzero(resident).flatten()
+    sel = res_ids[torch.randperm(res_ids.numel(), generator=wl.gen, device=dev)[:2048]]
+    out_a, out_b = sel[:1024].contiguous(), sel[1024:].contiguous()
+    kvm.kvm_pack(pool, wl.slot_tbl, wl.state, out_a, 1024, torch.arange(1024, dtype=torch.int32, device=dev),
+                 freed[:1024], None, host_tier[:1024 * rec], n_bad=n_bad)
+    torch.cuda.synchronize()
+    rec_a = host_tier[:1024 * rec].clone()                 # what is on the host for out_a
+    frames_b = wl.slot_tbl[out_b].clone()
+    k_b = wl.k_pool[frames_b[:256].long()].view(torch.uint8).cpu().numpy().reshape(256, -1)
+    v_b = wl.v_pool[frames_b[:256].long()].view(torch.uint8).cpu().numpy().reshape(256, -1)
+    xf_frame = torch.full((1024,), -1, dtype=torch.int32, device=dev)
+    xf_host = torch.full((1024,), -1, dtype=torch.int64, device=dev)
+    kvm.kvm_exchange_begin(pool, wl.slot_tbl, wl.state, out_b, out_a, 1024, 2048, xf_frame, xf_host, n_bad=n_bad)
+    q2 = wl.queries(102)
+    mass.fill_(-1.0)
+    kvm.kvm_score_step_xfer(pool, rows, q2, scale, mass, ws, xf_frame, xf_host, 1024, host_tier)
+    torch.cuda.synchronize()
+    check_sample(q2, "at budget, exchange riding along")
+    in_flight = torch.cat([out_a, out_b])
+    assert bool((mass[in_flight] == -1.0).all())           # neither side of a pair is in HBM for the scorer
+    kvm.kvm_exchange_end(wl.slot_tbl, wl.state, out_a, xf_frame, 1024)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    assert bool((xf_frame == frames_b).all()) and bool((wl.slot_tbl[out_a] == frames_b).all())
+    assert bool((wl.slot_tbl[out_b] == -1 - torch.arange(1024, dtype=torch.int32, device=dev)).all())
+    # frames of out_b now hold out_a's records; the tier slots hold out_b's old frames
+    got_k = wl.k_pool[frames_b[:256].long()].view(torch.uint8).cpu().numpy().reshape(256, -1)
+    want_a = rec_a.numpy().reshape(1024, rec)[:256]
+    np.testing.assert_array_equal(got_k, want_a[:, :shape.unit_k_bytes])
+    tier_now = host_tier.numpy().reshape(2048, rec)[:256]
+    np.testing.assert_array_equal(tier_now[:, :shape.unit_k_bytes], k_b)
+    np.testing.assert_array_equal(tier_now[:, shape.unit_k_bytes:], v_b)
+
+
+@pytest.mark.parametrize("name,need_gib", [("llama70b", 190), ("mla", 90)])
+def test_long_row_workloads_full_size_sampled(oracle, name, need_gib):
+    """Configs 3 and 4 at full size (8,192-block rows with g = 8; 2,048-block latent rows with g = 128),
+    in the launch configuration the benchmark times: all resident, then half / 40 % resident.  The oracle
+    scores sampled rows; over the whole array resident units are written, others untouched, and every
+    row's masses sum to a value in [1, g]."""
+    from paper_2604_26968_amd import kvm
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()               # give back what earlier tests' pools still hold in the allocator
+    free, _ = torch.cuda.mem_get_info()
+    if free < need_gib * 2**30:
+        pytest.skip("needs %d GiB of free HBM" % need_gib)
+    dev = "cuda"
+    shape = synth.llama70b_shape() if name == "llama70b" else synth.mla_shape()
+    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=synth.categorical_weights(3))
+    n, n_rows, g, dim = wl.n_uids, wl.n_rows, shape.g, shape.dim
+    pool = kvm.make_pool(wl.k_pool.view(torch.int16), None if wl.v_pool is None else wl.v_pool.view(torch.int16), dim,
+                         shape.dtype)
+    rows = kvm.make_rows(wl.row_ntok, wl.row_off, wl.row_q_off, wl.slot_tbl, g, wl.q_elems)
+    scale = 1.0 / float(np.sqrt(dim))
+    mass = torch.full((n,), -1.0, dtype=torch.float32, device=dev)
+    ws = torch.empty(kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, n_rows, g, dim), dtype=torch.uint8, device=dev)
+    sample = np.array([3, n_rows // 2, n_rows - 1] if name == "llama70b" else [n_rows // 3])
+    row_id = torch.repeat_interleave(torch.arange(n_rows, device=dev), torch.from_numpy(wl.nb).to(dev))
+    for phase, frac in (("all resident", 1.0), ("at budget", 0.5 if name == "llama70b" else 0.4)):
+        if frac < 1.0:
+            # take a random share of the units out of HBM (table and state only: the scorer must skip them)
+            drop = torch.rand(n, generator=wl.gen, device=dev) >= frac
+            drop &= (wl.state & PROT) == 0
+            wl.slot_tbl[drop] = -1
+            wl.state[drop] = (wl.state[drop] & (255 - RES)) | HOST
+        q = wl.queries(110)
+        mass.fill_(-1.0)
+        kvm.kvm_score_step(pool, rows, q, scale, mass, ws)
+        torch.cuda.synchronize()
+        case = wl.host_sample(rows=sample)
+        qh = q.view(torch.int16).cpu().numpy().view(np.uint16)
+        q_rows = np.concatenate([qh[r * g * dim:(r + 1) * g * dim] for r in case.sample_rows])
+        ref = np.full(case.n_uids, -1.0, np.float32)
+        oracle.score_step(case.k_pool, dim, shape.dtype, case.row_ntok, case.row_off, case.row_q_off, case.slot_tbl,
+                          q_rows, g, scale, ref)
+        got = mass[torch.from_numpy(case.sample_uids).to(dev)].cpu().numpy()
+        res = case.slot_tbl >= 0
+        assert res.sum() > 500, phase
+        np.testing.assert_allclose(got[res], ref[res], rtol=1e-3, atol=1e-9, err_msg=phase)
+        np.testing.assert_array_equal(got[~res], -1.0)
+        resident = (wl.state & 1) != 0
+        assert bool((mass[resident] >= 0).all()) and bool((mass[~resident] == -1.0).all()), phase
+        row_sum = torch.zeros(n_rows, dtype=torch.float64, device=dev)
+        row_sum.index_add_(0, row_id[resident], mass[resident].double())
+        assert float(row_sum.min()) > 1.0 - 1e-4 and float(row_sum.max()) < g + 1e-3, phase
