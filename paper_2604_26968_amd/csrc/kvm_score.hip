@@ -793,7 +793,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
 #pragma unroll
                 for (int r = 0; r < 4; ++r) sm += __expf(z[r] - mx);
                 sm = rows4_sum(sm);
-                if (cg == 0) pl[ct * 16] = mx + __logf(sm);
+                // Stored from asm for the same reason the loads are: the number of vector memory
+                // operations per step must be exactly what the wait counts assume, whatever the
+                // optimiser would like to do with two plain stores.
+                if (cg == 0) {
+                    const float lse = mx + __logf(sm);
+                    asm volatile("global_store_dword %0, %1, off" : : "v"(pl + ct * 16), "v"(lse) : "memory");
+                }
                 run[ct] = mz_combine(run[ct], MZ{mx, sm});
             }
         };
@@ -1057,10 +1063,15 @@ struct Choice {
     int nct;           // Mfma: 16-query column tiles (1, 2, 4 or 8)
 };
 
+#ifndef KVM_DOT2_MAX_G
+#define KVM_DOT2_MAX_G 8
+#endif
+constexpr int kDot2MaxG = KVM_DOT2_MAX_G;   // larger groups of a small head go to the matrix-core kernel
+
 // Which kernel scores (g, dim), and with what tile size.  The block-value array in LDS takes
 // tile_blocks * (padded g) * 4 bytes: at most 32 KiB.
 Choice choose(int g, int dim) {
-    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8)) return Choice{Path::Dot2, 512, 1, 0};
+    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8) && g <= kDot2MaxG) return Choice{Path::Dot2, 512, 1, 0};
     if (dim <= 256) {
         const int nct = (g + 15) / 16;
         const int nct_p = nct <= 1 ? 1 : nct <= 2 ? 2 : nct <= 4 ? 4 : 8;
@@ -1170,6 +1181,19 @@ int launch_mfma_path(const ScoreArgs& a) {
 template <int DIM, int DT>
 int launch_wide_path(const ScoreArgs& a) {
     constexpr int TB = kWideTileBlocks;
+    {
+        // The kernel's wait counts assume that its only vector memory operations are the ones it issues
+        // itself; register spills would add scratch traffic to the count.  Refuse to run such a build.
+        static int scratch_bytes = -1;
+        if (scratch_bytes < 0) {
+            hipFuncAttributes attr;
+            KVM_HIP_TRY(hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(score_tile_wide_kernel<DIM, DT, TB>)));
+            scratch_bytes = (int)attr.localSizeBytes;
+        }
+        if (scratch_bytes != 0)
+            return fail(KVM_EHIP, "kvm_score_step: the wide kernel was built with %d bytes of scratch per lane",
+                        scratch_bytes);
+    }
     {
         TimedLaunch tl("score_partial", a.st);
         score_tile_wide_kernel<DIM, DT, TB><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
