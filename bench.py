@@ -414,6 +414,20 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- plain read ceiling of this chip over the K pool (what a kernel that only reads could reach) ----
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    probe_bytes = min(wl.k_pool.numel() * wl.k_pool.element_size(), 16 * 2**30)
+    probe_buf = wl.k_pool.view(torch.uint8).flatten()[:probe_bytes]
+    kvm.kvm_probe_read(probe_buf, sink)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        kvm.kvm_probe_read(probe_buf, sink)
+    torch.cuda.synchronize()
+    ceiling = 3 * probe_bytes / (time.perf_counter() - t0) / 1e9
+    out["read_ceiling_GBps"] = round(ceiling, 1)
+    out["roofline"]["frac_of_read_ceiling"] = round(out["roofline"]["achieved"] / ceiling, 4)
+
     # ---- host link measured in the same run (pinned, 1 GiB, both directions) -----------------------
     link_n = 1 << 30
     hbuf = host_tier[:link_n] if host_tier.numel() >= link_n else torch.empty(link_n, dtype=torch.uint8, pin_memory=True)

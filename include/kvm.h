@@ -524,6 +524,13 @@ const char* kvm_last_error(void);
 /* Library version, "major.minor". */
 const char* kvm_version(void);
 
+/* Measurement aid: reads every byte of a device buffer once (16-byte non-temporal
+ * loads, nothing else).  Its rate is the ceiling for any kernel that has to read
+ * the same bytes; time it with kvm_timing_* ("probe_read") or with events.
+ * *sink is a device word the kernel may increment.  Errors: KVM_EINVAL.         */
+int kvm_probe_read(const void* buf /* dev, 16-byte aligned */, size_t bytes /* multiple of 16 */,
+                   uint32_t* sink /* dev [1] */, void* stream);
+
 /* Kernel timing.  While enabled, the device entry points bracket each kernel
  * they launch with HIP events on the caller's stream.  kvm_timing_read
  * synchronises on the recorded events, adds up the elapsed time of every
@@ -531,7 +538,7 @@ const char* kvm_version(void);
  * returns the launch count (0 if the name is unknown); *total_ms gets the sum.
  * Names: "score_partial", "score_finalize", "score_plan", "ema_prio",
  * "beta", "select_hist", "select_emit", "pack", "unpack", "swap", "span",
- * "prefetch_keys", "hash", "dedup", "exchange_flip".                        */
+ * "prefetch_keys", "hash", "dedup", "exchange_flip", "probe_read".          */
 int  kvm_timing_enable(int on);
 void kvm_timing_reset(void);
 int  kvm_timing_read(const char* name, double* total_ms);

@@ -25,7 +25,7 @@ OP_SCORE, OP_SELECT = 0, 1
 
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
-           "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version",
+           "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version", "kvm_probe_read",
            "kvm_timing_enable", "kvm_timing_reset", "kvm_timing_read"]
 
 
@@ -121,6 +121,7 @@ def _load() -> C.CDLL:
                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p]
     lib.kvm_exchange_end.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.kvm_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
     return lib
 
@@ -351,6 +352,10 @@ def kvm_exchange_begin(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, t
 def kvm_exchange_end(slot_tbl, state, in_uids, frame, n: int, stream=None):
     _check(lib.kvm_exchange_end(_ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
                                 _ptr(in_uids, torch.int64), _ptr(frame, torch.int32), n, _stream(stream)))
+
+
+def kvm_probe_read(buf, sink, stream=None):
+    _check(lib.kvm_probe_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink, torch.int32), _stream(stream)))
 
 
 def kvm_last_error() -> str:

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(kvm):
     assert declared == set(kvm.EXPORTS)
     for name in declared:
         assert getattr(kvm.lib, name) is not None
-    assert kvm.kvm_version() == "0.1"
+    assert kvm.kvm_version() == "0.2"
 
 
 def test_struct_layouts_match_header(kvm):
@@ -135,6 +135,21 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_dedup_insert(C.byref(st), 4, 8, 5, 8, None, None, 8, 16, None) == kvm.ENOSPC
     assert lib.kvm_dedup_release(None, None, 1, None, None) == kvm.EINVAL
     assert lib.kvm_dedup_release(C.byref(st), None, 1, None, None) == kvm.EINVAL
+    assert lib.kvm_probe_read(None, 16, None, None) == kvm.EINVAL
+    assert lib.kvm_probe_read(16, 24, 16, None) == kvm.EINVAL          # size not a multiple of 16
+    assert lib.kvm_probe_read(16, 0, 16, None) == kvm.OK
+    assert lib.kvm_score_step_xfer(C.byref(pool), C.byref(empty), None, 1.0, 0, None, None, 0, None, None, -1, None,
+                                   None) == kvm.EINVAL
+    assert lib.kvm_score_step_xfer(C.byref(pool), C.byref(empty), None, 1.0, 0, None, None, 0, None, None, 5, None,
+                                   None) == kvm.EINVAL                   # pairs without buffers
+    assert lib.kvm_score_step_xfer(C.byref(pool), C.byref(empty), None, 1.0, 0, None, None, 0, None, None, 0, None,
+                                   None) == kvm.OK
+    assert lib.kvm_exchange(None, None, None, 0, None, None, 0, None, None, None, 0, None, None) == kvm.EINVAL
+    assert lib.kvm_exchange(C.byref(pool), None, None, 8, None, None, 4, None, None, None, 4, None, None) == kvm.EINVAL
+    assert lib.kvm_exchange_begin(C.byref(pool), None, None, 8, None, None, 4, None, None, 4, None, None, None,
+                                  None) == kvm.EINVAL
+    assert lib.kvm_exchange_end(None, None, 8, None, None, 4, None) == kvm.EINVAL
+    assert lib.kvm_exchange_end(None, None, 8, None, None, 0, None) == kvm.OK
     assert lib.kvm_select_victims(None, None, -1, 0, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_select_victims(None, None, 10, -2, 0, None, 0, None, None, 0, None) == kvm.EINVAL
     assert lib.kvm_pack(None, None, None, 0, None, 0, None, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
