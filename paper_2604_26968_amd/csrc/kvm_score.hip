@@ -744,7 +744,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
         for (int kk = 0; kk < NK; ++kk) qb[ct][kk] = qj[4 * kk];
     }
     const int n_res = build_unit_list<TB>(slot_tbl, c.uid0, c.nbt, n_slots, s_list, s_cnt);
-    MZ run[2] = {{-INFINITY, 0.f}, {-INFINITY, 0.f}};
+    constexpr float kLn2 = 0.6931471805599453f;
+    const float scale2 = scale * 1.4426950408889634f;          // logits in log2 units
+    MZ run[2] = {{-INFINITY, 0.f}, {-INFINITY, 0.f}};          // base-2 running maximum and sum
     if (n_res > 0) {                                  // uniform
         // global -> LDS, 16 bytes per lane, LDS destination = m0 + 16 * lane.  Written as asm so that
         // the waits stay under this kernel's control (see the wait counts below).
@@ -777,30 +779,38 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
                 acc[0] = mfma16<DT>(a[kk % AHEAD], qb[0][kk], acc[0]);
                 acc[1] = mfma16<DT>(a[kk % AHEAD], qb[1][kk], acc[1]);
             }
+            // Softmax statistics in the base-2 domain: one multiply takes the accumulator to
+            // log2 units, v_exp / v_log are base 2 already; natural-log values are formed only
+            // where they leave the kernel.
             const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));
             float* pl = out.part_lse + (size_t)(c.uid0 + i_cur) * 128 + 32 * wave + n;
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
                 float z[4];
-                float mx = -INFINITY;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    z[r] = (4 * cg + r) < tok_in_block ? acc[ct][r] * scale : -INFINITY;
-                    mx = fmaxf(mx, z[r]);
+                for (int r = 0; r < 4; ++r) z[r] = acc[ct][r] * scale2;
+                if (tok_in_block < 16) {              // only a row's last block can be short (uniform)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (4 * cg + r >= tok_in_block) z[r] = -INFINITY;
                 }
-                mx = rows4_max(mx);
+                float mx = rows4_max(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
                 float sm = 0.f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) sm += __expf(z[r] - mx);
+                for (int r = 0; r < 4; ++r) sm += __builtin_amdgcn_exp2f(z[r] - mx);
                 sm = rows4_sum(sm);
                 // Stored from asm for the same reason the loads are: the number of vector memory
                 // operations per step must be exactly what the wait counts assume, whatever the
                 // optimiser would like to do with two plain stores.
                 if (cg == 0) {
-                    const float lse = mx + __logf(sm);
+                    const float lse = (mx + __builtin_amdgcn_logf(sm)) * kLn2;
                     asm volatile("global_store_dword %0, %1, off" : : "v"(pl + ct * 16), "v"(lse) : "memory");
                 }
-                run[ct] = mz_combine(run[ct], MZ{mx, sm});
+                // running (max, sum) of the tile, one exponential: the smaller maximum is rescaled
+                const float d = mx - run[ct].m;
+                const float e = __builtin_amdgcn_exp2f(-fabsf(d));
+                run[ct].z = d <= 0.f ? run[ct].z + sm * e : run[ct].z * e + sm;
+                run[ct].m = fmaxf(run[ct].m, mx);
             }
         };
         // vmcnt(N): at most N vector memory operations of this wavefront still outstanding.  Behind
@@ -840,7 +850,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
 #pragma unroll
         for (int ct = 0; ct < 2; ++ct) {
             const int j = 32 * wave + ct * 16 + n;
-            if (j < G) out.tile_lse[(size_t)tile_id * G + j] = mz_lse(run[ct]);
+            if (j < G)
+                out.tile_lse[(size_t)tile_id * G + j] =
+                    run[ct].z > 0.f ? (run[ct].m + __builtin_amdgcn_logf(run[ct].z)) * kLn2 : -INFINITY;
         }
     }
 }
