@@ -8,22 +8,23 @@
 //   plan_*          build the list of tiles = (row, first block) of at most T blocks for the
 //                   active rows, on the device, so the scorer's grid has no idle workgroups
 //                   whatever the spread of row lengths.  T depends on the kernel (64 .. 512).
-//   score_tile_*    one workgroup per tile.  Per (unit, query) the kernel keeps
-//                   lse = log sum_t exp(z_t) over the block's tokens in LDS (the block's
-//                   softmax mass is exp(lse - row lse)); the workgroup reduces them to the
-//                   tile's lse per query.  A row that fits one tile is finished on the spot
-//                   (only its masses are written); otherwise the tile writes its block
-//                   values, coalesced, plus the tile value, and score_rowmerge combines the
-//                   tiles of the row.
+//   score_tile_*    one workgroup per tile.  Per (unit, query) the kernel forms
+//                   lse = log sum_t exp(z_t) over the block's tokens (the block's softmax
+//                   mass is exp(lse - row lse)) and the tile's lse per query.  The dot2 and
+//                   mfma kernels keep the block values in LDS: a row that fits one tile is
+//                   finished on the spot (only its masses are written); otherwise the tile
+//                   writes its block values, coalesced, plus the tile value, and
+//                   score_rowmerge combines the tiles of the row.  The wide kernel always
+//                   writes block values and leaves every row to the merge.
+//   score_rowmerge* one workgroup per tile again: row lse from the tile values, masses from
+//                   the block values.
+//   xfer_*          bytes of a deferred exchange that ride along with a tile kernel.
 //       _dot2       g in {1, 2, 4, 8}, dim <= 128: queries in registers, v_dot2 with fp32
 //                   accumulate, one wavefront per unit
 //       _mfma       any other g <= 128, dim <= 256: queries as matrix-core operands in
 //                   registers, one wavefront per unit
 //       _wide       dim 576 (MLA latent): the four wavefronts split up to 128 queries and
-//                   share each unit through LDS
-//   score_partial_generic / score_finalize
-//                   fallback for any other (g, dim): queries staged in LDS, (m, s) pairs
-//                   through global memory, one workgroup per row to finish
+//                   share each unit through LDS; frames go global -> LDS directly
 //
 // The tile kernels are the only ones that touch K; they read every resident unit
 // exactly once with non-temporal 16-byte loads that cover 1 KiB contiguous per
@@ -976,97 +977,8 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_big_kernel(
     }
 }
 
-// ---- score_partial_generic: any g and dim, queries staged in LDS, (m, s) pairs to global -----
-constexpr int kGenericTile = 256;
-template <int DIM, int DT>
-__global__ __launch_bounds__(kThreads) void score_partial_generic_kernel(
-    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
-    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
-    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
-    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale,
-    float2* __restrict__ part) {
-    constexpr int NK = DIM / 32;
-    constexpr int QROW_V4 = DIM / 8;
-    extern __shared__ uint4 q_lds[];      // [g][QROW_V4]
-    __shared__ int2 s_list[kGenericTile];
-    __shared__ int s_cnt[4];
-
-    if (blockIdx.x >= *n_tiles) return;
-    const TileCtx c = tile_ctx<kGenericTile>(tiles, row_ntok, row_off, blockIdx.x);
-    const int lane = threadIdx.x & 63;
-    const int t = lane & 15, cg = lane >> 4;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
-    for (int i = threadIdx.x; i < G * QROW_V4; i += kThreads) q_lds[i] = qrow[i];
-    const int n_res = build_unit_list<kGenericTile>(slot_tbl, c.uid0, c.nbt, n_slots, s_list, s_cnt);  // barriers cover q_lds
-
-    for_each_unit<NK>(s_list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
-        const bool valid = t < min(16, c.ntok - 16 * (c.b0 + i_cur));
-        float2* out = part + (c.uid0 + i_cur) * G;
-        for (int j0 = 0; j0 < G; j0 += 4) {
-            float a[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                if (j0 + jj < G) {
-                    const uint4* qj = q_lds + (j0 + jj) * QROW_V4 + cg;
-#pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) a[jj] = dot8<DT>(cur[kk], qj[4 * kk], a[jj]);
-                }
-            const float z = fold_rows(fold_halves(a[0], a[1]), fold_halves(a[2], a[3])) * scale;
-            const float zz = valid ? z : -INFINITY;
-            const float mx = row16_max(zz);
-            const float e = valid ? __expf(zz - mx) : 0.f;
-            const float s = row16_sum(e);
-            const int jq = j0 + query_of_row(cg);
-            if (t == 0 && jq < G) out[jq] = make_float2(mx, s);
-        }
-    });
-}
-
-// ---- score_finalize (generic path) -----------------------------------------------------
-// GP = smallest power of two >= g.  Thread (bsub, j) = (tid / GP, tid % GP)
-// handles query j of blocks bsub, bsub + 256/GP, ...
-template <int GP>
-__global__ __launch_bounds__(kThreads) void score_finalize_kernel(
-    PlanRows pr, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, const float2* __restrict__ part, int agg,
-    float* __restrict__ mass) {
-    constexpr int BS = kThreads / GP;
-    __shared__ float2 s_red[kThreads];
-    __shared__ float s_v[4];
-    const int row = blockIdx.x;
-    if (!row_scorable(pr, row)) return;
-    const int g = pr.g;
-    const int nb = (pr.row_ntok[row] + 15) >> 4;
-    const int64_t uid0 = pr.row_off[row];
-    const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
-    const bool jv = j < g;
-
-    MZ acc{-INFINITY, 0.f};
-    if (jv)
-        for (int b = bsub; b < nb; b += BS) {
-            if ((uint32_t)slot_tbl[uid0 + b] >= n_slots) continue;
-            const float2 p = part[(uid0 + b) * g + j];
-            acc = mz_combine(acc, MZ{p.x, p.y});
-        }
-    const MZ tot = wg_total<GP>(acc, s_red);
-    const float inv = tot.z > 0.f ? 1.f / tot.z : 0.f;
-
-    for (int b0 = 0; b0 < nb; b0 += BS) {
-        const int b = b0 + bsub;
-        const bool res = b < nb && (uint32_t)slot_tbl[uid0 + (b < nb ? b : 0)] < n_slots;
-        float v = 0.f;
-        if (res && jv) {
-            const float2 p = part[(uid0 + b) * g + j];
-            v = p.y * __expf(p.x - tot.m) * inv;
-        }
-        float vv[1] = {v};
-        if (GP > 64) __syncthreads();
-        group_agg<GP, 1>(vv, agg, s_v);
-        if (res && j == 0) mass[uid0 + b] = agg == KVM_AGG_MAX ? vv[0] : vv[0] / (float)g;
-    }
-}
-
 // ---- host side ----------------------------------------------------------------
-enum class Path { Dot2, Mfma, Wide, Generic };
+enum class Path { Dot2, Mfma, Wide, None };
 
 struct Choice {
     Path path;
@@ -1090,7 +1002,7 @@ Choice choose(int g, int dim) {
         return Choice{Path::Mfma, 512 / nct_p, 1, nct_p};
     }
     if (dim == 576) return Choice{Path::Wide, kWideTileBlocks, 1, 0};
-    return Choice{Path::Generic, kGenericTile, 1, 0};
+    return Choice{Path::None, 256, 1, 0};
 }
 
 inline int64_t max_tiles(int64_t n_uids, int64_t n_rows, int tile_blocks) {
@@ -1104,7 +1016,7 @@ struct ScoreWs {
     Tile* tiles;
     uint32_t* row_tile0;
     float* tile_lse;    // [tiles][g]
-    float2* part;       // (m, s) pairs [n_uids][g] (generic path) or floats [n_uids][g] (tile paths)
+    float* part;        // block values [n_uids][g] (row stride 128 on the wide path)
     size_t bytes;
 };
 
@@ -1124,12 +1036,9 @@ ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, const Choice&
     w.tiles = reinterpret_cast<Tile*>(base + off_tiles);
     w.row_tile0 = reinterpret_cast<uint32_t*>(base + off_row0);
     w.tile_lse = reinterpret_cast<float*>(base + off_tmz);
-    w.part = reinterpret_cast<float2*>(base + off_part);
-    // per unit: g floats on the tile paths (128 on the wide path, whose rows are padded), g (m, s) pairs on
-    // the generic path
-    const size_t per_uid = ch.path == Path::Wide      ? 128 * sizeof(float)
-                           : ch.path == Path::Generic ? (size_t)g * sizeof(float2)
-                                                      : (size_t)g * sizeof(float);
+    w.part = reinterpret_cast<float*>(base + off_part);
+    // per unit: g floats (128 on the wide path, whose rows are padded)
+    const size_t per_uid = ch.path == Path::Wide ? 128 * sizeof(float) : (size_t)g * sizeof(float);
     w.bytes = off_part + align_up((size_t)n_uids * per_uid, 256);
     return w;
 }
@@ -1221,47 +1130,6 @@ int launch_wide_path(const ScoreArgs& a) {
     return launch_status("score_rowmerge_big");
 }
 
-// Any g and dim: queries staged in LDS, vector dot products, (m, s) pairs through global memory.
-template <int DIM, int DT>
-int launch_generic_path(const ScoreArgs& a) {
-    const int g = a.rows->g;
-    const uint32_t ns = (uint32_t)a.pool->n_slots;
-    const size_t lds = (size_t)g * (DIM / 8) * sizeof(uint4);
-    auto kern = score_partial_generic_kernel<DIM, DT>;
-    if (lds + 8 * 1024 > 160 * 1024)
-        return fail(KVM_ESHAPE, "kvm_score_step: g %d x dim %d queries do not fit LDS", g, DIM);
-    if (lds > 32 * 1024)
-        KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    if (a.xf.n) {                                   // no room in this kernel: the bytes move first, on their own
-        TimedLaunch tl("swap", a.st);
-        xfer_kernel<<<a.xf.n, kThreads, 0, a.st>>>(a.xf);
-        if (int rc = launch_status("xfer")) return rc;
-    }
-    {
-        TimedLaunch tl("score_partial", a.st);
-        kern<<<a.grid, kThreads, lds, a.st>>>(a.w.tiles, a.w.n_tiles, g, a.rows->row_ntok, a.rows->row_off,
-                                              a.rows->row_q_off, a.rows->slot_tbl,
-                                              static_cast<const uint4*>(a.pool->k_pool), ns,
-                                              static_cast<const uint16_t*>(a.q), a.scale, a.w.part);
-        if (int rc = launch_status("score_partial_generic")) return rc;
-    }
-    TimedLaunch tl("score_finalize", a.st);
-    int gp = 1;
-    while (gp < g) gp <<= 1;
-#define KVM_FIN(GP)                                                                                               \
-    case GP:                                                                                                      \
-        score_finalize_kernel<GP><<<a.rows->n_rows, kThreads, 0, a.st>>>(a.pr, a.rows->slot_tbl, ns, a.w.part,    \
-                                                                         a.out.agg, a.out.mass);                  \
-        break;
-    switch (gp) {
-        KVM_FIN(1) KVM_FIN(2) KVM_FIN(4) KVM_FIN(8) KVM_FIN(16) KVM_FIN(32) KVM_FIN(64) KVM_FIN(128)
-        default: return fail(KVM_ESHAPE, "kvm_score_step: g %d", g);
-    }
-#undef KVM_FIN
-    return launch_status("score_finalize");
-}
-
 template <int DIM, int DT>
 int launch_dim(const ScoreArgs& a, const Choice& ch) {
     if constexpr (DIM <= 128) {
@@ -1287,7 +1155,7 @@ int launch_dim(const ScoreArgs& a, const Choice& ch) {
     if constexpr (DIM == 576) {
         if (ch.path == Path::Wide) return launch_wide_path<DIM, DT>(a);
     }
-    return launch_generic_path<DIM, DT>(a);
+    return fail(KVM_ESHAPE, "kvm_score_step: no kernel for g %d, dim %d", a.rows->g, a.pool->dim);
 }
 
 template <int DT>
@@ -1346,7 +1214,7 @@ int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, fl
     KVM_REQUIRE(ws_bytes >= a.w.bytes, KVM_ENOSPC, "kvm_score_step: workspace %zu < %zu bytes", ws_bytes, a.w.bytes);
     const int64_t tiles_max = max_tiles(rows->n_uids, rows->n_rows, ch.tile_blocks);
     KVM_REQUIRE(tiles_max <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: too many tiles");
-    a.out = TileOut{agg, mass, reinterpret_cast<float*>(a.w.part), a.w.tile_lse};
+    a.out = TileOut{agg, mass, a.w.part, a.w.tile_lse};
     a.xf = xf;
     KVM_REQUIRE(tiles_max + xf.n <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: grid too large");
     if (xf.n) {
