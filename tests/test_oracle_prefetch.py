@@ -189,3 +189,17 @@ def test_nearer_blocks_and_likelier_pairs_come_first(oracle):
     oracle.prefetch_keys(ntok, off, np.zeros(1, np.int32), np.array([nb * 16 - 1], np.int32),
                          np.array([10000], np.int32), state, pair, p_est, 0.9, key, cand)
     assert oracle.select_victims(key, cand, k=1)[0] == 5
+
+
+def test_distance_is_counted_from_the_block_of_the_decode_position(oracle):
+    """Decode position inside block 6 of a 12-block row: block b <= 6 is 6 - b blocks away (not
+    counted from the end of the stored row); blocks after the position are no candidates."""
+    nb = 12
+    ntok, off = np.array([nb * 16], np.int32), np.array([0], np.int64)
+    state = np.full(nb, HOST, np.uint8)
+    key, cand = np.zeros(nb, np.float32), np.zeros(nb, np.uint8)
+    oracle.prefetch_keys(ntok, off, np.zeros(1, np.int32), np.array([100], np.int32), np.array([10000], np.int32),
+                         state, np.zeros(nb, np.uint8), np.ones(16, np.float32), 0.5, key, cand)
+    assert list(np.flatnonzero(cand)) == [0, 1, 2, 3, 4, 5, 6]
+    np.testing.assert_array_equal(key[:7], (1 - 0.5 ** np.arange(7)[::-1]).astype(np.float32))
+    assert np.all(np.isposinf(key[7:]))
