@@ -551,7 +551,8 @@ __device__ __forceinline__ void tile_epilogue(const float* s_lse, float2* s_red 
         // the block values of the resident blocks (query 0 tells), g contiguous floats per block
         if (jv)
             for (int b = bsub; b < c.nbt; b += BS)
-                if (s_lse[b * g] > -INFINITY) o.part_lse[(c.uid0 + b) * g + j] = s_lse[b * g + j];
+                if (s_lse[b * g] > -INFINITY)   // read back once by the row merge: keep it out of the L2
+                    __builtin_nontemporal_store(s_lse[b * g + j], &o.part_lse[(c.uid0 + b) * g + j]);
     }
 }
 
@@ -805,7 +806,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
                 // optimiser would like to do with two plain stores.
                 if (cg == 0) {
                     const float lse = (mx + __builtin_amdgcn_logf(sm)) * kLn2;
-                    asm volatile("global_store_dword %0, %1, off" : : "v"(pl + ct * 16), "v"(lse) : "memory");
+                    asm volatile("global_store_dword %0, %1, off nt" : : "v"(pl + ct * 16), "v"(lse) : "memory");
                 }
                 // running (max, sum) of the tile, one exponential: the smaller maximum is rescaled
                 const float d = mx - run[ct].m;
@@ -892,7 +893,7 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
             const int b = k * BS + bsub;
             const int bc = b < nbt ? b : 0;
             slot[k] = slot_tbl[uid0 + bc];
-            v[k] = o.part_lse[(uid0 + bc) * g + (jv ? j : 0)];
+            v[k] = __builtin_nontemporal_load(&o.part_lse[(uid0 + bc) * g + (jv ? j : 0)]);
         }
 #pragma unroll
         for (int k = 0; k < SWEEPS; ++k) {
@@ -959,8 +960,8 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_big_kernel(
             const int i = idx + 4 * u;
             blk[u] = list_entry(s_list, i < n_res ? i : n_res - 1).x;
             const float* pl = o.part_lse + (size_t)(plan.uid0 + blk[u]) * gs;
-            a[u] = pl[v0 ? lane : 0];
-            b[u] = pl[v1 ? lane + 64 : 0];
+            a[u] = __builtin_nontemporal_load(pl + (v0 ? lane : 0));
+            b[u] = __builtin_nontemporal_load(pl + (v1 ? lane + 64 : 0));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
