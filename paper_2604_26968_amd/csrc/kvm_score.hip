@@ -748,7 +748,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     const int n_res = build_unit_list<TB>(slot_tbl, c.uid0, c.nbt, n_slots, s_list, s_cnt);
     constexpr float kLn2 = 0.6931471805599453f;
     const float scale2 = scale * 1.4426950408889634f;          // logits in log2 units
-    MZ run[2] = {{-INFINITY, 0.f}, {-INFINITY, 0.f}};          // base-2 running maximum and sum
+    MZ run[2] = {{-INFINITY, 0.f}, {-INFINITY, 0.f}};          // base-2 reference and sum of exp2(z - reference)
     if (n_res > 0) {                                  // uniform
         // global -> LDS, 16 bytes per lane, LDS destination = m0 + 16 * lane.  Written as asm so that
         // the waits stay under this kernel's control (see the wait counts below).
@@ -786,33 +786,46 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
             // where they leave the kernel.
             const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));
             float* pl = out.part_lse + (size_t)(c.uid0 + i_cur) * 128 + 32 * wave + n;
+            float z[2][4], ml[2];
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
-                float z[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) z[r] = acc[ct][r] * scale2;
+                for (int r = 0; r < 4; ++r) z[ct][r] = acc[ct][r] * scale2;
                 if (tok_in_block < 16) {              // only a row's last block can be short (uniform)
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        if (4 * cg + r >= tok_in_block) z[r] = -INFINITY;
+                        if (4 * cg + r >= tok_in_block) z[ct][r] = -INFINITY;
                 }
-                float mx = rows4_max(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])));
+                ml[ct] = fmaxf(fmaxf(z[ct][0], z[ct][1]), fmaxf(z[ct][2], z[ct][3]));
+            }
+            // Exponentials are taken against a reference that the four rows of a query share: the
+            // largest logit the query has met so far in this tile, refreshed only when a block
+            // comes within 2^-60 of overflowing against it (first unit included; the branch is
+            // uniform and almost never taken).  That saves the per-block maximum across rows and
+            // makes the tile statistic a plain sum.  A block more than 2^126 below the reference
+            // underflows to mass 0, which is what it is at any tolerance.
+            if (__ballot(ml[0] - run[0].m > 60.f || ml[1] - run[1].m > 60.f)) {
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct) {
+                    const float ref = rows4_max(fmaxf(run[ct].m, ml[ct]));
+                    run[ct].z *= __builtin_amdgcn_exp2f(run[ct].m - ref);
+                    run[ct].m = ref;
+                }
+            }
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct) {
                 float sm = 0.f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) sm += __builtin_amdgcn_exp2f(z[r] - mx);
+                for (int r = 0; r < 4; ++r) sm += __builtin_amdgcn_exp2f(z[ct][r] - run[ct].m);
                 sm = rows4_sum(sm);
                 // Stored from asm for the same reason the loads are: the number of vector memory
                 // operations per step must be exactly what the wait counts assume, whatever the
                 // optimiser would like to do with two plain stores.
                 if (cg == 0) {
-                    const float lse = (mx + __builtin_amdgcn_logf(sm)) * kLn2;
+                    const float lse = (run[ct].m + __builtin_amdgcn_logf(sm)) * kLn2;
                     asm volatile("global_store_dword %0, %1, off nt" : : "v"(pl + ct * 16), "v"(lse) : "memory");
                 }
-                // running (max, sum) of the tile, one exponential: the smaller maximum is rescaled
-                const float d = mx - run[ct].m;
-                const float e = __builtin_amdgcn_exp2f(-fabsf(d));
-                run[ct].z = d <= 0.f ? run[ct].z + sm * e : run[ct].z * e + sm;
-                run[ct].m = fmaxf(run[ct].m, mx);
+                run[ct].z += sm;
             }
         };
         // vmcnt(N): at most N vector memory operations of this wavefront still outstanding.  Behind

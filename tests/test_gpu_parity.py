@@ -130,6 +130,28 @@ def test_score_mla_latent_576_g128(oracle):
     check_mass(oracle, case, synth.make_queries(case, 23), 1 / 24)
 
 
+def test_score_mla_large_and_uneven_logits(oracle):
+    """The wide kernel takes exponentials against a running reference per query.  Small-integer keys
+    and queries make every logit exact in fp32, so logits of hundreds of nats can be used: heads of very
+    different scale, keys that grow along the row (the maximum keeps rising, the reference is refreshed
+    mid-tile) and blocks that vanish against it must all come out right, over several tiles."""
+    shape = synth.Shape(1, 128, 1, 576, synth.BF16, False, [6000, 300])
+    case = synth.make_case(shape, seed=19)
+    rng = np.random.default_rng(19)
+    for r in range(case.n_rows):
+        nb = (case.row_ntok[r] + 15) // 16
+        for b in range(nb):
+            slot = case.slot_tbl[case.row_off[r] + b]
+            k = rng.integers(-1, 2, 16 * 576).astype(np.float32) * (1 + (3 * b) // nb)      # growth 1, 2, 3
+            case.k_pool[slot] = synth.to_bits(k, shape.dtype)
+    evict_some(case, 0.3, 6)
+    q = rng.integers(-1, 2, (case.n_rows, 128, 576)).astype(np.float32)
+    q *= np.array([1, 2, 4, 8], np.float32)[np.arange(128) % 4][None, :, None]                 # per-head scales
+    qb = synth.to_bits(q.reshape(-1), shape.dtype)
+    got, want = check_mass(oracle, case, qb, 0.25)                # logits up to several hundred nats
+    assert np.isfinite(got).all() and got.max() > 0.3
+
+
 def test_score_properties(oracle):
     """Properties that hold at any size: per-query masses sum to 1 (mean aggregation),
     zero queries give token fractions exactly."""
