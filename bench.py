@@ -32,9 +32,9 @@ WORKLOADS = {
     "mla": ("deepseek-v3-shaped MLA: 61 layers, 576-channel latent, 128 absorbed queries, bf16, %d x 32768 tok",
             lambda synth, n: synth.mla_shape(n), 32, 0.40, 0.90, 1024, 2, 0),
 }
-# FETCH_SIZE 6,626,252.2 x 2 KiB + WRITE_SIZE 37,911.3 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
+# FETCH_SIZE 6,626,289.7 x 2 KiB + WRITE_SIZE 37,911.2 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
 # with the 1,024 transfer workgroups of --swap-mode overlap riding along
-SCORE_TILE_TRAFFIC_BYTES = int(6626252.2 * 2048 + 37911.3 * 1024)
+SCORE_TILE_TRAFFIC_BYTES = int(6626289.7 * 2048 + 37911.2 * 1024)
 
 
 def main():
