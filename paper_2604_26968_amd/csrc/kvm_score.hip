@@ -597,7 +597,11 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
 
     for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_lse[i] = -INFINITY;
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
-    if (n_res == 0) return;                      // nothing resident in this tile (uniform)
+    if (n_res == 0) {                            // nothing resident in this tile (uniform)
+        // a row of several tiles still folds this tile's statistic: it must read as empty
+        if (c.nb > T && threadIdx.x < G) out.tile_lse[(size_t)tile_id * G + threadIdx.x] = -INFINITY;
+        return;
+    }
 
     for_each_unit_deep<NK>(lds.list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
         const bool valid = t < min(16, c.ntok - 16 * (c.b0 + i_cur));
@@ -661,7 +665,11 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     }
     for (int i = threadIdx.x; i < c.nbt * G; i += kThreads) s_lse[i] = -INFINITY;
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
-    if (n_res == 0) return;
+    if (n_res == 0) {                            // nothing resident in this tile (uniform)
+        // a row of several tiles still folds this tile's statistic: it must read as empty
+        if (c.nb > T && threadIdx.x < G) out.tile_lse[(size_t)tile_id * G + threadIdx.x] = -INFINITY;
+        return;
+    }
 
     for_each_unit<NK>(lds.list, n_res, k_pool, DIM * 2, [&](const uint4 (&cur)[NK], int i_cur) {
         const int tok_in_block = min(16, c.ntok - 16 * (c.b0 + i_cur));

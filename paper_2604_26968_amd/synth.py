@@ -362,3 +362,19 @@ def llama70b_shape(n_seq: int = 4, n_tok: int = 131072) -> Shape:
 def mla_shape(n_seq: int = 32, n_tok: int = 32768) -> Shape:
     """DeepSeek-V3-shaped MLA: 61 layers, one 576-channel latent head scored by 128 queries, no V."""
     return Shape(61, 128, 1, 576, BF16, False, [n_tok] * n_seq)
+
+
+def lognormal_lengths(n_seq: int, seed: int, mu: float = 7.0, sigma: float = 1.0, lo: int = 16, hi: int = 32768):
+    """Prompt lengths of the fleet workload: lognormal(mu, sigma) tokens clipped to [lo, hi]."""
+    rng = np.random.default_rng(seed)
+    return [int(x) for x in np.clip(np.exp(rng.normal(mu, sigma, n_seq)), lo, hi)]
+
+
+def mha_fleet_shape(n_seq: int = 48, seed: int = 5) -> Shape:
+    """MHA half of the fleet workload: 32 layers, 32 q = 32 KV heads (g = 1), d 128, bf16, lognormal lengths."""
+    return Shape(32, 32, 32, 128, BF16, True, lognormal_lengths(n_seq, seed))
+
+
+def mqa_fleet_shape(n_seq: int = 1536, seed: int = 6) -> Shape:
+    """MQA half of the fleet workload: 32 layers, 32 q / 1 KV head (g = 32), d 128, bf16, lognormal lengths."""
+    return Shape(32, 32, 1, 128, BF16, True, lognormal_lengths(n_seq, seed))

@@ -44,7 +44,9 @@ class DeviceCase:
         self.q_elems = case.n_rows * sh.g * sh.dim
         ws_bytes = max(kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, case.n_rows, sh.g, sh.dim),
                        kvm.kvm_workspace_bytes(kvm.OP_SELECT, n), 256)
-        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
+        # The workspace is handed over with garbage in it (floats of 3.4e38, huge counters): no entry
+        # point may depend on what it held before the call.
+        self.ws = torch.full((ws_bytes,), 0x7F, dtype=torch.uint8, device="cuda")
         self.rec = sh.unit_k_bytes + sh.unit_v_bytes
         self.staging_records = staging_records
         self.row_active = None

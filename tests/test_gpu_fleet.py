@@ -66,7 +66,7 @@ def run_fleet(oracle, shape_a, shape_b, steps=5, seed=40):
     n_bad = torch.zeros(1, dtype=torch.int32, device=dev)
     ws_bytes = max([kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, len(r["ntok"]), r["g"], fl.dim) for r in fl.rows]
                    + [kvm.kvm_workspace_bytes(kvm.OP_SELECT, n)])
-    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+    ws = torch.full((ws_bytes,), 0x7F, dtype=torch.uint8, device=dev)
     dev_rows = [dict(ntok=t(r["ntok"]), off=t(r["off"]), q_off=t(r["q_off"]), weight=t(r["weight"])) for r in fl.rows]
     rec = 2 * 16 * fl.dim * 2
 

@@ -470,7 +470,7 @@ def test_dedup_store_matches_the_sequential_definition(oracle):
         want = uids.copy()
         want[keep] = ref.insert(digests[keep], uids[keep])
         canon = torch.zeros(n, dtype=torch.int64, device="cuda")
-        ws = torch.zeros(n, dtype=torch.int64, device="cuda")
+        ws = torch.full((n,), 0x7F7F7F7F7F7F7F7F, dtype=torch.int64, device="cuda")
         kvm.kvm_dedup_insert(store, dev_of(digests), dev_of(uids), n, canon, ws, n_full=n_full, n_collide=n_col)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(canon.cpu().numpy(), want)
@@ -496,7 +496,7 @@ def test_hash_then_dedup_finds_the_planted_duplicates(oracle):
     kvm.kvm_hash_units(dev.pool, dev.slot_tbl, dev.state, dev_of(uids), n, d)
     store = kvm.make_store(1 << 12)
     canon = torch.zeros(n, dtype=torch.int64, device="cuda")
-    ws = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ws = torch.full((n,), 0x7F7F7F7F7F7F7F7F, dtype=torch.int64, device="cuda")
     kvm.kvm_dedup_insert(store, d, dev_of(uids), n, canon, ws)
     torch.cuda.synchronize()
     canon = canon.cpu().numpy()
@@ -518,7 +518,7 @@ def test_dedup_table_too_small_reports_it():
     store = kvm.make_store(16)
     n_full = torch.zeros(1, dtype=torch.int32, device="cuda")
     canon = torch.zeros(100, dtype=torch.int64, device="cuda")
-    ws = torch.zeros(100, dtype=torch.int64, device="cuda")
+    ws = torch.full((100,), 0x7F7F7F7F7F7F7F7F, dtype=torch.int64, device="cuda")
     uids = np.arange(100, dtype=np.int64)
     kvm.kvm_dedup_insert(store, dev_of(digests), dev_of(uids), 100, canon, ws, n_full=n_full)
     torch.cuda.synchronize()

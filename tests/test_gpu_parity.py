@@ -112,6 +112,29 @@ def test_score_tile_boundaries(oracle):
         check_mass(oracle, case, q, 0.125, agg=1)
 
 
+@pytest.mark.parametrize("hq,hkv,dim", [(1, 1, 128), (4, 1, 128), (32, 1, 128), (128, 1, 576)])
+def test_score_rows_with_wholly_evicted_tiles(oracle, hq, hkv, dim):
+    """Rows of several tiles in which the first, a middle or the last tile holds no resident block
+    (after heavy eviction only a handful of blocks of a long row remain): the empty tile must count
+    as nothing in the row's normaliser, whatever the workspace held before."""
+    has_v = dim != 576
+    lens = [16 * 780 - 2, 16 * 1537, 16 * 2048, 16 * 600 + 7]
+    case = synth.make_case(synth.Shape(1, hq, hkv, dim, synth.BF16, has_v, lens), seed=5 + hq)
+    keep = {0: [779, 521], 1: [600, 1536], 2: [3, 2047], 3: [599]}
+    for r in range(case.n_rows):
+        o, nb = int(case.row_off[r]), (int(case.row_ntok[r]) + 15) // 16
+        gone = np.setdiff1d(np.arange(nb), keep[r])
+        case.slot_tbl[o + gone] = -3
+        case.state[o + gone] = HOST
+    q = synth.make_queries(case, 23)
+    got, want = check_mass(oracle, case, q, 1.0 / np.sqrt(dim))
+    for r in range(case.n_rows):
+        o = int(case.row_off[r])
+        if hq == 1:
+            assert abs(sum(got[o + b] for b in keep[r]) - 1.0) < 1e-5
+    check_mass(oracle, case, q, 1.0 / np.sqrt(dim), agg=1)
+
+
 def test_score_llama8b_twin(oracle):
     case = synth.llama8b_twin(n_seq=2, n_layers=1)
     evict_some(case, 0.4, 9)
@@ -226,7 +249,7 @@ def select_both(oracle, dev, prio, state, k=-1, budget=0, cap=None):
     dev.prio = torch.from_numpy(prio).cuda()
     dev.state = torch.from_numpy(state).cuda()
     dev.victims = torch.full((max(len(prio), 1),), -1, dtype=torch.int64, device="cuda")
-    dev.ws = torch.zeros(max(kvm.kvm_workspace_bytes(kvm.OP_SELECT, len(prio)), 256), dtype=torch.uint8,
+    dev.ws = torch.full((max(kvm.kvm_workspace_bytes(kvm.OP_SELECT, len(prio)), 256),), 0x7F, dtype=torch.uint8,
                          device="cuda")
     got = dev.select(k=k, budget=budget, cap=cap)
     want = oracle.select_victims(prio, state, k=k, budget_units=budget, victims_cap=cap)
