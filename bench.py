@@ -33,9 +33,9 @@ WORKLOADS = {
             lambda synth, n: synth.mla_shape(n), 32, 0.40, 0.90, 1024, 2, 0),
     # the two halves of the fleet configuration, each on its own (prompt lengths lognormal(7, 1))
     "mha": ("fleet, MHA half: 32 layers, 32q/32kv heads (g 1), d128, bf16, %d seqs lognormal(7,1) tok",
-            lambda synth, n: synth.mha_fleet_shape(n), 72, 0.60, 0.90, 1024, 4096, 0),
+            lambda synth, n: synth.mha_fleet_shape(n), 72, 0.60, 0.90, 1024, 32768, 0),
     "mqa": ("fleet, MQA half: 32 layers, 32q/1kv head (g 32), d128, bf16, %d seqs lognormal(7,1) tok",
-            lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 256, 0),
+            lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 8192, 0),
 }
 # FETCH_SIZE 6,626,289.7 x 2 KiB + WRITE_SIZE 37,911.2 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
 # with the 1,024 transfer workgroups of --swap-mode overlap riding along
