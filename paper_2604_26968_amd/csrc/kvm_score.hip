@@ -16,7 +16,8 @@
 //                   writes its block values, coalesced, plus the tile value, and
 //                   score_rowmerge combines the tiles of the row.  The wide kernel always
 //                   writes block values and leaves every row to the merge.
-//   score_rowmerge* one workgroup per tile again: row lse from the tile values, masses from
+//   score_rowmerge* a fixed grid strides over the tiles of the rows that are not finished yet
+//                   (a list the plan also makes): row lse from the tile values, masses from
 //                   the block values.
 //   xfer_*          bytes of a deferred exchange that ride along with a tile kernel.
 //       _dot2       g in {1, 2, 4, 8}, dim <= 128: queries in registers, v_dot2 with fp32
@@ -161,6 +162,30 @@ __device__ __forceinline__ float rows4_sum(float v) {
     return x + y;
 }
 
+// Maximum (MAX) or sum over each aligned group of N lanes (N a power of two up to 64), result in
+// every lane of the group: DPP permutes within a row of 16 lanes, lane swaps across rows.  No LDS
+// crossbar traffic (ds_bpermute, which is what __shfl_xor becomes, takes an LDS issue slot per
+// value and the row merge reduces dozens of values per thread).
+template <int N, bool MAX>
+__device__ __forceinline__ float lanes_allreduce(float v) {
+    auto op = [](float a, float b) { return MAX ? fmaxf(a, b) : a + b; };
+    if constexpr (N >= 2) v = op(v, dpp_f<0xB1>(v));
+    if constexpr (N >= 4) v = op(v, dpp_f<0x4E>(v));
+    if constexpr (N >= 8) v = op(v, dpp_f<0x141>(v));
+    if constexpr (N >= 16) v = op(v, dpp_f<0x140>(v));
+    if constexpr (N >= 32) {
+        float x, y;
+        swap16(v, v, x, y);
+        v = op(x, y);
+    }
+    if constexpr (N >= 64) {
+        float x, y;
+        swap32(v, v, x, y);
+        v = op(x, y);
+    }
+    return v;
+}
+
 // Running softmax statistics: maximum m and z = sum exp(x - m).
 struct MZ {
     float m, z;
@@ -185,6 +210,7 @@ struct PlanRows {
     const int64_t* row_off;
     const int64_t* row_q_off;
     const uint8_t* row_active;
+    int merge_all;      // the row merge visits every tile (wide path), not only those of rows with several
 };
 
 __device__ __forceinline__ bool row_scorable(const PlanRows& p, int r) {
@@ -207,19 +233,19 @@ __device__ __forceinline__ uint32_t tiles_of_row(const PlanRows& p, int r) {
 
 // Exclusive scan of one value per thread over a workgroup of kPlanThreads; returns the
 // exclusive prefix and stores the workgroup total in *total.
-__device__ uint32_t wg_exclusive_scan(uint32_t v, uint32_t* total) {
-    __shared__ uint32_t wave_sums[kPlanThreads / kWave];
+__device__ uint64_t wg_exclusive_scan(uint64_t v, uint64_t* total) {
+    __shared__ uint64_t wave_sums[kPlanThreads / kWave];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t inc = v;
+    uint64_t inc = v;
     for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(inc, d);
+        const uint64_t o = (uint64_t)__shfl_up((unsigned long long)inc, d);
         if (lane >= d) inc += o;
     }
     if (lane == 63) wave_sums[wave] = inc;
     __syncthreads();
-    uint32_t base = 0, tot = 0;
+    uint64_t base = 0, tot = 0;
     for (int w = 0; w < kPlanThreads / kWave; ++w) {
-        const uint32_t s = wave_sums[w];
+        const uint64_t s = wave_sums[w];
         if (w < wave) base += s;
         tot += s;
     }
@@ -228,35 +254,64 @@ __device__ uint32_t wg_exclusive_scan(uint32_t v, uint32_t* total) {
     return base + inc - v;
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanRows p, uint32_t* wg_sum) {
+// What a row adds to the two counts the plan scans together: its tiles in the low half and, in
+// the high half, those of them that the row merge has to visit (all of them if the row has
+// more than one tile, none otherwise).  Both totals stay below 2^32 (checked on the host).
+__device__ __forceinline__ uint64_t plan_counts(const PlanRows& p, uint32_t nt) {
+    return (uint64_t)nt | ((uint64_t)((nt > 1 || p.merge_all) ? nt : 0) << 32);
+}
+
+// What the row merge needs to know of a tile it visits, in one 32-byte record, so that a
+// workgroup reaches its data after a single dependent load.
+struct alignas(16) MergeTile {
+    int64_t uid0;       // first unit of the tile
+    uint32_t tile0;     // first tile of its row (the row's tile statistics start there)
+    int32_t nbt;        // blocks in the tile
+    int32_t n_t;        // tiles of its row
+    int32_t pad[3];
+};
+
+__global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanRows p, uint64_t* wg_sum) {
     const int r = blockIdx.x * kPlanThreads + threadIdx.x;
-    uint32_t total;
-    (void)wg_exclusive_scan(tiles_of_row(p, r), &total);
+    uint64_t total;
+    (void)wg_exclusive_scan(plan_counts(p, tiles_of_row(p, r)), &total);
     if (threadIdx.x == 0) wg_sum[blockIdx.x] = total;
 }
 
-// One workgroup: turns wg_sum[0..n) into exclusive prefixes in place and writes the grand total.
-__global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(int n, uint32_t* wg_sum, uint32_t* n_tiles) {
-    uint32_t carry = 0;
+// One workgroup: turns wg_sum[0..n) into exclusive prefixes in place and writes the grand totals:
+// counts[0] = tiles, counts[1] = tiles of rows with more than one tile.
+__global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(int n, uint64_t* wg_sum, uint32_t* counts) {
+    uint64_t carry = 0;
     for (int base = 0; base < n; base += kPlanThreads) {
         const int i = base + threadIdx.x;
-        const uint32_t v = i < n ? wg_sum[i] : 0;
-        uint32_t total;
-        const uint32_t ex = wg_exclusive_scan(v, &total);
+        const uint64_t v = i < n ? wg_sum[i] : 0;
+        uint64_t total;
+        const uint64_t ex = wg_exclusive_scan(v, &total);
         if (i < n) wg_sum[i] = carry + ex;
         carry += total;
     }
-    if (threadIdx.x == 0) *n_tiles = carry;
+    if (threadIdx.x == 0) {
+        counts[0] = (uint32_t)carry;
+        counts[1] = (uint32_t)(carry >> 32);
+    }
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, const uint32_t* wg_base, Tile* tiles,
-                                                                 uint32_t* row_tile0) {
+__global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, const uint64_t* wg_base, Tile* tiles,
+                                                                 MergeTile* merge) {
     const int r = blockIdx.x * kPlanThreads + threadIdx.x;
     const uint32_t nt = tiles_of_row(p, r);
-    uint32_t total;
-    const uint32_t first = wg_base[blockIdx.x] + wg_exclusive_scan(nt, &total);
-    if (r < p.n_rows) row_tile0[r] = first;
+    uint64_t total;
+    const uint64_t at = wg_base[blockIdx.x] + wg_exclusive_scan(plan_counts(p, nt), &total);
+    const uint32_t first = (uint32_t)at, mfirst = (uint32_t)(at >> 32);
     for (uint32_t i = 0; i < nt; ++i) tiles[first + i] = Tile{r, (int32_t)(i * p.tile_blocks)};
+    if (nt > 1 || (nt && p.merge_all)) {
+        const int32_t nb = (p.row_ntok[r] + 15) >> 4;
+        const int64_t off = p.row_off[r];
+        for (uint32_t i = 0; i < nt; ++i) {
+            const int32_t b0 = (int32_t)(i * p.tile_blocks);
+            merge[mfirst + i] = MergeTile{off + b0, first, min(p.tile_blocks, nb - b0), (int32_t)nt, {0, 0, 0}};
+        }
+    }
 }
 
 // ---- bytes of a deferred exchange riding along with a scoring launch ----------------------
@@ -343,15 +398,31 @@ __device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, const int32_t* ro
 // block order: every thread looks at up to T/256 table entries, a ballot + popcount
 // gives each resident entry its place.  Returns the list length.  Contains two barriers.
 template <int T>
-__device__ __forceinline__ int build_unit_list(const int32_t* __restrict__ slot_tbl, int64_t uid0, int nbt,
-                                               uint32_t n_slots, int2* s_list, int* s_cnt /* [E * 4] */) {
+struct TileSlots {
+    int v[(T + kThreads - 1) / kThreads];
+};
+
+// The table entries of a tile, thread t holding blocks t, t + 256, ... (-1 past the end).
+template <int T>
+__device__ __forceinline__ TileSlots<T> load_tile_slots(const int32_t* __restrict__ slot_tbl, int64_t uid0, int nbt) {
+    TileSlots<T> s;
+#pragma unroll
+    for (int e = 0; e < (T + kThreads - 1) / kThreads; ++e) {
+        const int b = e * kThreads + threadIdx.x;
+        s.v[e] = b < nbt ? slot_tbl[uid0 + b] : -1;
+    }
+    return s;
+}
+
+template <int T>
+__device__ __forceinline__ int build_unit_list(TileSlots<T> slots, uint32_t n_slots, int2* s_list,
+                                               int* s_cnt /* [E * 4] */) {
     constexpr int E = (T + kThreads - 1) / kThreads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int slot[E], within[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-        const int b = e * kThreads + threadIdx.x;
-        slot[e] = b < nbt ? slot_tbl[uid0 + b] : -1;
+        slot[e] = slots.v[e];
         if ((uint32_t)slot[e] >= n_slots) slot[e] = -1;
         const uint64_t bal = __ballot(slot[e] >= 0);
         within[e] = __popcll(bal & ((1ull << lane) - 1ull));
@@ -371,6 +442,12 @@ __device__ __forceinline__ int build_unit_list(const int32_t* __restrict__ slot_
     }
     __syncthreads();
     return total;
+}
+
+template <int T>
+__device__ __forceinline__ int build_unit_list(const int32_t* __restrict__ slot_tbl, int64_t uid0, int nbt,
+                                               uint32_t n_slots, int2* s_list, int* s_cnt /* [E * 4] */) {
+    return build_unit_list<T>(load_tile_slots<T>(slot_tbl, uid0, nbt), n_slots, s_list, s_cnt);
 }
 
 template <int NK>
@@ -456,8 +533,10 @@ __device__ __forceinline__ void for_each_unit_deep(const int2* s_list, int n_res
 struct TileOut {
     int agg;
     float* mass;        // [n_uids]
-    float* part_lse;    // [n_uids][g]: log sum exp of the block's logits, rows of more than one tile only
-    float* tile_lse;    // [n_tiles][g]: log sum exp over the tile, same rows
+    // Rows of more than one tile only.  Row stride of both: g rounded up to a power of two on the dot2 and
+    // mfma paths (vector loads in the row merge stay aligned); on the wide path 128 and g.
+    float* part_lse;    // [n_uids][stride]: log sum exp of the block's logits
+    float* tile_lse;    // [n_tiles][stride]: log sum exp over the tile
 };
 
 // Group aggregation of N values per thread over the GP lanes / threads that hold the
@@ -466,13 +545,13 @@ struct TileOut {
 template <int GP, int N>
 __device__ __forceinline__ void group_agg(float (&v)[N], int agg, float* s_v) {
     constexpr int IN_WAVE = GP <= 64 ? GP : 64;
+    if (agg == KVM_AGG_MAX) {
 #pragma unroll
-    for (int k = 0; k < N; ++k)
+        for (int k = 0; k < N; ++k) v[k] = lanes_allreduce<IN_WAVE, true>(v[k]);
+    } else {
 #pragma unroll
-        for (int d = IN_WAVE / 2; d >= 1; d >>= 1) {
-            const float o = __shfl_xor(v[k], d);
-            v[k] = agg == KVM_AGG_MAX ? fmaxf(v[k], o) : v[k] + o;
-        }
+        for (int k = 0; k < N; ++k) v[k] = lanes_allreduce<IN_WAVE, false>(v[k]);
+    }
     if constexpr (GP > 64) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         if (lane == 0)
@@ -547,12 +626,12 @@ __device__ __forceinline__ void tile_epilogue(const float* s_lse, float2* s_red 
             }
         }
     } else {
-        if (bsub == 0 && jv) o.tile_lse[tile_index * g + j] = tile_lse;
+        if (bsub == 0 && jv) o.tile_lse[tile_index * GP + j] = tile_lse;
         // the block values of the resident blocks (query 0 tells), g contiguous floats per block
         if (jv)
             for (int b = bsub; b < c.nbt; b += BS)
                 if (s_lse[b * g] > -INFINITY)   // read back once by the row merge: keep it out of the L2
-                    __builtin_nontemporal_store(s_lse[b * g + j], &o.part_lse[(c.uid0 + b) * g + j]);
+                    __builtin_nontemporal_store(s_lse[b * g + j], &o.part_lse[(c.uid0 + b) * GP + j]);
     }
 }
 
@@ -667,7 +746,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) {                            // nothing resident in this tile (uniform)
         // a row of several tiles still folds this tile's statistic: it must read as empty
-        if (c.nb > T && threadIdx.x < G) out.tile_lse[(size_t)tile_id * G + threadIdx.x] = -INFINITY;
+        if (c.nb > T && threadIdx.x < G) out.tile_lse[(size_t)tile_id * GP + threadIdx.x] = -INFINITY;
         return;
     }
 
@@ -880,122 +959,204 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     }
 }
 
+// Log-sum-exp of query j over the tile values first, first + STEP, ... of a row (n_t tiles, g
+// values per tile), in two calls so that other loads can be issued in between: the first
+// sixteen values are loaded at once, without a branch (most rows have no more), and folded
+// later; a plain loop over the tiles would wait for every load in turn, and with sixteen tiles
+// per row that chain was most of the kernel's time.
+constexpr int kFoldBatch = 16;
+struct TileVals {
+    float x[kFoldBatch];
+};
+template <int STEP>
+__device__ __forceinline__ TileVals load_tile_values(const float* __restrict__ tl, int g, int j, int first, int n_t) {
+    TileVals t;
+#pragma unroll
+    for (int u = 0; u < kFoldBatch; ++u) {
+        const int i = first + u * STEP;
+        t.x[u] = tl[(size_t)(i < n_t ? i : 0) * g + j];
+    }
+    return t;
+}
+// (maximum, sum of exp(x - maximum)) of one batch whose first value is tile i0; no branches.
+template <int STEP>
+__device__ __forceinline__ MZ fold_batch(const TileVals& t, int i0, int n_t) {
+    float x[kFoldBatch];
+    float M = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kFoldBatch; ++u) {
+        x[u] = i0 + u * STEP < n_t ? t.x[u] : -INFINITY;
+        M = fmaxf(M, x[u]);
+    }
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float z = 0.f;
+#pragma unroll
+    for (int u = 0; u < kFoldBatch; ++u) z += __expf(x[u] - Ms);
+    return MZ{M, z};
+}
+template <int STEP>
+__device__ __forceinline__ MZ fold_tile_values(const TileVals& head, const float* __restrict__ tl, int g, int j,
+                                               int first, int n_t) {
+    MZ t = fold_batch<STEP>(head, first, n_t);
+    for (int i0 = first + kFoldBatch * STEP; i0 < n_t; i0 += kFoldBatch * STEP) {     // rows of more than 16 tiles
+        const TileVals more = load_tile_values<STEP>(tl, g, j, i0, n_t);
+        t = mz_combine(t, fold_batch<STEP>(more, i0, n_t));
+    }
+    return t;
+}
+
 // ---- score_rowmerge: rows of more than one tile ---------------------------------------
-// One workgroup per tile again: it folds the tile values of its row into the row's log sum
-// exp (a few numbers, read by every thread) and turns its own tile's block values into masses.
-template <int GP, int T, int SUB>
+// A fixed grid strides over the plan's list of tiles to visit (one 32-byte record each).  Per
+// tile the first GP threads fold the tile values of the tile's row into the row's log sum exp
+// (one query each, through LDS to the others); then every thread turns block values into
+// masses, V = min(4, GP) queries of a block at a time from one vector load, GP / V lanes per
+// block.  The kernel is bound by instruction issue and by the latency of its dependent loads,
+// not by bytes: the record is the only load the data loads wait for, and those are issued, all
+// of them, before anything is used.
+template <int V>
+struct RowVec;
+template <>
+struct RowVec<1> {
+    typedef float type;
+};
+template <>
+struct RowVec<2> {
+    typedef float type __attribute__((ext_vector_type(2)));
+};
+template <>
+struct RowVec<4> {
+    typedef float type __attribute__((ext_vector_type(4)));
+};
+template <int V>
+__device__ __forceinline__ float vec_elem(const typename RowVec<V>::type& v, int i) {
+    if constexpr (V == 1)
+        return v;
+    else
+        return v[i];
+}
+
+template <int GP, int T>
 __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
-    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int g,
-    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
-    const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
-    constexpr int BS = kThreads / GP;
+    const uint32_t* __restrict__ counts, const MergeTile* __restrict__ merge, int g,
+    const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
+    static_assert(GP <= 64, "larger groups take score_rowmerge_big");
+    constexpr int V = GP < 4 ? GP : 4;      // queries per thread
+    constexpr int LP = GP / V;              // lanes per block
+    constexpr int BS = kThreads / LP;       // blocks per sweep
     constexpr int SWEEPS = (T + BS - 1) / BS;
-    __shared__ float s_v[GP > 64 ? 4 * SWEEPS : 1];
-    if (blockIdx.x >= *n_tiles) return;
-    const TileCtx plan = tile_ctx<T * SUB>(tiles, row_ntok, row_off, blockIdx.x);
-    if (plan.nb <= T) return;                        // finished by its tile
-    const float* tl = o.tile_lse + (size_t)row_tile0[plan.row] * SUB * g;
-    const int n_t = (plan.nb + T - 1) / T;
-    const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
-    const bool jv = j < g;
-    MZ tot{-INFINITY, 0.f};
-    if (jv)
-        for (int i = 0; i < n_t; ++i) tot = mz_combine(tot, MZ{tl[i * g + j], 1.f});
-    const float row_lse = mz_lse(tot);
-    for (int sub = 0; sub < SUB && sub * T < plan.nbt; ++sub) {
-        const int nbt = min(T, plan.nbt - sub * T);
-        const int64_t uid0 = plan.uid0 + sub * T;
+    typedef typename RowVec<V>::type vec_t;
+    __shared__ float s_row[GP];
+    const int l = threadIdx.x & (LP - 1), bsub = threadIdx.x / LP;
+    const bool folds = threadIdx.x < GP;
+    const int jf = folds && (int)threadIdx.x < g ? threadIdx.x : 0;
+    const uint32_t n_merge = counts[1];
+    for (uint32_t m = blockIdx.x; m < n_merge; m += gridDim.x) {
+        const MergeTile e = merge[m];
+        const int nbt = e.nbt;
+        const int64_t uid0 = e.uid0;
         // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
         // Entries of blocks that are not resident were never written and are masked out.
-        float v[SWEEPS];
+        const float* tl = o.tile_lse + (size_t)e.tile0 * GP;
+        TileVals head;
+        if (folds) head = load_tile_values<1>(tl, GP, jf, 0, e.n_t);
+        vec_t v[SWEEPS];
         int32_t slot[SWEEPS];
 #pragma unroll
         for (int k = 0; k < SWEEPS; ++k) {
             const int b = k * BS + bsub;
             const int bc = b < nbt ? b : 0;
             slot[k] = slot_tbl[uid0 + bc];
-            v[k] = __builtin_nontemporal_load(&o.part_lse[(uid0 + bc) * g + (jv ? j : 0)]);
+            v[k] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(o.part_lse + (uid0 + bc) * GP) + l);
         }
+        if (folds) s_row[threadIdx.x] = mz_lse(fold_tile_values<1>(head, tl, GP, jf, 0, e.n_t));
+        __syncthreads();
+        float lse[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) lse[i] = s_row[l * V + i];
 #pragma unroll
         for (int k = 0; k < SWEEPS; ++k) {
-            const bool res = k * BS + bsub < nbt && (uint32_t)slot[k] < n_slots;
-            v[k] = (res && jv) ? __expf(v[k] - row_lse) : 0.f;
-        }
-        if (GP > 64 && sub > 0) __syncthreads();     // s_v of the previous sub-tile has been read
-        group_agg<GP, SWEEPS>(v, o.agg, s_v);
+            // masses are >= 0, so 0 is neutral for the maximum as well as for the sum
+            float r = 0.f;
 #pragma unroll
-        for (int k = 0; k < SWEEPS; ++k) {
+            for (int i = 0; i < V; ++i) {
+                const float x = l * V + i < g ? __expf(vec_elem<V>(v[k], i) - lse[i]) : 0.f;
+                r = o.agg == KVM_AGG_MAX ? fmaxf(r, x) : r + x;
+            }
+            r = o.agg == KVM_AGG_MAX ? lanes_allreduce<LP, true>(r) : lanes_allreduce<LP, false>(r);
             const int b = k * BS + bsub;
-            if (j == 0 && b < nbt && (uint32_t)slot[k] < n_slots)
-                o.mass[uid0 + b] = o.agg == KVM_AGG_MAX ? v[k] : v[k] / (float)g;
+            if (l == 0 && b < nbt && (uint32_t)slot[k] < n_slots)
+                o.mass[uid0 + b] = o.agg == KVM_AGG_MAX ? r : r / (float)g;
         }
+        __syncthreads();                     // s_row is rewritten for the next tile
     }
 }
 
 // The same for groups of more than 64 queries (g <= 128).  There a block's values fill 512
-// bytes, so a wavefront takes a whole resident block (two coalesced loads, the group
-// aggregate is a plain wavefront reduction, no LDS exchange) and blocks that are not resident
-// are never read: the workgroup first compacts the resident blocks of its tile into a list.
-template <int TB /* blocks per workgroup = plan tile */, int T /* blocks per statistic tile */,
-          bool ALL /* also rows of a single tile; block values then have a row stride of 128 floats */>
+// bytes, so half a wavefront takes a whole resident block (one 16-byte load per lane, the
+// group aggregate is a reduction over 32 lanes, no LDS exchange) and blocks that are not
+// resident are never read: the workgroup first compacts the resident blocks of its tile into
+// a list.
+template <int TB /* blocks per tile of the plan */,
+          bool ALL /* every tile of the plan (wide path: tile values have a row stride of g, not 128) */>
 __global__ __launch_bounds__(kThreads) void score_rowmerge_big_kernel(
-    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int g,
-    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
-    const uint32_t* __restrict__ row_tile0, const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
-    constexpr int SUB = TB / T;
+    const uint32_t* __restrict__ counts, const MergeTile* __restrict__ merge, int g,
+    const int32_t* __restrict__ slot_tbl, uint32_t n_slots, TileOut o) {
     __shared__ int2 s_list[TB];
     __shared__ int s_cnt[((TB + kThreads - 1) / kThreads) * 4];
     __shared__ float2 s_mz[kThreads];
     __shared__ float s_rowlse[128];
-    if (blockIdx.x >= *n_tiles) return;
-    const TileCtx plan = tile_ctx<TB>(tiles, row_ntok, row_off, blockIdx.x);
-    if (!ALL && plan.nb <= T) return;                // finished by its tile
-    const int gs = ALL ? 128 : g;                    // row stride of the block values
+    constexpr int gs = 128;                          // row stride of the block values
+    const int ts = ALL ? g : 128;                    // row stride of the tile values
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n_res = build_unit_list<TB>(slot_tbl, plan.uid0, plan.nbt, n_slots, s_list, s_cnt);
-    // Row log-sum-exp per query, once per workgroup: thread (half, j) folds every second tile value
-    // of query j, the two halves meet in LDS; then every lane picks up its two queries (lane, lane + 64).
-    const float* tl = o.tile_lse + (size_t)row_tile0[plan.row] * SUB * g;
-    const int n_t = (plan.nb + T - 1) / T;
-    {
-        const int j = threadIdx.x & 127, half = threadIdx.x >> 7;
-        MZ t{-INFINITY, 0.f};
-        if (j < g)
-            for (int i = half; i < n_t; i += 2) t = mz_combine(t, MZ{tl[i * g + j], 1.f});
-        s_mz[threadIdx.x] = make_float2(t.m, t.z);
-        __syncthreads();
+    const uint32_t n_merge = counts[1];
+    for (uint32_t m = blockIdx.x; m < n_merge; m += gridDim.x) {
+        const MergeTile e = merge[m];
+        const TileSlots<TB> slots = load_tile_slots<TB>(slot_tbl, e.uid0, e.nbt);   // in flight with the tile values
+        // Row log-sum-exp per query, once per workgroup: thread (half, j) folds every second tile value
+        // of query j, the two halves meet in LDS; then every lane picks up its two queries (lane, lane + 64).
+        const float* tl = o.tile_lse + (size_t)e.tile0 * ts;
+        {
+            const int j = threadIdx.x & 127, half = threadIdx.x >> 7;
+            const int jq = j < g ? j : 0;
+            const MZ t = fold_tile_values<2>(load_tile_values<2>(tl, ts, jq, half, e.n_t), tl, ts, jq, half, e.n_t);
+            s_mz[threadIdx.x] = make_float2(t.m, t.z);
+        }
+        const int n_res = build_unit_list<TB>(slots, n_slots, s_list, s_cnt);      // two barriers: s_mz is complete
         if (threadIdx.x < 128) {
             const float2 x = s_mz[threadIdx.x], y = s_mz[threadIdx.x + 128];
             s_rowlse[threadIdx.x] = mz_lse(mz_combine(MZ{x.x, x.y}, MZ{y.x, y.y}));
         }
         __syncthreads();
-    }
-    const bool v0 = lane < g, v1 = lane + 64 < g;
-    const float lse0 = s_rowlse[lane], lse1 = s_rowlse[lane + 64];
-    constexpr int U = 8;                             // resident blocks in flight per wavefront
-    for (int idx = wave; idx < n_res; idx += 4 * U) {
-        float a[U], b[U];
-        int blk[U];
+        // Half a wavefront per resident block: a lane takes four queries (one 16-byte load).
+        const int ql = lane & 31, half = lane >> 5;
+        float lse[4];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = idx + 4 * u;
-            blk[u] = list_entry(s_list, i < n_res ? i : n_res - 1).x;
-            const float* pl = o.part_lse + (size_t)(plan.uid0 + blk[u]) * gs;
-            a[u] = __builtin_nontemporal_load(pl + (v0 ? lane : 0));
-            b[u] = __builtin_nontemporal_load(pl + (v1 ? lane + 64 : 0));
-        }
+        for (int i = 0; i < 4; ++i) lse[i] = s_rowlse[4 * ql + i];
+        constexpr int U = 8;                             // loads in flight per lane
+        for (int base = 0; base < n_res; base += 8 * U) {
+            f32x4_t a[U];
+            int blk[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float e0 = v0 ? __expf(a[u] - lse0) : 0.f, e1 = v1 ? __expf(b[u] - lse1) : 0.f;
-            float r = o.agg == KVM_AGG_MAX ? fmaxf(e0, e1) : e0 + e1;
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) {
-                const float x = __shfl_xor(r, d);
-                r = o.agg == KVM_AGG_MAX ? fmaxf(r, x) : r + x;
+            for (int u = 0; u < U; ++u) {
+                const int i = base + 8 * u + 2 * wave + half;
+                blk[u] = s_list[i < n_res ? i : n_res - 1].x;
+                a[u] = __builtin_nontemporal_load(
+                    reinterpret_cast<const f32x4_t*>(o.part_lse + (size_t)(e.uid0 + blk[u]) * gs) + ql);
             }
-            if (lane == 0 && idx + 4 * u < n_res)
-                o.mass[plan.uid0 + blk[u]] = o.agg == KVM_AGG_MAX ? r : r / (float)g;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float r = 0.f;                           // masses are >= 0: neutral for maximum and sum
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float x = 4 * ql + i < g ? __expf(a[u][i] - lse[i]) : 0.f;
+                    r = o.agg == KVM_AGG_MAX ? fmaxf(r, x) : r + x;
+                }
+                r = o.agg == KVM_AGG_MAX ? lanes_allreduce<32, true>(r) : lanes_allreduce<32, false>(r);
+                if (ql == 0 && base + 8 * u + 2 * wave + half < n_res)
+                    o.mass[e.uid0 + blk[u]] = o.agg == KVM_AGG_MAX ? r : r / (float)g;
+            }
         }
+        __syncthreads();                                 // the LDS arrays are rebuilt for the next tile
     }
 }
 
@@ -1005,7 +1166,6 @@ enum class Path { Dot2, Mfma, Wide, None };
 struct Choice {
     Path path;
     int tile_blocks;   // blocks per workgroup (what the plan cuts rows into)
-    int sub;           // statistic tiles per workgroup
     int nct;           // Mfma: 16-query column tiles (1, 2, 4 or 8)
 };
 
@@ -1017,14 +1177,14 @@ constexpr int kDot2MaxG = KVM_DOT2_MAX_G;   // larger groups of a small head go 
 // Which kernel scores (g, dim), and with what tile size.  The block-value array in LDS takes
 // tile_blocks * (padded g) * 4 bytes: at most 32 KiB.
 Choice choose(int g, int dim) {
-    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8) && g <= kDot2MaxG) return Choice{Path::Dot2, 512, 1, 0};
+    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8) && g <= kDot2MaxG) return Choice{Path::Dot2, 512, 0};
     if (dim <= 256) {
         const int nct = (g + 15) / 16;
         const int nct_p = nct <= 1 ? 1 : nct <= 2 ? 2 : nct <= 4 ? 4 : 8;
-        return Choice{Path::Mfma, 512 / nct_p, 1, nct_p};
+        return Choice{Path::Mfma, 512 / nct_p, nct_p};
     }
-    if (dim == 576) return Choice{Path::Wide, kWideTileBlocks, 1, 0};
-    return Choice{Path::None, 256, 1, 0};
+    if (dim == 576) return Choice{Path::Wide, kWideTileBlocks, 0};
+    return Choice{Path::None, 256, 0};
 }
 
 inline int64_t max_tiles(int64_t n_uids, int64_t n_rows, int tile_blocks) {
@@ -1033,35 +1193,35 @@ inline int64_t max_tiles(int64_t n_uids, int64_t n_rows, int tile_blocks) {
 }
 
 struct ScoreWs {
-    uint32_t* n_tiles;
-    uint32_t* wg_sum;
+    uint32_t* n_tiles;  // [2]: tiles of the plan, tiles of rows with more than one tile
+    uint64_t* wg_sum;
     Tile* tiles;
-    uint32_t* row_tile0;
-    float* tile_lse;    // [tiles][g]
+    MergeTile* merge;   // [tiles]: what the row merge visits
+    float* tile_lse;    // [tiles][stride]
     float* part;        // block values [n_uids][g] (row stride 128 on the wide path)
     size_t bytes;
 };
 
 ScoreWs carve(void* ws, int64_t n_uids, int32_t n_rows, int32_t g, const Choice& ch) {
-    const int tile_blocks = ch.tile_blocks, sub = ch.sub;
+    const int tile_blocks = ch.tile_blocks;
     const size_t n_wg = ((size_t)n_rows + kPlanThreads - 1) / kPlanThreads;
     const size_t tiles_max = (size_t)max_tiles(n_uids, n_rows, tile_blocks);
     const size_t off_sum = 256;
-    const size_t off_tiles = off_sum + align_up(n_wg * sizeof(uint32_t), 256);
-    const size_t off_row0 = off_tiles + align_up(tiles_max * sizeof(Tile), 256);
-    const size_t off_tmz = off_row0 + align_up((size_t)n_rows * sizeof(uint32_t), 256);
-    const size_t off_part = off_tmz + align_up(tiles_max * (size_t)sub * (size_t)g * sizeof(float), 256);
+    const size_t off_tiles = off_sum + align_up(n_wg * sizeof(uint64_t), 256);
+    const size_t off_merge = off_tiles + align_up(tiles_max * sizeof(Tile), 256);
+    const size_t off_tmz = off_merge + align_up(tiles_max * sizeof(MergeTile), 256);
+    // row stride of the block and tile values: see TileOut
+    const size_t stride = ch.path == Path::Wide ? 128 : ch.path == Path::Mfma ? (size_t)ch.nct * 16 : (size_t)g;
+    const size_t off_part = off_tmz + align_up(tiles_max * stride * sizeof(float), 256);
     const uintptr_t base = reinterpret_cast<uintptr_t>(ws);
     ScoreWs w;
     w.n_tiles = reinterpret_cast<uint32_t*>(base);
-    w.wg_sum = reinterpret_cast<uint32_t*>(base + off_sum);
+    w.wg_sum = reinterpret_cast<uint64_t*>(base + off_sum);
     w.tiles = reinterpret_cast<Tile*>(base + off_tiles);
-    w.row_tile0 = reinterpret_cast<uint32_t*>(base + off_row0);
+    w.merge = reinterpret_cast<MergeTile*>(base + off_merge);
     w.tile_lse = reinterpret_cast<float*>(base + off_tmz);
     w.part = reinterpret_cast<float*>(base + off_part);
-    // per unit: g floats (128 on the wide path, whose rows are padded)
-    const size_t per_uid = ch.path == Path::Wide ? 128 * sizeof(float) : (size_t)g * sizeof(float);
-    w.bytes = off_part + align_up((size_t)n_uids * per_uid, 256);
+    w.bytes = off_part + align_up((size_t)n_uids * stride * sizeof(float), 256);
     return w;
 }
 
@@ -1078,19 +1238,23 @@ struct ScoreArgs {
     hipStream_t st;
 };
 
-template <int GP, int T, int SUB = 1>
+// Workgroups of a row-merge launch: enough to fill every compute unit several times over; they
+// stride over the list of tiles to visit.
+constexpr unsigned kMergeGrid = 8192;
+
+template <int GP, int T>
 int launch_rowmerge(const ScoreArgs& a) {
     TimedLaunch tl("score_finalize", a.st);
+    const unsigned grid = a.grid < kMergeGrid ? a.grid : kMergeGrid;
     if constexpr (GP > 64) {
-        score_rowmerge_big_kernel<T * SUB, T, false><<<a.grid, kThreads, 0, a.st>>>(
-            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
-            (uint32_t)a.pool->n_slots, a.out);
+        score_rowmerge_big_kernel<T, false><<<grid, kThreads, 0, a.st>>>(a.w.n_tiles, a.w.merge, a.rows->g,
+                                                                        a.rows->slot_tbl, (uint32_t)a.pool->n_slots, a.out);
         return launch_status("score_rowmerge_big");
+    } else {
+        score_rowmerge_kernel<GP, T><<<grid, kThreads, 0, a.st>>>(a.w.n_tiles, a.w.merge, a.rows->g, a.rows->slot_tbl,
+                                                            (uint32_t)a.pool->n_slots, a.out);
+        return launch_status("score_rowmerge");
     }
-    score_rowmerge_kernel<GP, T, SUB><<<a.grid, kThreads, 0, a.st>>>(a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok,
-                                                               a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
-                                                               (uint32_t)a.pool->n_slots, a.out);
-    return launch_status("score_rowmerge");
 }
 
 template <int G, int DIM, int DT>
@@ -1146,9 +1310,8 @@ int launch_wide_path(const ScoreArgs& a) {
         if (int rc = launch_status("score_tile_wide")) return rc;
     }
     TimedLaunch tl("score_finalize", a.st);
-    score_rowmerge_big_kernel<TB, TB, true><<<a.grid, kThreads, 0, a.st>>>(
-        a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.w.row_tile0, a.rows->slot_tbl,
-        (uint32_t)a.pool->n_slots, a.out);
+    score_rowmerge_big_kernel<TB, true><<<a.grid < kMergeGrid ? a.grid : kMergeGrid, kThreads, 0, a.st>>>(
+        a.w.n_tiles, a.w.merge, a.rows->g, a.rows->slot_tbl, (uint32_t)a.pool->n_slots, a.out);
     return launch_status("score_rowmerge_big");
 }
 
@@ -1247,13 +1410,14 @@ int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, fl
     a.grid = (unsigned)tiles_max;
     a.st = static_cast<hipStream_t>(stream);
     a.pr = PlanRows{rows->n_rows, rows->g,        pool->dim,     ch.tile_blocks,  rows->n_uids,
-                    rows->q_elems, rows->row_ntok, rows->row_off, rows->row_q_off, rows->row_active};
+                    rows->q_elems, rows->row_ntok, rows->row_off, rows->row_q_off, rows->row_active,
+                    ch.path == Path::Wide};
     const int n_wg = (rows->n_rows + kPlanThreads - 1) / kPlanThreads;
     {
         TimedLaunch tl("score_plan", a.st);
         plan_count_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum);
         plan_scan_kernel<<<1, kPlanThreads, 0, a.st>>>(n_wg, a.w.wg_sum, a.w.n_tiles);
-        plan_emit_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum, a.w.tiles, a.w.row_tile0);
+        plan_emit_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum, a.w.tiles, a.w.merge);
         if (int rc = launch_status("score_plan")) return rc;
     }
     return pool->dtype == KVM_BF16 ? launch_dtype<KVM_BF16>(a, ch) : launch_dtype<KVM_FP16>(a, ch);
