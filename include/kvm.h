@@ -540,6 +540,10 @@ int kvm_probe_read(const void* buf /* dev, 16-byte aligned */, size_t bytes /* m
  * "beta", "select_hist", "select_emit", "pack", "unpack", "swap", "span",
  * "prefetch_keys", "hash", "dedup", "exchange_flip", "probe_read".          */
 int  kvm_timing_enable(int on);
+/* Restricts timing to the kernels called `name` (NULL: all of them again).  An event pair
+ * costs a few microseconds on the stream, which shows in a pass of twenty small launches;
+ * a caller that wants the duration of one kernel and an undisturbed total asks for that one. */
+int  kvm_timing_only(const char* name);
 void kvm_timing_reset(void);
 int  kvm_timing_read(const char* name, double* total_ms);
 

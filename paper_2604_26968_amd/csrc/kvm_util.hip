@@ -28,6 +28,7 @@ struct Span {
 };
 std::mutex g_mu;
 bool g_on = false;
+std::string g_only;                 // if not empty: the one span name that is timed
 std::vector<Span> g_spans;          // spans recorded since the last reset
 std::vector<hipEvent_t> g_free;     // events ready for reuse
 
@@ -46,6 +47,7 @@ hipEvent_t take_event() {
 TimedLaunch::TimedLaunch(const char* name, hipStream_t stream) : slot_(-1), stream_(stream) {
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_on) return;
+    if (!g_only.empty() && g_only != name) return;
     Span s{name, take_event(), take_event()};
     if (!s.start || !s.stop) return;
     if (hipEventRecord(s.start, stream) != hipSuccess) return;
@@ -121,6 +123,12 @@ int kvm_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) 
 int kvm_timing_enable(int on) {
     std::lock_guard<std::mutex> lk(kvm::g_mu);
     kvm::g_on = on != 0;
+    return KVM_OK;
+}
+
+int kvm_timing_only(const char* name) {
+    std::lock_guard<std::mutex> lk(kvm::g_mu);
+    kvm::g_only = name ? name : "";
     return KVM_OK;
 }
 

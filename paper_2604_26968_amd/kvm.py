@@ -26,7 +26,7 @@ OP_SCORE, OP_SELECT = 0, 1
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
            "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version", "kvm_probe_read",
-           "kvm_timing_enable", "kvm_timing_reset", "kvm_timing_read"]
+           "kvm_timing_enable", "kvm_timing_only", "kvm_timing_reset", "kvm_timing_read"]
 
 
 class KvmError(RuntimeError):
@@ -123,6 +123,7 @@ def _load() -> C.CDLL:
     lib.kvm_exchange_end.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.kvm_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
+    lib.kvm_timing_only.argtypes = [C.c_char_p]
     return lib
 
 
@@ -368,6 +369,10 @@ def kvm_version() -> str:
 
 def kvm_timing_enable(on: bool):
     lib.kvm_timing_enable(1 if on else 0)
+
+
+def kvm_timing_only(name):
+    lib.kvm_timing_only(name.encode() if name is not None else None)
 
 
 def kvm_timing_reset():

@@ -578,3 +578,32 @@ def test_end_to_end_eviction_dynamics(oracle):
     resident_slots = case.slot_tbl[(case.state & RES) != 0]
     np.testing.assert_array_equal(gk[resident_slots], k8[resident_slots])
     np.testing.assert_array_equal(gvv[resident_slots], v8[resident_slots])
+
+
+# ------------------------------------------------------------------- timing
+def test_kernel_timing_counts_and_filter():
+    """kvm_timing_* brackets launches with events while enabled; kvm_timing_only restricts it to one name."""
+    from paper_2604_26968_amd import kvm
+    buf = torch.zeros(1 << 22, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kvm.kvm_timing_only(None)
+    kvm.kvm_timing_reset()
+    kvm.kvm_probe_read(buf, sink)                   # not enabled: not recorded
+    kvm.kvm_timing_enable(True)
+    try:
+        kvm.kvm_probe_read(buf, sink)
+        kvm.kvm_probe_read(buf, sink)
+        kvm.kvm_timing_only("score_partial")
+        kvm.kvm_probe_read(buf, sink)               # filtered out
+        kvm.kvm_timing_only("probe_read")
+        kvm.kvm_probe_read(buf, sink)
+    finally:
+        kvm.kvm_timing_enable(False)
+        kvm.kvm_timing_only(None)
+    torch.cuda.synchronize()
+    cnt, ms = kvm.kvm_timing_read("probe_read")
+    assert cnt == 3 and 0.0 < ms < 1000.0
+    assert kvm.kvm_timing_read("score_partial")[0] == 0
+    assert kvm.kvm_timing_read("no such kernel")[0] == 0
+    kvm.kvm_timing_reset()
+    assert kvm.kvm_timing_read("probe_read")[0] == 0
