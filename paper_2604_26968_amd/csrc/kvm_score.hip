@@ -318,10 +318,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, con
 // `n` workgroups of a tile kernel's grid each swap one (frame, host tier record) pair in place
 // (what kvm_exchange_begin prepared) while the rest of the grid scores: the host link works
 // during the scoring instead of after it.  They are interleaved with the scoring workgroups at
-// the front of the grid (every stride-th one): all at the very front they would fill every
-// compute unit with waves that only wait for the link and scoring would start after them.  The frames involved belong to units the
-// scoring cannot see (kvm_exchange_begin has taken them out of the table), so the two kinds
-// of workgroup never touch the same memory.
+// the front of the grid (every stride-th one; the host picks a stride that is no multiple of
+// the number of XCDs, so that they spread over all of them): all at the very front they would
+// fill every compute unit with waves that only wait for the link and scoring would start
+// after them.  The frames involved belong to units the scoring cannot see (kvm_exchange_begin
+// has taken them out of the table), so the two kinds of workgroup never touch the same memory.
 struct Xfer {
     uint32_t n;
     uint32_t stride;        // every stride-th workgroup of the first n * stride moves pair number (index / stride)
@@ -1403,9 +1404,14 @@ int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, fl
     a.xf = xf;
     KVM_REQUIRE(tiles_max + xf.n <= 0x7fffffffll, KVM_ESHAPE, "kvm_score_step: grid too large");
     if (xf.n) {
-        // spread the transfers over the first half of the tiles, at most one workgroup in eight
+        // Spread the transfers over the first half of the tiles, at most one workgroup in seven, and with
+        // an odd stride: workgroups go to the eight XCDs in turn, so a stride of 8 puts every transfer
+        // workgroup on the same XCD, whose compute units then finish late (the wide kernel's launch was
+        // 4 % longer), and an even one on half or a quarter of them.
         int64_t stride = tiles_max / (2 * (int64_t)xf.n);
-        a.xf.stride = (uint32_t)(stride < 1 ? 1 : stride > 8 ? 8 : stride);
+        stride = stride < 1 ? 1 : stride > 7 ? 7 : stride;
+        if (stride % 2 == 0) --stride;
+        a.xf.stride = (uint32_t)stride;
     }
     a.grid = (unsigned)tiles_max;
     a.st = static_cast<hipStream_t>(stream);
