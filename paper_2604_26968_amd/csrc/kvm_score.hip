@@ -356,8 +356,27 @@ __device__ __forceinline__ void xfer_pair(const Xfer& x, uint32_t i) {
 
 __global__ __launch_bounds__(kThreads) void xfer_kernel(Xfer x) { xfer_pair(x, blockIdx.x); }
 
-// Which role workgroup `b` of a tile kernel's grid plays: returns true and the pair number for a
-// transfer workgroup, false and the tile number otherwise.
+// Position in the tile kernels' work order of workgroup `b` of a grid of `n`.  Workgroups go to the
+// eight XCDs in turn (b mod 8) and every XCD has its own L2, so eight neighbouring tiles, which
+// mostly belong to one row and read the same queries (147 KB for a row of latent frames), would
+// each fetch them into a different L2.  Inside every aligned run of 64 workgroups the order is
+// transposed: positions 8x .. 8x + 7 are the eight workgroups that run on XCD x.  A bijection
+// whatever the hardware does; the last, partial run keeps its order.
+#ifndef KVM_XCD_ORDER
+#define KVM_XCD_ORDER 1
+#endif
+#ifndef KVM_XCD_RUN
+#define KVM_XCD_RUN 8
+#endif
+__device__ __forceinline__ uint32_t xcd_order(uint32_t b, uint32_t n) {
+    constexpr uint32_t C = KVM_XCD_RUN, G = 8 * C;      // C neighbouring positions per XCD, groups of 8 C
+    if (!KVM_XCD_ORDER || b >= n / G * G) return b;
+    const uint32_t r = b % G;
+    return b - r + (r & 7u) * C + (r >> 3);
+}
+
+// Which role the workgroup at position `b` of a tile kernel's work order plays: returns true and
+// the pair number for a transfer workgroup, false and the tile number otherwise.
 __device__ __forceinline__ bool xfer_role(const Xfer& x, uint32_t b, uint32_t* index) {
     const uint32_t region = x.n * x.stride;
     if (b < region) {
@@ -659,7 +678,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
     __shared__ TileLds<T, G> lds;
 
     uint32_t tile_id;
-    if (xfer_role(xf, blockIdx.x, &tile_id)) {     // this workgroup moves bytes instead of scoring
+    if (xfer_role(xf, xcd_order(blockIdx.x, gridDim.x), &tile_id)) {     // this workgroup moves bytes instead of scoring
         xfer_pair(xf, tile_id);
         return;
     }
@@ -725,7 +744,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     __shared__ TileLds<T, GP> lds;
 
     uint32_t tile_id;
-    if (xfer_role(xf, blockIdx.x, &tile_id)) {     // this workgroup moves bytes instead of scoring
+    if (xfer_role(xf, xcd_order(blockIdx.x, gridDim.x), &tile_id)) {     // this workgroup moves bytes instead of scoring
         xfer_pair(xf, tile_id);
         return;
     }
@@ -815,7 +834,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     __shared__ int s_cnt[((TB + kThreads - 1) / kThreads) * 4];
 
     uint32_t tile_id;
-    if (xfer_role(xf, blockIdx.x, &tile_id)) {     // this workgroup moves bytes instead of scoring
+    if (xfer_role(xf, xcd_order(blockIdx.x, gridDim.x), &tile_id)) {     // this workgroup moves bytes instead of scoring
         xfer_pair(xf, tile_id);
         return;
     }
