@@ -555,7 +555,9 @@ struct TileOut {
     float* mass;        // [n_uids]
     // Rows of more than one tile only.  Row stride of both: g rounded up to a power of two on the dot2 and
     // mfma paths (vector loads in the row merge stay aligned); on the wide path 128 and g.
-    float* part_lse;    // [n_uids][stride]: log sum exp of the block's logits
+    // part_lse: log sum exp of a block's logits per query.  Dot2 and mfma paths: the i-th resident block of
+    // a tile at entry (tile's first uid + i); wide path: block of uid u at entry u.
+    float* part_lse;    // [n_uids][stride]
     float* tile_lse;    // [n_tiles][stride]: log sum exp over the tile
 };
 
@@ -614,7 +616,8 @@ __device__ __forceinline__ float mz_lse(MZ a) { return a.z > 0.f ? a.m + __logf(
 // bsub + 256/GP, ...
 template <int GP, int T>
 __device__ __forceinline__ void tile_epilogue(const float* s_lse, float2* s_red /* [256] */, float* s_v, int g,
-                                              const TileCtx& c, size_t tile_index, const TileOut& o) {
+                                              const TileCtx& c, size_t tile_index, const TileOut& o,
+                                              const int2* s_list, int n_res) {
     constexpr int BS = kThreads / GP;
     constexpr int SWEEPS = (T + BS - 1) / BS;
     const int j = threadIdx.x & (GP - 1), bsub = threadIdx.x / GP;
@@ -647,11 +650,14 @@ __device__ __forceinline__ void tile_epilogue(const float* s_lse, float2* s_red 
         }
     } else {
         if (bsub == 0 && jv) o.tile_lse[tile_index * GP + j] = tile_lse;
-        // the block values of the resident blocks (query 0 tells), g contiguous floats per block
+        // The block values of the resident blocks, packed: the i-th resident block of the tile goes to
+        // entry uid0 + i, GP floats per entry (the row merge rebuilds the same list from the table).
+        // What these stores cost is the number of 128-byte lines they touch, not their bytes (measured:
+        // 0.2 ns per line on the 70B-shaped launch, 13 % of it with one entry per block and half the
+        // blocks resident), so they are written without holes.  Non-temporal: read back once.
         if (jv)
-            for (int b = bsub; b < c.nbt; b += BS)
-                if (s_lse[b * g] > -INFINITY)   // read back once by the row merge: keep it out of the L2
-                    __builtin_nontemporal_store(s_lse[b * g + j], &o.part_lse[(c.uid0 + b) * GP + j]);
+            for (int i = bsub; i < n_res; i += BS)
+                __builtin_nontemporal_store(s_lse[s_list[i].x * g + j], &o.part_lse[(c.uid0 + i) * GP + j]);
     }
 }
 
@@ -724,7 +730,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
         }
     });
     __syncthreads();
-    tile_epilogue<G, T>(s_lse, lds.red, lds.v, G, c, tile_id, out);
+    tile_epilogue<G, T>(s_lse, lds.red, lds.v, G, c, tile_id, out, lds.list, n_res);
 }
 
 // ---- score_tile_mfma: any g <= 16 * NCT, queries as matrix-core operands -----------
@@ -794,7 +800,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
         }
     });
     __syncthreads();
-    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, tile_id, out);
+    tile_epilogue<GP, T>(s_lse, lds.red, lds.v, G, c, tile_id, out, lds.list, n_res);
 }
 
 // ---- score_tile_wide: wide frames (MLA latent, dim 576) scored by up to 128 queries ---
@@ -1066,27 +1072,27 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
     constexpr int SWEEPS = (T + BS - 1) / BS;
     typedef typename RowVec<V>::type vec_t;
     __shared__ float s_row[GP];
+    __shared__ int2 s_list[T];
+    __shared__ int s_cnt[((T + kThreads - 1) / kThreads) * 4];
     const int l = threadIdx.x & (LP - 1), bsub = threadIdx.x / LP;
     const bool folds = threadIdx.x < GP;
     const int jf = folds && (int)threadIdx.x < g ? threadIdx.x : 0;
     const uint32_t n_merge = counts[1];
     for (uint32_t m = blockIdx.x; m < n_merge; m += gridDim.x) {
         const MergeTile e = merge[m];
-        const int nbt = e.nbt;
         const int64_t uid0 = e.uid0;
-        // All loads first (unconditional, clamped), then the arithmetic: one round trip per tile.
-        // Entries of blocks that are not resident were never written and are masked out.
         const float* tl = o.tile_lse + (size_t)e.tile0 * GP;
+        // table entries and tile values first, in flight together; then the list of resident blocks
+        // (the tile kernel packed its block values in the same order), then all the block values at once
+        const TileSlots<T> slots = load_tile_slots<T>(slot_tbl, uid0, e.nbt);
         TileVals head;
         if (folds) head = load_tile_values<1>(tl, GP, jf, 0, e.n_t);
+        const int n_res = build_unit_list<T>(slots, n_slots, s_list, s_cnt);
         vec_t v[SWEEPS];
-        int32_t slot[SWEEPS];
 #pragma unroll
         for (int k = 0; k < SWEEPS; ++k) {
-            const int b = k * BS + bsub;
-            const int bc = b < nbt ? b : 0;
-            slot[k] = slot_tbl[uid0 + bc];
-            v[k] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(o.part_lse + (uid0 + bc) * GP) + l);
+            const int i = k * BS + bsub;
+            v[k] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(o.part_lse + (uid0 + (i < n_res ? i : 0)) * GP) + l);
         }
         if (folds) s_row[threadIdx.x] = mz_lse(fold_tile_values<1>(head, tl, GP, jf, 0, e.n_t));
         __syncthreads();
@@ -1103,11 +1109,10 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_kernel(
                 r = o.agg == KVM_AGG_MAX ? fmaxf(r, x) : r + x;
             }
             r = o.agg == KVM_AGG_MAX ? lanes_allreduce<LP, true>(r) : lanes_allreduce<LP, false>(r);
-            const int b = k * BS + bsub;
-            if (l == 0 && b < nbt && (uint32_t)slot[k] < n_slots)
-                o.mass[uid0 + b] = o.agg == KVM_AGG_MAX ? r : r / (float)g;
+            const int i = k * BS + bsub;
+            if (l == 0 && i < n_res) o.mass[uid0 + s_list[i].x] = o.agg == KVM_AGG_MAX ? r : r / (float)g;
         }
-        __syncthreads();                     // s_row is rewritten for the next tile
+        __syncthreads();                     // s_row and the list are rebuilt for the next tile
     }
 }
 
@@ -1161,7 +1166,7 @@ __global__ __launch_bounds__(kThreads) void score_rowmerge_big_kernel(
                 const int i = base + 8 * u + 2 * wave + half;
                 blk[u] = s_list[i < n_res ? i : n_res - 1].x;
                 a[u] = __builtin_nontemporal_load(
-                    reinterpret_cast<const f32x4_t*>(o.part_lse + (size_t)(e.uid0 + blk[u]) * gs) + ql);
+                    reinterpret_cast<const f32x4_t*>(o.part_lse + (size_t)(e.uid0 + (ALL ? blk[u] : (i < n_res ? i : n_res - 1))) * gs) + ql);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
