@@ -63,18 +63,32 @@ __global__ __launch_bounds__(kThreads) void select_hist_kernel(const float* __re
     const uint32_t prefix = PASS == 0 ? 0u : ctrl->prefix;
     uint32_t n_res = 0, n_el = 0;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t u = (int64_t)blockIdx.x * kThreads + threadIdx.x; u < n; u += stride) {
-        const uint8_t st = state[u];
-        if (PASS == 0 && (st & KVM_ST_RESIDENT)) ++n_res;
-        if (!eligible(st)) continue;
-        const uint32_t key = order_key(prio[u]);
-        if (PASS == 0) {
-            ++n_el;
-            atomicAdd(&h[key >> 21], 1u);
-        } else if (PASS == 1) {
-            if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
-        } else {
-            if ((key >> 10) == prefix) atomicAdd(&h[key & 1023u], 1u);
+    // Four elements per thread and trip: all eight loads first, unconditionally (a priority loaded only
+    // once its state byte says "eligible" makes every element two dependent round trips, and the
+    // pass is bound by that latency, not by its bytes or its LDS atomics).
+    constexpr int B = 4;
+    for (int64_t u0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; u0 < n; u0 += stride * B) {
+        uint8_t st[B];
+        float pr[B];
+#pragma unroll
+        for (int i = 0; i < B; ++i) {
+            const int64_t u = u0 + i * stride;
+            st[i] = u < n ? state[u] : 0;
+            pr[i] = prio[u < n ? u : 0];
+        }
+#pragma unroll
+        for (int i = 0; i < B; ++i) {
+            if (PASS == 0 && (st[i] & KVM_ST_RESIDENT)) ++n_res;
+            if (!eligible(st[i])) continue;
+            const uint32_t key = order_key(pr[i]);
+            if (PASS == 0) {
+                ++n_el;
+                atomicAdd(&h[key >> 21], 1u);
+            } else if (PASS == 1) {
+                if ((key >> 21) == prefix) atomicAdd(&h[(key >> 10) & 2047u], 1u);
+            } else {
+                if ((key >> 10) == prefix) atomicAdd(&h[key & 1023u], 1u);
+            }
         }
     }
     if (PASS == 0) {

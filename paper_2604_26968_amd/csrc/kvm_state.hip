@@ -199,10 +199,13 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
     const float keep = decay, take = 1.0f - decay;
     for (int64_t b = threadIdx.x % LANES; b < nb; b += LANES) {
         const int64_t uid = off + b;
+        // the four loads of a unit at once: a mass loaded only after the state byte has arrived
+        // would put two round trips in a row, and the kernel is bound by that latency
         uint8_t st = state[uid];
         float s = S[uid];
+        float x = mass[uid];
+        const uint8_t pr = pair[uid];
         if (active && (st & KVM_ST_RESIDENT)) {
-            float x = mass[uid];
             if (EX) x *= pow_by_distance(ex.lg_pos_decay, nb - 1 - b);
             if (!(st & KVM_ST_SCORED)) {
                 s = x;
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
             }
             S[uid] = s;
         }
-        prio[uid] = (st & KVM_ST_SCORED) ? w * s * ph[pair[uid] & 15] : INFINITY;
+        prio[uid] = (st & KVM_ST_SCORED) ? w * s * ph[pr & 15] : INFINITY;
     }
 }
 
