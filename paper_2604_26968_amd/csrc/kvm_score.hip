@@ -41,9 +41,16 @@
 namespace kvm {
 namespace {
 
-struct Tile {
-    int32_t row;
-    int32_t b0;
+// What a tile kernel needs to know of its tile, in one 32-byte record written by the plan, so that
+// a workgroup reaches its table entries and queries after a single dependent load (tile -> row
+// -> row arrays was two, and on workloads of short rows the set-up chain is a good part of a
+// workgroup's lifetime).
+struct alignas(16) Tile {
+    int64_t uid0;       // uid of the tile's first block
+    int64_t q_off;      // element offset of the row's queries
+    int32_t b0;         // the tile's first block in its row
+    int32_t ntok;       // tokens of the row
+    int32_t pad[2];
 };
 
 constexpr int kThreads = 256;   // workgroup size of every scorer kernel (4 wavefronts)
@@ -303,10 +310,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, con
     uint64_t total;
     const uint64_t at = wg_base[blockIdx.x] + wg_exclusive_scan(plan_counts(p, nt), &total);
     const uint32_t first = (uint32_t)at, mfirst = (uint32_t)(at >> 32);
-    for (uint32_t i = 0; i < nt; ++i) tiles[first + i] = Tile{r, (int32_t)(i * p.tile_blocks)};
-    if (nt > 1 || (nt && p.merge_all)) {
-        const int32_t nb = (p.row_ntok[r] + 15) >> 4;
-        const int64_t off = p.row_off[r];
+    if (nt == 0) return;
+    const int32_t ntok = p.row_ntok[r];
+    const int32_t nb = (ntok + 15) >> 4;
+    const int64_t off = p.row_off[r], q_off = p.row_q_off[r];
+    for (uint32_t i = 0; i < nt; ++i) {
+        const int32_t b0 = (int32_t)(i * p.tile_blocks);
+        tiles[first + i] = Tile{off + b0, q_off, b0, ntok, {0, 0}};
+    }
+    if (nt > 1 || p.merge_all) {
         for (uint32_t i = 0; i < nt; ++i) {
             const int32_t b0 = (int32_t)(i * p.tile_blocks);
             merge[mfirst + i] = MergeTile{off + b0, first, min(p.tile_blocks, nb - b0), (int32_t)nt, {0, 0, 0}};
@@ -396,21 +408,21 @@ __device__ __forceinline__ bool xfer_role(const Xfer& x, uint32_t b, uint32_t* i
 
 // What every tile kernel derives from its tile.
 struct TileCtx {
-    int row, b0;
+    int b0;
     int ntok, nb, nbt;       // tokens and blocks of the row, blocks of this tile
     int64_t uid0;            // uid of the tile's block 0
+    int64_t q_off;           // element offset of the row's queries
 };
 template <int T>
-__device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, const int32_t* row_ntok, const int64_t* row_off,
-                                            uint32_t tile_id) {
+__device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, uint32_t tile_id) {
     const Tile tile = tiles[tile_id];
     TileCtx c;
-    c.row = tile.row;
     c.b0 = tile.b0;
-    c.ntok = row_ntok[tile.row];
+    c.ntok = tile.ntok;
     c.nb = (c.ntok + 15) >> 4;
     c.nbt = min(T, c.nb - tile.b0);
-    c.uid0 = row_off[tile.row] + tile.b0;
+    c.uid0 = tile.uid0;
+    c.q_off = tile.q_off;
     return c;
 }
 
@@ -673,8 +685,7 @@ struct TileLds {
 // ---- score_tile_dot2: g in {1, 2, 4, 8}, queries in registers ----------------------
 template <int G, int DIM, int DT, int T>
 __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
-    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, const int32_t* __restrict__ row_ntok,
-    const int64_t* __restrict__ row_off, const int64_t* __restrict__ row_q_off,
+    const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles,
     const int32_t* __restrict__ slot_tbl, const uint4* __restrict__ k_pool, uint32_t n_slots,
     const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
     static_assert(G == 1 || G == 2 || G == 4 || G == 8, "power-of-two group sizes only");
@@ -688,11 +699,12 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
         xfer_pair(xf, tile_id);
         return;
     }
+    // record and tile count are loaded together; the record of a position past the count is never used
+    const TileCtx c = tile_ctx<T>(tiles, tile_id);
     if (tile_id >= *n_tiles) return;
-    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off, tile_id);
     const int lane = threadIdx.x & 63;
     const int t = lane & 15, cg = lane >> 4;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + c.q_off);
 
     uint4 qv[G][NK];
 #pragma unroll
@@ -740,9 +752,8 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
 template <int NCT, int DIM, int DT, int T>
 __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
-    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
-    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
-    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
+    const int32_t* __restrict__ slot_tbl, const uint4* __restrict__ k_pool, uint32_t n_slots,
+    const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
     constexpr int NK = DIM / 32;
     constexpr int QROW_V4 = DIM / 8;
     constexpr int GP = NCT * 16;          // 16, 32, 64 or 128
@@ -754,11 +765,12 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
         xfer_pair(xf, tile_id);
         return;
     }
+    // record and tile count are loaded together; the record of a position past the count is never used
+    const TileCtx c = tile_ctx<T>(tiles, tile_id);
     if (tile_id >= *n_tiles) return;
-    const TileCtx c = tile_ctx<T>(tiles, row_ntok, row_off, tile_id);
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, cg = lane >> 4;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + c.q_off);
 
     uint4 qb[NCT][NK];
 #pragma unroll
@@ -821,9 +833,8 @@ constexpr int kWideTileBlocks = 256;
 template <int DIM, int DT, int TB>
 __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     const Tile* __restrict__ tiles, const uint32_t* __restrict__ n_tiles, int G,
-    const int32_t* __restrict__ row_ntok, const int64_t* __restrict__ row_off,
-    const int64_t* __restrict__ row_q_off, const int32_t* __restrict__ slot_tbl,
-    const uint4* __restrict__ k_pool, uint32_t n_slots, const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
+    const int32_t* __restrict__ slot_tbl, const uint4* __restrict__ k_pool, uint32_t n_slots,
+    const uint16_t* __restrict__ q, float scale, TileOut out, Xfer xf) {
     constexpr int NK = DIM / 32;
     constexpr int UNIT_V4 = DIM * 2;
     constexpr int QROW_V4 = DIM / 8;
@@ -844,11 +855,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
         xfer_pair(xf, tile_id);
         return;
     }
+    // record and tile count are loaded together; the record of a position past the count is never used
+    const TileCtx c = tile_ctx<TB>(tiles, tile_id);
     if (tile_id >= *n_tiles) return;
-    const TileCtx c = tile_ctx<TB>(tiles, row_ntok, row_off, tile_id);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, cg = lane >> 4;
-    const uint4* qrow = reinterpret_cast<const uint4*>(q + row_q_off[c.row]);
+    const uint4* qrow = reinterpret_cast<const uint4*>(q + c.q_off);
 
     uint4 qb[2][NK];
 #pragma unroll
@@ -1287,7 +1299,7 @@ int launch_dot2_path(const ScoreArgs& a) {
     {
         TimedLaunch tl("score_partial", a.st);
         score_tile_dot2_kernel<G, DIM, DT, 512><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
-            a.w.tiles, a.w.n_tiles, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off, a.rows->slot_tbl,
+            a.w.tiles, a.w.n_tiles, a.rows->slot_tbl,
             static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots, static_cast<const uint16_t*>(a.q),
             a.scale, a.out, a.xf);
         if (int rc = launch_status("score_tile_dot2")) return rc;
@@ -1301,8 +1313,7 @@ int launch_mfma_path(const ScoreArgs& a) {
     {
         TimedLaunch tl("score_partial", a.st);
         score_tile_mfma_kernel<NCT, DIM, DT, T><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
-            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off,
-            a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
+            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
             static_cast<const uint16_t*>(a.q), a.scale, a.out, a.xf);
         if (int rc = launch_status("score_tile_mfma")) return rc;
     }
@@ -1329,8 +1340,7 @@ int launch_wide_path(const ScoreArgs& a) {
     {
         TimedLaunch tl("score_partial", a.st);
         score_tile_wide_kernel<DIM, DT, TB><<<a.grid + a.xf.n, kThreads, 0, a.st>>>(
-            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->row_ntok, a.rows->row_off, a.rows->row_q_off,
-            a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
+            a.w.tiles, a.w.n_tiles, a.rows->g, a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
             static_cast<const uint16_t*>(a.q), a.scale, a.out, a.xf);
         if (int rc = launch_status("score_tile_wide")) return rc;
     }
