@@ -5,17 +5,18 @@
 // query heads that share the KV head (GQA grouping rule, section 3.4).
 //
 // Structure (all kernels in this file):
-//   plan_*          build the list of tiles = (row, first block) of at most T blocks for the
-//                   active rows, on the device, so the scorer's grid has no idle workgroups
-//                   whatever the spread of row lengths.  T depends on the kernel (64 .. 512).
-//   score_tile_*    one workgroup per tile.  Per (unit, query) the kernel forms
-//                   lse = log sum_t exp(z_t) over the block's tokens (the block's softmax
-//                   mass is exp(lse - row lse)) and the tile's lse per query.  The dot2 and
-//                   mfma kernels keep the block values in LDS: a row that fits one tile is
-//                   finished on the spot (only its masses are written); otherwise the tile
-//                   writes its block values, coalesced, plus the tile value, and
-//                   score_rowmerge combines the tiles of the row.  The wide kernel always
-//                   writes block values and leaves every row to the merge.
+//   plan_*          build the list of tiles (a record per run of at most T blocks of an active
+//                   row), on the device, so the scorer's grid has no idle workgroups whatever
+//                   the spread of row lengths, and the list of the tiles the row merge has
+//                   to visit.  T depends on the kernel (64 .. 512).
+//   score_tile_*    one workgroup per tile, taken in an XCD-aware order.  Per (unit, query)
+//                   the kernel forms lse = log sum_t exp(z_t) over the block's tokens (the
+//                   block's softmax mass is exp(lse - row lse)) and the tile's lse per query.
+//                   The dot2 and mfma kernels keep the block values in LDS: a row that fits
+//                   one tile is finished on the spot (only its masses are written); otherwise
+//                   the tile writes the block values of its resident blocks, packed, plus the
+//                   tile value, and score_rowmerge combines the tiles of the row.  The wide
+//                   kernel always writes block values and leaves every row to the merge.
 //   score_rowmerge* a fixed grid strides over the tiles of the rows that are not finished yet
 //                   (a list the plan also makes): row lse from the tile values, masses from
 //                   the block values.
