@@ -823,7 +823,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
 // lane, no staging registers) into a ring of kWideBufs buffers: while one unit is being
 // multiplied the next kWideBufs - 1 are in flight, which is what the memory latency asks for
 // at 18 KiB per unit and two workgroups per compute unit.  One barrier per unit.
-// Every wavefront issues exactly kWideDma loads and 2 stores per unit, all unconditional, so
+// Every wavefront issues exactly kWideDma loads and one store per unit, all unconditional, so
 // that "at most N vector memory operations outstanding" identifies which frames have landed.
 // Block values go straight to part_lse (row stride 128 floats, padded queries land in the
 // padding), the tile's own log-sum-exp per query is carried in registers; score_rowmerge_big
@@ -842,7 +842,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
     constexpr int PER_WAVE = UNIT_V4 / 4;          // 16-byte vectors each wavefront moves per unit
     constexpr int FULL = PER_WAVE / 64, REM = PER_WAVE % 64;
     constexpr int DMA = FULL + (REM ? 1 : 0);      // loads per wavefront per unit
-    constexpr int OPS = DMA + 2;                   // vector memory operations per wavefront per unit
+    constexpr int OPS = DMA + 1;                   // vector memory operations per wavefront per unit
     static_assert(UNIT_V4 % 4 == 0, "unit must split over four wavefronts");
     __shared__ uint4 kb0[UNIT_V4];
     __shared__ uint4 kb1[UNIT_V4];
@@ -938,32 +938,35 @@ __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
                     run[ct].m = ref;
                 }
             }
+            float lse[2];
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
                 float sm = 0.f;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) sm += __builtin_amdgcn_exp2f(z[ct][r] - run[ct].m);
-                sm = rows4_sum(sm);
-                // Stored from asm for the same reason the loads are: the number of vector memory
-                // operations per step must be exactly what the wait counts assume, whatever the
-                // optimiser would like to do with two plain stores.
-                if (cg == 0) {
-                    const float lse = (run[ct].m + __builtin_amdgcn_logf(sm)) * kLn2;
-                    asm volatile("global_store_dword %0, %1, off nt" : : "v"(pl + ct * 16), "v"(lse) : "memory");
-                }
+                sm = rows4_sum(sm);                   // every row of lanes now holds the block's sum
+                lse[ct] = (run[ct].m + __builtin_amdgcn_logf(sm)) * kLn2;
                 run[ct].z += sm;
+            }
+            // One store per wavefront and unit: lane rows 0 and 1 write the wavefront's 32 queries
+            // (column tile 0 and 1), a whole 128-byte line; what block-value stores cost is the
+            // number of line writes.  From asm for the same reason the loads are: the number of
+            // vector memory operations per step must be exactly what the wait counts assume.
+            if (cg < 2) {
+                const float v = cg == 0 ? lse[0] : lse[1];
+                asm volatile("global_store_dword %0, %1, off nt" : : "v"(pl + cg * 16), "v"(v) : "memory");
             }
         };
         // vmcnt(N): at most N vector memory operations of this wavefront still outstanding.  Behind
-        // the loads of unit idx sit, in issue order, the rest of iteration idx - 3 (2 stores) and the
-        // whole of iterations idx - 2 and idx - 1: 2 + 2 * OPS operations.
-        constexpr int LAG = 2 + 2 * OPS;
+        // the loads of unit idx sit, in issue order, the rest of iteration idx - 3 (its store) and the
+        // whole of iterations idx - 2 and idx - 1: 1 + 2 * OPS operations.
+        constexpr int LAG = 1 + 2 * OPS;
         static_assert(kWideBufs == 4 && LAG < 64, "wait count assumes three units in flight");
         dma(kb0, 0);
         dma(kb1, 1);
         dma(kb2, 2);
         // the first three iterations have fewer operations behind the loads they wait for
-        constexpr int W0 = 2 * DMA, W1 = 2 * DMA + 2, W2 = 2 * DMA + 4;
+        constexpr int W0 = 2 * DMA, W1 = 2 * DMA + 1, W2 = 2 * DMA + 2;
         int idx = 0;
 #define KVM_VMCNT(N) (((N) & 15) | (7 << 4) | (15 << 8) | (((N) >> 4) << 14))
 #define KVM_WIDE_STEP(CUR, TGT, N)                       \
