@@ -37,9 +37,9 @@ WORKLOADS = {
     "mqa": ("fleet, MQA half: 32 layers, 32q/1kv head (g 32), d128, bf16, %d seqs lognormal(7,1) tok",
             lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 8192, 0),
 }
-# FETCH_SIZE 6,625,601.1 x 2 KiB + WRITE_SIZE 37,635.7 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
+# FETCH_SIZE 6,623,602.1 x 2 KiB + WRITE_SIZE 37,636.6 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
 # with the 1,024 transfer workgroups of --swap-mode overlap riding along
-SCORE_TILE_TRAFFIC_BYTES = int(6625601.1 * 2048 + 37635.7 * 1024)
+SCORE_TILE_TRAFFIC_BYTES = int(6623602.1 * 2048 + 37636.6 * 1024)
 
 
 def main():
