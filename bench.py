@@ -400,7 +400,9 @@ def main():
                 "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}
 
     out = {
-        "metric": "KV scored GB/s (whole management pass, 1 MI355X)",
+        "metric": "KV scored GB/s (frac of HBM peak) + evicted/prefetched blocks/s, 1 MI355X",
+        "metric_parts": "value = K bytes scored per second over the whole management pass; frac_of_hbm_peak = "
+                        "value / 8000; evicted_units_per_s, prefetched_units_per_s = the per-step exchange",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
