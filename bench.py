@@ -37,9 +37,9 @@ WORKLOADS = {
     "mqa": ("fleet, MQA half: 32 layers, 32q/1kv head (g 32), d128, bf16, %d seqs lognormal(7,1) tok",
             lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 8192, 0),
 }
-# FETCH_SIZE 6,623,602.1 x 2 KiB + WRITE_SIZE 37,636.6 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
-# with the 1,024 transfer workgroups of --swap-mode overlap riding along
-SCORE_TILE_TRAFFIC_BYTES = int(6623602.1 * 2048 + 37636.6 * 1024)
+# FETCH_SIZE 6,622,957.5 x 2 KiB + WRITE_SIZE 37,636.3 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
+# with the 1,024 transfer workgroups of --swap-mode pipelined / overlap riding along
+SCORE_TILE_TRAFFIC_BYTES = int(6622957.5 * 2048 + 37636.3 * 1024)
 
 
 def main():
@@ -51,10 +51,12 @@ def main():
                     help="llama8b is the named benchmark workload; the others are the larger configurations")
     ap.add_argument("--n-seq", type=int, default=0, help="sequences in the batch (0 = the workload's own number)")
     ap.add_argument("--swap-units", type=int, default=0, help="units evicted and prefetched per step (0 = workload default)")
-    ap.add_argument("--swap-mode", choices=["overlap", "fused", "staged", "direct", "side-stream"], default="overlap",
+    ap.add_argument("--swap-mode", choices=["pipelined", "overlap", "fused", "staged", "direct", "side-stream"], default="pipelined",
                     help="how the per-step victims / prefetch records cross the host link: in-place exchange whose "
                          "bytes move inside the next step's scoring launch (kvm_exchange_begin / "
-                         "kvm_score_step_xfer / kvm_exchange_end); one fused two-way zero-copy kernel after the "
+                         "kvm_score_step_xfer / kvm_exchange_end), with the selection on a second stream beside "
+                         "the scoring launch; the same with the selection in line after the EMA; "
+                         "one fused two-way zero-copy kernel after the "
                          "selection (kvm_swap); kvm_pack then kvm_unpack through device staging and hipMemcpyAsync; "
                          "the same with zero-copy kernels; or gather / scatter in line with the copies on a side "
                          "stream")
@@ -104,6 +106,8 @@ def main():
     ws_bytes = max(kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, n_rows, g, dim),
                    kvm.kvm_workspace_bytes(kvm.OP_SELECT, n))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    # a selection that runs beside a scoring launch needs a workspace of its own
+    ws_select = torch.empty(max(kvm.kvm_workspace_bytes(kvm.OP_SELECT, n), 256), dtype=torch.uint8, device=dev)
 
     n_q_sets = 4
     qs = [wl.queries(100 + i) for i in range(n_q_sets)]
@@ -234,6 +238,27 @@ def main():
         kvm.kvm_exchange_begin(pool, wl.slot_tbl, wl.state, step_victims, xf_in[0], swap, tier_slots, xf_frame,
                                xf_host, n_out_dev=n_victims, n_bad=n_bad)
 
+    def step_pipelined(i):
+        """step_overlap with the selection moved off the critical path: the victims are chosen, from the
+        priorities the previous step left, on a second stream beside this step's scoring launch (a small
+        kernel there costs the scorer next to nothing; the posterior update goes with it).  They leave HBM
+        inside the next step's scoring launch, one step later than in step_overlap.  While the selection
+        runs the units of the last exchange are still on their way, so the budget it is given is the
+        budget minus what is in flight."""
+        ev = evs[i % n_q_sets]
+        side.wait_stream(main)
+        kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad, stream=side)
+        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws_select, k=-1, budget_units=budget - swap,
+                               stream=side)
+        kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
+        main.wait_stream(side)
+        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_exchange_end(wl.slot_tbl, wl.state, xf_in[0], xf_frame, swap)
+        nxt = (i + 1) * swap
+        xf_in[0] = host_uids[nxt:nxt + swap]
+        kvm.kvm_exchange_begin(pool, wl.slot_tbl, wl.state, step_victims, xf_in[0], swap, tier_slots, xf_frame,
+                               xf_host, n_out_dev=n_victims, n_bad=n_bad)
+
     def finish_overlap():
         """Lets the last transfer land (untimed) so that the final state can be checked like the other modes'."""
         kvm.kvm_score_step_xfer(pool, rows, qs[0], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
@@ -322,6 +347,7 @@ def main():
         ev_scattered[b].record(main)
 
     step = step_overlapped if args.swap_mode == "side-stream" else step_overlap if args.swap_mode == "overlap" \
+        else step_pipelined if args.swap_mode == "pipelined" \
         else step_serial
     if args.refined:
         assert keep == k0, "the refined pass addresses the whole host tier by slot"
@@ -349,7 +375,7 @@ def main():
     for name in KERNEL_NAMES:
         cnt, ms = kvm.kvm_timing_read(name)
         warm_kernels[name] = {"launches": cnt, "avg_ms": (ms / cnt) if cnt else None}
-    overlap = step is step_overlap or step is step_refined
+    overlap = step is step_overlap or step is step_refined or step is step_pipelined
     resident = int((wl.state & 1).sum().item())
     # with the transfer overlapped the victims have left the table and their replacements are still on their way
     assert resident == (budget if overlap else budget + swap), (resident, budget, swap)
@@ -394,7 +420,7 @@ def main():
     # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload
     # (profiles/score_tile_dot2_llama8b_pmc.md); valid for the default workload only.
     traffic = SCORE_TILE_TRAFFIC_BYTES if (args.workload == "llama8b" and n_seq == 64 and swap == 1024
-                                           and args.swap_mode == "overlap" and not args.refined) else None
+                                           and args.swap_mode in ("overlap", "pipelined") and not args.refined) else None
     roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}

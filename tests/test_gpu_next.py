@@ -711,3 +711,113 @@ def test_end_to_end_overlapped_exchange_dynamics(oracle):
         np.testing.assert_array_equal(dev.state.cpu().numpy(), case.state)
         pending = (ins, frames, hosts, want)
     assert int(dev.n_bad.item()) == 0
+
+
+def test_end_to_end_pipelined_selection_dynamics(oracle):
+    """The pass as the bench runs it by default: the victims are chosen from the priorities the previous
+    step left, on a second stream, while the scoring launch (with the previous exchange's bytes riding
+    along) runs on the first; then ema -> exchange_end -> exchange_begin with those victims.  Nothing is
+    synchronised inside a step on the GPU side; at the end of every step masses, EMA state, victims,
+    tables, pools and the host tier are compared with the oracle, which takes the same stages in order."""
+    from paper_2604_26968_amd import kvm
+    from tests.harness import oracle_score
+    from tests.test_gpu_parity import victims_agree, MASS_RTOL, MASS_ATOL
+    shape = synth.Shape(2, 8, 2, 128, synth.BF16, True, [700, 2100, 333])
+    case = synth.make_case(shape, seed=62, pair_weights=synth.categorical_weights(3))
+    sh = case.shape
+    uk, uv = sh.unit_k_bytes, sh.unit_v_bytes
+    rec = uk + uv
+    rng = np.random.default_rng(3)
+    k8, v8 = host_pools(case)
+    res = np.flatnonzero((case.state & RES) != 0)
+    res = res[(case.state[res] & PROT) == 0]
+    first_out = np.sort(rng.choice(res, size=int(0.4 * len(res)), replace=False)).astype(np.int64)
+    n_tier = len(first_out)
+    hs = rng.permutation(n_tier).astype(np.int32)
+    staging, _ = oracle.pack(k8, v8, uk, uv, case.slot_tbl, case.state, first_out, hs)
+    tier = np.zeros((n_tier, rec), np.uint8)
+    tier[hs] = staging
+    dev = DeviceCase(case)
+    d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
+    n = 24
+    S, prio = np.zeros(case.n_uids, np.float32), np.zeros(case.n_uids, np.float32)
+    hits, misses = np.zeros(16, np.uint32), np.zeros(16, np.uint32)
+    frame = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    host = torch.full((n,), -1, dtype=torch.int64, device="cuda")
+    d_ins = torch.full((n,), -1, dtype=torch.int64, device="cuda")
+    d_outs = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ws_select = torch.full((max(kvm.kvm_workspace_bytes(kvm.OP_SELECT, case.n_uids), 256),), 0x7F, dtype=torch.uint8,
+                           device="cuda")
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    pending = None
+    w = synth.categorical_weights(8)
+    scale = 1 / np.sqrt(128)
+    # one plain step first, so that there are scored units to choose from
+    q = synth.make_queries(case, 70)
+    omass = oracle_score(oracle, case, q, scale, fill=-1.0)
+    dev.score(q, scale, fill=-1.0)
+    p_hat = oracle.beta_update(np.zeros(0, np.uint8), np.zeros(0, np.uint8), hits, misses)
+    dev.beta(np.zeros(0, np.uint8), np.zeros(0, np.uint8))
+    oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, case.row_weight, case.pair, p_hat, case.state, S, prio)
+    dev.ema(0.95)
+    for step in range(5):
+        q = synth.make_queries(case, 80 + step)
+        ev = synth.make_events(512, 600 + step, pair_weights=w, reuse_prob=np.linspace(0.2, 0.95, 16))
+        d_q = torch.from_numpy(q.view(np.int16)).cuda()
+        d_ev = (torch.from_numpy(ev[0]).cuda(), torch.from_numpy(ev[1]).cuda())
+        dev.mass.fill_(-1.0)
+        # ---- GPU: the whole step without a synchronisation
+        side.wait_stream(main)
+        kvm.kvm_beta_update(d_ev[0], d_ev[1], dev.hits, dev.misses, dev.p_hat, n_bad=dev.n_bad, stream=side)
+        kvm.kvm_select_victims(dev.prio, dev.state, d_outs, dev.n_victims, ws_select, k=n, stream=side)
+        kvm.kvm_score_step_xfer(dev.pool, dev.rows(), d_q, scale, dev.mass, dev.ws, frame, host, n, d_tier)
+        main.wait_stream(side)
+        kvm.kvm_ema_update(dev.rows(), dev.mass, 0.95, dev.row_weight, dev.pair, dev.p_hat, dev.state, dev.S, dev.prio)
+        kvm.kvm_exchange_end(dev.slot_tbl, dev.state, d_ins, frame, n)
+        torch.cuda.synchronize()
+        # ---- oracle: the same stages in order
+        p_hat = oracle.beta_update(ev[0], ev[1], hits, misses)
+        ov = oracle.select_victims(prio, case.state, k=n)
+        gv = d_outs[: int(dev.n_victims.item())].cpu().numpy()
+        victims_agree(gv, ov, prio, case.state)
+        assert len(ov) == n
+        omass = oracle_score(oracle, case, q, scale, fill=-1.0)
+        gmass = dev.mass.cpu().numpy()
+        np.testing.assert_array_equal(gmass != -1.0, omass != -1.0)
+        wr = omass != -1.0
+        np.testing.assert_allclose(gmass[wr], omass[wr], rtol=MASS_RTOL, atol=MASS_ATOL)
+        oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, case.row_weight, case.pair, p_hat, case.state,
+                          S, prio)
+        resm = (case.state & RES) != 0
+        np.testing.assert_allclose(dev.S.cpu().numpy()[resm], S[resm], rtol=MASS_RTOL)
+        np.testing.assert_array_equal(dev.hits.cpu().numpy().view(np.uint32), hits)
+        if pending is not None:
+            ins, frames, hosts = pending
+            k8[frames], tier[hosts, :uk] = tier[hosts, :uk].copy(), k8[frames].copy()
+            v8[frames], tier[hosts, uk:] = tier[hosts, uk:].copy(), v8[frames].copy()
+            case.slot_tbl[ins] = frames
+            case.state[ins] = (case.state[ins] & ~np.uint8(HOST)) | RES
+            case.k_pool[:] = k8.view(np.uint16).reshape(case.k_pool.shape)
+        np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), case.slot_tbl)
+        np.testing.assert_array_equal(dev.state.cpu().numpy(), case.state)
+        gk, gvv = dev.pools_host()
+        np.testing.assert_array_equal(gk, k8)
+        np.testing.assert_array_equal(gvv, v8)
+        np.testing.assert_array_equal(d_tier.numpy().reshape(n_tier, rec), tier)
+        # ---- both sides continue with the oracle's victims
+        on_host = np.flatnonzero(((case.state & HOST) != 0) & ((case.state & RES) == 0))
+        ins = rng.choice(on_host, size=n, replace=False).astype(np.int64)
+        outs = ov.astype(np.int64)
+        frames, hosts = case.slot_tbl[outs].copy(), (-1 - case.slot_tbl[ins]).astype(np.int64)
+        case.slot_tbl[outs] = (-1 - hosts).astype(np.int32)
+        case.state[outs] = (case.state[outs] & ~np.uint8(RES)) | HOST
+        d_outs.copy_(torch.from_numpy(outs))
+        d_ins.copy_(torch.from_numpy(ins))
+        kvm.kvm_exchange_begin(dev.pool, dev.slot_tbl, dev.state, d_outs, d_ins, n, n_tier, frame, host,
+                               n_bad=dev.n_bad)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(frame.cpu().numpy(), frames)
+        np.testing.assert_array_equal(host.cpu().numpy(), hosts)
+        np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), case.slot_tbl)
+        pending = (ins, frames, hosts)
+    assert int(dev.n_bad.item()) == 0
