@@ -269,14 +269,19 @@ def main():
         per-layer window behind the decode position, ranked by blended reuse estimate x positional decay); its
         records and the victims' trade places in the slot-addressed tier while the next step is scored."""
         ev = evs[i % n_q_sets]
-        kvm.kvm_beta_blend_update(ev[0], ev[1], hits, misses, win, win_head, 64.0, p_hat, conf, p_blend, n_bad=n_bad)
         # Content addressing of the units that entered HBM in the previous step (stands in for newly allocated
         # blocks): one SHA-256 chain per unit is 0.5 ms of latency for 16 wavefronts of work, so it runs on a
         # second stream beside the scoring launch (a small compute kernel there costs the scorer 0.01 ms; it
         # was copies on a second stream that slowed it down).  Nobody writes those units meanwhile: they were
         # not yet scored when the last victims were chosen.  Before the first transfer the list holds -1s and
         # every digest is the zero of a skipped unit.
+        # The reuse estimates and the victims (from the priorities the previous step left, as in
+        # step_pipelined) are worked out on the same stream.
         side.wait_stream(main)
+        kvm.kvm_beta_blend_update(ev[0], ev[1], hits, misses, win, win_head, 64.0, p_hat, conf, p_blend, n_bad=n_bad,
+                                  stream=side)
+        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws_select, k=-1, budget_units=budget - swap,
+                               stream=side)
         kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, arrived, swap, digests, stream=side)
         kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
         main.wait_stream(side)
@@ -285,7 +290,6 @@ def main():
         kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window)
         kvm.kvm_exchange_end(wl.slot_tbl, wl.state, pf_list, xf_frame, swap)
         arrived.copy_(pf_list)
-        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         kvm.kvm_prefetch_keys(rows, row_layer, wl.row_ntok, layer_window, wl.state, wl.pair, p_blend, 0.9995,
                               pf_key, pf_cand)
         kvm.kvm_select_victims(pf_key, pf_cand, pf_list, n_pf, ws, k=swap)
