@@ -829,7 +829,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
 // padding), the tile's own log-sum-exp per query is carried in registers; score_rowmerge_big
 // finishes every row.
 constexpr int kWideBufs = 4;
-constexpr int kWideTileBlocks = 256;
+constexpr int kWideTileBlocks = 512;
 
 template <int DIM, int DT, int TB>
 __global__ __launch_bounds__(kThreads, 2) void score_tile_wide_kernel(
