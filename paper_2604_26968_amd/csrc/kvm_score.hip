@@ -205,7 +205,7 @@ __device__ __forceinline__ MZ mz_combine(MZ a, MZ b) {
 }
 
 // ---- plan: tiles of the active rows ------------------------------------------
-constexpr int kPlanThreads = 1024;
+constexpr int kPlanThreads = 128;     // small workgroups: the emit loop of a long row is serial per thread
 
 // Row metadata the plan needs; a row whose blocks or queries would fall outside the
 // arrays is dropped here (it gets no tile) so that no kernel can index out of bounds.
