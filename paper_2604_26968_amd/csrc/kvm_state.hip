@@ -176,18 +176,21 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
                                                        const float* __restrict__ p_hat, uint8_t* __restrict__ state,
                                                        float* __restrict__ S, float* __restrict__ prio, EmaEx ex) {
     __shared__ float ph[KVM_N_PAIRS];
-    if (threadIdx.x < KVM_N_PAIRS) ph[threadIdx.x] = p_hat[threadIdx.x];
-    __syncthreads();
     constexpr int ROWS_PER_WG = 256 / LANES;
     const int row = blockIdx.x * ROWS_PER_WG + threadIdx.x / LANES;
+    // the row's entries are loaded together with the posterior means, ahead of the barrier: the kernel
+    // is a chain of dependent round trips for short rows
+    const int rc = row < n_rows ? row : n_rows - 1;
+    const int n = row_ntok[rc];
+    const int64_t off = row_off[rc];
+    const bool active = row_active ? row_active[rc] != 0 : true;
+    float w = row_weight[rc];
+    if (threadIdx.x < KVM_N_PAIRS) ph[threadIdx.x] = p_hat[threadIdx.x];
+    __syncthreads();
     if (row >= n_rows) return;
-    const int n = row_ntok[row];
     if (n <= 0) return;
     const int64_t nb = ((int64_t)n + 15) >> 4;
-    const int64_t off = row_off[row];
     if (off < 0 || off + nb > n_uids) return;
-    const bool active = row_active ? row_active[row] != 0 : true;
-    float w = row_weight[row];
     if (EX && ex.head_mult) {
         // Out-of-range indices cannot be reported from here: such a row keeps multiplier 1.
         const int sq = ex.row_seq[row], hd = ex.row_head[row];
@@ -197,26 +200,40 @@ __global__ __launch_bounds__(256) void ema_prio_kernel(int n_rows, int64_t n_uid
         }
     }
     const float keep = decay, take = 1.0f - decay;
-    for (int64_t b = threadIdx.x % LANES; b < nb; b += LANES) {
-        const int64_t uid = off + b;
-        // the four loads of a unit at once: a mass loaded only after the state byte has arrived
-        // would put two round trips in a row, and the kernel is bound by that latency
-        uint8_t st = state[uid];
-        float s = S[uid];
-        float x = mass[uid];
-        const uint8_t pr = pair[uid];
-        if (active && (st & KVM_ST_RESIDENT)) {
-            if (EX) x *= pow_by_distance(ex.lg_pos_decay, nb - 1 - b);
-            if (!(st & KVM_ST_SCORED)) {
-                s = x;
-                st |= KVM_ST_SCORED;
-                state[uid] = st;
-            } else {
-                s = keep * s + take * x;
-            }
-            S[uid] = s;
+    // Four units per lane and trip, all sixteen loads before the first use: a mass loaded only after
+    // the state byte has arrived would put two round trips in a row, and a long row handled by one
+    // wavefront is a chain of such trips (the kernel is bound by that latency, not by bytes).
+    constexpr int U = 4;
+    for (int64_t b0 = threadIdx.x % LANES; b0 < nb; b0 += U * LANES) {
+        uint8_t st[U], pr[U];
+        float s[U], x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t b = b0 + u * LANES;
+            const int64_t uid = off + (b < nb ? b : b0);
+            st[u] = state[uid];
+            s[u] = S[uid];
+            x[u] = mass[uid];
+            pr[u] = pair[uid];
         }
-        prio[uid] = (st & KVM_ST_SCORED) ? w * s * ph[pr & 15] : INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t b = b0 + u * LANES;
+            if (b >= nb) break;
+            const int64_t uid = off + b;
+            if (active && (st[u] & KVM_ST_RESIDENT)) {
+                if (EX) x[u] *= pow_by_distance(ex.lg_pos_decay, nb - 1 - b);
+                if (!(st[u] & KVM_ST_SCORED)) {
+                    s[u] = x[u];
+                    st[u] |= KVM_ST_SCORED;
+                    state[uid] = st[u];
+                } else {
+                    s[u] = keep * s[u] + take * x[u];
+                }
+                S[uid] = s[u];
+            }
+            prio[uid] = (st[u] & KVM_ST_SCORED) ? w * s[u] * ph[pr[u] & 15] : INFINITY;
+        }
     }
 }
 
