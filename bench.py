@@ -37,9 +37,9 @@ WORKLOADS = {
     "mqa": ("fleet, MQA half: 32 layers, 32q/1kv head (g 32), d128, bf16, %d seqs lognormal(7,1) tok",
             lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 8192, 0),
 }
-# FETCH_SIZE 6,622,957.5 x 2 KiB + WRITE_SIZE 37,636.3 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
+# FETCH_SIZE 6,619,938.2 x 2 KiB + WRITE_SIZE 37,635.7 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
 # with the 1,024 transfer workgroups of --swap-mode pipelined / overlap riding along
-SCORE_TILE_TRAFFIC_BYTES = int(6622957.5 * 2048 + 37636.3 * 1024)
+SCORE_TILE_TRAFFIC_BYTES = int(6619938.2 * 2048 + 37635.7 * 1024)
 
 
 def main():
