@@ -70,7 +70,7 @@ def main():
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the pass has no cross-GPU step); run with --gpus 1",
+        print("bench.py measures one GPU only (the pass has no cross-GPU step); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 

@@ -60,7 +60,7 @@ extern "C" {
 /* ---- return codes ------------------------------------------------------ */
 #define KVM_OK       0
 #define KVM_EINVAL  (-1)   /* null pointer, negative count, value out of range   */
-#define KVM_ESHAPE  (-2)   /* a shape this build has no kernel for               */
+#define KVM_ESHAPE  (-2)   /* a shape the library has no kernel for            */
 #define KVM_ENOSPC  (-3)   /* workspace / staging / output capacity too small    */
 #define KVM_EHIP    (-4)   /* a HIP runtime call failed                          */
 
