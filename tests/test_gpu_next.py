@@ -531,7 +531,7 @@ def test_dedup_table_too_small_reports_it():
 @pytest.mark.parametrize("shape,n_pairs", [
     (synth.Shape(2, 8, 2, 128, synth.BF16, True, [700, 77, 1300]), 60),       # dot2 kernel, g = 4
     (synth.Shape(2, 32, 1, 128, synth.FP16, True, [900]), 20),                # matrix-core kernel, g = 32
-    (synth.Shape(3, 128, 1, 576, synth.BF16, False, [4500, 300]), 30),        # wide kernel, rows of several tiles
+    (synth.Shape(3, 128, 1, 576, synth.BF16, False, [9000, 300]), 30),        # wide kernel, rows of several tiles
 ])
 def test_exchange_in_three_parts_rides_along_with_scoring(oracle, shape, n_pairs):
     """begin -> score with the transfer in the same launch -> end.  Masses equal the oracle's scoring of

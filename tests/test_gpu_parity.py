@@ -197,7 +197,7 @@ def test_score_mla_large_and_uneven_logits(oracle):
     and queries make every logit exact in fp32, so logits of hundreds of nats can be used: heads of very
     different scale, keys that grow along the row (the maximum keeps rising, the reference is refreshed
     mid-tile) and blocks that vanish against it must all come out right, over several tiles."""
-    shape = synth.Shape(1, 128, 1, 576, synth.BF16, False, [6000, 300])
+    shape = synth.Shape(1, 128, 1, 576, synth.BF16, False, [10000, 300])
     case = synth.make_case(shape, seed=19)
     rng = np.random.default_rng(19)
     for r in range(case.n_rows):
