@@ -39,7 +39,7 @@ constexpr int kSeg = 8;
 // Consecutive rows one wavefront handles, one after the other.  Rows next to each other usually
 // belong to the same layer, so the wavefront adds their spans up in registers and touches the
 // per-layer accumulators (32 hot addresses for a 32-layer model) once per run of equal layers.
-constexpr int kSpanRowsPerWave = 8;
+constexpr int kSpanRowsPerWave = 4;
 
 // Span of one row (0 = the row does not count: inactive, empty, out of range, no mass).
 __device__ inline int64_t row_span(int row, int lane, int64_t n_uids, int n_layers,
@@ -57,7 +57,19 @@ __device__ inline int64_t row_span(int row, int lane, int64_t n_uids, int n_laye
     if (layer < 0 || layer >= n_layers) return 0;
 
     uint64_t total = 0;
-    for (int64_t b = lane; b < nb; b += kWave) total += fixed_mass(mass[off + b], state[off + b]);
+    for (int64_t b0 = lane; b0 < nb; b0 += 4 * kWave) {      // four blocks per lane and trip, loads first
+        float m[4];
+        uint8_t st[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t b = b0 + u * kWave;
+            m[u] = mass[off + (b < nb ? b : b0)];
+            st[u] = state[off + (b < nb ? b : b0)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (b0 + u * kWave < nb) total += fixed_mass(m[u], st[u]);
+    }
 #pragma unroll
     for (int m = 1; m < kWave; m <<= 1) total += shfl_xor_u64(total, m);
     if (total == 0) return 0;
