@@ -163,8 +163,23 @@ def test_llama8b_shaped_full_size(oracle):
     kvm.kvm_exchange_begin(pool, wl.slot_tbl, wl.state, out_b, out_a, 1024, 2048, xf_frame, xf_host, n_bad=n_bad)
     q2 = wl.queries(102)
     mass.fill_(-1.0)
-    kvm.kvm_score_step_xfer(pool, rows, q2, scale, mass, ws, xf_frame, xf_host, 1024, host_tier)
+    # ... and with the next victims chosen meanwhile on a second stream, as the default step does it
+    ws_sel = torch.empty(kvm.kvm_workspace_bytes(kvm.OP_SELECT, n), dtype=torch.uint8, device=dev)
+    vic_seq = torch.zeros(1024, dtype=torch.int64, device=dev)
+    vic_par = torch.zeros(1024, dtype=torch.int64, device=dev)
+    n_par = torch.zeros(1, dtype=torch.int64, device=dev)
+    kvm.kvm_select_victims(prio, wl.state, vic_seq, n_victims, ws_sel, k=1024)
     torch.cuda.synchronize()
+    assert int(n_victims.item()) == 1024
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    side.wait_stream(main)
+    kvm.kvm_select_victims(prio, wl.state, vic_par, n_par, ws_sel, k=1024, stream=side)
+    kvm.kvm_score_step_xfer(pool, rows, q2, scale, mass, ws, xf_frame, xf_host, 1024, host_tier)
+    main.wait_stream(side)
+    torch.cuda.synchronize()
+    assert int(n_par.item()) == 1024 and bool((vic_par == vic_seq).all())
+    want_v2 = oracle.select_victims(prio.cpu().numpy(), wl.state.cpu().numpy(), k=1024)
+    np.testing.assert_array_equal(vic_par.cpu().numpy(), want_v2)
     check_sample(q2, "at budget, exchange riding along")
     in_flight = torch.cat([out_a, out_b])
     assert bool((mass[in_flight] == -1.0).all())           # neither side of a pair is in HBM for the scorer
