@@ -542,6 +542,22 @@ def main():
                                "sample": "%d of %d rows (%d resident units, %.2f GB of K): score + ema + select, "
                                          "%.1f s" % (case.n_rows, n_rows, int(res.sum()), cpu_bytes / 1e9, t_cpu)}
         out["parity_sample_max_rel_err"] = float(rel.max())
+        # the same oracle on one core, on a sixteenth of the sample's rows
+        n_all = oracle.threads()
+        sub = max(1, case.n_rows // 16)
+        sub_units = int(case.row_off[sub]) if sub < case.n_rows else case.n_uids
+        oracle.set_threads(1)
+        try:
+            one_mass = np.zeros(case.n_uids, np.float32)
+            t0 = time.perf_counter()
+            oracle.score_step(case.k_pool, dim, shape.dtype, case.row_ntok[:sub], case.row_off[:sub],
+                              case.row_q_off[:sub], case.slot_tbl, q_rows, g, scale, one_mass)
+            t_one = time.perf_counter() - t0
+        finally:
+            oracle.set_threads(n_all)
+        one_bytes = int((case.slot_tbl[:sub_units] >= 0).sum()) * shape.unit_k_bytes
+        out["cpu_baseline"]["one_core"] = {"value": round(one_bytes / t_one / 1e9, 4), "unit": "GB/s",
+                                           "sample": "scoring of the first %d rows of that sample, %.1f s" % (sub, t_one)}
     print(json.dumps(out))
 
 

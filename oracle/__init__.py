@@ -79,6 +79,11 @@ def threads() -> int:
     return int(lib().kvm_ref_threads())
 
 
+def set_threads(n: int) -> int:
+    """Number of threads the row loops use from now on; returns what is in force."""
+    return int(lib().kvm_ref_set_threads(int(n)))
+
+
 def size(n_layers, n_q_heads, n_kv_heads, head_dim, d_latent=0, d_rope=0, bits_per_elem=16,
          block_tokens=16, head_divisor=1, n_max=0, mem_target=0) -> dict:
     m = _Model(n_layers, n_q_heads, n_kv_heads, head_dim, d_latent, d_rope, bits_per_elem,

@@ -796,3 +796,14 @@ int kvm_ref_threads(void) {
     return 1;
 #endif
 }
+
+/* Sets that number (timing on one core and on all of them); returns what is in force. */
+int kvm_ref_set_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+    return omp_get_max_threads();
+#else
+    (void)n;
+    return 1;
+#endif
+}
