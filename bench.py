@@ -556,6 +556,12 @@ def main():
         finally:
             oracle.set_threads(n_all)
         one_bytes = int((case.slot_tbl[:sub_units] >= 0).sum()) * shape.unit_k_bytes
+        try:
+            model = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+        except Exception:
+            model = "unknown"
+        out["cpu_baseline"]["cpu_model"] = model
+        out["cpu_baseline"]["nproc"] = os.cpu_count()
         out["cpu_baseline"]["one_core"] = {"value": round(one_bytes / t_one / 1e9, 4), "unit": "GB/s",
                                            "sample": "scoring of the first %d rows of that sample, %.1f s" % (sub, t_one)}
     print(json.dumps(out))
