@@ -504,6 +504,23 @@ def main():
             dst.copy_(src, non_blocking=True)
         torch.cuda.synchronize()
         link[name + "_GBps"] = round(3 * link_n / (time.perf_counter() - t0) / 1e9, 2)
+    # both directions at once, each on a stream of its own (needs a second pair of buffers)
+    if host_tier.numel() >= 2 * link_n:
+        hbuf2 = host_tier[link_n:2 * link_n]
+    else:
+        hbuf2 = torch.empty(link_n, dtype=torch.uint8, pin_memory=True)
+    dbuf2 = torch.empty(link_n, dtype=torch.uint8, device=dev)
+    s_out, s_in = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        with torch.cuda.stream(s_out):
+            hbuf.copy_(dbuf, non_blocking=True)
+        with torch.cuda.stream(s_in):
+            dbuf2.copy_(hbuf2, non_blocking=True)
+    torch.cuda.synchronize()
+    link["both_at_once_GBps"] = round(2 * 3 * link_n / (time.perf_counter() - t0) / 1e9, 2)
+    del dbuf2
     out["host_link"] = link
     out["step0"]["bulk_pack_frac_of_link"] = round(out["step0"]["bulk_pack_GBps"] / link["d2h_GBps"], 3)
 
