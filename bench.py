@@ -388,12 +388,16 @@ def main():
     kvm.kvm_timing_reset()
     kvm.kvm_timing_only("score_partial")
     kvm.kvm_timing_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # one per step boundary
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record(main)
     for i in range(args.warmup, total_steps):
         step(i)
+        marks[i - args.warmup + 1].record(main)
     torch.cuda.synchronize()                      # both streams: the last victims have reached the host
     elapsed = time.perf_counter() - t0
+    per_step = sorted(marks[j].elapsed_time(marks[j + 1]) for j in range(args.steps))
     kvm.kvm_timing_enable(False)
     kvm.kvm_timing_only(None)
     assert int(n_bad.item()) == 0, int(n_bad.item())
@@ -434,7 +438,9 @@ def main():
         "metric_parts": "value = K bytes scored per second over the whole management pass; frac_of_hbm_peak = "
                         "value / 8000; evicted_units_per_s, prefetched_units_per_s = the per-step exchange",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4),
+        "ms_per_step_min_max": [round(per_step[0], 4), round(per_step[-1], 4)], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": (wdesc % n_seq) + ", block 16, decay %g, budget %d%%, 4096 events/step"
                                % (decay, round(100 * w_budget)),
