@@ -399,8 +399,9 @@ int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uin
  *       (slot_tbl = frame[i], ON_HOST off, RESIDENT on).
  * After the three calls tables, pools and tier equal what kvm_exchange leaves.
  * Between begin and end neither unit of a pair is in HBM for the scorer, the
- * EMA or the selector, and both table entries name the same host slot: the
- * caller must not build another prefetch or victim list in between.
+ * EMA or the selector (a victim list built in between cannot contain them),
+ * and both table entries name the same host slot with ON_HOST set: the caller
+ * must not build a prefetch list in between, it could name either of them.
  * Errors: as kvm_exchange; null frame / host.                                */
 int kvm_exchange_begin(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
                        int64_t n_uids, const int64_t* out_uids /* dev [n] */, const int64_t* in_uids /* dev [n] */,
