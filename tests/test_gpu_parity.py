@@ -174,6 +174,26 @@ def test_score_random_configurations(oracle, seed):
     check_mass(oracle, case, q, scale, agg=int(rng.integers(2)), row_active=active, need_written=False)
 
 
+@pytest.mark.parametrize("hq,hkv,dim", [(8, 2, 128), (32, 1, 128), (128, 1, 576)])
+def test_score_rows_listed_in_arbitrary_order(oracle, hq, hkv, dim):
+    """Nothing ties a row's place in the row arrays to the place of its units or of its queries:
+    rows listed in a shuffled order (short and long ones mixed, one of several tiles) give the same
+    masses, bit for bit, as the same rows listed in order."""
+    lens = [16 * 700 + 3, 40, 16 * 90, 16 * 1300 + 9, 500, 16]
+    case = synth.make_case(synth.Shape(2, hq, hkv, dim, synth.BF16, dim != 576, lens), seed=77 + hq, uid_gap=2,
+                           poison_tail=True)
+    evict_some(case, 0.4, 11)
+    q = synth.make_queries(case, 41)
+    scale = 1.0 / np.sqrt(dim)
+    got_in_order, _ = check_mass(oracle, case, q, scale)
+    perm = np.random.default_rng(5).permutation(case.n_rows)
+    case.row_ntok, case.row_off, case.row_q_off = case.row_ntok[perm].copy(), case.row_off[perm].copy(), \
+        case.row_q_off[perm].copy()
+    case.row_seq, case.row_weight = case.row_seq[perm].copy(), case.row_weight[perm].copy()
+    got_shuffled, _ = check_mass(oracle, case, q, scale)
+    np.testing.assert_array_equal(got_shuffled, got_in_order)
+
+
 def test_score_llama8b_twin(oracle):
     case = synth.llama8b_twin(n_seq=2, n_layers=1)
     evict_some(case, 0.4, 9)
