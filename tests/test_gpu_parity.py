@@ -194,6 +194,15 @@ def test_score_rows_listed_in_arbitrary_order(oracle, hq, hkv, dim):
     np.testing.assert_array_equal(got_shuffled, got_in_order)
 
 
+@pytest.mark.parametrize("hq,dim,n_blocks", [(64, 128, 2200), (128, 128, 4500), (8, 128, 9000)])
+def test_score_rows_of_more_tiles_than_one_fold_batch(oracle, hq, dim, n_blocks):
+    """The row merge folds a row's tile values sixteen (or, with two threads per query, thirty-two) at
+    a time: rows of 18, 71 and 18 tiles take it through more than one batch on each of its kernels."""
+    case = synth.make_case(synth.Shape(1, hq, 1, dim, synth.BF16, True, [16 * n_blocks - 5, 300]), seed=hq + 3)
+    evict_some(case, 0.5, 2)
+    check_mass(oracle, case, synth.make_queries(case, 9), 1.0 / np.sqrt(dim))
+
+
 def test_score_llama8b_twin(oracle):
     case = synth.llama8b_twin(n_seq=2, n_layers=1)
     evict_some(case, 0.4, 9)
