@@ -203,6 +203,18 @@ def test_score_rows_of_more_tiles_than_one_fold_batch(oracle, hq, dim, n_blocks)
     check_mass(oracle, case, synth.make_queries(case, 9), 1.0 / np.sqrt(dim))
 
 
+def test_score_tens_of_thousands_of_short_rows(oracle):
+    """40,000 rows of one to three blocks: the plan's scan runs over hundreds of workgroup totals and
+    carries across its own chunks; a few rows are inactive or empty."""
+    rng = np.random.default_rng(8)
+    lens = [int(x) for x in rng.integers(0, 41, size=1000)]
+    case = synth.make_case(synth.Shape(1, 40, 40, 64, synth.FP16, True, lens), seed=4, poison_tail=True)
+    assert case.n_rows == 40000
+    evict_some(case, 0.25, 3)
+    active = (rng.random(case.n_rows) < 0.97).astype(np.uint8)
+    check_mass(oracle, case, synth.make_queries(case, 10), 0.125, row_active=active)
+
+
 def test_score_llama8b_twin(oracle):
     case = synth.llama8b_twin(n_seq=2, n_layers=1)
     evict_some(case, 0.4, 9)
