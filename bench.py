@@ -37,9 +37,14 @@ WORKLOADS = {
     "mqa": ("fleet, MQA half: 32 layers, 32q/1kv head (g 32), d128, bf16, %d seqs lognormal(7,1) tok",
             lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 8192, 0),
 }
-# FETCH_SIZE 6,619,938.2 x 2 KiB + WRITE_SIZE 37,635.7 x 1 KiB per launch of score_tile_dot2_kernel<4, 128, bf16, 512>
-# with the 1,024 transfer workgroups of --swap-mode pipelined / overlap riding along
-SCORE_TILE_TRAFFIC_BYTES = int(6619938.2 * 2048 + 37635.7 * 1024)
+# HBM bytes per launch of the tile kernel from rocprofv3 --pmc (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB), with the
+# transfer workgroups of --swap-mode pipelined / overlap riding along; one entry per workload at its default size
+# (profiles/score_tile_dot2_llama8b_pmc.md, score_tile_dot2_llama70b_pmc.md, score_tile_wide_mla_pmc.md).
+SCORE_TILE_TRAFFIC_BYTES = {
+    "llama8b": int(6619938.2 * 2048 + 37635.7 * 1024),       # score_tile_dot2_kernel<4, 128, bf16, 512>
+    "llama70b": int(21149948.2 * 2048 + 394499.9 * 1024),    # score_tile_dot2_kernel<8, 128, bf16, 512>
+    "mla": int(14694104.5 * 2048 + 840307.0 * 1024),         # score_tile_wide_kernel<576, bf16, 512>
+}
 
 
 def main():
@@ -425,10 +430,10 @@ def main():
     algo_bytes = scored_units * (shape.unit_k_bytes + 4) + n_blocks_active * 4 + n_rows * g * dim * 2
     sp = kernels["score_partial"]["avg_ms"]
     achieved = algo_bytes / (sp * 1e-3) / 1e9
-    # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this workload
-    # (profiles/score_tile_dot2_llama8b_pmc.md); valid for the default workload only.
-    traffic = SCORE_TILE_TRAFFIC_BYTES if (args.workload == "llama8b" and n_seq == 64 and swap == 1024
-                                           and args.swap_mode in ("overlap", "pipelined") and not args.refined) else None
+    # measured HBM bytes per launch: only for the sizes the counters were taken at
+    traffic = SCORE_TILE_TRAFFIC_BYTES.get(args.workload) if (n_seq == w_nseq and swap == w_swap
+                                                              and args.swap_mode in ("overlap", "pipelined")
+                                                              and not args.refined) else None
     roofline = {"kernel": "score_partial", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": algo_bytes, "avg_ms": round(sp, 4)}
