@@ -158,6 +158,7 @@ def main():
         span_sum = torch.zeros(L, dtype=torch.int64, device=dev)
         span_cnt = torch.zeros(L, dtype=torch.int32, device=dev)
         layer_window = torch.full((L,), 1 << 30, dtype=torch.int32, device=dev)
+        ws_span = torch.empty(max(kvm.kvm_workspace_bytes(kvm.OP_SPAN, n, n_rows), 256), dtype=torch.uint8, device=dev)
         pf_key = torch.zeros(n, dtype=torch.float32, device=dev)
         pf_cand = torch.zeros(n, dtype=torch.uint8, device=dev)
         n_pf = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -295,7 +296,8 @@ def main():
         main.wait_stream(side)
         kvm.kvm_dedup_insert(store, digests, arrived, swap, canon, dedup_ws)
         kvm.kvm_ema_update_ex(rows, mass, decay, ex, wl.row_weight, wl.pair, p_blend, wl.state, S, prio)
-        kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window)
+        kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window,
+                            ws_span)
         kvm.kvm_exchange_end(wl.slot_tbl, wl.state, pf_list, xf_frame, swap)
         arrived.copy_(pf_list)
         kvm.kvm_prefetch_keys(rows, row_layer, wl.row_ntok, layer_window, wl.state, wl.pair, p_blend, 0.9995,

@@ -428,14 +428,19 @@ int kvm_exchange_end(int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev i
  * in tokens; other layers keep their window.  Masses enter as fixed point,
  * floor(min(m, 1) * 2^32) (0 for m <= 0 or NaN), sums and comparisons are exact
  * integers: the result does not depend on summation order.
+ * ws: dev scratch of at least kvm_workspace_bytes(KVM_OP_SPAN, ...) bytes
+ * (one 32-bit span per row, folded per layer by a second kernel), 4-byte
+ * aligned, contents irrelevant before and undefined after; not needed when
+ * n_rows or n_uids is 0.
  * Errors: KVM_EINVAL (null pointers, n_layers <= 0, theta outside [0, 1] or
- * theta_den > 65536, w_min < 0, w_max < w_min).  Rows with row_layer outside
- * [0, n_layers) are skipped.                                                */
+ * theta_den > 65536, w_min < 0, w_max < w_min), KVM_ENOSPC (ws_bytes too
+ * small).  Rows with row_layer outside [0, n_layers) are skipped.           */
 int kvm_span_update(const kvm_rows_t* rows, const int32_t* row_layer /* dev [n_rows] */, int32_t n_layers,
                     const float* mass /* dev [n_uids] */, const uint8_t* state /* dev [n_uids] */,
                     uint32_t theta_num, uint32_t theta_den,
                     uint64_t* span_sum /* dev [n_layers] in/out */, uint32_t* span_cnt /* dev [n_layers] in/out */,
-                    int32_t w_min, int32_t w_max, int32_t* layer_window /* dev [n_layers] in/out */, void* stream);
+                    int32_t w_min, int32_t w_max, int32_t* layer_window /* dev [n_layers] in/out */,
+                    void* ws, size_t ws_bytes, void* stream);
 
 /* kvm_prefetch_keys: which host-resident units to promote ahead of use.  While
  * a request decodes at position n the blocks within a window w of n are the
@@ -516,7 +521,9 @@ int kvm_dedup_release(const kvm_store_t* store, const uint8_t* digests /* dev [n
  * ======================================================================== */
 #define KVM_OP_SCORE  0
 #define KVM_OP_SELECT 1
-/* Bytes of device scratch the op needs for these sizes (n_rows, g, dim ignored by SELECT). */
+#define KVM_OP_SPAN   2
+/* Bytes of device scratch the op needs for these sizes (SELECT looks at n_uids only, SPAN at
+ * n_rows only); 0 for an unknown op or a negative size. */
 size_t kvm_workspace_bytes(int op, int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim);
 
 /* Text describing the last error returned on this thread ("" if none). */

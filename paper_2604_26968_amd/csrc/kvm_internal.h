@@ -70,5 +70,6 @@ constexpr int kWave = 64;
 // Workspace sizes, defined next to the kernels that use them.
 size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t dim);
 size_t select_workspace_bytes(int64_t n_uids);
+size_t span_workspace_bytes(int32_t n_rows);
 
 }  // namespace kvm

@@ -36,10 +36,6 @@ __device__ inline uint64_t shfl_xor_u64(uint64_t v, int mask) {
 // contiguous memory), one prefix scan over the lane sums per chunk finds the lane in which the
 // running sum reaches theta * total, and that lane walks its kSeg values to the exact block.
 constexpr int kSeg = 8;
-// Consecutive rows one wavefront handles, one after the other.  Rows next to each other usually
-// belong to the same layer, so the wavefront adds their spans up in registers and touches the
-// per-layer accumulators (32 hot addresses for a 32-layer model) once per run of equal layers.
-constexpr int kSpanRowsPerWave = 4;
 
 // Span of one row (0 = the row does not count: inactive, empty, out of range, no mass).
 __device__ inline int64_t row_span(int row, int lane, int64_t n_uids, int n_layers,
@@ -47,13 +43,13 @@ __device__ inline int64_t row_span(int row, int lane, int64_t n_uids, int n_laye
                                    const uint8_t* __restrict__ row_active, const int32_t* __restrict__ row_layer,
                                    const float* __restrict__ mass, const uint8_t* __restrict__ state,
                                    uint32_t theta_num, uint32_t theta_den) {
-    const int n = row_ntok[row];
-    if (n <= 0) return 0;
-    const int64_t nb = ((int64_t)n + 15) >> 4;
+    const int n = row_ntok[row];                             // the row's four records in one round trip
     const int64_t off = row_off[row];
-    if (off < 0 || off + nb > n_uids) return 0;
-    if (row_active && !row_active[row]) return 0;
     const int layer = row_layer[row];
+    const bool active = row_active ? row_active[row] != 0 : true;
+    if (n <= 0 || !active) return 0;
+    const int64_t nb = ((int64_t)n + 15) >> 4;
+    if (off < 0 || off + nb > n_uids) return 0;
     if (layer < 0 || layer >= n_layers) return 0;
 
     uint64_t total = 0;
@@ -119,6 +115,7 @@ __device__ inline int64_t row_span(int row, int lane, int64_t n_uids, int n_laye
     return nb;
 }
 
+// One wavefront per row; the row's span goes to row_span[row] (0 = the row does not count).
 __global__ __launch_bounds__(256) void span_rows_kernel(int n_rows, int64_t n_uids, int n_layers,
                                                         const int32_t* __restrict__ row_ntok,
                                                         const int64_t* __restrict__ row_off,
@@ -126,36 +123,66 @@ __global__ __launch_bounds__(256) void span_rows_kernel(int n_rows, int64_t n_ui
                                                         const int32_t* __restrict__ row_layer,
                                                         const float* __restrict__ mass,
                                                         const uint8_t* __restrict__ state, uint32_t theta_num,
-                                                        uint32_t theta_den, unsigned long long* span_sum,
-                                                        uint32_t* span_cnt) {
+                                                        uint32_t theta_den, int32_t* __restrict__ row_span_out) {
     const int lane = threadIdx.x % kWave;
-    const int64_t row0 = ((int64_t)blockIdx.x * 4 + threadIdx.x / kWave) * kSpanRowsPerWave;
-    int cur_layer = -1;
-    unsigned long long sum = 0;
-    uint32_t cnt = 0;
-    for (int i = 0; i < kSpanRowsPerWave; ++i) {
-        const int64_t row = row0 + i;
-        if (row >= n_rows) break;
-        const int64_t span = row_span((int)row, lane, n_uids, n_layers, row_ntok, row_off, row_active, row_layer, mass,
-                                      state, theta_num, theta_den);
-        if (span == 0) continue;
-        const int layer = row_layer[row];
-        if (layer != cur_layer) {
-            if (cnt && lane == 0) {
-                atomicAdd(&span_sum[cur_layer], sum);
-                atomicAdd(&span_cnt[cur_layer], cnt);
-            }
-            cur_layer = layer;
-            sum = 0;
-            cnt = 0;
+    const int64_t row = (int64_t)blockIdx.x * 4 + threadIdx.x / kWave;
+    if (row >= n_rows) return;
+    const int64_t span = row_span((int)row, lane, n_uids, n_layers, row_ntok, row_off, row_active, row_layer, mass,
+                                  state, theta_num, theta_den);
+    if (lane == 0) row_span_out[row] = (int32_t)span;        // at most 2^27 blocks in a row of 2^31 tokens
+}
+
+// Per-layer sums of the row spans.  Adding each row's span straight to its layer's accumulator
+// costs far more than finding the span: the adds of one layer all meet at one address (32
+// layers: 64 hot addresses for every row of the model) and are served one after the other.  So
+// a workgroup folds kSpanFoldRows rows into per-layer cells in LDS first and then adds each cell
+// it touched to the accumulators once.  n_layers <= kSpanFoldLayers.
+constexpr int kSpanFoldLayers = 2048;
+constexpr int kSpanFoldRows = 4096;
+__global__ __launch_bounds__(1024) void span_fold_kernel(int n_rows, int n_layers,
+                                                         const int32_t* __restrict__ row_layer,
+                                                         const int32_t* __restrict__ row_span_in,
+                                                         unsigned long long* span_sum, uint32_t* span_cnt) {
+    __shared__ unsigned long long s_sum[kSpanFoldLayers];
+    __shared__ uint32_t s_cnt[kSpanFoldLayers];
+    for (int l = threadIdx.x; l < n_layers; l += blockDim.x) {
+        s_sum[l] = 0;
+        s_cnt[l] = 0;
+    }
+    __syncthreads();
+    const int64_t row0 = (int64_t)blockIdx.x * kSpanFoldRows;
+    constexpr int PER = kSpanFoldRows / 1024;
+    int32_t span[PER], layer[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int64_t row = row0 + u * 1024 + threadIdx.x;
+        span[u] = row < n_rows ? row_span_in[row] : 0;
+        layer[u] = row < n_rows ? row_layer[row] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+        if (span[u] > 0) {                                   // a counted row has a layer in range
+            atomicAdd(&s_sum[layer[u]], (unsigned long long)span[u]);
+            atomicAdd(&s_cnt[layer[u]], 1u);
         }
-        sum += (unsigned long long)span;
-        cnt += 1;
-    }
-    if (cnt && lane == 0) {
-        atomicAdd(&span_sum[cur_layer], sum);
-        atomicAdd(&span_cnt[cur_layer], cnt);
-    }
+    __syncthreads();
+    for (int l = threadIdx.x; l < n_layers; l += blockDim.x)
+        if (s_cnt[l]) {
+            atomicAdd(&span_sum[l], s_sum[l]);
+            atomicAdd(&span_cnt[l], s_cnt[l]);
+        }
+}
+
+// The same without the fold, for models of more layers than the fold has cells.
+__global__ __launch_bounds__(256) void span_add_kernel(int n_rows, const int32_t* __restrict__ row_layer,
+                                                       const int32_t* __restrict__ row_span_in,
+                                                       unsigned long long* span_sum, uint32_t* span_cnt) {
+    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= n_rows) return;
+    const int32_t span = row_span_in[row];
+    if (span <= 0) return;
+    atomicAdd(&span_sum[row_layer[row]], (unsigned long long)span);
+    atomicAdd(&span_cnt[row_layer[row]], 1u);
 }
 
 __global__ void span_window_kernel(int n_layers, const unsigned long long* span_sum, const uint32_t* span_cnt,
@@ -224,12 +251,15 @@ int check_rows(const char* who, const kvm_rows_t* rows, bool* nothing) {
 }
 
 }  // namespace
+
+size_t span_workspace_bytes(int32_t n_rows) { return ((size_t)(n_rows > 0 ? n_rows : 0) * sizeof(int32_t) + 255) & ~(size_t)255; }
+
 }  // namespace kvm
 
 extern "C" int kvm_span_update(const kvm_rows_t* rows, const int32_t* row_layer, int32_t n_layers, const float* mass,
                                const uint8_t* state, uint32_t theta_num, uint32_t theta_den, uint64_t* span_sum,
-                               uint32_t* span_cnt, int32_t w_min, int32_t w_max, int32_t* layer_window,
-                               void* stream) {
+                               uint32_t* span_cnt, int32_t w_min, int32_t w_max, int32_t* layer_window, void* ws,
+                               size_t ws_bytes, void* stream) {
     using namespace kvm;
     clear_error();
     KVM_REQUIRE(n_layers > 0, KVM_EINVAL, "kvm_span_update: n_layers %d <= 0", n_layers);
@@ -241,13 +271,28 @@ extern "C" int kvm_span_update(const kvm_rows_t* rows, const int32_t* row_layer,
     bool nothing;
     if (int rc = check_rows("kvm_span_update", rows, &nothing)) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    TimedLaunch tl("span", st);
     if (!nothing) {
         KVM_REQUIRE(row_layer && mass && state, KVM_EINVAL, "kvm_span_update: null buffer");
-        const int64_t rows_per_wg = 4 * kSpanRowsPerWave;
-        span_rows_kernel<<<(unsigned)((rows->n_rows + rows_per_wg - 1) / rows_per_wg), 256, 0, st>>>(
-            rows->n_rows, rows->n_uids, n_layers, rows->row_ntok, rows->row_off, rows->row_active, row_layer, mass,
-            state, theta_num, theta_den, reinterpret_cast<unsigned long long*>(span_sum), span_cnt);
+        KVM_REQUIRE(ws && reinterpret_cast<uintptr_t>(ws) % 4 == 0, KVM_EINVAL,
+                    "kvm_span_update: workspace null or not 4-byte aligned");
+        KVM_REQUIRE(ws_bytes >= span_workspace_bytes(rows->n_rows), KVM_ENOSPC,
+                    "kvm_span_update: workspace of %zu bytes, %zu needed", ws_bytes,
+                    span_workspace_bytes(rows->n_rows));
+    }
+    TimedLaunch tl("span", st);
+    if (!nothing) {
+        const int n_rows = rows->n_rows;
+        int32_t* row_span_buf = static_cast<int32_t*>(ws);
+        span_rows_kernel<<<(unsigned)((n_rows + 3) / 4), 256, 0, st>>>(
+            n_rows, rows->n_uids, n_layers, rows->row_ntok, rows->row_off, rows->row_active, row_layer, mass, state,
+            theta_num, theta_den, row_span_buf);
+        unsigned long long* sum = reinterpret_cast<unsigned long long*>(span_sum);
+        if (n_layers <= kSpanFoldLayers)
+            span_fold_kernel<<<(unsigned)((n_rows + kSpanFoldRows - 1) / kSpanFoldRows), 1024, 0, st>>>(
+                n_rows, n_layers, row_layer, row_span_buf, sum, span_cnt);
+        else
+            span_add_kernel<<<(unsigned)((n_rows + 255) / 256), 256, 0, st>>>(n_rows, row_layer, row_span_buf, sum,
+                                                                             span_cnt);
     }
     span_window_kernel<<<(unsigned)((n_layers + 255) / 256), 256, 0, st>>>(
         n_layers, reinterpret_cast<const unsigned long long*>(span_sum), span_cnt, w_min, w_max, layer_window);

@@ -351,6 +351,7 @@ extern "C" size_t kvm_workspace_bytes(int op, int64_t n_uids, int32_t n_rows, in
     if (n_uids < 0 || n_rows < 0) return 0;
     if (op == KVM_OP_SCORE) return kvm::score_workspace_bytes(n_uids, n_rows, g < 1 ? 1 : g, dim);
     if (op == KVM_OP_SELECT) return kvm::select_workspace_bytes(n_uids);
+    if (op == KVM_OP_SPAN) return kvm::span_workspace_bytes(n_rows);
     return 0;
 }
 

@@ -21,7 +21,7 @@ BF16, FP16 = 0, 1
 ARCH_MHA, ARCH_GQA, ARCH_MQA, ARCH_MLA = 0, 1, 2, 3
 ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
 AGG_MAX, AGG_MEAN = 0, 1
-OP_SCORE, OP_SELECT = 0, 1
+OP_SCORE, OP_SELECT, OP_SPAN = 0, 1, 2
 
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
@@ -104,7 +104,8 @@ def _load() -> C.CDLL:
     lib.kvm_ema_update_ex.argtypes = [C.POINTER(Rows), C.c_void_p, C.c_float, C.POINTER(EmaEx), C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_span_update.argtypes = [C.POINTER(Rows), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
-                                    C.c_uint32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+                                    C.c_uint32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.c_size_t, C.c_void_p]
     lib.kvm_prefetch_keys.argtypes = [C.POINTER(Rows), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_exchange.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64,
@@ -231,12 +232,14 @@ def kvm_ema_update_ex(rows: Rows, mass, ema_decay: float, ex: EmaEx, row_weight,
 
 
 def kvm_span_update(rows: Rows, row_layer, mass, state, theta_num: int, theta_den: int, span_sum, span_cnt,
-                    w_min: int, w_max: int, layer_window, stream=None):
-    """span_sum: int64 [n_layers] (read as unsigned), span_cnt / layer_window: int32 [n_layers]."""
+                    w_min: int, w_max: int, layer_window, ws, stream=None):
+    """span_sum: int64 [n_layers] (read as unsigned), span_cnt / layer_window: int32 [n_layers];
+    ws: uint8 scratch of kvm_workspace_bytes(OP_SPAN, 0, n_rows) bytes (None when there are no rows)."""
     _check(lib.kvm_span_update(C.byref(rows), _ptr(row_layer, torch.int32), layer_window.numel(),
                                _ptr(mass, torch.float32), _ptr(state, torch.uint8), theta_num, theta_den,
                                _ptr(span_sum, torch.int64), _ptr(span_cnt, torch.int32), w_min, w_max,
-                               _ptr(layer_window, torch.int32), _stream(stream)))
+                               _ptr(layer_window, torch.int32), _ptr(ws, torch.uint8) if ws is not None else None,
+                               ws.numel() if ws is not None else 0, _stream(stream)))
 
 
 def kvm_prefetch_keys(rows: Rows, row_layer, row_pos, layer_window, state, pair, p_est, pos_decay: float, key, cand,

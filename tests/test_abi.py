@@ -110,7 +110,7 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert blend(0, 8, -1.0, 1) == kvm.EINVAL and "kappa" in kvm.kvm_last_error()
     assert blend(5, 8, 1.0, 1) == kvm.EINVAL                # events without arrays
     span = lambda n_layers, num, den, w_min, w_max, ptr: lib.kvm_span_update(
-        C.byref(rows), None, n_layers, None, None, num, den, ptr, ptr, w_min, w_max, ptr, None)
+        C.byref(rows), None, n_layers, None, None, num, den, ptr, ptr, w_min, w_max, ptr, None, 0, None)
     assert span(0, 9, 10, 0, 100, 1) == kvm.EINVAL
     assert span(4, 11, 10, 0, 100, 1) == kvm.EINVAL and "theta" in kvm.kvm_last_error()
     assert span(4, 9, 0, 0, 100, 1) == kvm.EINVAL
@@ -158,4 +158,5 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_unpack(C.byref(pool), None, None, 8, None, -3, None, None, None, 0, None, 0, None, None) == kvm.EINVAL
     assert kvm.kvm_workspace_bytes(kvm.OP_SCORE, 1000, 10, 4, 128) >= 1000 * 4 * 4
     assert kvm.kvm_workspace_bytes(kvm.OP_SELECT, 1000) > 0
+    assert kvm.kvm_workspace_bytes(kvm.OP_SPAN, 0, 1000) >= 4000
     assert kvm.kvm_workspace_bytes(99, 1000) == 0

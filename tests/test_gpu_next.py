@@ -182,6 +182,12 @@ def prefetch_case(seed=4):
     return case
 
 
+def span_ws(n_rows):
+    """Scratch for kvm_span_update, handed over with garbage in it."""
+    from paper_2604_26968_amd import kvm
+    return torch.full((max(kvm.kvm_workspace_bytes(kvm.OP_SPAN, 0, n_rows), 4),), 0x7F, dtype=torch.uint8, device="cuda")
+
+
 @pytest.mark.parametrize("theta", [(9, 10), (1, 2), (1, 1), (0, 1), (65535, 65536)])
 def test_span_update_exact(oracle, theta):
     """Integer results: span sums, counts and windows are bit-exact."""
@@ -212,7 +218,7 @@ def test_span_update_exact(oracle, theta):
                            32, 2000, win, row_active=active)
         dev.mass.copy_(torch.from_numpy(mass))
         kvm.kvm_span_update(dev.rows(active), d_layer, dev.mass, dev.state, theta[0], theta[1], d_sum, d_cnt, 32, 2000,
-                            d_win)
+                            d_win, span_ws(case.n_rows))
         torch.cuda.synchronize()
         np.testing.assert_array_equal(d_sum.cpu().numpy().view(np.uint64), s_sum)
         np.testing.assert_array_equal(d_cnt.cpu().numpy().view(np.uint32), s_cnt)
@@ -236,12 +242,61 @@ def test_span_long_rows(oracle):
         d_cnt = torch.zeros(2, dtype=torch.int32, device="cuda")
         d_win = torch.zeros(2, dtype=torch.int32, device="cuda")
         dev.mass.copy_(torch.from_numpy(mass))
-        kvm.kvm_span_update(dev.rows(), dev_of(row_layer), dev.mass, dev.state, 9, 10, d_sum, d_cnt, 0, 1 << 30, d_win)
+        kvm.kvm_span_update(dev.rows(), dev_of(row_layer), dev.mass, dev.state, 9, 10, d_sum, d_cnt, 0, 1 << 30, d_win,
+                            span_ws(case.n_rows))
         torch.cuda.synchronize()
         np.testing.assert_array_equal(d_sum.cpu().numpy().view(np.uint64), s_sum)
         np.testing.assert_array_equal(d_win.cpu().numpy(), win)
         if kind == "uniform":
             assert s_sum[0] == -(-9 * 8192 // 10) + -(-9 * 4375 // 10)
+
+
+@pytest.mark.parametrize("n_layers", [7, 2048, 2500])
+def test_span_many_rows_and_layers(oracle, n_layers):
+    """10,000 short rows (several workgroups of the per-layer fold, a ragged last one) dealt over few,
+    many and more layers than the fold has cells; rows given in an order unrelated to their layers;
+    some rows with a layer out of range.  Accumulators start non-zero."""
+    from paper_2604_26968_amd import kvm
+    rng = np.random.default_rng(n_layers)
+    n_rows = 10000
+    row_ntok = rng.integers(0, 400, n_rows).astype(np.int32)
+    nb = (row_ntok.astype(np.int64) + 15) // 16
+    row_off = np.zeros(n_rows, np.int64)
+    row_off[1:] = np.cumsum(nb[:-1])
+    n = int(nb.sum())
+    row_layer = rng.integers(0, n_layers, n_rows).astype(np.int32)
+    row_layer[rng.random(n_rows) < 0.01] = n_layers
+    row_layer[rng.random(n_rows) < 0.01] = -1
+    mass = (rng.random(n) ** 6).astype(np.float32)
+    state = np.where(rng.random(n) < 0.7, 9, 2).astype(np.uint8)
+    s_sum = rng.integers(0, 1000, n_layers).astype(np.uint64)
+    s_cnt = rng.integers(1, 5, n_layers).astype(np.uint32)
+    win = np.full(n_layers, -3, np.int32)
+    d_sum, d_cnt, d_win = dev_of(s_sum.view(np.int64)), dev_of(s_cnt.view(np.int32)), dev_of(win)
+    # the library skips rows whose layer is out of range; the oracle refuses them, so it gets them as inactive rows
+    in_range = (row_layer >= 0) & (row_layer < n_layers)
+    oracle.span_update(row_ntok, row_off, np.where(in_range, row_layer, 0).astype(np.int32), mass, state, 4, 5, s_sum,
+                       s_cnt, 16, 4096, win, row_active=in_range.astype(np.uint8))
+    rows = kvm.make_rows(dev_of(row_ntok), dev_of(row_off), torch.zeros(n_rows, dtype=torch.int64, device="cuda"),
+                         torch.zeros(n, dtype=torch.int32, device="cuda"), 1, n_rows)
+    kvm.kvm_span_update(rows, dev_of(row_layer), dev_of(mass), dev_of(state), 4, 5, d_sum, d_cnt, 16, 4096, d_win,
+                        span_ws(n_rows))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d_sum.cpu().numpy().view(np.uint64), s_sum)
+    np.testing.assert_array_equal(d_cnt.cpu().numpy().view(np.uint32), s_cnt)
+    np.testing.assert_array_equal(d_win.cpu().numpy(), win)
+
+
+def test_span_workspace_too_small():
+    from paper_2604_26968_amd import kvm
+    case = synth.tiny_gqa()
+    dev = DeviceCase(case)
+    L = case.shape.n_layers
+    z64, z32 = torch.zeros(L, dtype=torch.int64, device="cuda"), torch.zeros(L, dtype=torch.int32, device="cuda")
+    with pytest.raises(kvm.KvmError) as e:
+        kvm.kvm_span_update(dev.rows(), dev_of(synth.row_layer_index(case)), dev.mass, dev.state, 9, 10, z64, z32, 0, 100,
+                            z32.clone(), torch.zeros(4 * case.n_rows - 4, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == kvm.ENOSPC
 
 
 @pytest.mark.parametrize("pos_decay", [1.0, 0.98, 0.5])
