@@ -182,7 +182,8 @@ int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q
  * below): n_pairs extra workgroups at the front of the scorer's grid each swap
  * one (pool frame, host tier record) pair in place while the rest of the grid
  * scores, so the host link works during the scoring and not after it.
- * xfer_frame[i] < 0 skips pair i.  The frames named belong to units the scorer
+ * xfer_frame[i] outside [0, n_slots) skips pair i (kvm_exchange_begin writes -1
+ * for a pair it refused).  The frames named belong to units the scorer
  * cannot see (kvm_exchange_begin took them out of the table), so scoring and
  * transfer never touch the same memory; results equal kvm_score_step followed
  * by the same transfer.  n_pairs == 0 is kvm_score_step.

@@ -313,7 +313,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, con
     const uint32_t first = (uint32_t)at, mfirst = (uint32_t)(at >> 32);
     if (nt == 0) return;
     const int32_t ntok = p.row_ntok[r];
-    const int32_t nb = (ntok + 15) >> 4;
+    const int32_t nb = (int32_t)(((uint32_t)ntok + 15u) >> 4);
     const int64_t off = p.row_off[r], q_off = p.row_q_off[r];
     for (uint32_t i = 0; i < nt; ++i) {
         const int32_t b0 = (int32_t)(i * p.tile_blocks);
@@ -345,11 +345,12 @@ struct Xfer {
     uint4* v_pool;
     uint4* tier;
     uint32_t k_v4, v_v4;
+    uint32_t n_slots;       // frames of the pool: a frame number outside it is skipped like -1
 };
 
 __device__ __forceinline__ void xfer_pair(const Xfer& x, uint32_t i) {
     const int32_t f = x.frame[i];
-    if (f < 0) return;
+    if ((uint32_t)f >= x.n_slots) return;
     uint4* rec = x.tier + (size_t)x.host[i] * ((size_t)x.k_v4 + x.v_v4);
     uint4* kf = x.k_pool + (size_t)f * x.k_v4;
     for (uint32_t v = threadIdx.x; v < x.k_v4; v += kThreads) {
@@ -420,22 +421,18 @@ __device__ __forceinline__ TileCtx tile_ctx(const Tile* tiles, uint32_t tile_id)
     TileCtx c;
     c.b0 = tile.b0;
     c.ntok = tile.ntok;
-    c.nb = (c.ntok + 15) >> 4;
+    c.nb = (int)(((uint32_t)c.ntok + 15u) >> 4);
     c.nbt = min(T, c.nb - tile.b0);
     c.uid0 = tile.uid0;
     c.q_off = tile.q_off;
     return c;
 }
 
-// Resident units of a tile, compacted into LDS as (block index in tile, pool frame), in
-// block order: every thread looks at up to T/256 table entries, a ballot + popcount
-// gives each resident entry its place.  Returns the list length.  Contains two barriers.
+// The table entries of a tile, thread t holding blocks t, t + 256, ... (-1 past the end).
 template <int T>
 struct TileSlots {
     int v[(T + kThreads - 1) / kThreads];
 };
-
-// The table entries of a tile, thread t holding blocks t, t + 256, ... (-1 past the end).
 template <int T>
 __device__ __forceinline__ TileSlots<T> load_tile_slots(const int32_t* __restrict__ slot_tbl, int64_t uid0, int nbt) {
     TileSlots<T> s;
@@ -447,6 +444,9 @@ __device__ __forceinline__ TileSlots<T> load_tile_slots(const int32_t* __restric
     return s;
 }
 
+// Resident units of a tile, compacted into LDS as (block index in tile, pool frame), in
+// block order: every thread looks at up to T/256 table entries, a ballot + popcount
+// gives each resident entry its place.  Returns the list length.  Contains two barriers.
 template <int T>
 __device__ __forceinline__ int build_unit_list(TileSlots<T> slots, uint32_t n_slots, int2* s_list,
                                                int* s_cnt /* [E * 4] */) {
@@ -1403,9 +1403,6 @@ size_t score_workspace_bytes(int64_t n_uids, int32_t n_rows, int32_t g, int32_t 
     return carve(nullptr, n_uids, n_rows, g, ch).bytes;
 }
 
-}  // namespace kvm
-
-namespace kvm {
 namespace {
 int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, float softmax_scale, int agg,
                float* mass, void* ws, size_t ws_bytes, const Xfer& xf, void* stream) {
@@ -1496,7 +1493,7 @@ extern "C" int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* row
                     "kvm_score_step_xfer: host tier must be 16-byte aligned");
         xf = Xfer{(uint32_t)n_pairs, 1u, xfer_frame, xfer_host, static_cast<uint4*>(pool->k_pool),
                   static_cast<uint4*>(pool->v_pool), static_cast<uint4*>(host_tier), pool->unit_k_bytes / 16,
-                  pool->unit_v_bytes / 16};
+                  pool->unit_v_bytes / 16, (uint32_t)(pool->n_slots < 0x7fffffffull ? pool->n_slots : 0x7fffffffull)};
     }
     if (rows && (rows->n_rows == 0 || rows->n_uids == 0) && xf.n) {
         // nothing to score: the bytes still have to move
