@@ -42,11 +42,11 @@ WORKLOADS = {
 # (profiles/score_tile_dot2_llama8b_pmc.md, score_tile_dot2_llama70b_pmc.md, score_tile_wide_mla_pmc.md,
 # score_tile_dot2_mha_pmc.md, score_tile_mfma_mqa_pmc.md).
 SCORE_TILE_TRAFFIC_BYTES = {
-    "llama8b": int(6619938.2 * 2048 + 37635.7 * 1024),       # score_tile_dot2_kernel<4, 128, bf16, 512>
-    "llama70b": int(21149948.2 * 2048 + 394499.9 * 1024),    # score_tile_dot2_kernel<8, 128, bf16, 512>
-    "mla": int(14694104.5 * 2048 + 840307.0 * 1024),         # score_tile_wide_kernel<576, bf16, 512>
-    "mha": int(8385047.0 * 2048 + 38954.5 * 1024),           # score_tile_dot2_kernel<1, 128, bf16, 512>
-    "mqa": int(7097904.8 * 2048 + 77694.4 * 1024),           # score_tile_mfma_kernel<2, 128, bf16, 256>
+    "llama8b": int(6624565.3 * 2048 + 37635.2 * 1024),       # score_tile_dot2_kernel<4, 128, bf16, 512>
+    "llama70b": int(21145350.4 * 2048 + 394499.5 * 1024),    # score_tile_dot2_kernel<8, 128, bf16, 512>
+    "mla": int(14695344.6 * 2048 + 840307.0 * 1024),         # score_tile_wide_kernel<576, bf16, 512>
+    "mha": int(8384514.6 * 2048 + 38952.9 * 1024),           # score_tile_dot2_kernel<1, 128, bf16, 512>
+    "mqa": int(7092831.4 * 2048 + 77716.1 * 1024),           # score_tile_mfma_kernel<2, 128, bf16, 256>
 }
 
 
