@@ -62,6 +62,9 @@ def test_score_tiny_gqa_fp16(oracle):
     (24, 1, 256, synth.BF16),    # g = 24, dim 256: two column tiles
     (40, 1, 64, synth.BF16),     # g = 40: three column tiles (padded to four)
     (128, 1, 128, synth.FP16),   # g = 128, dim 128: eight column tiles
+    (4, 1, 32, synth.BF16),      # the smallest head the library takes: one 16-byte load per lane and unit
+    (16, 4, 192, synth.FP16),    # g = 4, dim 192: beyond the dot-product kernel's 128 channels
+    (3, 1, 192, synth.BF16),     # odd g, dim 192
 ])
 def test_score_shapes_ragged_rows(oracle, hq, hkv, dim, dtype):
     """Rows of 1 .. 200 blocks with ragged tails, gaps in uid space, spare pool frames,
