@@ -785,7 +785,7 @@ __global__ __launch_bounds__(kThreads) void score_tile_mfma_kernel(
     const int n_res = build_unit_list<T>(slot_tbl, c.uid0, c.nbt, n_slots, lds.list, lds.cnt);
     if (n_res == 0) {                            // nothing resident in this tile (uniform)
         // a row of several tiles still folds this tile's statistic: it must read as empty
-        if (c.nb > T && threadIdx.x < G) out.tile_lse[(size_t)tile_id * GP + threadIdx.x] = -INFINITY;
+        if (c.nb > T && (int)threadIdx.x < G) out.tile_lse[(size_t)tile_id * GP + threadIdx.x] = -INFINITY;
         return;
     }
 
