@@ -876,3 +876,40 @@ def test_end_to_end_pipelined_selection_dynamics(oracle):
         np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), case.slot_tbl)
         pending = (ins, frames, hosts)
     assert int(dev.n_bad.item()) == 0
+
+
+def test_transfer_pairs_with_frame_numbers_outside_the_pool_are_skipped(oracle):
+    """kvm_score_step_xfer takes the pair lists as they are: a frame number that is negative or not below
+    n_slots (a caller's mistake; kvm_exchange_begin never writes one) moves nothing, the other pairs trade
+    contents with their tier records, and scoring is unaffected."""
+    from paper_2604_26968_amd import kvm
+    from tests.harness import oracle_score
+    shape = synth.Shape(1, 8, 2, 128, synth.BF16, True, [700, 1200])
+    case = synth.make_case(shape, seed=61, spare_slots=8)
+    dev = DeviceCase(case)
+    rec = shape.unit_k_bytes + shape.unit_v_bytes
+    rng = np.random.default_rng(3)
+    spare = np.setdiff1d(np.arange(case.n_slots), case.slot_tbl[case.slot_tbl >= 0])[:8].astype(np.int32)
+    frames = spare.copy()                     # frames no unit uses: scoring cannot see them
+    frames[1], frames[4], frames[6] = -1, case.n_slots, 2**31 - 1
+    valid = (frames >= 0) & (frames < case.n_slots)
+    tier = rng.integers(0, 256, size=(8, rec), dtype=np.uint8)
+    d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
+    k_before, v_before = dev.pools_host()
+    k_before, v_before = k_before.copy(), v_before.copy()
+    q = synth.make_queries(case, 8)
+    scale = 1.0 / np.sqrt(shape.dim)
+    kvm.kvm_score_step_xfer(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws, dev_of(frames),
+                            dev_of(np.arange(8, dtype=np.int64)), 8, d_tier)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(dev.mass.cpu().numpy(), oracle_score(oracle, case, q, scale), rtol=1e-3, atol=1e-9)
+    k_after, v_after = dev.pools_host()
+    tier_after = d_tier.numpy().reshape(8, rec)
+    want_k, want_v, want_tier = k_before.copy(), v_before.copy(), tier.copy()
+    for i in np.flatnonzero(valid):
+        f = frames[i]
+        want_tier[i] = np.concatenate([k_before[f], v_before[f]])
+        want_k[f], want_v[f] = tier[i, :shape.unit_k_bytes], tier[i, shape.unit_k_bytes:]
+    np.testing.assert_array_equal(k_after, want_k)
+    np.testing.assert_array_equal(v_after, want_v)
+    np.testing.assert_array_equal(tier_after, want_tier)
