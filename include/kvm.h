@@ -182,8 +182,8 @@ int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q
  * below): n_pairs extra workgroups at the front of the scorer's grid each swap
  * one (pool frame, host tier record) pair in place while the rest of the grid
  * scores, so the host link works during the scoring and not after it.
- * xfer_frame[i] outside [0, n_slots) skips pair i (kvm_exchange_begin writes -1
- * for a pair it refused).  The frames named belong to units the scorer
+ * xfer_frame[i] outside [0, n_slots) or xfer_host[i] outside [0, tier_slots)
+ * skips pair i (kvm_exchange_begin writes -1 to both for a pair it refused).  The frames named belong to units the scorer
  * cannot see (kvm_exchange_begin took them out of the table), so scoring and
  * transfer never touch the same memory; results equal kvm_score_step followed
  * by the same transfer.  n_pairs == 0 is kvm_score_step.
@@ -192,7 +192,8 @@ int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* rows, const vo
                         float softmax_scale, int agg, float* mass /* dev [n_uids] */,
                         void* ws, size_t ws_bytes,
                         const int32_t* xfer_frame /* dev [n_pairs] */, const int64_t* xfer_host /* dev [n_pairs] */,
-                        int64_t n_pairs, void* host_tier /* pinned */, void* stream);
+                        int64_t n_pairs, void* host_tier /* pinned, tier_slots records */, uint64_t tier_slots,
+                        void* stream);
 
 /* ======================================================================== *
  * 1. Beta posteriors — section 3.3, Eq. 5.

@@ -346,12 +346,14 @@ struct Xfer {
     uint4* tier;
     uint32_t k_v4, v_v4;
     uint32_t n_slots;       // frames of the pool: a frame number outside it is skipped like -1
+    uint64_t tier_slots;    // records of the tier: likewise
 };
 
 __device__ __forceinline__ void xfer_pair(const Xfer& x, uint32_t i) {
     const int32_t f = x.frame[i];
-    if ((uint32_t)f >= x.n_slots) return;
-    uint4* rec = x.tier + (size_t)x.host[i] * ((size_t)x.k_v4 + x.v_v4);
+    const int64_t h = x.host[i];
+    if ((uint32_t)f >= x.n_slots || (uint64_t)h >= x.tier_slots) return;
+    uint4* rec = x.tier + (size_t)h * ((size_t)x.k_v4 + x.v_v4);
     uint4* kf = x.k_pool + (size_t)f * x.k_v4;
     for (uint32_t v = threadIdx.x; v < x.k_v4; v += kThreads) {
         const uint4 a = kf[v], b = rec[v];
@@ -1476,7 +1478,7 @@ extern "C" int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, co
 extern "C" int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
                                    float softmax_scale, int agg, float* mass, void* ws, size_t ws_bytes,
                                    const int32_t* xfer_frame, const int64_t* xfer_host, int64_t n_pairs,
-                                   void* host_tier, void* stream) {
+                                   void* host_tier, uint64_t tier_slots, void* stream) {
     using namespace kvm;
     clear_error();
     KVM_REQUIRE(pool, KVM_EINVAL, "kvm_score_step_xfer: null pool");
@@ -1493,7 +1495,7 @@ extern "C" int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* row
                     "kvm_score_step_xfer: host tier must be 16-byte aligned");
         xf = Xfer{(uint32_t)n_pairs, 1u, xfer_frame, xfer_host, static_cast<uint4*>(pool->k_pool),
                   static_cast<uint4*>(pool->v_pool), static_cast<uint4*>(host_tier), pool->unit_k_bytes / 16,
-                  pool->unit_v_bytes / 16, (uint32_t)(pool->n_slots < 0x7fffffffull ? pool->n_slots : 0x7fffffffull)};
+                  pool->unit_v_bytes / 16, (uint32_t)(pool->n_slots < 0x7fffffffull ? pool->n_slots : 0x7fffffffull), tier_slots};
     }
     if (rows && (rows->n_rows == 0 || rows->n_uids == 0) && xf.n) {
         // nothing to score: the bytes still have to move

@@ -117,7 +117,7 @@ def _load() -> C.CDLL:
     lib.kvm_dedup_release.argtypes = [C.POINTER(Store), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.kvm_score_step_xfer.argtypes = [C.POINTER(Pool), C.POINTER(Rows), C.c_void_p, C.c_float, C.c_int, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
-                                        C.c_void_p]
+                                        C.c_uint64, C.c_void_p]
     lib.kvm_exchange_begin.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p]
@@ -338,10 +338,13 @@ def kvm_dedup_release(store: Store, digests, n: int, n_bad=None, stream=None):
 
 def kvm_score_step_xfer(pool: Pool, rows: Rows, q, softmax_scale: float, mass, ws, xfer_frame, xfer_host, n_pairs: int,
                         host_tier, agg: int = AGG_MAX, stream=None):
+    """host_tier: pinned uint8 tensor of whole records; its record count is passed on as tier_slots."""
+    rec = pool.unit_k_bytes + pool.unit_v_bytes
+    tier_slots = 0 if host_tier is None else host_tier.numel() * host_tier.element_size() // rec
     _check(lib.kvm_score_step_xfer(C.byref(pool), C.byref(rows), _ptr(q), softmax_scale, agg,
                                    _ptr(mass, torch.float32), _ptr(ws), ws.numel() * ws.element_size(),
                                    _ptr(xfer_frame, torch.int32), _ptr(xfer_host, torch.int64), n_pairs,
-                                   _ptr(host_tier, None, "cpu"), _stream(stream)))
+                                   _ptr(host_tier, None, "cpu"), tier_slots, _stream(stream)))
 
 
 def kvm_exchange_begin(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, tier_slots: int, frame, host,

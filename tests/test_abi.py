@@ -139,11 +139,11 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_probe_read(16, 24, 16, None) == kvm.EINVAL          # size not a multiple of 16
     assert lib.kvm_probe_read(16, 0, 16, None) == kvm.OK
     assert lib.kvm_score_step_xfer(C.byref(pool), C.byref(empty), None, 1.0, 0, None, None, 0, None, None, -1, None,
-                                   None) == kvm.EINVAL
+                                   0, None) == kvm.EINVAL
     assert lib.kvm_score_step_xfer(C.byref(pool), C.byref(empty), None, 1.0, 0, None, None, 0, None, None, 5, None,
-                                   None) == kvm.EINVAL                   # pairs without buffers
+                                   0, None) == kvm.EINVAL                   # pairs without buffers
     assert lib.kvm_score_step_xfer(C.byref(pool), C.byref(empty), None, 1.0, 0, None, None, 0, None, None, 0, None,
-                                   None) == kvm.OK
+                                   0, None) == kvm.OK
     assert lib.kvm_exchange(None, None, None, 0, None, None, 0, None, None, None, 0, None, None) == kvm.EINVAL
     assert lib.kvm_exchange(C.byref(pool), None, None, 8, None, None, 4, None, None, None, 4, None, None) == kvm.EINVAL
     assert lib.kvm_exchange_begin(C.byref(pool), None, None, 8, None, None, 4, None, None, 4, None, None, None,

@@ -880,7 +880,7 @@ def test_end_to_end_pipelined_selection_dynamics(oracle):
 
 def test_transfer_pairs_with_frame_numbers_outside_the_pool_are_skipped(oracle):
     """kvm_score_step_xfer takes the pair lists as they are: a frame number that is negative or not below
-    n_slots (a caller's mistake; kvm_exchange_begin never writes one) moves nothing, the other pairs trade
+    n_slots, or a tier slot outside the tier (a caller's mistake; kvm_exchange_begin never writes one), moves nothing, the other pairs trade
     contents with their tier records, and scoring is unaffected."""
     from paper_2604_26968_amd import kvm
     from tests.harness import oracle_score
@@ -892,7 +892,9 @@ def test_transfer_pairs_with_frame_numbers_outside_the_pool_are_skipped(oracle):
     spare = np.setdiff1d(np.arange(case.n_slots), case.slot_tbl[case.slot_tbl >= 0])[:8].astype(np.int32)
     frames = spare.copy()                     # frames no unit uses: scoring cannot see them
     frames[1], frames[4], frames[6] = -1, case.n_slots, 2**31 - 1
-    valid = (frames >= 0) & (frames < case.n_slots)
+    hosts = np.arange(8, dtype=np.int64)
+    hosts[0], hosts[3] = 8, -2                # tier records that do not exist
+    valid = (frames >= 0) & (frames < case.n_slots) & (hosts >= 0) & (hosts < 8)
     tier = rng.integers(0, 256, size=(8, rec), dtype=np.uint8)
     d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
     k_before, v_before = dev.pools_host()
@@ -900,7 +902,7 @@ def test_transfer_pairs_with_frame_numbers_outside_the_pool_are_skipped(oracle):
     q = synth.make_queries(case, 8)
     scale = 1.0 / np.sqrt(shape.dim)
     kvm.kvm_score_step_xfer(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws, dev_of(frames),
-                            dev_of(np.arange(8, dtype=np.int64)), 8, d_tier)
+                            dev_of(hosts), 8, d_tier)
     torch.cuda.synchronize()
     np.testing.assert_allclose(dev.mass.cpu().numpy(), oracle_score(oracle, case, q, scale), rtol=1e-3, atol=1e-9)
     k_after, v_after = dev.pools_host()
