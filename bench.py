@@ -42,11 +42,11 @@ WORKLOADS = {
 # (profiles/score_tile_dot2_llama8b_pmc.md, score_tile_dot2_llama70b_pmc.md, score_tile_wide_mla_pmc.md,
 # score_tile_dot2_mha_pmc.md, score_tile_mfma_mqa_pmc.md).
 SCORE_TILE_TRAFFIC_BYTES = {
-    "llama8b": int(6624565.3 * 2048 + 37635.2 * 1024),       # score_tile_dot2_kernel<4, 128, bf16, 512>
-    "llama70b": int(21145350.4 * 2048 + 394499.5 * 1024),    # score_tile_dot2_kernel<8, 128, bf16, 512>
-    "mla": int(14695344.6 * 2048 + 840307.0 * 1024),         # score_tile_wide_kernel<576, bf16, 512>
-    "mha": int(8384514.6 * 2048 + 38952.9 * 1024),           # score_tile_dot2_kernel<1, 128, bf16, 512>
-    "mqa": int(7092831.4 * 2048 + 77716.1 * 1024),           # score_tile_mfma_kernel<2, 128, bf16, 256>
+    "llama8b": int(6624641.7 * 2048 + 37636.7 * 1024),       # score_tile_dot2_kernel<4, 128, bf16, 512>
+    "llama70b": int(21135248.4 * 2048 + 394499.4 * 1024),    # score_tile_dot2_kernel<8, 128, bf16, 512>
+    "mla": int(14707914.7 * 2048 + 840307.0 * 1024),         # score_tile_wide_kernel<576, bf16, 512>
+    "mha": int(8385917.2 * 2048 + 38958.0 * 1024),           # score_tile_dot2_kernel<1, 128, bf16, 512>
+    "mqa": int(7100460.9 * 2048 + 77685.8 * 1024),           # score_tile_mfma_kernel<2, 128, bf16, 256>
 }
 
 
