@@ -306,6 +306,29 @@ int kvm_select_victims(const float* prio /* dev [n_uids] */, const uint8_t* stat
                        int64_t* victims /* dev [victims_cap] */, int64_t victims_cap,
                        int64_t* n_victims /* dev [1] */, void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate or hand over device memory at the time of the
+ * call (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): kvm_select_victims with the workspace replaced by a scratch array
+ * built into the library's device code, KVM_SELECT_STATIC_SCRATCH_BYTES per GPU,
+ * held from the time the library is loaded on a GPU until the process ends.
+ * Same arguments otherwise, same result bit for bit.  The call allocates nothing
+ * (no hipMalloc / hipFree, no event creation: it is never timed by kvm_timing_*)
+ * and records only kernel launches on `stream`, no memset.  The device of
+ * `stream` and of the buffers must be the current device; the scratch address is
+ * looked up once per device, on the first call made with that device current.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU
+ * (two streams, two threads) race and give undefined victims; calls in sequence
+ * on one stream, or ordered by events, are fine, and nothing has to be cleared
+ * in between (the kernels initialise what they read).
+ * Errors: as kvm_select_victims; KVM_ENOSPC when n_uids exceeds
+ * KVM_SELECT_STATIC_MAX_UIDS (nothing is launched).                          */
+#define KVM_SELECT_STATIC_MAX_UIDS      (1 << 26)
+#define KVM_SELECT_STATIC_SCRATCH_BYTES (20480 + 256 + 2 * (KVM_SELECT_STATIC_MAX_UIDS / 4096) * 4)
+int kvm_select_victims_static(const float* prio /* dev [n_uids] */, const uint8_t* state /* dev [n_uids] */,
+                              int64_t n_uids, int64_t k_or_neg1, int64_t budget_units,
+                              int64_t* victims /* dev [victims_cap] */, int64_t victims_cap,
+                              int64_t* n_victims /* dev [1] */, void* stream);
+
 /* ======================================================================== *
  * 5. Pack / unpack — tier 0 (HBM pool) <-> tier 1 (pinned host), section 3.2.
  *

@@ -31,7 +31,8 @@ void clear_error();
 
 // ---- kernel timing ---------------------------------------------------------
 // Scope object: records a start event now and a stop event when it goes out of
-// scope, both on `stream`, if timing is enabled.  Does nothing otherwise.
+// scope, both on `stream`, if timing is enabled.  Does nothing otherwise, and
+// nothing at all when `name` is null.
 class TimedLaunch {
   public:
     TimedLaunch(const char* name, hipStream_t stream);

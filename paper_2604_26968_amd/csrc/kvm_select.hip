@@ -9,7 +9,15 @@
 // LDS histograms merged by atomics, then an order-preserving compaction
 // (per-chunk counts, one scan over chunks, per-chunk emit).  Each pass streams
 // prio (4 B) and state (1 B) once.
+#include <mutex>
+
 #include "kvm_internal.h"
+
+// Scratch of kvm_select_victims_static: histograms, control block and per-chunk counts for up to
+// KVM_SELECT_STATIC_MAX_UIDS units (2^26 / 4096 chunks).  Every GPU the library runs on holds its
+// own copy at its own address; host code reaches it only through the pointer that
+// hipGetSymbolAddress returns for the current device, never through this name.
+static __device__ __align__(256) unsigned char scratch[KVM_SELECT_STATIC_SCRATCH_BYTES];
 
 namespace kvm {
 namespace {
@@ -355,23 +363,14 @@ extern "C" size_t kvm_workspace_bytes(int op, int64_t n_uids, int32_t n_rows, in
     return 0;
 }
 
-extern "C" int kvm_select_victims(const float* prio, const uint8_t* state, int64_t n_uids, int64_t k_or_neg1,
-                                  int64_t budget_units, int64_t* victims, int64_t victims_cap, int64_t* n_victims,
-                                  void* ws, size_t ws_bytes, void* stream) {
-    using namespace kvm;
-    clear_error();
-    KVM_REQUIRE(n_uids >= 0 && k_or_neg1 >= -1 && budget_units >= 0 && victims_cap >= 0, KVM_EINVAL,
-                "kvm_select_victims: negative argument");
-    KVM_REQUIRE(n_uids < (1ll << 32), KVM_ESHAPE, "kvm_select_victims: n_uids %lld needs 64-bit ranks",
-                (long long)n_uids);
-    KVM_REQUIRE(n_victims && ws, KVM_EINVAL, "kvm_select_victims: null output or workspace");
-    KVM_REQUIRE(victims || victims_cap == 0, KVM_EINVAL, "kvm_select_victims: null victims");
-    KVM_REQUIRE(n_uids == 0 || (prio && state), KVM_EINVAL, "kvm_select_victims: null input");
-    KVM_REQUIRE(reinterpret_cast<uintptr_t>(ws) % 256 == 0, KVM_EINVAL, "kvm_select_victims: ws not 256-byte aligned");
-    const SelectWs w = carve(ws, n_uids);
-    KVM_REQUIRE(ws_bytes >= w.bytes, KVM_ENOSPC, "kvm_select_victims: workspace %zu < %zu bytes", ws_bytes, w.bytes);
+namespace kvm {
+namespace {
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
+// The launches of one selection over a carved workspace.  `timed` brackets the two phases with the
+// library's timing events (which may create events on first use).
+int launch_select(const float* prio, const uint8_t* state, int64_t n_uids, int64_t k_or_neg1, int64_t budget_units,
+                  int64_t* victims, int64_t victims_cap, int64_t* n_victims, const SelectWs& w, hipStream_t st,
+                  bool timed) {
     const int n_chunks = (int)((n_uids + kChunk - 1) / kChunk);
     int64_t hist_grid = (n_uids + (int64_t)kThreads * 16 - 1) / ((int64_t)kThreads * 16);
     if (hist_grid > 2048) hist_grid = 2048;
@@ -380,7 +379,7 @@ extern "C" int kvm_select_victims(const float* prio, const uint8_t* state, int64
     uint32_t* h1 = w.hist + kBins0;
     uint32_t* h2 = w.hist + kBins0 + kBins1;
     {
-        TimedLaunch tl("select_hist", st);
+        TimedLaunch tl(timed ? "select_hist" : nullptr, st);
         select_init_kernel<<<8, 256, 0, st>>>(w.hist, kBins0 + kBins1 + kBins2, w.ctrl);
         select_hist_kernel<0><<<(unsigned)hist_grid, kThreads, 0, st>>>(prio, state, n_uids, h0, w.ctrl);
         select_scan_kernel<0><<<1, 1024, 0, st>>>(h0, w.ctrl, k_or_neg1, budget_units, victims_cap, n_victims);
@@ -391,7 +390,7 @@ extern "C" int kvm_select_victims(const float* prio, const uint8_t* state, int64
         if (int rc = launch_status("select_hist")) return rc;
     }
     if (n_chunks > 0) {
-        TimedLaunch tl("select_emit", st);
+        TimedLaunch tl(timed ? "select_emit" : nullptr, st);
         select_count_kernel<<<n_chunks, kThreads, 0, st>>>(prio, state, n_uids, w.ctrl, w.chunk_less, w.chunk_eq);
         select_chunk_scan_kernel<<<1, 1024, 0, st>>>(n_chunks, w.chunk_less, w.chunk_eq);
         select_emit_kernel<<<n_chunks, kThreads, 0, st>>>(prio, state, n_uids, w.ctrl, w.chunk_less, w.chunk_eq,
@@ -399,4 +398,82 @@ extern "C" int kvm_select_victims(const float* prio, const uint8_t* state, int64
         if (int rc = launch_status("select_emit")) return rc;
     }
     return KVM_OK;
+}
+
+int check_select_args(const char* who, const float* prio, const uint8_t* state, int64_t n_uids, int64_t k_or_neg1,
+                      int64_t budget_units, const int64_t* victims, int64_t victims_cap, const int64_t* n_victims) {
+    KVM_REQUIRE(n_uids >= 0 && k_or_neg1 >= -1 && budget_units >= 0 && victims_cap >= 0, KVM_EINVAL,
+                "%s: negative argument", who);
+    KVM_REQUIRE(n_uids < (1ll << 32), KVM_ESHAPE, "%s: n_uids %lld needs 64-bit ranks", who, (long long)n_uids);
+    KVM_REQUIRE(n_victims, KVM_EINVAL, "%s: null n_victims", who);
+    KVM_REQUIRE(victims || victims_cap == 0, KVM_EINVAL, "%s: null victims", who);
+    KVM_REQUIRE(n_uids == 0 || (prio && state), KVM_EINVAL, "%s: null input", who);
+    return KVM_OK;
+}
+
+}  // namespace
+}  // namespace kvm
+
+extern "C" int kvm_select_victims(const float* prio, const uint8_t* state, int64_t n_uids, int64_t k_or_neg1,
+                                  int64_t budget_units, int64_t* victims, int64_t victims_cap, int64_t* n_victims,
+                                  void* ws, size_t ws_bytes, void* stream) {
+    using namespace kvm;
+    clear_error();
+    if (int rc = check_select_args("kvm_select_victims", prio, state, n_uids, k_or_neg1, budget_units, victims,
+                                   victims_cap, n_victims))
+        return rc;
+    KVM_REQUIRE(ws, KVM_EINVAL, "kvm_select_victims: null workspace");
+    KVM_REQUIRE(reinterpret_cast<uintptr_t>(ws) % 256 == 0, KVM_EINVAL, "kvm_select_victims: ws not 256-byte aligned");
+    const SelectWs w = carve(ws, n_uids);
+    KVM_REQUIRE(ws_bytes >= w.bytes, KVM_ENOSPC, "kvm_select_victims: workspace %zu < %zu bytes", ws_bytes, w.bytes);
+    return launch_select(prio, state, n_uids, k_or_neg1, budget_units, victims, victims_cap, n_victims, w,
+                         static_cast<hipStream_t>(stream), true);
+}
+
+namespace kvm {
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};      // per device: address of its copy of `scratch`
+
+// Address of the current device's scratch array, resolved once per device.
+int static_scratch(void** out) {
+    int dev = -1;
+    KVM_HIP_TRY(hipGetDevice(&dev));
+    KVM_REQUIRE(dev >= 0 && dev < kMaxDevices, KVM_EHIP, "kvm_select_victims_static: device %d out of range", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        KVM_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        KVM_REQUIRE(p && reinterpret_cast<uintptr_t>(p) % 256 == 0, KVM_EHIP,
+                    "kvm_select_victims_static: bad scratch address %p on device %d", p, dev);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return KVM_OK;
+}
+}  // namespace
+}  // namespace kvm
+
+extern "C" int kvm_select_victims_static(const float* prio, const uint8_t* state, int64_t n_uids, int64_t k_or_neg1,
+                                         int64_t budget_units, int64_t* victims, int64_t victims_cap,
+                                         int64_t* n_victims, void* stream) {
+    using namespace kvm;
+    clear_error();
+    if (int rc = check_select_args("kvm_select_victims_static", prio, state, n_uids, k_or_neg1, budget_units, victims,
+                                   victims_cap, n_victims))
+        return rc;
+    KVM_REQUIRE(n_uids <= (int64_t)KVM_SELECT_STATIC_MAX_UIDS, KVM_ENOSPC,
+                "kvm_select_victims_static: n_uids %lld exceeds the built-in scratch's limit of %lld units; "
+                "use kvm_select_victims with a workspace",
+                (long long)n_uids, (long long)KVM_SELECT_STATIC_MAX_UIDS);
+    void* ptr = nullptr;
+    if (int rc = static_scratch(&ptr)) return rc;
+    const SelectWs w = carve(ptr, n_uids);
+    KVM_REQUIRE(w.bytes <= (size_t)KVM_SELECT_STATIC_SCRATCH_BYTES, KVM_ENOSPC,
+                "kvm_select_victims_static: scratch %zu < %zu bytes", (size_t)KVM_SELECT_STATIC_SCRATCH_BYTES, w.bytes);
+    // Histograms and the control block are cleared by select_init_kernel, the per-chunk counts are
+    // written before they are read: nothing of the previous call's contents is used.
+    return launch_select(prio, state, n_uids, k_or_neg1, budget_units, victims, victims_cap, n_victims, w,
+                         static_cast<hipStream_t>(stream), false);
 }

@@ -45,6 +45,7 @@ hipEvent_t take_event() {
 }  // namespace
 
 TimedLaunch::TimedLaunch(const char* name, hipStream_t stream) : slot_(-1), stream_(stream) {
+    if (!name) return;                  // a launch that must not touch the event pool
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_on) return;
     if (!g_only.empty() && g_only != name) return;

@@ -22,9 +22,10 @@ ARCH_MHA, ARCH_GQA, ARCH_MQA, ARCH_MLA = 0, 1, 2, 3
 ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
 AGG_MAX, AGG_MEAN = 0, 1
 OP_SCORE, OP_SELECT, OP_SPAN = 0, 1, 2
+SELECT_STATIC_MAX_UIDS = 1 << 26
 
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
-           "kvm_ema_update_ex", "kvm_select_victims", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
+           "kvm_ema_update_ex", "kvm_select_victims", "kvm_select_victims_static", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
            "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version", "kvm_probe_read",
            "kvm_timing_enable", "kvm_timing_only", "kvm_timing_reset", "kvm_timing_read"]
 
@@ -89,6 +90,8 @@ def _load() -> C.CDLL:
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_select_victims.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
                                        C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.kvm_select_victims_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                              C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.kvm_pack.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
                              C.c_void_p, C.c_void_p]
@@ -262,6 +265,12 @@ def kvm_select_victims(prio, state, victims, n_victims, ws, k: int = -1, budget_
                                   budget_units, _ptr(victims, torch.int64), victims.numel(),
                                   _ptr(n_victims, torch.int64), _ptr(ws), ws.numel() * ws.element_size(),
                                   _stream(stream)))
+
+
+def kvm_select_victims_static(prio, state, victims, n_victims, k: int = -1, budget_units: int = 0, stream=None):
+    _check(lib.kvm_select_victims_static(_ptr(prio, torch.float32), _ptr(state, torch.uint8), state.numel(), k,
+                                         budget_units, _ptr(victims, torch.int64), victims.numel(),
+                                         _ptr(n_victims, torch.int64), _stream(stream)))
 
 
 def _nbytes(t: Optional[torch.Tensor]) -> int:
