@@ -95,13 +95,23 @@ def main():
     shape = wshape(synth, n_seq)
     pair_w = synth.categorical_weights(3)
     reuse_p = np.linspace(0.15, 0.95, 16)
-    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=pair_w)
+    # the pool is dimensioned by the sizing call: units per token block x blocks of the batch, at the unit
+    # bytes it reports
+    blocks = sum((int(t) + 15) // 16 for t in shape.seq_lens)
+    sizing = kvm.kvm_size(**shape.model_args(), n_max=max(shape.seq_lens))
+    sizing = kvm.kvm_size(**shape.model_args(), n_max=max(shape.seq_lens),
+                          mem_target=blocks * sizing["units_per_block"] * (sizing["unit_k_bytes"] + sizing["unit_v_bytes"]))
+    assert (sizing["unit_k_bytes"], sizing["unit_v_bytes"], sizing["group_size"]) == \
+        (shape.unit_k_bytes, shape.unit_v_bytes, shape.g)
+    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=pair_w, pool_units=sizing["pool_units"])
     n, n_rows, g, dim = wl.n_uids, wl.n_rows, shape.g, shape.dim
+    assert n == sizing["pool_units"]
     rec = shape.unit_k_bytes + shape.unit_v_bytes
     pool = kvm.make_pool(wl.k_pool.view(torch.int16), None if wl.v_pool is None else wl.v_pool.view(torch.int16), dim,
                          shape.dtype)
     rows = kvm.make_rows(wl.row_ntok, wl.row_off, wl.row_q_off, wl.slot_tbl, g, wl.q_elems)
     scale = 1.0 / float(np.sqrt(dim))
+    row_weight = torch.full((n_rows,), float(sizing["head_weight"]), dtype=torch.float32, device=dev)
 
     mass = torch.zeros(n, dtype=torch.float32, device=dev)
     S = torch.zeros(n, dtype=torch.float32, device=dev)
@@ -172,7 +182,7 @@ def main():
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
         kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
-        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_ema_update(rows, mass, decay, row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_select_victims(prio, wl.state, victims, n_victims, ws, k=k_arg, budget_units=budget_arg)
 
     # ---- step 0: everything resident; evict down to the budget in one go ------------------------
@@ -239,7 +249,7 @@ def main():
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
         kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
-        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_ema_update(rows, mass, decay, row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_exchange_end(wl.slot_tbl, wl.state, xf_in[0], xf_frame, swap)
         kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         nxt = (i + 1) * swap
@@ -261,7 +271,7 @@ def main():
                                stream=side)
         kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
         main.wait_stream(side)
-        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_ema_update(rows, mass, decay, row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_exchange_end(wl.slot_tbl, wl.state, xf_in[0], xf_frame, swap)
         nxt = (i + 1) * swap
         xf_in[0] = host_uids[nxt:nxt + swap]
@@ -295,7 +305,7 @@ def main():
         kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
         main.wait_stream(side)
         kvm.kvm_dedup_insert(store, digests, arrived, swap, canon, dedup_ws)
-        kvm.kvm_ema_update_ex(rows, mass, decay, ex, wl.row_weight, wl.pair, p_blend, wl.state, S, prio)
+        kvm.kvm_ema_update_ex(rows, mass, decay, ex, row_weight, wl.pair, p_blend, wl.state, S, prio)
         kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window,
                             ws_span)
         kvm.kvm_exchange_end(wl.slot_tbl, wl.state, pf_list, xf_frame, swap)
@@ -315,7 +325,7 @@ def main():
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
         kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
-        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_ema_update(rows, mass, decay, row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         lo = i * swap
         # the segment's old records were prefetched by the previous step, so it is free to take the victims
@@ -343,7 +353,7 @@ def main():
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
         kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
-        kvm.kvm_ema_update(rows, mass, decay, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+        kvm.kvm_ema_update(rows, mass, decay, row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         lo = i * swap
         main.wait_event(ev_d2h[b])                                   # out_dev[b] has left for the host
@@ -562,7 +572,8 @@ def main():
         prio_ref = np.zeros(case.n_uids, np.float32)
         st_ref = case.state.copy()
         ph = p_hat.cpu().numpy()
-        oracle.ema_update(case.row_ntok, case.row_off, ref_mass, decay, case.row_weight, case.pair, ph, st_ref, S_ref,
+        ref_weight = np.full(case.n_rows, float(oracle.size(**shape.model_args())["head_weight"]), np.float32)
+        oracle.ema_update(case.row_ntok, case.row_off, ref_mass, decay, ref_weight, case.pair, ph, st_ref, S_ref,
                           prio_ref)
         oracle.select_victims(prio_ref, st_ref, k=-1, budget_units=int(w_budget * case.n_uids))
         t_cpu = time.perf_counter() - t0

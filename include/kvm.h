@@ -113,6 +113,10 @@ typedef struct kvm_sizing {
     uint32_t units_per_block;        /* units one token block spans: L * h_kv / head_divisor (MLA: L) */
     uint32_t unit_k_bytes;           /* block_tokens * d * p (MLA: latent + rope) */
     uint32_t unit_v_bytes;           /* same for V; 0 for MLA                     */
+    uint32_t head_weight;            /* weight of one KV head's importance in the eviction
+                                        priority (section 3.4): uniform (1) for MHA,
+                                        the group size for GQA and MQA, 1 for the single
+                                        latent head of MLA; the row_weight of kvm_ema_update */
     uint64_t pool_units;             /* floor(M_target / (unit_k + unit_v))       */
 } kvm_sizing_t;
 

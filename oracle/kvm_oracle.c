@@ -12,7 +12,7 @@
  *
  * What each function follows:
  *   kvm_ref_size            section 3.1, Eq. 3 (per-layer bytes) and Eq. 4 / the
- *                           max-batch formula that follows it
+ *                           max-batch formula that follows it; head weights of section 3.4
  *   kvm_ref_score_step      Eq. 1 (softmax(q k^T / sqrt(d))) summed per token block;
  *                           group maximum of section 3.4
  *   kvm_ref_ema_update      section 3.4 (EMA importance, head weights) times the
@@ -103,6 +103,7 @@ typedef struct {
     int32_t  arch, group_size;
     uint64_t bytes_per_token_layer, bytes_per_token, bytes_per_seq, max_batch;
     uint32_t units_per_block, unit_k_bytes, unit_v_bytes;
+    uint32_t head_weight;
     uint64_t pool_units;
 } ref_sizing_t;
 
@@ -147,6 +148,14 @@ int kvm_ref_size(const ref_model_t* m, uint64_t n_max, uint64_t mem_target, ref_
     o->unit_k_bytes = (uint32_t)(unit_k_bits / 8);
     o->unit_v_bytes = (uint32_t)(unit_v_bits / 8);
     o->pool_units = mem_target / ((uint64_t)o->unit_k_bytes + o->unit_v_bytes);
+    /* Head weights, section 3.4: uniform for MHA, proportional to the group size for grouped
+     * heads (GQA, and MQA as the group of all query heads); the MLA matrix has a single head. */
+    switch (o->arch) {
+        case 0: o->head_weight = 1; break;
+        case 1: o->head_weight = (uint32_t)(m->n_q_heads / m->n_kv_heads); break;
+        case 2: o->head_weight = (uint32_t)m->n_q_heads; break;
+        default: o->head_weight = 1; break;
+    }
     return REF_OK;
 }
 

@@ -211,6 +211,9 @@ int kvm_size(const kvm_model_t* m, uint64_t n_max, uint64_t mem_target_bytes, kv
     s.unit_k_bytes = (uint32_t)(unit_k_bits / 8);
     s.unit_v_bytes = (uint32_t)(unit_v_bits / 8);
     s.pool_units = mem_target_bytes / ((uint64_t)s.unit_k_bytes + s.unit_v_bytes);
+    // Head weights of the eviction priority (section 3.4): every head counts the same under MHA; a
+    // grouped KV head stands for all the query heads that share it; MLA has one latent head per layer.
+    s.head_weight = (s.arch == KVM_ARCH_GQA || s.arch == KVM_ARCH_MQA) ? (uint32_t)s.group_size : 1u;
     *out = s;
     return KVM_OK;
 }

@@ -47,7 +47,7 @@ class Sizing(C.Structure):
                 ("bytes_per_token_layer", C.c_uint64), ("bytes_per_token", C.c_uint64),
                 ("bytes_per_seq", C.c_uint64), ("max_batch", C.c_uint64),
                 ("units_per_block", C.c_uint32), ("unit_k_bytes", C.c_uint32),
-                ("unit_v_bytes", C.c_uint32), ("pool_units", C.c_uint64)]
+                ("unit_v_bytes", C.c_uint32), ("head_weight", C.c_uint32), ("pool_units", C.c_uint64)]
 
 
 class Pool(C.Structure):

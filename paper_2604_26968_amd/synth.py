@@ -78,6 +78,16 @@ class Shape:
     def unit_k_bytes(self) -> int:
         return BLOCK * self.dim * 2
 
+    def model_args(self) -> dict:
+        """The shape as the keyword arguments the sizing calls take (a latent row of 576 channels is
+        512 latent + 64 rope channels; any other latent width is passed as latent only)."""
+        if self.has_v:
+            return dict(n_layers=self.n_layers, n_q_heads=self.n_q_heads, n_kv_heads=self.n_kv_heads,
+                        head_dim=self.dim)
+        rope = 64 if self.dim == 576 else 0
+        return dict(n_layers=self.n_layers, n_q_heads=self.n_q_heads, n_kv_heads=self.n_q_heads,
+                    head_dim=self.dim, d_latent=self.dim - rope, d_rope=rope)
+
     @property
     def unit_v_bytes(self) -> int:
         return BLOCK * self.dim * 2 if self.has_v else 0
@@ -96,7 +106,6 @@ class Case:
     slot_tbl: np.ndarray      # int32 [n_uids]
     state: np.ndarray         # uint8 [n_uids]
     pair: np.ndarray          # uint8 [n_uids]
-    row_weight: np.ndarray    # float32 [n_rows]
     n_uids: int
 
     @property
@@ -163,11 +172,8 @@ def make_case(shape: Shape, seed: int, spare_slots: int = 0, uid_gap: int = 0,
             unit[:, tail:, :] = 0x7FC1 if shape.dtype == BF16 else 0x7E01
     g = shape.g
     row_q_off = (np.arange(len(nb), dtype=np.int64) * g * dim)
-    # head weight: group size for GQA/MQA, 1 for MHA; a single latent head (MLA) also gets 1
-    w = float(g) if (shape.has_v and g > 1) else 1.0
-    row_weight = np.full(len(nb), w, np.float32)
     return Case(shape, n_slots, k_pool, v_pool, row_ntok, row_off, row_q_off, row_seq, slot_tbl,
-                state, pair, row_weight, n_uids)
+                state, pair, n_uids)
 
 
 def row_head_index(case: Case) -> np.ndarray:
@@ -250,7 +256,7 @@ class DeviceWorkload:
     """
 
     def __init__(self, shape: Shape, seed: int, pair_weights: Optional[np.ndarray] = None,
-                 spare_slots: int = 0, device: str = "cuda"):
+                 spare_slots: int = 0, device: str = "cuda", pool_units: Optional[int] = None):
         import torch
         self.torch = torch
         self.shape = shape
@@ -266,6 +272,9 @@ class DeviceWorkload:
         self.n_rows = len(nb)
         self.n_uids = int(nb.sum())
         self.n_slots = self.n_uids + spare_slots
+        if pool_units is not None:          # frame count decided by the caller (from the sizing call)
+            assert pool_units >= self.n_uids, (pool_units, self.n_uids)
+            self.n_slots = int(pool_units)
         self.nb = nb
         g = shape.g
         if pair_weights is None:
@@ -304,8 +313,6 @@ class DeviceWorkload:
         self.row_q_off = (torch.arange(self.n_rows, dtype=torch.int64, device=device) * (g * dim))
         self.state = torch.from_numpy(state).to(device)
         self.pair = torch.from_numpy(pair).to(device)
-        w = float(g) if (shape.has_v and g > 1) else 1.0
-        self.row_weight = torch.full((self.n_rows,), w, dtype=torch.float32, device=device)
         self.q_elems = self.n_rows * g * dim
 
     def queries(self, seed: int):
@@ -343,7 +350,7 @@ class DeviceWorkload:
                              self.shape.dtype, self.shape.has_v, [self.shape.seq_lens[s] for s in seq_ids])
         case = Case(sample_shape, k_host.shape[0], k_host, None, self.host["row_ntok"][rows].copy(), new_off,
                     np.arange(len(rows), dtype=np.int64) * g * dim, self.row_seq[rows].copy(), new_tbl, state,
-                    pair, self.row_weight[torch.from_numpy(rows).to(self.k_pool.device)].cpu().numpy(), n_u)
+                    pair, n_u)
         case.sample_rows = rows
         case.sample_uids = old_uids
         return case

@@ -13,6 +13,33 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def gpu_row_weight(kvm, shape: synth.Shape, n_rows: int) -> np.ndarray:
+    """Per-row head weight as the library's sizing call gives it for the shape's architecture."""
+    return np.full(n_rows, float(kvm.kvm_size(**shape.model_args())["head_weight"]), np.float32)
+
+
+def ref_row_weight(o, case: synth.Case) -> np.ndarray:
+    """The same from the oracle's sizing function (its own statement of the head-weight rule)."""
+    return np.full(case.n_rows, float(o.size(**case.shape.model_args())["head_weight"]), np.float32)
+
+
+def sized_pool_units(kvm, o, shape: synth.Shape, spare_units: int = 0) -> int:
+    """Frames of a pool that holds every unit of the shape's sequences (plus `spare_units`), obtained the
+    way a caller of the library would: units per token block, unit bytes and the frame count for a byte
+    budget all come from kvm_size, and every field is checked against the oracle's sizing function."""
+    blocks = sum((int(n) + synth.BLOCK - 1) // synth.BLOCK for n in shape.seq_lens)
+    args = dict(shape.model_args(), n_max=max(shape.seq_lens, default=0))
+    probe = kvm.kvm_size(**args)
+    assert probe == o.size(**args)
+    want = blocks * probe["units_per_block"] + spare_units
+    target = want * (probe["unit_k_bytes"] + probe["unit_v_bytes"]) + 17      # a budget that is no multiple of a unit
+    s = kvm.kvm_size(**args, mem_target=target)
+    assert s == o.size(**args, mem_target=target)
+    assert (s["unit_k_bytes"], s["unit_v_bytes"], s["group_size"]) == (shape.unit_k_bytes, shape.unit_v_bytes, shape.g)
+    assert s["units_per_block"] == shape.n_layers * shape.n_kv_heads and s["pool_units"] == want
+    return int(s["pool_units"])
+
+
 class DeviceCase:
     """Device copies of a synth.Case plus the per-unit state the pass keeps."""
 
@@ -30,7 +57,7 @@ class DeviceCase:
         self.slot_tbl = _dev(case.slot_tbl)
         self.state = _dev(case.state)
         self.pair = _dev(case.pair)
-        self.row_weight = _dev(case.row_weight)
+        self.row_weight = _dev(gpu_row_weight(kvm, sh, case.n_rows))
         n = case.n_uids
         self.mass = torch.zeros(n, dtype=torch.float32, device="cuda")
         self.S = torch.zeros(n, dtype=torch.float32, device="cuda")
@@ -136,14 +163,17 @@ def oracle_score(o, case: synth.Case, q_bits, scale, agg=0, row_active=None, fil
     return mass
 
 
-def run_step_gpu(dev: DeviceCase, q_bits, events, scale, decay, k):
-    """beta -> score -> ema -> select k -> pack -> unpack back into the freed frames."""
+def run_step_gpu(dev: DeviceCase, q_bits, events, scale, decay, k, pack_uids=None):
+    """beta -> score -> ema -> select k -> pack -> unpack back into the freed frames.  With `pack_uids`
+    that list is moved instead of the selection's own (the oracle's victims, so that the bytes can be
+    compared record by record even when a near-tie at the cutoff makes the two selections differ)."""
     hits, misses, p_hat = dev.beta(*events)
     mass = dev.score(q_bits, scale)
     S, prio, state = dev.ema(decay)
     victims = dev.select(k=k)
-    staging, freed = dev.pack(victims, np.arange(len(victims), dtype=np.int32))
-    dev.unpack(victims, freed, staging)
+    moved = victims if pack_uids is None else np.asarray(pack_uids, np.int64)
+    staging, freed = dev.pack(moved, np.arange(len(moved), dtype=np.int32))
+    dev.unpack(moved, freed, staging)
     return dict(hits=hits, misses=misses, p_hat=p_hat, mass=mass, S=S, prio=prio, victims=victims,
                 staging=staging, freed=freed)
 
@@ -151,7 +181,7 @@ def run_step_gpu(dev: DeviceCase, q_bits, events, scale, decay, k):
 def run_step_oracle(o, case: synth.Case, q_bits, events, S, prio, hits, misses, scale, decay, k):
     p_hat = o.beta_update(events[0], events[1], hits, misses)
     mass = oracle_score(o, case, q_bits, scale)
-    o.ema_update(case.row_ntok, case.row_off, mass, decay, case.row_weight, case.pair, p_hat, case.state, S, prio)
+    o.ema_update(case.row_ntok, case.row_off, mass, decay, ref_row_weight(o, case), case.pair, p_hat, case.state, S, prio)
     victims = o.select_victims(prio, case.state, k=k)
     k8, v8 = host_pools(case)
     sh = case.shape

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from paper_2604_26968_amd import synth
+from tests.harness import gpu_row_weight, ref_row_weight
 
 pytestmark = pytest.mark.gpu
 
@@ -42,7 +43,7 @@ class Fleet:
         self.rows = []
         for grp, base in zip(self.groups, self.uid_base):
             self.rows.append(dict(ntok=grp.row_ntok, off=(grp.row_off + base).astype(np.int64), q_off=grp.row_q_off,
-                                  weight=grp.row_weight, seq=grp.row_seq, g=grp.shape.g,
+                                  seq=grp.row_seq, g=grp.shape.g,
                                   q_elems=grp.n_rows * grp.shape.g * grp.shape.dim))
 
 
@@ -67,7 +68,11 @@ def run_fleet(oracle, shape_a, shape_b, steps=5, seed=40):
     ws_bytes = max([kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, len(r["ntok"]), r["g"], fl.dim) for r in fl.rows]
                    + [kvm.kvm_workspace_bytes(kvm.OP_SELECT, n)])
     ws = torch.full((ws_bytes,), 0x7F, dtype=torch.uint8, device=dev)
-    dev_rows = [dict(ntok=t(r["ntok"]), off=t(r["off"]), q_off=t(r["q_off"]), weight=t(r["weight"])) for r in fl.rows]
+    # head weights: the library's sizing call for the GPU side, the oracle's sizing function for the oracle
+    dev_rows = [dict(ntok=t(r["ntok"]), off=t(r["off"]), q_off=t(r["q_off"]),
+                     weight=t(gpu_row_weight(kvm, grp.shape, grp.n_rows))) for r, grp in zip(fl.rows, fl.groups)]
+    for r, grp in zip(fl.rows, fl.groups):
+        r["weight"] = ref_row_weight(oracle, grp)
     rec = 2 * 16 * fl.dim * 2
 
     # oracle state (host)

@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from paper_2604_26968_amd import synth
+from tests.harness import gpu_row_weight, ref_row_weight, sized_pool_units
 
 pytestmark = pytest.mark.gpu
 
@@ -24,7 +25,7 @@ def test_llama8b_shaped_full_size(oracle):
     dev = "cuda"
     shape = synth.llama8b_shape(64, seed=2)
     pair_w = synth.categorical_weights(3)
-    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=pair_w)
+    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=pair_w, pool_units=sized_pool_units(kvm, oracle, shape))
     n, n_rows, g, dim = wl.n_uids, wl.n_rows, shape.g, shape.dim
     rec = shape.unit_k_bytes + shape.unit_v_bytes
     pool = kvm.make_pool(wl.k_pool.view(torch.int16), wl.v_pool.view(torch.int16), dim, shape.dtype)
@@ -71,11 +72,12 @@ def test_llama8b_shaped_full_size(oracle):
     torch.cuda.synchronize()
     case, ref_mass = check_sample(q0, "all resident")
 
-    kvm.kvm_ema_update(rows, mass, 0.95, wl.row_weight, wl.pair, p_hat, wl.state, S, prio)
+    row_weight = torch.from_numpy(gpu_row_weight(kvm, shape, n_rows)).to(dev)
+    kvm.kvm_ema_update(rows, mass, 0.95, row_weight, wl.pair, p_hat, wl.state, S, prio)
     torch.cuda.synchronize()
     S_ref, prio_ref, st_ref = np.zeros(case.n_uids, np.float32), np.zeros(case.n_uids, np.float32), case.state.copy()
-    oracle.ema_update(case.row_ntok, case.row_off, ref_mass, 0.95, case.row_weight, case.pair, op, st_ref, S_ref,
-                      prio_ref)
+    oracle.ema_update(case.row_ntok, case.row_off, ref_mass, 0.95, ref_row_weight(oracle, case), case.pair, op, st_ref,
+                      S_ref, prio_ref)
     idx = torch.from_numpy(case.sample_uids).to(dev)
     np.testing.assert_allclose(S[idx].cpu().numpy(), S_ref, rtol=1e-3)
     np.testing.assert_allclose(prio[idx].cpu().numpy(), prio_ref, rtol=1e-3)
@@ -212,7 +214,8 @@ def test_long_row_workloads_full_size_sampled(oracle, name, need_gib):
         pytest.skip("needs %d GiB of free HBM" % need_gib)
     dev = "cuda"
     shape = synth.llama70b_shape() if name == "llama70b" else synth.mla_shape()
-    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=synth.categorical_weights(3))
+    wl = synth.DeviceWorkload(shape, seed=1, pair_weights=synth.categorical_weights(3),
+                              pool_units=sized_pool_units(kvm, oracle, shape))
     n, n_rows, g, dim = wl.n_uids, wl.n_rows, shape.g, shape.dim
     pool = kvm.make_pool(wl.k_pool.view(torch.int16), None if wl.v_pool is None else wl.v_pool.view(torch.int16), dim,
                          shape.dtype)
@@ -220,7 +223,16 @@ def test_long_row_workloads_full_size_sampled(oracle, name, need_gib):
     scale = 1.0 / float(np.sqrt(dim))
     mass = torch.full((n,), -1.0, dtype=torch.float32, device=dev)
     ws = torch.empty(kvm.kvm_workspace_bytes(kvm.OP_SCORE, n, n_rows, g, dim), dtype=torch.uint8, device=dev)
-    sample = np.array([3, n_rows // 2, n_rows - 1] if name == "llama70b" else [n_rows // 3])
+    # at least 64 rows and 0.5 % of the K bytes: first, middle and last row always, the rest drawn with a seed
+    # (64 of 2,560 rows = 2.5 %, 64 of 1,952 = 3.3 %; rows all have the same length here)
+    drawn = np.random.default_rng(23).choice(n_rows, size=64, replace=False)
+    sample = np.unique(np.concatenate([[0, n_rows // 2, n_rows - 1], drawn]))
+    assert len(sample) >= 64 and len(sample) * 200 >= n_rows
+    # the oracle needs ~10 s of one core per all-resident latent row (128 queries x 576 channels x 32,768
+    # tokens in fp64): with everything resident that phase takes 24 of the rows (1.2 % of the K bytes),
+    # the launch the benchmark times (at budget) all of them
+    sample_all_resident = sample if name == "llama70b" else np.unique(np.concatenate(
+        [[0, n_rows // 2, n_rows - 1], drawn[:21]]))
     row_id = torch.repeat_interleave(torch.arange(n_rows, device=dev), torch.from_numpy(wl.nb).to(dev))
     for phase, frac in (("all resident", 1.0), ("at budget", 0.5 if name == "llama70b" else 0.4)):
         if frac < 1.0:
@@ -233,7 +245,8 @@ def test_long_row_workloads_full_size_sampled(oracle, name, need_gib):
         mass.fill_(-1.0)
         kvm.kvm_score_step(pool, rows, q, scale, mass, ws)
         torch.cuda.synchronize()
-        case = wl.host_sample(rows=sample)
+        case = wl.host_sample(rows=sample if frac < 1.0 else sample_all_resident)
+        print(name, phase, "oracle rows", case.n_rows, flush=True)
         qh = q.view(torch.int16).cpu().numpy().view(np.uint16)
         q_rows = np.concatenate([qh[r * g * dim:(r + 1) * g * dim] for r in case.sample_rows])
         ref = np.full(case.n_uids, -1.0, np.float32)

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2604_26968_amd import synth
-from tests.harness import DeviceCase, host_pools
+from tests.harness import DeviceCase, host_pools, ref_row_weight
 
 pytestmark = pytest.mark.gpu
 
@@ -117,7 +117,7 @@ def test_ema_ex_multi_step(oracle, pos_decay, with_mult):
         kvm.kvm_ema_update_ex(dev.rows(active), dev.mass, 0.9, ex, dev.row_weight, dev.pair, dev.p_hat, dev.state,
                               dev.S, dev.prio)
         torch.cuda.synchronize()
-        oracle.ema_update_ex(case.row_ntok, case.row_off, mass, 0.9, pos_decay, case.row_weight, case.pair, p_hat,
+        oracle.ema_update_ex(case.row_ntok, case.row_off, mass, 0.9, pos_decay, ref_row_weight(oracle, case), case.pair, p_hat,
                              state, S, prio, row_seq=case.row_seq if with_mult else None,
                              row_head=row_head if with_mult else None, seq_transition=trans if with_mult else None,
                              head_mult=mult, row_active=active)
@@ -167,7 +167,7 @@ def test_ema_ex_long_row_positional_factor(oracle):
         torch.cuda.synchronize()
         S, prio, state = (np.zeros(case.n_uids, np.float32), np.zeros(case.n_uids, np.float32), case.state.copy())
         oracle.ema_update_ex(case.row_ntok, case.row_off, np.ones(case.n_uids, np.float32), 0.9, pos_decay,
-                             case.row_weight, case.pair, np.ones(16, np.float32), state, S, prio)
+                             ref_row_weight(oracle, case), case.pair, np.ones(16, np.float32), state, S, prio)
         np.testing.assert_allclose(dev.S.cpu().numpy(), S, rtol=1e-6, atol=1e-37)
 
 
@@ -712,7 +712,7 @@ def test_end_to_end_overlapped_exchange_dynamics(oracle):
         wr = omass != -1.0
         np.testing.assert_allclose(gmass[wr], omass[wr], rtol=MASS_RTOL, atol=MASS_ATOL)
         gS, gprio, gstate = dev.ema(0.95)
-        oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, case.row_weight, case.pair, p_hat, case.state,
+        oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, ref_row_weight(oracle, case), case.pair, p_hat, case.state,
                           S, prio)
         np.testing.assert_array_equal(gstate, case.state)
         resm = (case.state & RES) != 0
@@ -813,7 +813,7 @@ def test_end_to_end_pipelined_selection_dynamics(oracle):
     dev.score(q, scale, fill=-1.0)
     p_hat = oracle.beta_update(np.zeros(0, np.uint8), np.zeros(0, np.uint8), hits, misses)
     dev.beta(np.zeros(0, np.uint8), np.zeros(0, np.uint8))
-    oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, case.row_weight, case.pair, p_hat, case.state, S, prio)
+    oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, ref_row_weight(oracle, case), case.pair, p_hat, case.state, S, prio)
     dev.ema(0.95)
     for step in range(5):
         q = synth.make_queries(case, 80 + step)
@@ -841,7 +841,7 @@ def test_end_to_end_pipelined_selection_dynamics(oracle):
         np.testing.assert_array_equal(gmass != -1.0, omass != -1.0)
         wr = omass != -1.0
         np.testing.assert_allclose(gmass[wr], omass[wr], rtol=MASS_RTOL, atol=MASS_ATOL)
-        oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, case.row_weight, case.pair, p_hat, case.state,
+        oracle.ema_update(case.row_ntok, case.row_off, omass, 0.95, ref_row_weight(oracle, case), case.pair, p_hat, case.state,
                           S, prio)
         resm = (case.state & RES) != 0
         np.testing.assert_allclose(dev.S.cpu().numpy()[resm], S[resm], rtol=MASS_RTOL)

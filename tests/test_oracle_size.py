@@ -84,6 +84,22 @@ def test_arch_inference_and_units(oracle):
     assert oracle.size(1, 8, 2, 64, bits_per_elem=4)["bytes_per_token_layer"] == 2 * 2 * 64 // 2
 
 
+def test_head_weight_rule_per_architecture(oracle):
+    """Section 3.4: the aggregate importance weights heads uniformly for MHA and in proportion to the
+    group size for GQA; MQA is the group of all query heads; the MLA matrix has one head per layer."""
+    assert oracle.size(32, 32, 32, 128)["head_weight"] == 1                      # MHA: uniform
+    assert oracle.size(4, 1, 1, 64)["head_weight"] == 1                          # one head each way is MHA
+    assert oracle.size(32, 32, 8, 128)["head_weight"] == 4                       # GQA, 4 query heads per KV head
+    assert oracle.size(80, 64, 8, 128)["head_weight"] == 8
+    assert oracle.size(1, 4, 2, 64, bits_per_elem=16)["head_weight"] == 2
+    assert oracle.size(32, 32, 1, 128)["head_weight"] == 32                      # MQA: all query heads in one group
+    assert oracle.size(61, 128, 128, 128, d_latent=512, d_rope=64)["head_weight"] == 1   # MLA: single latent head
+    # proportional: doubling the group doubles the weight; the tensor-parallel divisor does not enter
+    for hq, hkv in ((16, 8), (32, 8), (64, 8), (64, 2)):
+        assert oracle.size(2, hq, hkv, 64)["head_weight"] * hkv == hq
+    assert oracle.size(2, 64, 8, 64, head_divisor=8)["head_weight"] == 8
+
+
 def test_size_rejects_bad_models(oracle):
     for bad in (dict(n_layers=0), dict(n_q_heads=6, n_kv_heads=4), dict(bits_per_elem=7),
                 dict(head_divisor=3), dict(block_tokens=0), dict(head_dim=0)):
