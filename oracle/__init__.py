@@ -26,12 +26,29 @@ ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (``-O2 -fopenmp``); returns the library path."""
+    """Compile the oracle with gcc (``-O2 -fopenmp``); returns the library path.  With KVM_ORACLE_LIB
+    set, that file (a sanitizer build, see :func:`build_sanitized`) is used as it is."""
+    override = os.environ.get("KVM_ORACLE_LIB")
+    if override:
+        return override
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         )
     return _LIB
+
+
+def build_sanitized(out: str) -> str:
+    """The oracle compiled with AddressSanitizer and UndefinedBehaviorSanitizer (gcc), for the CPU test
+    that reruns the pins under them; returns ``out``.  A process loading it needs gcc's libasan preloaded."""
+    subprocess.check_call(
+        ["gcc", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+         "-shared", "-fPIC", "-Wall", "-Wextra", "-o", out, _SRC, "-lm"])
+    return out
+
+
+def asan_runtime() -> str:
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 class _Model(C.Structure):
