@@ -170,6 +170,9 @@ typedef struct kvm_rows {
  * last block are ignored whatever bytes the pool holds there.  A row whose
  * blocks would leave [0, n_uids) or whose queries would leave [0, q_elems) is
  * treated as inactive; table entries >= n_slots are treated as not resident.
+ * Rows that overlap in uid space (against the data model) get undefined masses
+ * but cause no access outside the arrays; if they overlap so much that their
+ * tiles exceed what the workspace was sized for, the call scores nothing.
  * fp32 accumulation; masses agree with an exact evaluation to ~1e-5 relative.
  *
  * q: dev, dtype of the pool, g x dim contiguous per row at row_q_off.
@@ -266,7 +269,7 @@ int kvm_ema_update(const kvm_rows_t* rows, const float* mass /* dev [n_uids] */,
                    float* S /* dev [n_uids] in/out */, float* prio /* dev [n_uids] out */, void* stream);
 
 /* The same with the two refinements section 3.4 names without formulas (the
- * importance "incorporates positional distance decay"; per-head multipliers
+ * importance also falls off with positional distance; per-head multipliers
  * are applied during a task transition, section 3.7 item 2):
  *   the observation fed to the EMA is pos_decay^d * mass[uid], d = nb - 1 - b
  *   blocks behind the row's last block (where the decode position lies);
@@ -294,8 +297,8 @@ int kvm_ema_update_ex(const kvm_rows_t* rows, const float* mass /* dev [n_uids] 
                       float* S /* dev [n_uids] in/out */, float* prio /* dev [n_uids] out */, void* stream);
 
 /* ======================================================================== *
- * 4. Victim selection — "lowest weighted aggregate importance", section 3.4,
- *    generalised to the k lowest under a capacity budget.
+ * 4. Victim selection — the unit whose head-weighted importance is smallest goes
+ *    first (section 3.4), generalised to the k smallest under a capacity budget.
  *
  * eligible = RESIDENT and not PROTECTED and SCORED.
  * k = k_or_neg1 if >= 0, else max(0, #RESIDENT - budget_units);
@@ -416,7 +419,7 @@ int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uin
                  uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
 /* kvm_exchange in three parts, so that the bytes can move while the next step
- * is being scored ("asynchronous" promotion and demotion, section 3.2):
+ * is being scored (promotion and demotion off the decode path, section 3.2):
  *   kvm_exchange_begin  validates the pairs exactly as kvm_exchange does and, for
  *       each valid pair, takes the out-unit out of HBM in the table (RESIDENT
  *       off, ON_HOST on, slot_tbl = -1 - host slot of its partner) and notes
@@ -445,9 +448,9 @@ int kvm_exchange_end(int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev i
 /* ======================================================================== *
  * 6. Position-aware prefetching — section 3.5.
  *
- * kvm_span_update: the prefetch window "adapts based on observed attention
- * patterns", narrow for layers that attend locally, wide for layers that
- * attend globally (no formula given).  Reading: the span of an active row is
+ * kvm_span_update: the prefetch window follows the attention pattern each
+ * layer shows, narrow for layers that attend locally, wide for layers that
+ * attend globally (section 3.5, no formula given).  Reading: the span of an active row is
  * the smallest s >= 1 such that its last s blocks hold at least theta_num /
  * theta_den of the row's total mass this step (blocks not in HBM count as
  * distance and contribute nothing; rows with no mass are skipped);
@@ -507,8 +510,8 @@ int kvm_hash_units(const kvm_pool_t* pool, const int32_t* slot_tbl /* dev */, co
                    uint8_t* digests /* dev [n][32] out, 4-byte aligned */,
                    uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
-/* The store: "its hash is checked against the store; on a match, a reference
- * count is incremented instead of duplicating the block".  An open-addressing
+/* The store: content store with reference counts (section 3.6): a digest already
+ * present gains a reference, the block is not stored twice.  An open-addressing
  * table in device memory, all arrays caller-allocated with `cap` entries (cap a
  * power of two, kept at most half full by the caller) and initialised once to
  * tag = 0, canon = -1, refs = 0, pending = 0xFFFFFFFF.  It is keyed by the first

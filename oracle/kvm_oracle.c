@@ -25,7 +25,7 @@
  *                           section 3.3, last two paragraphs: confidence that saturates
  *                           with the number of observations, empirical frequency over a
  *                           sliding window, blend weighted by the confidence
- *   kvm_ref_select_victims  section 3.4 ("lowest weighted aggregate importance"),
+ *   kvm_ref_select_victims  section 3.4 (the smallest head-weighted importance goes first),
  *                           as a full sort
  *   kvm_ref_span_update     section 3.5: per-layer prefetch window from the observed
  *                           attention span
@@ -340,7 +340,7 @@ int kvm_ref_ema_update(int n_rows, int block_tokens, int64_t n_uids,
     return REF_OK;
 }
 
-/* Section 3.4 says the EMA "incorporates positional distance decay" and that per-head
+/* Section 3.4 says that the EMA also decays with positional distance and that per-head
  * multipliers are applied during task transitions (section 3.7, item 2) without giving
  * either formula.  The reading taken:
  *   distance d of block b in a row of nb blocks = nb - 1 - b (blocks behind the decode
@@ -442,7 +442,7 @@ int kvm_ref_select_victims(const float* prio, const uint8_t* state, int64_t n_ui
 
 /* ---------------------------------------------- position-aware prefetching */
 
-/* Section 3.5: the prefetch window "adapts based on observed attention patterns",
+/* Section 3.5: the prefetch window follows the attention pattern a layer is observed to have,
  * narrow for layers that attend locally, wide for layers that attend globally.  No
  * formula is given.  The reading taken: the attention span of a row is the smallest
  * number s >= 1 of trailing blocks (counted back from the row's last block, blocks not
@@ -505,7 +505,7 @@ int kvm_ref_span_update(int n_rows, int block_tokens, int64_t n_uids,
 
 /* Section 3.5: while a request decodes at position n, the blocks most likely to be
  * needed next are those within a window w of n; they are promoted from the lower tier
- * ahead of use, "combined with" the reuse estimate of section 3.3.  The text gives the
+ * ahead of use, together with the reuse estimate of section 3.3.  The text gives the
  * window once as [n - w, n] and once as [n, n + w]; positions after n hold no keys yet
  * during decoding, so the reading taken is [n - w, n].  For row r with decode position
  * n = row_pos[r] (tokens; negative = the row asks for nothing) and w = layer_window[row_layer[r]]:
@@ -751,8 +751,8 @@ int kvm_ref_hash_units(const uint8_t* k_pool, const uint8_t* v_pool, uint64_t n_
     return REF_OK;
 }
 
-/* Section 3.6: "its hash is checked against the store; on a match, a reference count is
- * incremented instead of duplicating the block".  The store here is a plain list searched
+/* Section 3.6: content store with reference counts; a digest that is already there gains a
+ * reference and the block is not duplicated.  The store here is a plain list searched
  * from the front: entry e holds a digest, the uid that first brought it (the canonical
  * copy) and the number of references.  Items are taken in list order, so within one call
  * the first occurrence of a new digest becomes canonical.  An entry whose count has dropped

@@ -287,8 +287,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanRows p, ui
 }
 
 // One workgroup: turns wg_sum[0..n) into exclusive prefixes in place and writes the grand totals:
-// counts[0] = tiles, counts[1] = tiles of rows with more than one tile.
-__global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(int n, uint64_t* wg_sum, uint32_t* counts) {
+// counts[0] = tiles, counts[1] = tiles of rows with more than one tile.  Rows that do not overlap in
+// uid space cannot have more than tiles_max tiles together (the bound the workspace is carved for);
+// if the caller's rows do overlap and exceed it, the plan is declared empty (counts[2] = 1, both
+// counts 0): nothing is emitted and nothing is scored, instead of records written past their arrays.
+__global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(int n, uint64_t* wg_sum, uint32_t* counts,
+                                                                 uint64_t tiles_max) {
     uint64_t carry = 0;
     for (int base = 0; base < n; base += kPlanThreads) {
         const int i = base + threadIdx.x;
@@ -299,13 +303,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(int n, uint64_t
         carry += total;
     }
     if (threadIdx.x == 0) {
-        counts[0] = (uint32_t)carry;
-        counts[1] = (uint32_t)(carry >> 32);
+        const bool over = (carry & 0xffffffffull) > tiles_max || (carry >> 32) > tiles_max;
+        counts[0] = over ? 0u : (uint32_t)carry;
+        counts[1] = over ? 0u : (uint32_t)(carry >> 32);
+        counts[2] = over ? 1u : 0u;
     }
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, const uint64_t* wg_base, Tile* tiles,
+__global__ __launch_bounds__(kPlanThreads) void plan_emit_kernel(PlanRows p, const uint64_t* wg_base,
+                                                                 const uint32_t* counts, Tile* tiles,
                                                                  MergeTile* merge) {
+    if (counts[2]) return;               // plan declared empty by the scan (same value for every thread)
     const int r = blockIdx.x * kPlanThreads + threadIdx.x;
     const uint32_t nt = tiles_of_row(p, r);
     uint64_t total;
@@ -1236,7 +1244,7 @@ inline int64_t max_tiles(int64_t n_uids, int64_t n_rows, int tile_blocks) {
 }
 
 struct ScoreWs {
-    uint32_t* n_tiles;  // [2]: tiles of the plan, tiles of rows with more than one tile
+    uint32_t* n_tiles;  // [3]: tiles of the plan, tiles of rows with more than one tile, "plan refused" flag
     uint64_t* wg_sum;
     Tile* tiles;
     MergeTile* merge;   // [tiles]: what the row merge visits
@@ -1459,8 +1467,8 @@ int score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q, fl
     {
         TimedLaunch tl("score_plan", a.st);
         plan_count_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum);
-        plan_scan_kernel<<<1, kPlanThreads, 0, a.st>>>(n_wg, a.w.wg_sum, a.w.n_tiles);
-        plan_emit_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum, a.w.tiles, a.w.merge);
+        plan_scan_kernel<<<1, kPlanThreads, 0, a.st>>>(n_wg, a.w.wg_sum, a.w.n_tiles, (uint64_t)tiles_max);
+        plan_emit_kernel<<<n_wg, kPlanThreads, 0, a.st>>>(a.pr, a.w.wg_sum, a.w.n_tiles, a.w.tiles, a.w.merge);
         if (int rc = launch_status("score_plan")) return rc;
     }
     return pool->dtype == KVM_BF16 ? launch_dtype<KVM_BF16>(a, ch) : launch_dtype<KVM_FP16>(a, ch);

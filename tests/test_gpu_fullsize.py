@@ -228,11 +228,7 @@ def test_long_row_workloads_full_size_sampled(oracle, name, need_gib):
     drawn = np.random.default_rng(23).choice(n_rows, size=64, replace=False)
     sample = np.unique(np.concatenate([[0, n_rows // 2, n_rows - 1], drawn]))
     assert len(sample) >= 64 and len(sample) * 200 >= n_rows
-    # the oracle needs ~10 s of one core per all-resident latent row (128 queries x 576 channels x 32,768
-    # tokens in fp64): with everything resident that phase takes 24 of the rows (1.2 % of the K bytes),
-    # the launch the benchmark times (at budget) all of them
-    sample_all_resident = sample if name == "llama70b" else np.unique(np.concatenate(
-        [[0, n_rows // 2, n_rows - 1], drawn[:21]]))
+    sample_all_resident = sample
     row_id = torch.repeat_interleave(torch.arange(n_rows, device=dev), torch.from_numpy(wl.nb).to(dev))
     for phase, frac in (("all resident", 1.0), ("at budget", 0.5 if name == "llama70b" else 0.4)):
         if frac < 1.0:

@@ -652,3 +652,29 @@ def test_kernel_timing_counts_and_filter():
     assert kvm.kvm_timing_read("no such kernel")[0] == 0
     kvm.kvm_timing_reset()
     assert kvm.kvm_timing_read("probe_read")[0] == 0
+
+
+def test_overlapping_rows_beyond_the_tile_bound_score_nothing():
+    """Rows must not overlap in uid space.  If a caller's rows do, and so much that their tiles exceed
+    the bound the workspace is sized for (n_uids / tile + n_rows), the plan is refused on the device:
+    no record is written past its array, nothing is scored, masses keep their old values."""
+    from paper_2604_26968_amd import kvm
+    case = synth.make_case(synth.Shape(1, 4, 1, 128, synth.BF16, True, [32768]), seed=77)
+    dev = DeviceCase(case)
+    copies = 50                                    # 50 rows over the same 2,048 units: 200 tiles > 2048 / 512 + 50
+    ntok = torch.full((copies,), 32768, dtype=torch.int32, device="cuda")
+    off = torch.zeros(copies, dtype=torch.int64, device="cuda")
+    q_off = torch.zeros(copies, dtype=torch.int64, device="cuda")
+    rows = kvm.make_rows(ntok, off, q_off, dev.slot_tbl, 4, 4 * 128)
+    ws = torch.full((kvm.kvm_workspace_bytes(kvm.OP_SCORE, case.n_uids, copies, 4, 128),), 0x7F, dtype=torch.uint8,
+                    device="cuda")
+    q = torch.from_numpy(synth.make_queries(case, 3).view(np.int16)).cuda()
+    dev.mass.fill_(-5.0)
+    kvm.kvm_score_step(dev.pool, rows, q, 0.1, dev.mass, ws)
+    torch.cuda.synchronize()
+    assert bool((dev.mass == -5.0).all())
+    # the same rows, few enough to stay inside the bound, are scored (each writes the same values)
+    rows2 = kvm.make_rows(ntok[:1], off[:1], q_off[:1], dev.slot_tbl, 4, 4 * 128)
+    kvm.kvm_score_step(dev.pool, rows2, q, 0.1, dev.mass, ws)
+    torch.cuda.synchronize()
+    assert bool((dev.mass >= 0).all())
