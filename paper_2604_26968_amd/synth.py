@@ -385,3 +385,56 @@ def mha_fleet_shape(n_seq: int = 48, seed: int = 5) -> Shape:
 def mqa_fleet_shape(n_seq: int = 1536, seed: int = 6) -> Shape:
     """MQA half of the fleet workload: 32 layers, 32 q / 1 KV head (g = 32), d 128, bf16, lognormal lengths."""
     return Shape(32, 32, 1, 128, BF16, True, lognormal_lengths(n_seq, seed))
+
+
+# ------------------------------------------------------------ fleet request trace
+@dataclass
+class FleetRequest:
+    """One request of the heterogeneous-fleet trace (all times in decode steps)."""
+    arrival: int
+    model: int               # 0 = the MHA model, 1 = the MQA model
+    prefix: int              # id in that model's shared-prefix catalogue (0 = most popular)
+    prompt_len: int          # tokens, lognormal clipped
+    prefix_len: int          # leading tokens shared with every request of the same prefix id (whole blocks)
+    decode: List[int]        # decode steps of each turn of the session
+    gap: List[int]           # idle steps after each turn but the last
+
+
+@dataclass
+class FleetPrefix:
+    frac: float              # share of a prompt that the prefix makes up
+    block_type: int          # 0 system_prompt or 1 tool_context
+    transition: int          # transition type of the requests that use it, 0..3
+
+
+def fleet_catalogue(n_prefixes: int, seed: int) -> List[FleetPrefix]:
+    rng = np.random.default_rng(seed)
+    w = categorical_weights(seed + 1, 4)
+    return [FleetPrefix(float(rng.uniform(0.2, 0.9)), int(rng.integers(0, 2)), int(rng.choice(4, p=w)))
+            for _ in range(n_prefixes)]
+
+
+def fleet_requests(n_requests: int, seed: int, rate: float, n_prefixes: int, catalogues, zipf_a: float = 1.1,
+                   mean_turns: float = 3.0, mean_decode: float = 80.0, mean_gap: float = 150.0, mu: float = 7.0,
+                   sigma: float = 1.0, lo: int = 16, hi: int = 32768) -> List[FleetRequest]:
+    """A seeded request trace: Poisson arrivals (`rate` per decode step), model ~ Bernoulli(0.5), prefix id
+    ~ Zipf(zipf_a) over a catalogue of n_prefixes per model, prompt length ~ lognormal(mu, sigma) clipped to
+    [lo, hi], sessions of 1 + Poisson(mean_turns - 1) turns of 1 + Geometric(mean_decode) decode steps with
+    exponential idle gaps (mean mean_gap steps) between turns."""
+    rng = np.random.default_rng(seed)
+    ranks = np.arange(1, n_prefixes + 1, dtype=np.float64)
+    zipf = ranks ** (-zipf_a)
+    zipf /= zipf.sum()
+    t = 0.0
+    out = []
+    for _ in range(n_requests):
+        t += rng.exponential(1.0 / rate)
+        model = int(rng.random() < 0.5)
+        prefix = int(rng.choice(n_prefixes, p=zipf))
+        prompt = int(np.clip(np.exp(rng.normal(mu, sigma)), lo, hi))
+        plen = int(catalogues[model][prefix].frac * prompt) // BLOCK * BLOCK
+        turns = 1 + int(rng.poisson(max(mean_turns - 1.0, 0.0)))
+        decode = [1 + int(rng.geometric(1.0 / mean_decode)) for _ in range(turns)]
+        gap = [1 + int(rng.exponential(mean_gap)) for _ in range(turns - 1)]
+        out.append(FleetRequest(int(t), model, prefix, prompt, plen, decode, gap))
+    return out

@@ -1,0 +1,131 @@
+"""The fleet step on the CPU oracle: the same stages as paper_2604_26968_amd.fleet.FleetDevice, on
+numpy arrays, through the oracle's functions only.  Inputs (pools, tables, queries, fresh records) are
+copied from the device driver once, before any stage runs; from then on the two sides only meet where
+a test compares them."""
+from __future__ import annotations
+
+import numpy as np
+
+RES, HOST, PROT, SCORED = 1, 2, 4, 8
+
+
+class FleetRef:
+    def __init__(self, o, dev, plan):
+        """`dev`: a freshly constructed FleetDevice (nothing run yet)."""
+        self.o, self.plan = o, plan
+        t = lambda x: x.detach().cpu().numpy().copy()
+        self.k16 = t(dev.k_pool.view(dev.torch.int16)).view(np.uint16)
+        self.v16 = t(dev.v_pool.view(dev.torch.int16)).view(np.uint16)
+        self.k8 = self.k16.view(np.uint8).reshape(dev.pool_units, -1)
+        self.v8 = self.v16.view(np.uint8).reshape(dev.pool_units, -1)
+        self.uk, self.uv = self.k8.shape[1], self.v8.shape[1]
+        self.rec = self.uk + self.uv
+        self.tbl, self.state, self.pair = t(dev.slot_tbl), t(dev.state), plan.pair.copy()
+        self.free_frames = t(dev.free_frames)
+        n = plan.n_uids
+        self.mass = np.zeros(n, np.float32)
+        self.S, self.prio = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        self.key, self.cand = np.zeros(n, np.float32), np.zeros(n, np.uint8)
+        self.hits, self.misses = np.zeros(16, np.uint32), np.zeros(16, np.uint32)
+        self.p_hat = np.zeros(16, np.float32)
+        self.n_bad = np.zeros(1, np.uint32)
+        self.P, self.decay, self.pos_decay, self.scale = dev.P, dev.decay, dev.pos_decay, dev.scale
+        self.dim, self.dtype = dev.dim, dev.dtype
+        self.tier = np.zeros((dev.tier_slots, self.rec), np.uint8)
+        self.next_slot = 0
+        self.fresh = t(dev.fresh).reshape(-1, self.rec)
+        self.n_new = list(dev.n_new)
+        self.room = np.full(max(max(self.n_new), 1), -1, np.int32)
+        self.arch = []
+        for a, d in enumerate(dev.arch):
+            sh = d["shape"]
+            args = sh.model_args()
+            self.arch.append(dict(g=sh.g, n_rows=d["n_rows"], off=plan.rows[a]["off"], q_off=plan.rows[a]["q_off"],
+                                  layer=plan.rows[a]["layer"], ntok=plan.rows[a]["ntok"], active=plan.rows[a]["active"],
+                                  pos=plan.rows[a]["pos"], init_ntok=plan.init_ntok[a],
+                                  weight=np.full(d["n_rows"], float(o.size(**args)["head_weight"]), np.float32),
+                                  window=t(d["window"]),
+                                  q=[t(q.view(dev.torch.int16)).view(np.uint16) for q in d["q"]]))
+        self.victims = np.zeros(0, np.int64)
+        self.pf_list = np.zeros(0, np.int64)
+
+    def _rows(self, a, j):
+        d = self.arch[a]
+        return (d["init_ntok"], None) if j is None else (d["ntok"][j], d["active"][j])
+
+    def arrive(self, j):
+        n = self.n_new[j]
+        uids = self.plan.new_uids[j]
+        step = len(self.fresh)
+        for lo in range(0, n, step):
+            cnt = min(step, n - lo)
+            self.o.unpack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, uids[lo:lo + cnt],
+                          self.room[lo:lo + cnt], self.fresh[:cnt], n_bad=self.n_bad)
+        self.state[self.plan.prot_clear[j]] &= 255 - PROT
+        self.state[self.plan.prot_set[j]] |= PROT
+
+    def beta(self, j):
+        p, o_ = (np.zeros(0, np.uint8), np.zeros(0, np.uint8)) if j is None else self.plan.events[j]
+        self.p_hat = self.o.beta_update(p, o_, self.hits, self.misses)
+
+    def score(self, j, q_set=0):
+        for a, d in enumerate(self.arch):
+            if d["n_rows"]:
+                ntok, act = self._rows(a, j)
+                self.o.score_step(self.k16, self.dim, self.dtype, ntok, d["off"], d["q_off"], self.tbl,
+                                  d["q"][q_set % 4], d["g"], self.scale, self.mass, row_active=act)
+
+    def ema(self, j):
+        for a, d in enumerate(self.arch):
+            if d["n_rows"]:
+                ntok, act = self._rows(a, j)
+                self.o.ema_update(ntok, d["off"], self.mass, self.decay, d["weight"], self.pair, self.p_hat, self.state,
+                                  self.S, self.prio, row_active=act)
+
+    def prefetch_keys(self, j):
+        for a, d in enumerate(self.arch):
+            if d["n_rows"]:
+                self.o.prefetch_keys(d["ntok"][j], d["off"], d["layer"], d["pos"][j], d["window"], self.state, self.pair,
+                                     self.p_hat, self.pos_decay, self.key, self.cand)
+
+    def select(self, j):
+        self.pf_list = self.o.select_victims(self.key, self.cand, k=self.P)
+        self.victims = self.o.select_victims(self.prio, self.state, k=self.n_new[j + 1] + self.P)
+
+    def move(self, j):
+        P = self.P
+        n_pairs = min(P, len(self.victims), len(self.pf_list))
+        if n_pairs:
+            self.o.exchange(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, self.victims[:n_pairs],
+                            self.pf_list[:n_pairs], self.tier, n_bad=self.n_bad)
+        m = self.n_new[j + 1]
+        if m:
+            out = self.victims[P:P + m]
+            assert len(out) == m, "fewer eligible victims than the next step needs frames"
+            slots = np.arange(self.next_slot, self.next_slot + m, dtype=np.int32)
+            staging, freed = self.o.pack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, out, slots,
+                                         n_bad=self.n_bad)
+            self.tier[self.next_slot:self.next_slot + m] = staging
+            self.room[:m] = freed
+            self.next_slot += m
+
+    # ---- warm start ------------------------------------------------------------------------------------------
+    def first_pass(self):
+        self.beta(None)
+        self.score(None, 0)
+        self.ema(None)
+
+    def evict_to_budget(self, budget_units, keep_records, order):
+        victims = self.o.select_victims(self.prio, self.state, k=-1, budget_units=budget_units)
+        k0 = len(victims)
+        victims = victims[order[:k0]]
+        slots = np.arange(k0, dtype=np.int32)
+        staging, freed = self.o.pack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, victims, slots,
+                                     n_bad=self.n_bad)
+        keep = min(keep_records, k0)
+        self.tier[:keep] = staging[:keep]
+        self.state[victims[keep:]] &= 255 - HOST
+        self.next_slot = keep
+        frames = np.concatenate([freed[:k0], self.free_frames])
+        self.room[:self.n_new[0]] = frames[:self.n_new[0]]
+        return k0, victims

@@ -184,3 +184,148 @@ def test_fleet_mha_plus_mqa_g32(oracle):
     a = synth.Shape(1, 2, 2, 128, synth.BF16, True, lognormal_lengths(8, 3))
     b = synth.Shape(2, 32, 1, 128, synth.BF16, True, lognormal_lengths(8, 4))
     run_fleet(oracle, a, b, steps=4, seed=60)
+
+
+# ------------------------------------------------------------------ trace-driven fleet (fifth workload)
+def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=14, P=24, keep_all=True):
+    """The fleet as the benchmark drives it, at a size the oracle follows step by step: one pool sized by
+    kvm_size shared by an MHA and an MQA model, a seeded request trace (Zipf prefix ids, lognormal lengths,
+    multi-turn sessions with idle gaps), warm start (everything scored once, bulk eviction to the budget),
+    then per step: arrivals and growth into the frames the last step made room in, posteriors from the
+    step's lookups, scoring of the decoding rows of both architectures, EMA + priority with the head weight
+    of each architecture, position-aware prefetch list, ONE victim selection over the shared pool, exchange
+    and pack.  Every stage is compared with the oracle; the oracle's floating-point outputs are then handed
+    to the GPU side so that both stay on the same trajectory and the integer outputs can be compared exactly."""
+    from paper_2604_26968_amd import kvm, fleet
+    from tests.fleet_ref import FleetRef
+    shapes = [synth.Shape(2, 4, 4, 128, synth.BF16, True, []), synth.Shape(2, 32, 1, 128, synth.BF16, True, [])]
+    cats = [synth.fleet_catalogue(8, seed), synth.fleet_catalogue(8, seed + 1)]
+    reqs = synth.fleet_requests(n_requests, seed + 2, rate, 8, cats, mean_decode=20, mean_gap=30, mu=5.5, hi=4096)
+    target = 12000 * 8192 + 100
+    sizing = [kvm.kvm_size(**sh.model_args(), n_max=4096, mem_target=target) for sh in shapes]
+    for s, sh in zip(sizing, shapes):
+        assert s == oracle.size(**sh.model_args(), n_max=4096, mem_target=target)
+    assert sizing[0]["pool_units"] == sizing[1]["pool_units"] == 12000          # same unit bytes, one pool
+    assert [s["head_weight"] for s in sizing] == [1, 32] and [s["units_per_block"] for s in sizing] == [8, 2]
+    pool_units = sizing[0]["pool_units"]
+    plan = fleet.build_plan(shapes, cats, reqs, start, n_steps, capacity_units=int(0.9 * pool_units), max_tokens=4096)
+    st = plan.stats
+    print("fleet plan", {k: st[k] for k in ("entries_by_model", "hits", "misses", "retired", "init_units")},
+          "active", st["active_per_step"], "new", st["new_units_per_step"], "events", st["events_per_step"], flush=True)
+    assert st["init_units"] <= pool_units and min(st["entries_by_model"]) > 0
+    assert sum(st["new_units_per_step"]) > 0 and sum(st["events_per_step"]) > 0
+    rec = 8192
+    tier_slots = st["init_units"] + sum(st["new_units_per_step"]) + 8
+    tier = torch.zeros(tier_slots * rec, dtype=torch.uint8).pin_memory()
+    dev = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
+                            prefetch_cap=P, window_tokens=512, seed=seed, fresh_records=64)
+    ref = FleetRef(oracle, dev, plan)
+    n = plan.n_uids
+    cpu = lambda x: x.detach().cpu().numpy()
+
+    def same_tables(tag):
+        np.testing.assert_array_equal(cpu(dev.slot_tbl), ref.tbl, err_msg=tag)
+        np.testing.assert_array_equal(cpu(dev.state), ref.state, err_msg=tag)
+
+    def floats_then_align(tag, j, q_set):
+        dev.score(j, q_set)
+        ref.score(j, q_set)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(cpu(dev.mass), ref.mass, rtol=1e-3, atol=1e-9, err_msg=tag)
+        dev.mass.copy_(torch.from_numpy(ref.mass))
+        dev.ema(j)
+        ref.ema(j)
+        torch.cuda.synchronize()
+        same_tables(tag + " ema")
+        np.testing.assert_allclose(cpu(dev.S), ref.S, rtol=3e-6, err_msg=tag)
+        fin = np.isfinite(ref.prio)
+        np.testing.assert_allclose(cpu(dev.prio)[fin], ref.prio[fin], rtol=3e-6, err_msg=tag)
+        assert np.array_equal(np.isfinite(cpu(dev.prio)), fin)
+        dev.S.copy_(torch.from_numpy(ref.S))
+        dev.prio.copy_(torch.from_numpy(ref.prio))
+
+    # ---- warm start ---------------------------------------------------------------------------------------
+    dev.beta_none()
+    ref.beta(None)
+    floats_then_align("first pass", None, 0)
+    n_res = int((ref.state & RES).sum())
+    assert n_res == st["init_units"]
+    budget = int(0.6 * n_res)
+    order = np.random.default_rng(seed + 7).permutation(n_res - budget)
+    keep = (n_res - budget) if keep_all else (n_res - budget) // 2
+    scratch = torch.zeros(tier_slots * rec, dtype=torch.uint8).pin_memory()
+    k0, _ = dev.evict_to_budget(budget, keep, order, scratch, chunk=500)
+    k0_ref, _ = ref.evict_to_budget(budget, keep, order)
+    assert k0 == k0_ref == n_res - budget
+    same_tables("bulk eviction")
+    np.testing.assert_array_equal(tier.numpy().reshape(tier_slots, rec)[:keep], ref.tier[:keep])
+    np.testing.assert_array_equal(cpu(dev.room)[:dev.n_new[0]], ref.room[:dev.n_new[0]])
+
+    # ---- the window -----------------------------------------------------------------------------------------
+    n_pf_seen = n_moved = 0
+    for j in range(n_steps):
+        tag = "step %d" % j
+        dev.arrive(j)
+        ref.arrive(j)
+        same_tables(tag + " arrive")
+        dev.beta(j)
+        ref.beta(j)
+        np.testing.assert_array_equal(cpu(dev.hits).view(np.uint32), ref.hits)
+        np.testing.assert_array_equal(cpu(dev.misses).view(np.uint32), ref.misses)
+        np.testing.assert_allclose(cpu(dev.p_hat), ref.p_hat, rtol=1e-6)
+        dev.p_hat.copy_(torch.from_numpy(ref.p_hat))
+        floats_then_align(tag, j, j)
+        dev.prefetch_keys(j)
+        ref.prefetch_keys(j)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(cpu(dev.cand), ref.cand, err_msg=tag)
+        fin = np.isfinite(ref.key)
+        # key = 1 - p * decay^d in fp32: the power, the product and the difference each round once, on values
+        # of at most 1 (half an ulp of 1 = 6e-8 for each, 1.2e-7 where the exp2 is off by one ulp): 4e-7 in all
+        np.testing.assert_allclose(cpu(dev.key)[fin], ref.key[fin], atol=4e-7, rtol=0, err_msg=tag)
+        dev.key.copy_(torch.from_numpy(ref.key))
+        dev.select(j)
+        ref.select(j)
+        torch.cuda.synchronize()
+        k = dev.n_new[j + 1] + P
+        assert int(dev.n_v.item()) == len(ref.victims) == k, (tag, int(dev.n_v.item()), len(ref.victims), k)
+        np.testing.assert_array_equal(cpu(dev.victims)[:k], ref.victims, err_msg=tag)
+        n_pf = int(dev.n_pf.item())
+        assert n_pf == len(ref.pf_list)
+        np.testing.assert_array_equal(cpu(dev.pf_list)[:n_pf], ref.pf_list, err_msg=tag)
+        n_pf_seen += n_pf
+        dev.move(j)
+        ref.move(j)
+        torch.cuda.synchronize()
+        same_tables(tag + " move")
+        m = dev.n_new[j + 1]
+        np.testing.assert_array_equal(cpu(dev.room)[:m], ref.room[:m], err_msg=tag)
+        assert dev.next_slot == ref.next_slot
+        n_moved += m
+        assert int(dev.n_bad.item()) == 0 and int(ref.n_bad[0]) == 0, tag
+    # ---- bytes: pools of the units in HBM and the tier records of the units on the host -----------------------
+    res = (ref.state & RES) != 0
+    frames = ref.tbl[res]
+    gk = cpu(dev.k_pool.view(torch.int16)).view(np.uint8).reshape(pool_units, -1)
+    gv = cpu(dev.v_pool.view(torch.int16)).view(np.uint8).reshape(pool_units, -1)
+    np.testing.assert_array_equal(gk[frames], ref.k8[frames])
+    np.testing.assert_array_equal(gv[frames], ref.v8[frames])
+    on_host = (ref.state & HOST) != 0
+    slots = -1 - ref.tbl[on_host]
+    assert slots.min() >= 0 and len(np.unique(slots)) == len(slots)
+    np.testing.assert_array_equal(tier.numpy().reshape(tier_slots, rec)[slots], ref.tier[slots])
+    # the trace made the pass do all of its work: units were created, units of both models were evicted,
+    # prefetch candidates were found and traded, both outcomes of a lookup occurred
+    assert n_moved > 0 and n_pf_seen > 0 and ref.hits.sum() > 0 and ref.misses.sum() > 0
+    uid_model_b = plan.rows[1]["off"].min() if len(plan.rows[1]["off"]) else n
+    return dict(n_pf=n_pf_seen, moved=n_moved)
+
+
+def test_fleet_trace_twin_matches_oracle_step_by_step(oracle):
+    run_trace_fleet(oracle, seed=90)
+
+
+def test_fleet_trace_twin_with_records_dropped_below_tier_one(oracle):
+    """Half of the bulk eviction's records are not kept in tier 1 (demoted further down): those units must
+    never come back as prefetch candidates and never be scored."""
+    run_trace_fleet(oracle, seed=131, rate=0.4, start=300, n_steps=10, P=16, keep_all=False)
