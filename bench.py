@@ -45,7 +45,7 @@ WORKLOADS = {
     "mqa": ("fleet, MQA half alone: 32 layers, 32q/1kv head (g 32), d128, bf16, %d seqs lognormal(7,1) tok",
             lambda synth, n: synth.mqa_fleet_shape(n), 1536, 0.60, 0.90, 1024, 4096),
 }
-DEFAULT_ORDER = ["llama70b", "llama8b", "mla"]
+DEFAULT_ORDER = ["llama70b", "llama8b", "mla", "fleet"]
 
 # HBM bytes per launch of the tile kernel from rocprofv3 --pmc (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB), with
 # the transfer workgroups riding along, one entry per workload at its default size.  Each entry names the
@@ -548,6 +548,242 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
     return out
 
 
+FLEET = dict(n_requests=10000, rate=0.5, n_prefixes=64, start=15000, hbm_share=0.6, budget=0.60, decay=0.90,
+             prefetch_cap=1024, window_tokens=2048, keep_records=1 << 19, seed=11)
+
+
+def prepare_fleet(args, kvm, synth):
+    """Sizing of the shared pool and the host replay of the trace (no GPU work)."""
+    from paper_2604_26968_amd import fleet
+    F = FLEET
+    shapes = [synth.Shape(32, 32, 32, 128, synth.BF16, True, []), synth.Shape(32, 32, 1, 128, synth.BF16, True, [])]
+    target = int(F["hbm_share"] * 288 * 10**9)
+    sizing = [kvm.kvm_size(**sh.model_args(), n_max=32768, mem_target=target) for sh in shapes]
+    assert sizing[0]["pool_units"] == sizing[1]["pool_units"]               # same unit bytes: one pool serves both
+    cats = [synth.fleet_catalogue(F["n_prefixes"], F["seed"]), synth.fleet_catalogue(F["n_prefixes"], F["seed"] + 1)]
+    reqs = synth.fleet_requests(F["n_requests"], F["seed"] + 2, F["rate"], F["n_prefixes"], cats)
+    plan = fleet.build_plan(shapes, cats, reqs, F["start"], args.warmup + args.steps,
+                            capacity_units=int(0.97 * sizing[0]["pool_units"]))
+    rec = int(sizing[0]["unit_k_bytes"] + sizing[0]["unit_v_bytes"])
+    tier_slots = F["keep_records"] + sum(plan.stats["new_units_per_step"]) + 8
+    return dict(shapes=shapes, sizing=sizing, plan=plan, rec=rec, tier_slots=tier_slots,
+                pinned_bytes=(tier_slots + 32768) * rec + 2 * 4096)
+
+
+def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
+    """The heterogeneous fleet: an MHA model (32 layers, 32 KV heads, g 1) and an MQA model (32 layers, 1 KV
+    head, g 32) share ONE pool sized by kvm_size for 60 % of the GPU's HBM; a seeded trace of 10,000 requests
+    (Zipf(1.1) prefix ids, lognormal(7, 1) lengths, multi-turn sessions with exponential gaps) is replayed on
+    the host up to the measured window and then drives every step: arrivals and growth, lookups, decoding
+    rows of both architectures, one victim selection over the shared pool, prefetch by position."""
+    from paper_2604_26968_amd import fleet
+    dev = "cuda"
+    t_setup = time.time()
+    F = FLEET
+    shapes, sizing, plan, rec, tier_slots = prep["shapes"], prep["sizing"], prep["plan"], prep["rec"], prep["tier_slots"]
+    pool_units = int(sizing[0]["pool_units"])
+    unit_k = int(sizing[0]["unit_k_bytes"])
+    n_steps = args.warmup + args.steps
+    st = plan.stats
+    assert st["init_units"] <= pool_units
+    pinned.reset()
+    tier = pinned.take(tier_slots * rec)[:tier_slots * rec]
+    scratch = pinned.take(32768 * rec)[:32768 * rec]
+    fd = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
+                           prefetch_cap=F["prefetch_cap"], window_tokens=F["window_tokens"], decay=F["decay"],
+                           seed=F["seed"])
+    n = plan.n_uids
+    # per step: which uids belong to rows that decode (to count the units the scorer reads)
+    act_uid = []
+    for j in range(n_steps):
+        m = torch.zeros(n, dtype=torch.uint8, device=dev)
+        for a, d in enumerate(fd.arch):
+            rows_on = torch.nonzero(d["active"][j]).flatten()
+            nb = (d["ntok"][j][rows_on].long() + 15) // 16
+            starts = d["off"][rows_on]
+            tot = int(nb.sum().item())
+            if tot:
+                rep = torch.repeat_interleave(torch.arange(rows_on.numel(), device=dev), nb)
+                within = torch.arange(tot, device=dev) - torch.repeat_interleave(torch.cumsum(nb, 0) - nb, nb)
+                m[starts[rep] + within] = 1
+        act_uid.append(m)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    # ---- warm start: everything in HBM, every row decodes once; then bulk eviction to the budget ----------
+    fd.score(None, 0)                       # untimed: loads the code objects
+    torch.cuda.synchronize()
+    t_pass0 = timed(torch, fd.first_pass)
+    kvm.kvm_timing_only(None)
+    kvm.kvm_timing_reset()
+    kvm.kvm_timing_enable(True)
+    fd.first_pass()
+    torch.cuda.synchronize()
+    kvm.kvm_timing_enable(False)
+    pass0_kernels = read_kernel_times(kvm)
+    kvm.kvm_timing_reset()
+    n_res0 = int((fd.state & 1).sum().item())
+    budget = int(F["budget"] * n_res0)
+    order = np.random.default_rng(F["seed"] + 5).permutation(n_res0 - budget)
+    t0 = time.perf_counter()
+    k0, _ = fd.evict_to_budget(budget, F["keep_records"], order, scratch)
+    t_bulk = time.perf_counter() - t0
+
+    # ---- the window -------------------------------------------------------------------------------------
+    main = torch.cuda.current_stream()
+    scored = torch.zeros(n_steps, dtype=torch.int64, device=dev)
+    pairs = torch.zeros(n_steps, dtype=torch.int64, device=dev)
+
+    pass_marks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+
+    def step(j):
+        fd.arrive(j)
+        pass_marks[j][0].record(main)
+        fd.beta(j)
+        fd.score(j, j)
+        fd.ema(j)
+        fd.prefetch_keys(j)
+        fd.select(j)
+        pass_marks[j][1].record(main)
+        scored[j] = ((fd.state & 1) * act_uid[j]).sum()          # units the two scoring launches just read
+        pairs[j] = torch.minimum(fd.n_pf[0], fd.n_v[0]).clamp(max=fd.P)
+        fd.move(j)
+
+    kvm.kvm_timing_only(None)
+    kvm.kvm_timing_reset()
+    kvm.kvm_timing_enable(True)
+    for j in range(args.warmup):
+        if j == 1:
+            torch.cuda.synchronize()
+            kvm.kvm_timing_reset()
+        step(j)
+    torch.cuda.synchronize()
+    warm = read_kernel_times(kvm)
+    kvm.kvm_timing_reset()
+    kvm.kvm_timing_only("score_partial")
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record(main)
+    for j in range(args.warmup, n_steps):
+        step(j)
+        marks[j - args.warmup + 1].record(main)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kvm.kvm_timing_enable(False)
+    kvm.kvm_timing_only(None)
+    cnt, sp_ms = kvm.kvm_timing_read("score_partial")
+    kvm.kvm_timing_reset()
+    assert int(fd.n_bad.item()) == 0, int(fd.n_bad.item())
+    per_step = [marks[j].elapsed_time(marks[j + 1]) for j in range(args.steps)]
+    scored_h = scored.cpu().numpy()[args.warmup:]
+    pairs_h = pairs.cpu().numpy()[args.warmup:]
+    new_next = np.asarray(fd.n_new[args.warmup + 1:n_steps + 1])
+    scored_bytes = float(scored_h.sum()) * unit_k
+    value = scored_bytes / elapsed / 1e9
+    pass_ms = [pass_marks[j][0].elapsed_time(pass_marks[j][1]) for j in range(args.warmup, n_steps)]
+    pass_value = scored_bytes / (sum(pass_ms) * 1e-3) / 1e9
+    # steps without an arrival of a whole prompt: growth of the decoding sequences only
+    quiet = [t for t, m in zip(per_step, new_next) if m < 65536]
+    quiet_bytes = [b * unit_k for b, m in zip(scored_h, new_next) if m < 65536]
+    # roofline of the two scoring launches of a step together (g 1 rows on the dot-product kernel, g 32 rows on
+    # the matrix-core kernel): algorithmic bytes = K frames + masses of the units read, table entries of the
+    # decoding rows' blocks, their queries
+    blocks_active = sum(int(act_uid[j].sum().item()) for j in range(args.warmup, n_steps))
+    q_bytes = sum(int(fd.arch[a]["active"][j].sum().item()) * shapes[a].g * 128 * 2
+                  for j in range(args.warmup, n_steps) for a in range(2))
+    algo = float(scored_h.sum()) * (unit_k + 4) + blocks_active * 4 + q_bytes
+    achieved = algo / (sp_ms * 1e-3) / 1e9
+    warm["score_partial"] = round(sp_ms / max(cnt, 1), 4)
+    out = {
+        "value": round(value, 1), "unit": "GB/s", "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+        "ms_per_step_median": round(sorted(per_step)[len(per_step) // 2], 4),
+        "ms_per_step_min_max": [round(min(per_step), 4), round(max(per_step), 4)],
+        "config": {"workload": "heterogeneous fleet: MHA (32 layers, 32 KV heads, g 1) + MQA (32 layers, 1 KV head, g 32), "
+                               "d128, bf16, one pool of %d frames from kvm_size(%.0f %% of 288 GB); trace of %d requests, "
+                               "Zipf(1.1) over %d prefixes per model, lengths lognormal(7,1) clipped to 32768, window = "
+                               "steps %d..%d, budget %d%%, decay %g"
+                               % (pool_units, 100 * F["hbm_share"], F["n_requests"], F["n_prefixes"], F["start"],
+                                  F["start"] + n_steps - 1, round(100 * F["budget"]), F["decay"]),
+                   "units_total": int(st["init_units"]), "pool_units_from_kvm_size": pool_units,
+                   "head_weights": [int(s["head_weight"]) for s in sizing], "entries_by_model": st["entries_by_model"],
+                   "rows": [d["n_rows"] for d in fd.arch], "requests_replayed": st["requests_replayed"],
+                   "lookup_hits": st["hits"], "lookup_misses": st["misses"], "retired_before_window": st["retired"],
+                   "decoding_sequences_per_step": [int(min(st["active_per_step"])), int(max(st["active_per_step"]))],
+                   "units_scored_per_step": [int(scored_h.min()), int(scored_h.max())],
+                   "new_units_per_step": [int(new_next.min()), int(new_next.max())],
+                   "events_per_step": [int(min(st["events_per_step"])), int(max(st["events_per_step"]))],
+                   "prefetch_pairs_per_step": [int(pairs_h.min()), int(pairs_h.max())],
+                   "step_order": "arrivals into the frames made free, beta, score (2 launches), ema+priority (2), "
+                                 "prefetch keys (2) + list, ONE victim selection, exchange, pack"},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "in_order_ms_per_step": round(elapsed / args.steps * 1e3, 4),
+        "pass_without_transfers": {
+            "ms": round(sum(pass_ms) / len(pass_ms), 4), "value": round(pass_value, 1),
+            "frac_of_hbm_peak": round(pass_value / HBM_PEAK_GBPS, 4),
+            "what": "beta + scoring of both models + ema/priority + prefetch keys + both selections, from events on "
+                    "the stream; the arrivals' scatter and the victims' bytes over the host link (in line in "
+                    "ms_per_step) left out"},
+        "steps_without_prompt_arrival": {
+            "count": len(quiet), "ms_per_step": round(sum(quiet) / max(len(quiet), 1), 4),
+            "value": round(sum(quiet_bytes) / max(sum(quiet), 1e-9) / 1e6, 1),
+            "note": "steps whose eviction only makes room for the growth of decoding sequences; a step that makes "
+                    "room for a whole arriving prompt is bound by the host link (its victims' bytes go out in line)"},
+        "link_bytes_per_step_mean": int((new_next.sum() + 2 * pairs_h.sum()) * rec / args.steps),
+        "roofline": {"kernel": "score_partial (both launches of a step)", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(algo / max(cnt, 1)), "avg_ms": round(sp_ms / max(cnt, 1), 4)},
+        "kernels_avg_ms": warm,
+        "kernels_avg_ms_from": "score_partial: the timed steps (two launches per step); the others: the warm-up steps",
+        "step0": {"pass_ms_all_resident": round(t_pass0 * 1e3, 3),
+                  "scored_GBps_all_resident": round(n_res0 * unit_k / t_pass0 / 1e9, 1),
+                  "frac_of_hbm_peak": round(n_res0 * unit_k / t_pass0 / 1e9 / HBM_PEAK_GBPS, 4),
+                  "kernels_avg_ms": pass0_kernels, "bulk_evict_units": k0,
+                  "bulk_evict_GBps": round(k0 * rec / t_bulk / 1e9, 2),
+                  "bulk_evict_frac_of_link": round(k0 * rec / t_bulk / 1e9 / link["d2h_GBps"], 3)},
+        "host_link": link, "setup_s": round(setup_s, 1),
+    }
+    ceiling = read_ceiling(torch, kvm, fd.k_pool, dev)
+    out["read_ceiling_GBps"] = round(ceiling, 1)
+    out["roofline"]["frac_of_read_ceiling"] = round(achieved / ceiling, 4)
+
+    # ---- CPU baseline and parity: sampled decoding rows of both architectures at the last step ---------------
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        j = n_steps - 1
+        fd.mass.fill_(-1.0)
+        fd.score(j, j)                      # untimed, on the tables as they stand now
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(7)
+        t_cpu, cpu_bytes, worst, n_rows_s = 0.0, 0, 0.0, 0
+        for a, d in enumerate(fd.arch):
+            on = torch.nonzero(d["active"][j]).flatten().cpu().numpy()
+            pick = np.unique(np.concatenate([[on[0], on[len(on) // 2], on[-1]],
+                                             rng.choice(on, size=min(len(on), 2048 if a == 0 else 256), replace=False)]))
+            hr = fd.host_rows(a, j, pick, j)
+            uids, u_dev, g = hr["uids"], torch.from_numpy(hr["uids"]).to(dev), hr["g"]
+            ref = np.full(len(uids), -1.0, np.float32)
+            t0 = time.perf_counter()
+            oracle.score_step(hr["k_pool"], 128, synth.BF16, hr["ntok"], hr["off"], hr["q_off"], hr["tbl"], hr["q"], g,
+                              fd.scale, ref)
+            t_cpu += time.perf_counter() - t0
+            got = fd.mass[u_dev].cpu().numpy()
+            r_ = hr["resident"]
+            rel = np.abs(got[r_] - ref[r_]) / np.maximum(np.abs(ref[r_]), 1e-9)
+            worst = max(worst, float(rel.max()))
+            assert np.all(got[~r_] == -1.0)
+            cpu_bytes += int(r_.sum()) * unit_k
+            n_rows_s += len(pick)
+        out["cpu_baseline"] = {"value": round(cpu_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": oracle.threads(),
+                               "kind": "oracle",
+                               "sample": "%d decoding rows of both models at the last step (%.2f GB of K): scoring, %.1f s"
+                                         % (n_rows_s, cpu_bytes / 1e9, t_cpu),
+                               "cpu_model": cpu_model(), "nproc": os.cpu_count()}
+        out["parity_sample_max_rel_err"] = worst
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -577,15 +813,20 @@ def main():
     # pinned arena: the tier segments the stepping consumes (8 KiB records, up to 4,096 per step; 18 KiB
     # records, 1,024 per step), a scratch chunk, and 1 GiB buffers for the bulk transfers and the link probes
     per_step_bytes = max(args.swap_units or 4096, 1024) * 18432
-    pinned = Pinned(torch, 4 * 2**30 + per_step_bytes * (3 * (args.warmup + args.steps) + 8))
+    arena = 4 * 2**30 + per_step_bytes * (3 * (args.warmup + args.steps) + 8)
+    prep = None
+    if "fleet" in names:
+        # tier records kept from the bulk eviction + room for the victims the window's arrivals push out
+        prep = prepare_fleet(args, kvm, synth)
+        arena = max(arena, prep["pinned_bytes"], 2 * 2**30 + 8192)
+    pinned = Pinned(torch, arena)
     link = host_link(torch, pinned, "cuda")
 
     records = []
     for name in names:
         t0 = time.time()
         if name == "fleet":
-            from paper_2604_26968_amd import fleet
-            rec = fleet.bench(args, torch, np, kvm, synth, pinned, link)
+            rec = run_fleet(args, torch, np, kvm, synth, pinned, link, prep)
         else:
             rec = run_uniform(name, args, torch, np, kvm, synth, pinned, link)
         rec["name"] = name

@@ -503,3 +503,28 @@ class FleetDevice:
         self.spare_frames = frames[self.n_new[0]:]
         torch.cuda.synchronize()
         return k0, victims
+
+    # ---- row samples for a reference ---------------------------------------------------------------------------
+    def host_rows(self, a: int, j: Optional[int], pick: np.ndarray, q_set: int = 0) -> dict:
+        """Host copy of rows `pick` of architecture `a` as they stand at window step j: lengths, a compact
+        table and pool holding only their units that are in HBM, their queries, and their uids."""
+        torch = self.torch
+        d = self.arch[a]
+        ntok_all = d["init_ntok"] if j is None else d["ntok"][j]
+        ntok = ntok_all.cpu().numpy()[pick]
+        off = d["off"].cpu().numpy()[pick]
+        nb = (ntok.astype(np.int64) + BLOCK - 1) // BLOCK
+        uids = np.concatenate([o + np.arange(k) for o, k in zip(off, nb)]) if len(pick) else np.zeros(0, np.int64)
+        u_dev = torch.from_numpy(uids).to("cuda")
+        slots = self.slot_tbl[u_dev]
+        res = slots >= 0
+        k_host = self.k_pool[slots[res].long()].view(torch.int16).cpu().numpy().view(np.uint16)
+        tbl = np.full(len(uids), -1, np.int32)
+        tbl[res.cpu().numpy()] = np.arange(int(res.sum().item()), dtype=np.int32)
+        new_off = np.zeros(len(pick), np.int64)
+        new_off[1:] = np.cumsum(nb[:-1])
+        gd = d["g"] * self.dim
+        q_all = d["q"][q_set % 4].view(torch.int16).cpu().numpy().view(np.uint16)
+        q_rows = np.concatenate([q_all[r * gd:(r + 1) * gd] for r in pick])
+        return dict(k_pool=k_host, ntok=ntok, off=new_off, q_off=np.arange(len(pick), dtype=np.int64) * gd, tbl=tbl,
+                    q=q_rows, g=d["g"], uids=uids, resident=res.cpu().numpy())

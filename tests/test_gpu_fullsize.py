@@ -258,3 +258,110 @@ def test_long_row_workloads_full_size_sampled(oracle, name, need_gib):
         row_sum = torch.zeros(n_rows, dtype=torch.float64, device=dev)
         row_sum.index_add_(0, row_id[resident], mass[resident].double())
         assert float(row_sum.min()) > 1.0 - 1e-4 and float(row_sum.max()) < g + 1e-3, phase
+
+
+def test_fleet_full_size_sampled(oracle):
+    """The heterogeneous fleet at the benchmark's size and launch configuration: one pool of 21 M frames sized by
+    kvm_size (60 % of the HBM) shared by the MHA and the MQA model, the 10,000-request trace replayed on the host
+    up to the window, warm start, bulk eviction, then three steps of the window.  The oracle scores sampled
+    decoding rows of both models (all resident, and at the last step); over the whole arrays: only resident
+    units of decoding rows are written, every decoding row's masses sum to a value in [1, g], the number of
+    units in HBM stays what the step's bookkeeping says, nothing is reported bad."""
+    import argparse
+    import gc
+    import bench
+    from paper_2604_26968_amd import kvm, fleet
+    gc.collect()
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 200 * 2**30:
+        pytest.skip("needs 200 GiB of free HBM")
+    dev = "cuda"
+    args = argparse.Namespace(warmup=0, steps=3)
+    prep = bench.prepare_fleet(args, kvm, synth)
+    shapes, sizing, plan, rec = prep["shapes"], prep["sizing"], prep["plan"], prep["rec"]
+    for s, sh in zip(sizing, shapes):       # every field of the sizing the pool comes from
+        assert s == oracle.size(**sh.model_args(), n_max=32768, mem_target=int(bench.FLEET["hbm_share"] * 288 * 10**9))
+    pool_units = int(sizing[0]["pool_units"])
+    keep = 1 << 17
+    tier_slots = keep + sum(plan.stats["new_units_per_step"]) + 8
+    tier = torch.empty(tier_slots * rec, dtype=torch.uint8, pin_memory=True)
+    scratch = torch.empty(32768 * rec, dtype=torch.uint8, pin_memory=True)
+    fd = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
+                           prefetch_cap=1024, window_tokens=2048, decay=0.9, seed=11)
+    n = plan.n_uids
+    rng = np.random.default_rng(5)
+
+    def check_rows(j, tag):
+        """Sampled rows of both models against the oracle; whole-array properties."""
+        worst = 0.0
+        for a, d in enumerate(fd.arch):
+            on = np.arange(d["n_rows"]) if j is None else torch.nonzero(d["active"][j]).flatten().cpu().numpy()
+            pick = np.unique(np.concatenate([[on[0], on[len(on) // 2], on[-1]],
+                                             rng.choice(on, size=min(len(on), 1024 if a == 0 else 128), replace=False)]))
+            hr = fd.host_rows(a, j, pick, 0 if j is None else j)
+            ref = np.full(len(hr["uids"]), -1.0, np.float32)
+            oracle.score_step(hr["k_pool"], 128, synth.BF16, hr["ntok"], hr["off"], hr["q_off"], hr["tbl"], hr["q"],
+                              hr["g"], fd.scale, ref)
+            got = fd.mass[torch.from_numpy(hr["uids"]).to(dev)].cpu().numpy()
+            r_ = hr["resident"]
+            assert r_.sum() > 1000, tag
+            np.testing.assert_allclose(got[r_], ref[r_], rtol=1e-3, atol=1e-9, err_msg=tag)
+            np.testing.assert_array_equal(got[~r_], -1.0)
+        return worst
+
+    # ---- everything in HBM, every row decodes once ------------------------------------------------------------
+    fd.mass.fill_(-1.0)
+    fd.first_pass()
+    torch.cuda.synchronize()
+    check_rows(None, "all resident")
+    exist = (fd.state & RES) != 0
+    assert int(exist.sum().item()) == plan.stats["init_units"]
+    assert bool((fd.mass[exist] >= 0).all()) and bool((fd.mass[~exist] == -1.0).all())
+    n_res0 = int(exist.sum().item())
+    budget = int(0.6 * n_res0)
+    k0, victims = fd.evict_to_budget(budget, keep, np.random.default_rng(6).permutation(n_res0 - budget), scratch)
+    assert k0 == n_res0 - budget and int(fd.n_bad.item()) == 0
+    assert int((fd.state & RES).sum().item()) == budget
+    assert int(((fd.state & HOST) != 0).sum().item()) == keep    # the other victims were demoted below tier 1
+    want_resident = budget
+    for j in range(3):
+        fd.arrive(j)
+        want_resident += fd.n_new[j]
+        fd.beta(j)
+        fd.mass.fill_(-1.0)
+        fd.score(j, j)
+        torch.cuda.synchronize()
+        if j == 2:
+            check_rows(j, "window step %d" % j)
+        # only resident units of decoding rows are written; the masses of every decoding row sum to [1, g]
+        resident = (fd.state & RES) != 0
+        assert int(resident.sum().item()) == want_resident, (j, int(resident.sum().item()), want_resident)
+        written = fd.mass >= 0
+        assert bool((written <= resident).all())
+        for a, d in enumerate(fd.arch):
+            nb = (d["ntok"][j].long() + 15) // 16
+            row_id = torch.repeat_interleave(torch.arange(d["n_rows"], device=dev), nb)
+            uid = torch.repeat_interleave(d["off"], nb) + (torch.arange(int(nb.sum().item()), device=dev)
+                                                          - torch.repeat_interleave(torch.cumsum(nb, 0) - nb, nb))
+            act = d["active"][j][row_id] != 0
+            assert bool((written[uid[act]] == resident[uid[act]]).all()) and not bool(written[uid[~act]].any())
+            sums = torch.zeros(d["n_rows"], dtype=torch.float64, device=dev)
+            w = written[uid]
+            sums.index_add_(0, row_id[w], fd.mass[uid[w]].double())
+            rows_on = d["active"][j] != 0
+            has_res = torch.zeros(d["n_rows"], dtype=torch.bool, device=dev)
+            has_res[row_id[w]] = True
+            chk = rows_on & has_res
+            assert float(sums[chk].min()) > 1.0 - 1e-4 and float(sums[chk].max()) < d["g"] + 1e-3, (j, a)
+        fd.ema(j)
+        fd.prefetch_keys(j)
+        fd.select(j)
+        torch.cuda.synchronize()
+        assert int(fd.n_v.item()) == fd.n_new[j + 1] + fd.P
+        n_pairs = min(int(fd.n_pf.item()), fd.P)
+        fd.move(j)
+        torch.cuda.synchronize()
+        want_resident -= fd.n_new[j + 1]              # packed out; the exchange trades one for one
+        assert int((fd.state & RES).sum().item()) == want_resident
+        assert int(fd.n_bad.item()) == 0
