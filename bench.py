@@ -153,6 +153,88 @@ def cpu_model():
         return "unknown"
 
 
+def run_refined(args, torch, np, kvm, v):
+    """The pass with every refinement switched on (blended reuse estimate, EMA with positional decay and
+    transition multipliers, attention-span windows, a prefetch list chosen on the device by position and
+    served by the in-place exchange, content hashes of the units that entered HBM and the reference-counted
+    store), continued from the state the other step orders left.  `v`: the locals of run_uniform."""
+    dev = "cuda"
+    shape, wl, rows, pool, swap, budget = v["shape"], v["wl"], v["rows"], v["pool"], v["swap"], v["budget"]
+    n, n_rows, decay, row_weight = v["n"], v["n_rows"], v["decay"], v["row_weight"]
+    mass, S, prio, hits, misses, p_hat, n_bad, n_victims = (v[k] for k in ("mass", "S", "prio", "hits", "misses",
+                                                                           "p_hat", "n_bad", "n_victims"))
+    ws, ws_select, qs, evs, scale, host_tier = v["ws"], v["ws_select"], v["qs"], v["evs"], v["scale"], v["host_tier"]
+    step_victims, xf_frame, xf_host, tier_slots = v["step_victims"], v["xf_frame"], v["xf_host"], v["tier_slots"]
+    main, side, n_q_sets = v["main"], v["side"], v["n_q_sets"]
+    L, lh = shape.n_layers, shape.n_layers * shape.n_kv_heads
+    rng = np.random.default_rng(17)
+    head_idx = (np.arange(n_rows) % lh).astype(np.int32)
+    row_layer = torch.from_numpy(head_idx // shape.n_kv_heads).to(dev)
+    n_seqs = len(shape.seq_lens)
+    ex = kvm.make_ema_ex(0.9995, torch.from_numpy(wl.row_seq).to(dev), torch.from_numpy(head_idx).to(dev),
+                         torch.from_numpy(rng.choice(np.array([0, 1, 2, 3, 255], np.uint8), n_seqs)).to(dev),
+                         torch.from_numpy((0.5 + rng.random((4, lh))).astype(np.float32)).to(dev))
+    win = torch.full((16, 256), 255, dtype=torch.uint8, device=dev)
+    win_head = torch.zeros(16, dtype=torch.int32, device=dev)
+    conf = torch.zeros(16, dtype=torch.float32, device=dev)
+    p_blend = torch.zeros(16, dtype=torch.float32, device=dev)
+    span_sum = torch.zeros(L, dtype=torch.int64, device=dev)
+    span_cnt = torch.zeros(L, dtype=torch.int32, device=dev)
+    layer_window = torch.full((L,), 1 << 30, dtype=torch.int32, device=dev)
+    ws_span = torch.empty(max(kvm.kvm_workspace_bytes(kvm.OP_SPAN, n, n_rows), 256), dtype=torch.uint8, device=dev)
+    pf_key = torch.zeros(n, dtype=torch.float32, device=dev)
+    pf_cand = torch.zeros(n, dtype=torch.uint8, device=dev)
+    n_pf = torch.zeros(1, dtype=torch.int64, device=dev)
+    pf_list = torch.full((swap,), -1, dtype=torch.int64, device=dev)
+    arrived = torch.full((swap,), -1, dtype=torch.int64, device=dev)      # the units that came in one step ago
+    store = kvm.make_store(1 << 22)
+    digests = torch.zeros((swap, 32), dtype=torch.uint8, device=dev)
+    canon = torch.zeros(swap, dtype=torch.int64, device=dev)
+    dedup_ws = torch.zeros(swap, dtype=torch.int64, device=dev)
+
+    def step(i):
+        ev = evs[i % n_q_sets]
+        # The hash of the units that entered HBM in the previous step (one SHA-256 chain per unit: 0.5 ms of
+        # latency for 16 wavefronts of work), the reuse estimates and the victims (from the priorities the
+        # previous step left) are worked out on a second stream beside the scoring launch.
+        side.wait_stream(main)
+        kvm.kvm_beta_blend_update(ev[0], ev[1], hits, misses, win, win_head, 64.0, p_hat, conf, p_blend, n_bad=n_bad,
+                                  stream=side)
+        kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws_select, k=-1, budget_units=budget - swap,
+                               stream=side)
+        kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, arrived, swap, digests, stream=side)
+        kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
+        main.wait_stream(side)
+        kvm.kvm_dedup_insert(store, digests, arrived, swap, canon, dedup_ws)
+        kvm.kvm_ema_update_ex(rows, mass, decay, ex, row_weight, wl.pair, p_blend, wl.state, S, prio)
+        kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window,
+                            ws_span)
+        kvm.kvm_exchange_end(wl.slot_tbl, wl.state, pf_list, xf_frame, swap)
+        arrived.copy_(pf_list)
+        kvm.kvm_prefetch_keys(rows, row_layer, wl.row_ntok, layer_window, wl.state, wl.pair, p_blend, 0.9995,
+                              pf_key, pf_cand)
+        kvm.kvm_select_victims(pf_key, pf_cand, pf_list, n_pf, ws, k=swap)
+        kvm.kvm_exchange_begin(pool, wl.slot_tbl, wl.state, step_victims, pf_list, swap, tier_slots, xf_frame, xf_host,
+                               n_out_dev=n_victims, n_in_dev=n_pf, n_bad=n_bad)
+
+    res = v["run_mode"](step, 0)
+    kvm.kvm_score_step_xfer(pool, rows, qs[0], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
+    kvm.kvm_exchange_end(wl.slot_tbl, wl.state, pf_list, xf_frame, swap)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0, int(n_bad.item())
+    res["value"] = round(budget * shape.unit_k_bytes / (res["ms_per_step"] * 1e-3) / 1e9, 1)
+    res["note"] = "all refinements on; selection, estimates and content hashes beside the scoring launch"
+    # bulk hashing rate (checkpoint-style pass over many units): integer-ALU bound, one lane per unit
+    n_bulk = min(1 << 18, budget)
+    rec = shape.unit_k_bytes + shape.unit_v_bytes
+    bulk_uids = torch.nonzero(wl.state & 1).flatten()[:n_bulk].contiguous()
+    bulk_digests = torch.zeros((n_bulk, 32), dtype=torch.uint8, device=dev)
+    kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, bulk_uids, n_bulk, bulk_digests)
+    t_hash = timed(torch, lambda: kvm.kvm_hash_units(pool, wl.slot_tbl, wl.state, bulk_uids, n_bulk, bulk_digests))
+    res["hash_bulk"] = {"units": n_bulk, "ms": round(t_hash * 1e3, 3), "GBps": round(n_bulk * rec / t_hash / 1e9, 1)}
+    return res
+
+
 def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
     """One configuration whose rows all belong to one architecture (configurations 2, 3, 4)."""
     dev = "cuda"
@@ -205,11 +287,13 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
     budget = int(w_budget * n_res0)
     k0 = n_res0 - budget
     swap = args.swap_units or w_swap
-    n_modes = 3
+    n_modes = 4 if args.refined else 3
     steps_all = n_modes * (args.warmup + args.steps) + 4          # segments of the tier the stepping consumes
     n_bulk = min((1 << 30) // rec, k0 // 4)                       # records of the bulk transfer measurements (1 GiB)
     keep = swap * (steps_all + 2) + n_bulk                        # tier records that are read again later
     assert keep <= k0, "not enough host-resident units for this many steps"
+    if args.refined:
+        keep = k0          # a prefetch list chosen on the device can name any unit of tier 1: all records are kept
     chunk = min(k0, 32768)
 
     # Tier 1 keeps the records that later steps prefetch; the rest of the bulk eviction goes through a
@@ -218,7 +302,6 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
     host_tier = pinned.take(keep * rec)[:keep * rec]
     host_scratch = pinned.take(chunk * rec)[:chunk * rec]
     bulk_out = pinned.take(n_bulk * rec)[:n_bulk * rec]
-    fused_out = [pinned.take(swap * rec)[:swap * rec] for _ in range(2)]
     victims = torch.zeros(k0, dtype=torch.int64, device=dev)
     freed = torch.full((k0,), -1, dtype=torch.int32, device=dev)
     host_slots = torch.arange(k0, dtype=torch.int32, device=dev)
@@ -267,7 +350,6 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
     assert int((wl.state & 1).sum().item()) == budget
 
     step_victims = torch.zeros(swap, dtype=torch.int64, device=dev)
-    step_freed = torch.full((swap,), -1, dtype=torch.int32, device=dev)
     main = torch.cuda.current_stream()
     side = torch.cuda.Stream()
     xf_frame = torch.full((swap,), -1, dtype=torch.int32, device=dev)
@@ -318,18 +400,17 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
         xf_frame.fill_(-1)
 
     def step_in_line(i):
-        """Everything in line on one stream, the bytes included: the victims of this step leave and the next
-        prefetch segment enters through one fused two-way kernel after the selection.  Resident units at
-        entry: budget + swap."""
+        """Everything in line on one stream, the bytes included: the victims of this step and the next prefetch
+        segment trade places in the slot-addressed tier through one two-way kernel after the selection.
+        Resident units at entry: budget + swap."""
         ev = evs[i % n_q_sets]
         kvm.kvm_beta_update(ev[0], ev[1], hits, misses, p_hat, n_bad=n_bad)
         kvm.kvm_score_step(pool, rows, qs[i % n_q_sets], scale, mass, ws)
         kvm.kvm_ema_update(rows, mass, decay, row_weight, wl.pair, p_hat, wl.state, S, prio)
         kvm.kvm_select_victims(prio, wl.state, step_victims, n_victims, ws, k=-1, budget_units=budget)
         nxt = (i + 1) * swap
-        kvm.kvm_swap(pool, wl.slot_tbl, wl.state, step_victims, host_uids[nxt:nxt + swap], swap,
-                     host_slots[nxt:nxt + swap], step_freed, fused_out[i & 1],
-                     host_tier[nxt * rec:(nxt + swap) * rec], n_bad=n_bad, n_dev=n_victims)
+        kvm.kvm_exchange(pool, wl.slot_tbl, wl.state, step_victims, host_uids[nxt:nxt + swap], swap, host_tier,
+                         n_out_dev=n_victims, n_bad=n_bad)
 
     def run_mode(step_fn, first, dominant=False):
         """args.warmup untimed + args.steps timed steps of step_fn, step numbers from `first`."""
@@ -421,7 +502,7 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
             "pipelined": dict(pipelined, value=round(scored_bytes / (pipelined["ms_per_step"] * 1e-3) / 1e9, 1),
                               note="victims chosen beside the scoring launch from the previous step's priorities"),
             "in_line": dict(in_line, value=round((budget + swap) * shape.unit_k_bytes / (in_line["ms_per_step"] * 1e-3) / 1e9, 1),
-                            note="bytes moved by one fused two-way kernel after the selection"),
+                            note="bytes moved in line by kvm_exchange after the selection"),
         },
         "roofline": roofline,
         "kernels_avg_ms": in_order["kernels_avg_ms"],
@@ -488,6 +569,9 @@ def run_uniform(name, args, torch, np, kvm, synth, pinned, link):
     ceiling = read_ceiling(torch, kvm, wl.k_pool, dev)
     out["read_ceiling_GBps"] = round(ceiling, 1)
     out["roofline"]["frac_of_read_ceiling"] = round(achieved / ceiling, 4)
+
+    if args.refined:
+        out["step_orders"]["refined"] = run_refined(args, torch, np, kvm, locals())
 
     # ---- CPU baseline: the oracle on a bounded sample of the same workload -------------------------
     if not args.no_cpu_baseline:
@@ -794,6 +878,9 @@ def main():
                          "Llama-3-8B-shaped, MLA and fleet configurations under 'workloads'")
     ap.add_argument("--n-seq", type=int, default=0, help="sequences in the batch (0 = the workload's own number)")
     ap.add_argument("--swap-units", type=int, default=0, help="units evicted and prefetched per step (0 = workload default)")
+    ap.add_argument("--refined", action="store_true",
+                    help="also time the pass with every refinement switched on (single-architecture workloads; "
+                         "keeps all of tier 1 in pinned memory)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
@@ -814,6 +901,8 @@ def main():
     # records, 1,024 per step), a scratch chunk, and 1 GiB buffers for the bulk transfers and the link probes
     per_step_bytes = max(args.swap_units or 4096, 1024) * 18432
     arena = 4 * 2**30 + per_step_bytes * (3 * (args.warmup + args.steps) + 8)
+    if args.refined:
+        arena = max(arena, 24 * 2**30)
     prep = None
     if "fleet" in names:
         # tier records kept from the bulk eviction + room for the victims the window's arrivals push out
