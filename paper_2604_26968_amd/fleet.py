@@ -202,7 +202,8 @@ def build_plan(shapes: List[synth.Shape], catalogues, requests: List[synth.Fleet
 
     # ---- arena: window entries only, rows of an entry adjacent, one uid range per row ---------------------
     win_entries = [i for i, e in enumerate(entries) if e.in_window and e.status != RETIRED]
-    n_rows = [0, 0]
+    n_arch = len(shapes)
+    n_rows = [0] * n_arch
     base = 0
     for i in win_entries:
         e = entries[i]
@@ -219,7 +220,7 @@ def build_plan(shapes: List[synth.Shape], catalogues, requests: List[synth.Fleet
 
     pair = np.zeros(n_uids, np.uint8)
     init_parts = []
-    init_ntok = [np.zeros(n_rows[a], np.int32) for a in range(2)]
+    init_ntok = [np.zeros(n_rows[a], np.int32) for a in range(n_arch)]
     for i in win_entries:
         e = entries[i]
         pair[unit_ids(e, 0, e.cap)] = np.tile(np.asarray(e.blk_pair[:e.cap], np.uint8), upb[e.model])
@@ -262,7 +263,7 @@ def build_plan(shapes: List[synth.Shape], catalogues, requests: List[synth.Fleet
         prev_prot = dict(cur)
 
     stats = dict(requests_replayed=req_i, hits=n_hit, misses=n_miss, retired=n_retired, entries=len(win_entries),
-                 entries_by_model=[sum(1 for i in win_entries if entries[i].model == a) for a in range(2)],
+                 entries_by_model=[sum(1 for i in win_entries if entries[i].model == a) for a in range(n_arch)],
                  active_per_step=[len(r["active"]) for r in win_steps],
                  new_units_per_step=[int(len(u)) for u in new_uids], init_units=int(len(init_units)),
                  events_per_step=[int(len(e[0])) for e in events])
@@ -409,6 +410,8 @@ class FleetDevice:
                                         self.state, self.S, self.prio)
 
     def prefetch_keys(self, j: int):
+        if not self.P:
+            return
         for a, d in enumerate(self.arch):
             if d["n_rows"]:
                 self.kvm.kvm_prefetch_keys(self.rows(a, j), d["layer"], d["pos"][j], d["window"], self.state, self.pair,
@@ -418,7 +421,8 @@ class FleetDevice:
         """One selection of victims over the shared pool (room for the next step's new units + the units
         that trade places with prefetched ones) and one of the prefetch list."""
         kvm = self.kvm
-        kvm.kvm_select_victims(self.key, self.cand, self.pf_list, self.n_pf, self.ws, k=self.P)
+        if self.P:
+            kvm.kvm_select_victims(self.key, self.cand, self.pf_list, self.n_pf, self.ws, k=self.P)
         k = self.n_new[j + 1] + self.P
         self.victims.fill_(-1)
         kvm.kvm_select_victims(self.prio, self.state, self.victims[:max(k, 1)], self.n_v, self.ws, k=k)

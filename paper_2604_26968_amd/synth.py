@@ -438,3 +438,11 @@ def fleet_requests(n_requests: int, seed: int, rate: float, n_prefixes: int, cat
         gap = [1 + int(rng.exponential(mean_gap)) for _ in range(turns - 1)]
         out.append(FleetRequest(int(t), model, prefix, prompt, plen, decode, gap))
     return out
+
+
+def growing_batch_requests(seq_lens: List[int]) -> List[FleetRequest]:
+    """A batch that only decodes: every sequence is there from step 0 with its prompt and appends one token
+    per step for ever (no prefix, one endless turn).  Replayed by the fleet's plan builder this gives the
+    Llama-3-8B-shaped configuration's growth: a new block, hence new units, whenever a sequence crosses a block
+    boundary, the block being written PROTECTED."""
+    return [FleetRequest(0, 0, 0, int(n), 0, [1 << 30], []) for n in seq_lens]

@@ -83,13 +83,15 @@ class FleetRef:
                                   self.S, self.prio, row_active=act)
 
     def prefetch_keys(self, j):
+        if not self.P:
+            return
         for a, d in enumerate(self.arch):
             if d["n_rows"]:
                 self.o.prefetch_keys(d["ntok"][j], d["off"], d["layer"], d["pos"][j], d["window"], self.state, self.pair,
                                      self.p_hat, self.pos_decay, self.key, self.cand)
 
     def select(self, j):
-        self.pf_list = self.o.select_victims(self.key, self.cand, k=self.P)
+        self.pf_list = self.o.select_victims(self.key, self.cand, k=self.P) if self.P else np.zeros(0, np.int64)
         self.victims = self.o.select_victims(self.prio, self.state, k=self.n_new[j + 1] + self.P)
 
     def move(self, j):
