@@ -48,16 +48,18 @@ WORKLOADS = {
 }
 DEFAULT_ORDER = ["llama70b", "llama8b", "mla", "fleet"]
 
-# HBM bytes per launch of the tile kernel from rocprofv3 --pmc (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB), with
-# the transfer workgroups riding along, one entry per workload at its default size.  Each entry names the
-# summary it comes from and the library version whose kernels were profiled: a run of any other version
-# reports traffic null, because the counters no longer describe its kernels.
+# HBM bytes per scoring launch from rocprofv3 --pmc (FETCH_SIZE x 2 KiB + WRITE_SIZE x 1 KiB, mean over the 20
+# timed steps, all scoring kernels of a step divided by its scoring launches), one entry per workload at its
+# default size and default --steps/--warmup.  Each entry names the summary it comes from and the library version
+# whose kernels were profiled: a run of any other version, size or step count reports traffic null, because the
+# counters no longer describe what it launches.
 PROFILED_TRAFFIC = {
-    "llama8b_static": ("0.2", "profiles/score_tile_dot2_llama8b_pmc.md", int(6624641.7 * 2048 + 37636.7 * 1024)),
-    "llama70b": ("0.2", "profiles/score_tile_dot2_llama70b_pmc.md", int(21135248.4 * 2048 + 394499.4 * 1024)),
-    "mla": ("0.2", "profiles/score_tile_wide_mla_pmc.md", int(14707914.7 * 2048 + 840307.0 * 1024)),
-    "mha": ("0.2", "profiles/score_tile_dot2_mha_pmc.md", int(8385917.2 * 2048 + 38958.0 * 1024)),
-    "mqa": ("0.2", "profiles/score_tile_mfma_mqa_pmc.md", int(7100460.9 * 2048 + 77685.8 * 1024)),
+    "llama70b": ("0.3", "profiles/score_row_dot2_llama70b.md", int(21062935.6 * 2048 + 147102.7 * 1024)),
+    "llama8b": ("0.3", "profiles/score_tile_dot2_llama8b_growing.md", int((6612857.2 + 18.0) * 2048 + 22260.8 * 1024)),
+    "mla": ("0.3", "profiles/score_tile_wide_mla.md",
+            int((14707484.5 + 416518.4) * 2048 + (840307.0 + 15347.0) * 1024)),
+    "fleet": ("0.3", "profiles/score_tile_fleet.md",
+              int(((11188650.8 + 7090.9 + 784008.8 + 11504.3) * 2048 + (27588.5 + 1875.3 + 23777.2 + 701.1) * 1024) / 2)),
 }
 KERNEL_NAMES = ("score_plan", "score_partial", "score_finalize", "ema_prio", "beta", "select_hist", "select_emit",
                 "pack", "unpack", "swap", "span", "prefetch_keys", "hash", "dedup", "exchange_flip")
@@ -830,6 +832,9 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
                   for j in range(args.warmup, n_steps) for a in range(len(shapes)))
     algo = float(scored_h.sum()) * (unit_k + 4) + blocks_active * 4 + q_bytes
     achieved = algo / (sp_ms * 1e-3) / 1e9
+    prof = PROFILED_TRAFFIC.get(prep["name"])
+    at_defaults = args.steps == 20 and args.warmup == 5 and not args.n_seq
+    traffic = prof[2] if (prof and prof[0] == kvm.kvm_version() and at_defaults) else None
     warm["score_partial"] = round(sp_ms / max(cnt, 1), 4)
     out = {
         "value": round(value, 1), "unit": "GB/s", "ms_per_step": round(elapsed / args.steps * 1e3, 4),
@@ -861,7 +866,8 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
                     "room for a whole arriving prompt is bound by the host link (its victims' bytes go out in line)"},
         "link_bytes_per_step_mean": int((new_next.sum() + 2 * pairs_h.sum()) * rec / args.steps),
         "roofline": {"kernel": "score_partial (all scoring launches of a step)", "bound": "hbm", "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_from": (prof[1] + " (library " + prof[0] + ")") if traffic else None,
                      "algorithmic_bytes_per_launch": int(algo / max(cnt, 1)), "avg_ms": round(sp_ms / max(cnt, 1), 4)},
         "kernels_avg_ms": warm,
         "kernels_avg_ms_from": "score_partial: the timed steps (one launch per architecture and step); the others: the "
@@ -953,9 +959,9 @@ def main():
     preps = {}
     if "fleet" in names:
         # tier records kept from the bulk eviction + room for the victims the window's arrivals push out
-        preps["fleet"] = prepare_fleet(args, kvm, synth)
+        preps["fleet"] = dict(prepare_fleet(args, kvm, synth), name="fleet")
     if "llama8b" in names:
-        preps["llama8b"] = prepare_growing(args, kvm, synth, np)
+        preps["llama8b"] = dict(prepare_growing(args, kvm, synth, np), name="llama8b")
     for pr in preps.values():
         arena = max(arena, pr["pinned_bytes"], 2 * 2**30 + 8192)
     pinned = Pinned(torch, arena)
