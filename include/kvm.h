@@ -330,7 +330,7 @@ int kvm_select_victims(const float* prio /* dev [n_uids] */, const uint8_t* stat
  * Errors: as kvm_select_victims; KVM_ENOSPC when n_uids exceeds
  * KVM_SELECT_STATIC_MAX_UIDS (nothing is launched).                          */
 #define KVM_SELECT_STATIC_MAX_UIDS      (1 << 26)
-#define KVM_SELECT_STATIC_SCRATCH_BYTES (20480 + 256 + 2 * (KVM_SELECT_STATIC_MAX_UIDS / 4096) * 4)
+#define KVM_SELECT_STATIC_SCRATCH_BYTES (145408 + 256 + 2 * ((KVM_SELECT_STATIC_MAX_UIDS / 4096) * 4 + 256))
 int kvm_select_victims_static(const float* prio /* dev [n_uids] */, const uint8_t* state /* dev [n_uids] */,
                               int64_t n_uids, int64_t k_or_neg1, int64_t budget_units,
                               int64_t* victims /* dev [victims_cap] */, int64_t victims_cap,

@@ -759,15 +759,20 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
 }
 
 
-// ---- score_row_dot2: one large workgroup per row, block values never leave the chip -----------
+// ---- score_row: one large workgroup per row, block values never leave the chip -----------
 // For launches made of long rows (thousands of blocks each, g <= 8).  The tile kernels hand the
 // block values of a row of several tiles to the row merge through HBM; those stores cost far more
 // than their bytes (measured: 13 % of the launch on rows of 8,192 blocks) and the merge is a second
-// pass.  Here one workgroup of twelve wavefronts owns the whole row: the log-sum-exp of every
-// resident block per query stays in LDS (the 160 KB of a compute unit hold 4,392 blocks of eight
-// queries; what does not fit spills to the workspace and is read back by the same workgroup), the
-// row's log-sum-exp is folded at the end and the masses are written once.  No plan, no tile
+// pass.  Here one workgroup of eight or twelve wavefronts owns the whole row: the log-sum-exp of
+// every resident block per query stays in LDS (the 160 KB of a compute unit hold 4,456 blocks of
+// eight queries; what does not fit spills to the workspace and is read back by the same workgroup),
+// the row's log-sum-exp is folded at the end and the masses are written once.  No plan, no tile
 // statistics, no merge launch.
+//   - Logits: packed dot products for g < 8.  With eight queries those are 128 vector instructions
+//     per block and the loop runs out of issue slots (the chip also lowers its clock under that
+//     load: 1.8 GHz measured against 2.2 GHz for g 4), so g 8 takes them from the matrix cores:
+//     four 16x16x32 products per block with the queries as a half-empty column tile, 16 registers
+//     of query operands instead of 128 (measured on rows of 8,192 blocks: 6.55 -> 6.38 ms).
 //   - The row is walked in segments of 4,096 blocks: table entries -> compacted list of frames in
 //     LDS (ballot + popcount), then the unit loop.
 //   - Wavefronts take units from the list through a counter in LDS, so a wavefront that starts
@@ -776,11 +781,20 @@ __global__ __launch_bounds__(kThreads) void score_tile_dot2_kernel(
 //     with its last wavefront before that wavefront joins the scoring.
 constexpr int kRowSeg = 4096;
 constexpr int kRowLdsBytes = 160 * 1024;
-// Workgroup size by group size: eight queries in registers leave room for two wavefronts per SIMD
-// (as in the tile kernel), smaller groups for three.
+// Workgroup size by group size: twelve wavefronts for one or two queries in registers, eight otherwise
+// (four queries at twelve wavefronts spill; the matrix-core variant measures the same at eight and twelve).
+#ifndef KVM_ROW_MF_MIN_G
+#define KVM_ROW_MF_MIN_G 8
+#endif
+#ifndef KVM_ROW_MF_THREADS
+#define KVM_ROW_MF_THREADS 512
+#endif
+// Groups of at least this many queries take their logits from the matrix cores in the row kernel.
+constexpr int kRowMfMinG = KVM_ROW_MF_MIN_G;
 template <int G>
 struct RowShape {
-    static constexpr int kThreads = G >= 8 ? 512 : 768;
+    static constexpr bool kMf = G >= kRowMfMinG;
+    static constexpr int kThreads = kMf ? KVM_ROW_MF_THREADS : G >= 4 ? 512 : 768;
     static constexpr int kWaves = kThreads / 64;
     static constexpr int kE = (kRowSeg + kThreads - 1) / kThreads;              // table entries per thread and segment
     static constexpr int kFixed = kRowSeg * 4 + 512 + kThreads * 8 + 256;        // list, counts, reduction, misc
@@ -870,7 +884,7 @@ __device__ __forceinline__ int row_segment_rank(const int (&slot)[E], int* s_slo
 }
 
 template <int G, int DIM, int DT>
-__global__ __launch_bounds__(RowShape<G>::kThreads) void score_row_dot2_kernel(PlanRows pr, RowArgs a, Xfer xf) {
+__global__ __launch_bounds__(RowShape<G>::kThreads) void score_row_kernel(PlanRows pr, RowArgs a, Xfer xf) {
     static_assert(G == 1 || G == 2 || G == 4 || G == 8, "power-of-two group sizes only");
     using RS = RowShape<G>;
     constexpr int THREADS = RS::kThreads, WAVES = RS::kWaves, E = RS::kE, CAP = RS::kCap;
@@ -909,17 +923,24 @@ __global__ __launch_bounds__(RowShape<G>::kThreads) void score_row_dot2_kernel(P
     const int nb = (int)(((uint32_t)ntok + 15u) >> 4);
     const int64_t uid0 = pr.row_off[row];
     const int tail = ntok - 16 * (nb - 1);                                // tokens of the last block, 1..16
-    const int t = lane & 15, cg = lane >> 4;
+    constexpr bool MF = RS::kMf;
+    const int t = lane & 15, cg = lane >> 4;   // dot2: token and channel group; MF: query column and token group
     const uint4* qrow = reinterpret_cast<const uint4*>(a.q + pr.row_q_off[row]);
     // table entries of the first segment, the queries and whether the row's last block is in HBM: one round trip
     int slot_cur[E], slot_nxt[E];
     row_segment_load<THREADS, E>(slot_tbl, uid0, min(kRowSeg, nb), n_slots, slot_cur);
     const bool last_resident = (uint32_t)slot_tbl[uid0 + nb - 1] < n_slots;
-    uint4 qv[G][NK];
+    // dot2: every lane holds its channel group of all G queries; MF: the B operands of one 16-column tile
+    // (column = query t, zero beyond G)
+    constexpr int NQ = MF ? 1 : G;
+    uint4 qv[NQ][NK];
 #pragma unroll
-    for (int j = 0; j < G; ++j)
+    for (int j = 0; j < NQ; ++j)
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) qv[j][kk] = qrow[j * QROW_V4 + 4 * kk + cg];
+        for (int kk = 0; kk < NK; ++kk) {
+            if constexpr (MF) qv[j][kk] = t < G ? qrow[t * QROW_V4 + 4 * kk + cg] : make_uint4(0, 0, 0, 0);
+            else qv[j][kk] = qrow[j * QROW_V4 + 4 * kk + cg];
+        }
 
     int rank_keep[KEEP][E], nseg_keep[KEEP] = {0, 0};
     int n_tot = 0;                                                        // resident blocks so far (uniform)
@@ -949,8 +970,33 @@ __global__ __launch_bounds__(RowShape<G>::kThreads) void score_row_dot2_kernel(P
                 return idx < n_seg ? idx : -1;
             };
             auto unit = [&](const uint4 (&cur)[NK], int i) {
-                const bool valid = !(last_listed && i == n_seg - 1) || t < tail;
                 const int vi = n_tot + i;
+                if constexpr (MF) {
+                    // [16 tokens x DIM] . [DIM x 16 queries]: lane holds tokens 4 cg + 0..3 of query t
+                    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) acc = mfma16<DT>(cur[kk], qv[0][kk], acc);
+                    const int ntk = (last_listed && i == n_seg - 1) ? tail : 16;
+                    float z[4];
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        z[r] = 4 * cg + r < ntk ? acc[r] * scale : -INFINITY;
+                        mx = fmaxf(mx, z[r]);
+                    }
+                    mx = rows4_max(mx);                       // a block has at least one token: finite
+                    float sm = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sm += __expf(z[r] - mx);
+                    sm = rows4_sum(sm);
+                    if (cg == 0 && t < G) {
+                        const float lse = mx + __logf(sm);
+                        if (vi < CAP) s_val[vi * G + t] = lse;
+                        else spill[(size_t)(uid0 + vi) * G + t] = lse;
+                    }
+                    return;
+                }
+                const bool valid = !(last_listed && i == n_seg - 1) || t < tail;
 #pragma unroll
                 for (int j0 = 0; j0 < G; j0 += 4) {
                     float acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -958,7 +1004,7 @@ __global__ __launch_bounds__(RowShape<G>::kThreads) void score_row_dot2_kernel(P
                     for (int jj = 0; jj < 4; ++jj)
                         if (j0 + jj < G) {
 #pragma unroll
-                            for (int kk = 0; kk < NK; ++kk) acc[jj] = dot8<DT>(cur[kk], qv[(j0 + jj) % G][kk], acc[jj]);
+                            for (int kk = 0; kk < NK; ++kk) acc[jj] = dot8<DT>(cur[kk], qv[(j0 + jj) % NQ][kk], acc[jj]);
                         }
                     const float z = fold_rows(fold_halves(acc[0], acc[1]), fold_halves(acc[2], acc[3])) * scale;
                     const float zz = valid ? z : -INFINITY;
@@ -1672,14 +1718,14 @@ int launch_dot2_path(const ScoreArgs& a) {
 
 template <int G, int DIM, int DT>
 int launch_row_path(const ScoreArgs& a) {
-    auto kern = score_row_dot2_kernel<G, DIM, DT>;
+    auto kern = score_row_kernel<G, DIM, DT>;
     KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     kRowLdsBytes));
     RowArgs ra{a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
                static_cast<const uint16_t*>(a.q), a.scale, a.out.agg, a.out.mass, a.w.part};
     TimedLaunch tl("score_partial", a.st);
     kern<<<(unsigned)a.rows->n_rows, RowShape<G>::kThreads, kRowLdsBytes, a.st>>>(a.pr, ra, a.xf);
-    return launch_status("score_row_dot2");
+    return launch_status("score_row");
 }
 
 template <int NCT, int DIM, int DT>

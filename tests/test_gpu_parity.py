@@ -327,10 +327,12 @@ def test_ema_priority_multi_step(oracle):
 
 
 # -------------------------------------------------------------------- select
-def select_both(oracle, dev, prio, state, k=-1, budget=0, cap=None):
+def select_both(oracle, dev, prio, state, k=-1, budget=0, cap=None, shift=0):
     from paper_2604_26968_amd import kvm
-    dev.prio = torch.from_numpy(prio).cuda()
-    dev.state = torch.from_numpy(state).cuda()
+    # shift > 0: the arrays start `shift` elements into their allocations (no 16-byte alignment)
+    dev.prio = torch.cat([torch.zeros(shift), torch.from_numpy(prio)]).cuda()[shift:]
+    dev.state = torch.cat([torch.zeros(shift, dtype=torch.uint8), torch.from_numpy(state)]).cuda()[shift:]
+    assert shift == 0 or dev.prio.data_ptr() % 16 != 0 or dev.state.data_ptr() % 16 != 0
     dev.victims = torch.full((max(len(prio), 1),), -1, dtype=torch.int64, device="cuda")
     dev.ws = torch.full((max(kvm.kvm_workspace_bytes(kvm.OP_SELECT, len(prio)), 256),), 0x7F, dtype=torch.uint8,
                          device="cuda")
@@ -357,6 +359,34 @@ def test_select_matches_oracle_on_identical_keys(oracle, n, levels):
     select_both(oracle, dev, prio, state, k=-1, budget=int(0.6 * n_res))
     select_both(oracle, dev, prio, state, k=-1, budget=n_res + 3)
     select_both(oracle, dev, prio, state, k=n_el, cap=min(5, n))
+
+
+@pytest.mark.parametrize("n", [4097, 300_000])
+@pytest.mark.parametrize("shift", [1, 3, 4])
+def test_select_arrays_without_vector_alignment(oracle, n, shift):
+    # the emit kernel fetches 16-byte vectors only from aligned arrays; these take its element-wise path
+    rng = np.random.default_rng(n + shift)
+    prio = (np.floor(rng.random(n) ** 4 * 50) / 50).astype(np.float32)
+    state = rng.choice(np.array([RES | SCORED, RES | SCORED, HOST | SCORED, RES | SCORED | PROT], np.uint8), size=n)
+    dev = DeviceCase(synth.tiny_gqa(1))
+    for k in (1, 37, n // 5):
+        select_both(oracle, dev, prio, state, k=k, shift=shift)
+
+
+def test_select_few_victims_among_many_units(oracle):
+    # k far below the number of chunks: most chunks of the emit pass hold nothing to write, and the ties of
+    # the threshold value (a seventh of the units) that are still wanted end in the first chunks
+    n = 1_200_000
+    rng = np.random.default_rng(12)
+    prio = (np.floor(rng.random(n) * 7) / 7 + 0.5).astype(np.float32)
+    lows = rng.choice(n, size=150, replace=False)
+    prio[lows] = rng.random(150).astype(np.float32) * 0.4
+    state = np.full(n, RES | SCORED, np.uint8)
+    state[rng.choice(n, size=n // 10, replace=False)] = HOST | SCORED
+    dev = DeviceCase(synth.tiny_gqa(1))
+    for k in (3, 150, 151, 190, 4000):
+        got = select_both(oracle, dev, prio, state, k=k)
+        assert len(got) == k
 
 
 def test_select_special_values(oracle):
