@@ -194,7 +194,12 @@ int kvm_score_step(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q
  * cannot see (kvm_exchange_begin took them out of the table), so scoring and
  * transfer never touch the same memory; results equal kvm_score_step followed
  * by the same transfer.  n_pairs == 0 is kvm_score_step.
+ * A pair whose xfer_host[i] carries KVM_XFER_OUT_ONLY (what kvm_pack_begin
+ * writes) is one-way: the frame's bytes are copied to host slot
+ * xfer_host[i] & ~KVM_XFER_OUT_ONLY, nothing is read from the host and the
+ * frame keeps its bytes.  Pairs of both kinds may share one list.
  * Errors: as kvm_score_step; KVM_EINVAL for null transfer buffers.           */
+#define KVM_XFER_OUT_ONLY (1ll << 62)
 int kvm_score_step_xfer(const kvm_pool_t* pool, const kvm_rows_t* rows, const void* q,
                         float softmax_scale, int agg, float* mass /* dev [n_uids] */,
                         void* ws, size_t ws_bytes,
@@ -444,6 +449,30 @@ int kvm_exchange_begin(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out *
 int kvm_exchange_end(int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */, int64_t n_uids,
                      const int64_t* in_uids /* dev [n] */, const int32_t* frame /* dev [n] */, int64_t n,
                      void* stream);
+
+/* kvm_pack in two parts against a slot-addressed tier, for evictions whose bytes
+ * may leave while the next step is being scored (demotion off the decode path,
+ * section 3.2):
+ *   kvm_pack_begin  validates entry i as kvm_pack does (uid in range and resident,
+ *       frame inside the pool; here also host_slots[i] in [0, tier_slots)) and
+ *       takes the unit out of HBM in the table (RESIDENT off, ON_HOST on,
+ *       slot_tbl = -1 - host_slots[i]); frame[i] = the frame it held, host[i] =
+ *       host_slots[i] | KVM_XFER_OUT_ONLY; both -1 for a skipped entry (counted in
+ *       *n_bad) and for i at or beyond *n_dev.
+ *   kvm_score_step_xfer(frame, host, n)  copies the frames to their records
+ *       during the next scoring launch.
+ * After that launch tables, state and tier equal what kvm_pack leaves with
+ * staging_host = the tier and record i at slot host_slots[i], and frame[] is
+ * kvm_pack's freed_slots.  Until then the frames still hold the units' bytes and
+ * must not be given to other units; the records are not valid yet, so the units
+ * must not be prefetched in between (a prefetch list built in between could
+ * name them: build it after the launch).
+ * Errors: KVM_EINVAL (null buffers, negative counts, slot ids beyond int32).  */
+int kvm_pack_begin(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+                   int64_t n_uids, const int64_t* uids /* dev [n] */, int64_t n,
+                   const int64_t* n_dev /* dev [1] or NULL */, const int32_t* host_slots /* dev [n] */,
+                   uint64_t tier_slots, int32_t* frame /* dev [n] out */, int64_t* host /* dev [n] out */,
+                   uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
 /* ======================================================================== *
  * 6. Position-aware prefetching — section 3.5.

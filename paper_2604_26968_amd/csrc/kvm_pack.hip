@@ -246,6 +246,35 @@ __global__ __launch_bounds__(kThreads) void exchange_begin_kernel(uint32_t n_slo
     host[i] = slot >= 0 ? h : -1;
 }
 
+// First part of a pack whose bytes move during the next scoring launch: entry i leaves HBM in the table
+// exactly as pack_kernel's thread 0 does it, and the pair (frame, host slot | one-way flag) is noted.
+__global__ __launch_bounds__(kThreads) void pack_begin_kernel(uint32_t n_slots, int32_t* __restrict__ slot_tbl,
+                                                              uint8_t* __restrict__ state, int64_t n_uids,
+                                                              const int64_t* __restrict__ uids, int64_t n,
+                                                              const int64_t* __restrict__ n_dev,
+                                                              const int32_t* __restrict__ host_slots,
+                                                              uint64_t tier_slots, int32_t* __restrict__ frame,
+                                                              int64_t* __restrict__ host, uint32_t* n_bad) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    int32_t slot = -1;
+    int64_t h = -1;
+    if (!(n_dev && i >= *n_dev)) {
+        const int64_t uid = uids[i];
+        h = host_slots[i];
+        if (uid >= 0 && uid < n_uids && (state[uid] & KVM_ST_RESIDENT)) slot = slot_tbl[uid];
+        if ((uint32_t)slot >= n_slots || (uint64_t)h >= tier_slots) slot = -1;
+        if (slot >= 0) {
+            slot_tbl[uid] = (int32_t)(-1 - h);
+            state[uid] = (uint8_t)((state[uid] & ~KVM_ST_RESIDENT) | KVM_ST_ON_HOST);
+        } else if (n_bad) {
+            atomicAdd(n_bad, 1u);
+        }
+    }
+    frame[i] = slot;
+    host[i] = slot >= 0 ? (h | KVM_XFER_OUT_ONLY) : -1;
+}
+
 __global__ __launch_bounds__(kThreads) void exchange_end_kernel(int32_t* __restrict__ slot_tbl,
                                                                 uint8_t* __restrict__ state, int64_t n_uids,
                                                                 const int64_t* __restrict__ in_uids,
@@ -447,6 +476,24 @@ extern "C" int kvm_exchange_begin(const kvm_pool_t* pool, int32_t* slot_tbl, uin
         (uint32_t)pool->n_slots, slot_tbl, state, n_uids, out_uids, in_uids, n, n_out_dev, n_in_dev, tier_slots, frame,
         host, n_bad);
     return launch_status("exchange_begin");
+}
+
+extern "C" int kvm_pack_begin(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                              const int64_t* uids, int64_t n, const int64_t* n_dev, const int32_t* host_slots,
+                              uint64_t tier_slots, int32_t* frame, int64_t* host, uint32_t* n_bad, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(pool, KVM_EINVAL, "kvm_pack_begin: null pool");
+    KVM_REQUIRE(n >= 0 && n_uids >= 0, KVM_EINVAL, "kvm_pack_begin: negative count");
+    KVM_REQUIRE(pool->n_slots <= 0x7fffffffull, KVM_EINVAL, "kvm_pack_begin: n_slots exceeds int32 slot ids");
+    KVM_REQUIRE(tier_slots <= 0x7fffffffull, KVM_EINVAL, "kvm_pack_begin: tier_slots exceeds int32 slot ids");
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(slot_tbl && state && uids && host_slots && frame && host, KVM_EINVAL, "kvm_pack_begin: null buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("exchange_flip", st);
+    pack_begin_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, st>>>(
+        (uint32_t)pool->n_slots, slot_tbl, state, n_uids, uids, n, n_dev, host_slots, tier_slots, frame, host, n_bad);
+    return launch_status("pack_begin");
 }
 
 extern "C" int kvm_exchange_end(int32_t* slot_tbl, uint8_t* state, int64_t n_uids, const int64_t* in_uids,

@@ -357,12 +357,31 @@ struct Xfer {
     uint64_t tier_slots;    // records of the tier: likewise
 };
 
+// Pair i decoded: frame, host slot and direction (one-way = the frame is copied out, nothing comes back).
+// Returns false for a pair to skip.
+__device__ __forceinline__ bool xfer_decode(const Xfer& x, uint32_t i, int32_t* f, int64_t* h, bool* one_way) {
+    *f = x.frame[i];
+    const int64_t hv = x.host[i];
+    *one_way = hv >= 0 && (hv & KVM_XFER_OUT_ONLY) != 0;
+    *h = *one_way ? (hv & ~KVM_XFER_OUT_ONLY) : hv;
+    return (uint32_t)*f < x.n_slots && (uint64_t)*h < x.tier_slots;
+}
+
 __device__ __forceinline__ void xfer_pair(const Xfer& x, uint32_t i) {
-    const int32_t f = x.frame[i];
-    const int64_t h = x.host[i];
-    if ((uint32_t)f >= x.n_slots || (uint64_t)h >= x.tier_slots) return;
+    int32_t f;
+    int64_t h;
+    bool one_way;
+    if (!xfer_decode(x, i, &f, &h, &one_way)) return;
     uint4* rec = x.tier + (size_t)h * ((size_t)x.k_v4 + x.v_v4);
     uint4* kf = x.k_pool + (size_t)f * x.k_v4;
+    if (one_way) {                                                        // uniform for the workgroup
+        for (uint32_t v = threadIdx.x; v < x.k_v4; v += kThreads) rec[v] = kf[v];
+        if (x.v_v4) {
+            const uint4* vf = x.v_pool + (size_t)f * x.v_v4;
+            for (uint32_t v = threadIdx.x; v < x.v_v4; v += kThreads) rec[x.k_v4 + v] = vf[v];
+        }
+        return;
+    }
     for (uint32_t v = threadIdx.x; v < x.k_v4; v += kThreads) {
         const uint4 a = kf[v], b = rec[v];
         kf[v] = b;
@@ -827,12 +846,35 @@ __device__ __forceinline__ void swap_pieces_wave(uint4* __restrict__ dev, uint4*
         if (i3 < n) { dev[i3] = h3; host[i3] = a3; }
     }
 }
-// One wavefront swaps frame and host record of pair i in place.
+// One wavefront copies n 16-byte pieces of a frame to its host record, eight loads in flight per lane.
+__device__ __forceinline__ void copy_pieces_wave(const uint4* __restrict__ dev, uint4* __restrict__ host, uint32_t n,
+                                                 int lane) {
+    for (uint32_t v0 = 0; v0 < n; v0 += 512) {
+        uint4 a[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = v0 + j * 64 + lane;
+            a[j] = dev[i < n ? i : n - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = v0 + j * 64 + lane;
+            if (i < n) host[i] = a[j];
+        }
+    }
+}
+// One wavefront moves pair i: frame and host record swapped in place, or the frame copied out.
 __device__ __forceinline__ void xfer_pair_wave(const Xfer& x, uint32_t i, int lane) {
-    const int32_t f = x.frame[i];
-    const int64_t h = x.host[i];
-    if ((uint32_t)f >= x.n_slots || (uint64_t)h >= x.tier_slots) return;
+    int32_t f;
+    int64_t h;
+    bool one_way;
+    if (!xfer_decode(x, i, &f, &h, &one_way)) return;
     uint4* rec = x.tier + (size_t)h * ((size_t)x.k_v4 + x.v_v4);
+    if (one_way) {
+        copy_pieces_wave(x.k_pool + (size_t)f * x.k_v4, rec, x.k_v4, lane);
+        if (x.v_v4) copy_pieces_wave(x.v_pool + (size_t)f * x.v_v4, rec + x.k_v4, x.v_v4, lane);
+        return;
+    }
     swap_pieces_wave(x.k_pool + (size_t)f * x.k_v4, rec, x.k_v4, lane);
     if (x.v_v4) swap_pieces_wave(x.v_pool + (size_t)f * x.v_v4, rec + x.k_v4, x.v_v4, lane);
 }
@@ -1599,10 +1641,13 @@ struct Choice {
     int nct;           // Mfma: 16-query column tiles (1, 2, 4 or 8)
 };
 
+// Larger groups of a small head go to the matrix-core kernel.  Eight queries as packed dot products are
+// 128 vector instructions per block and 128 registers of query operands: measured against the matrix-core
+// tile kernel (one half-empty column tile), rows of 512 blocks are a tie and rows of 128 blocks 8 % slower.
 #ifndef KVM_DOT2_MAX_G
-#define KVM_DOT2_MAX_G 8
+#define KVM_DOT2_MAX_G 4
 #endif
-constexpr int kDot2MaxG = KVM_DOT2_MAX_G;   // larger groups of a small head go to the matrix-core kernel
+constexpr int kDot2MaxG = KVM_DOT2_MAX_G;
 
 // Which kernel scores (g, dim), and with what tile size.  The block-value array in LDS takes
 // tile_blocks * (padded g) * 4 bytes: at most 32 KiB.
@@ -1613,10 +1658,10 @@ constexpr int kDot2MaxG = KVM_DOT2_MAX_G;   // larger groups of a small head go 
 constexpr int kRowMinRows = 256;
 constexpr int kRowMinMeanBlocks = 2048;
 Choice choose(int g, int dim, int64_t n_uids, int64_t n_rows) {
-    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8) && g <= kDot2MaxG) {
+    if (dim <= 128 && (g == 1 || g == 2 || g == 4 || g == 8)) {
         if (n_rows >= kRowMinRows && n_uids / n_rows >= kRowMinMeanBlocks && n_rows <= 0x7fffffff)
             return Choice{Path::Row, kRowSeg, 0};
-        return Choice{Path::Dot2, 512, 0};
+        if (g <= kDot2MaxG) return Choice{Path::Dot2, 512, 0};
     }
     if (dim <= 256) {
         const int nct = (g + 15) / 16;
@@ -1786,8 +1831,7 @@ int launch_dim(const ScoreArgs& a, const Choice& ch) {
             switch (a.rows->g) {
                 case 1: return launch_dot2_path<1, DIM, DT>(a);
                 case 2: return launch_dot2_path<2, DIM, DT>(a);
-                case 4: return launch_dot2_path<4, DIM, DT>(a);
-                default: return launch_dot2_path<8, DIM, DT>(a);
+                default: return launch_dot2_path<4, DIM, DT>(a);
             }
         }
     }

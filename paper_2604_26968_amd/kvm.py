@@ -23,8 +23,9 @@ ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
 AGG_MAX, AGG_MEAN = 0, 1
 OP_SCORE, OP_SELECT, OP_SPAN = 0, 1, 2
 SELECT_STATIC_MAX_UIDS = 1 << 26
+XFER_OUT_ONLY = 1 << 62
 
-EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
+EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_pack_begin", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_select_victims_static", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
            "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version", "kvm_probe_read",
            "kvm_timing_enable", "kvm_timing_only", "kvm_timing_reset", "kvm_timing_read"]
@@ -124,6 +125,8 @@ def _load() -> C.CDLL:
     lib.kvm_exchange_begin.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p]
+    lib.kvm_pack_begin.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                   C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_exchange_end.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.kvm_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.kvm_timing_read.argtypes = [C.c_char_p, C.POINTER(C.c_double)]
@@ -363,6 +366,14 @@ def kvm_exchange_begin(pool: Pool, slot_tbl, state, out_uids, in_uids, n: int, t
                                   _ptr(n_out_dev, torch.int64), _ptr(n_in_dev, torch.int64), tier_slots,
                                   _ptr(frame, torch.int32), _ptr(host, torch.int64), _ptr(n_bad, torch.int32),
                                   _stream(stream)))
+
+
+def kvm_pack_begin(pool: Pool, slot_tbl, state, uids, n: int, host_slots, tier_slots: int, frame, host, n_dev=None,
+                   n_bad=None, stream=None):
+    _check(lib.kvm_pack_begin(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                              _ptr(uids, torch.int64), n, _ptr(n_dev, torch.int64), _ptr(host_slots, torch.int32),
+                              tier_slots, _ptr(frame, torch.int32), _ptr(host, torch.int64), _ptr(n_bad, torch.int32),
+                              _stream(stream)))
 
 
 def kvm_exchange_end(slot_tbl, state, in_uids, frame, n: int, stream=None):

@@ -659,6 +659,99 @@ def test_exchange_in_three_parts_rides_along_with_scoring(oracle, shape, n_pairs
     np.testing.assert_array_equal(dev.state.cpu().numpy(), st_f)
 
 
+@pytest.mark.parametrize("shape,n_pairs,n_out", [
+    (synth.Shape(2, 8, 2, 128, synth.BF16, True, [700, 77, 1300]), 40, 70),   # dot2 kernel, g = 4
+    (synth.Shape(2, 16, 2, 128, synth.BF16, True, [900, 200]), 0, 50),        # matrix-core kernel, g = 8, no swaps
+    (synth.Shape(2, 32, 1, 128, synth.FP16, True, [900]), 20, 33),            # matrix-core kernel, g = 32
+    (synth.Shape(3, 128, 1, 576, synth.BF16, False, [9000, 300]), 30, 25),    # wide kernel, rows of several tiles
+])
+def test_pack_in_two_parts_rides_along_with_scoring(oracle, shape, n_pairs, n_out):
+    """kvm_pack_begin -> the scoring launch copies the frames out (one-way pairs, in one list with the
+    swap pairs of a deferred exchange) -> tables, state and tier equal the oracle's pack (records at their
+    host slots) and exchange; masses equal the oracle's scoring of the table without the units that left."""
+    from paper_2604_26968_amd import kvm
+    from tests.harness import oracle_score
+    case = synth.make_case(shape, seed=77)
+    k8, v8 = host_pools(case)
+    rng = np.random.default_rng(21)
+    uk, uv = shape.unit_k_bytes, shape.unit_v_bytes
+    rec = uk + uv
+    res = np.flatnonzero(case.state & RES)
+    first_out = np.sort(rng.choice(res, size=len(res) // 3, replace=False)).astype(np.int64)
+    n_tier = len(first_out) + n_out + 5
+    hs = rng.permutation(len(first_out) + 2)[:len(first_out)].astype(np.int32)      # slots below len(first_out) + 2
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    staging, _ = oracle.pack(k8, v8, uk, uv, tbl, st, first_out, hs)
+    tier = rng.integers(0, 256, size=(n_tier, rec), dtype=np.uint8)
+    tier[hs] = staging
+    case.slot_tbl[:], case.state[:] = tbl, st
+    dev = DeviceCase(case)
+    d_tier = torch.from_numpy(tier.reshape(-1).copy()).pin_memory()
+    res_now = np.flatnonzero(st & RES)
+    pick = rng.choice(res_now, size=n_pairs + n_out, replace=False).astype(np.int64)
+    outs, packs = pick[:n_pairs].copy(), pick[n_pairs:].copy()
+    ins = rng.choice(first_out, size=n_pairs, replace=False).astype(np.int64)
+    pack_slots = (len(first_out) + 2 + np.arange(n_out)).astype(np.int32)             # free slots of the tier
+    packs[2] = -7                                     # malformed uid
+    packs[5] = first_out[0]                           # not in HBM
+    pack_slots[9] = n_tier + 4                        # slot outside the tier
+    # oracle: exchange of the pairs, pack of the list; records of accepted entries go to their slots
+    tbl_f, st_f, k_f, tier_f = tbl.copy(), st.copy(), k8.copy(), tier.copy()
+    v_f = v8.copy() if v8 is not None else None
+    bad = np.zeros(1, np.uint32)
+    if n_pairs:
+        oracle.exchange(k_f, v_f, uk, uv, tbl_f, st_f, outs, ins, tier_f, n_bad=bad)
+    ok_pack = np.array([0 <= u < case.n_uids and bool(st[u] & RES) and 0 <= h < n_tier
+                        for u, h in zip(packs, pack_slots)])
+    assert ok_pack.sum() == n_out - 3
+    # the oracle's pack takes any host slot number; entries the device refuses for their slot are left out here
+    want_staging, want_freed = oracle.pack(k_f, v_f, uk, uv, tbl_f, st_f, packs[ok_pack], pack_slots[ok_pack])
+    tier_f[pack_slots[ok_pack]] = want_staging
+    tbl_mid = tbl.copy()
+    tbl_mid[outs] = -1
+    tbl_mid[packs[ok_pack]] = -1
+    q = synth.make_queries(case, 5)
+    scale = 1.0 / np.sqrt(shape.dim)
+    want_mass = oracle_score(oracle, case, q, scale, fill=-1.0, slot_tbl=tbl_mid)
+    # device: one list, swap pairs first
+    n = n_pairs + n_out
+    frame = torch.full((n,), -5, dtype=torch.int32, device="cuda")
+    host = torch.full((n,), -5, dtype=torch.int64, device="cuda")
+    if n_pairs:
+        kvm.kvm_exchange_begin(dev.pool, dev.slot_tbl, dev.state, dev_of(outs), dev_of(ins), n_pairs, n_tier,
+                               frame[:n_pairs], host[:n_pairs], n_bad=dev.n_bad)
+    kvm.kvm_pack_begin(dev.pool, dev.slot_tbl, dev.state, dev_of(packs), n_out, dev_of(pack_slots), n_tier,
+                       frame[n_pairs:], host[n_pairs:], n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    # after begin: tables and state are final for the packed units, their frames still hold their bytes
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy()[packs[ok_pack]], tbl_f[packs[ok_pack]])
+    np.testing.assert_array_equal(dev.state.cpu().numpy()[packs[ok_pack]], st_f[packs[ok_pack]])
+    got_frame = frame.cpu().numpy()[n_pairs:]
+    np.testing.assert_array_equal(got_frame[ok_pack], want_freed)
+    np.testing.assert_array_equal(got_frame[~ok_pack], -1)
+    got_host = host.cpu().numpy()[n_pairs:]
+    np.testing.assert_array_equal(got_host[ok_pack], pack_slots[ok_pack].astype(np.int64) | kvm.XFER_OUT_ONLY)
+    np.testing.assert_array_equal(got_host[~ok_pack], -1)
+    assert int(dev.n_bad.item()) == 3
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step_xfer(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws, frame, host, n,
+                            d_tier)
+    if n_pairs:
+        kvm.kvm_exchange_end(dev.slot_tbl, dev.state, dev_of(ins), frame[:n_pairs], n_pairs)
+    torch.cuda.synchronize()
+    got_mass = dev.mass.cpu().numpy()
+    written = want_mass != -1.0
+    np.testing.assert_array_equal(got_mass != -1.0, written)
+    np.testing.assert_allclose(got_mass[written], want_mass[written], rtol=1e-3, atol=1e-9)
+    gk, gv = dev.pools_host()
+    np.testing.assert_array_equal(gk, k_f)              # one-way: the frames keep their bytes
+    if v8 is not None:
+        np.testing.assert_array_equal(gv, v_f)
+    np.testing.assert_array_equal(d_tier.numpy().reshape(n_tier, rec), tier_f)
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl_f)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st_f)
+
+
 def test_end_to_end_overlapped_exchange_dynamics(oracle):
     """The pass as the bench runs it by default, five steps on a twin of the Llama-3-8B-shaped workload:
     beta -> score (with the previous step's exchange bytes in the same launch) -> ema -> exchange_end ->

@@ -122,3 +122,31 @@ def test_long_rows_in_one_workgroup_each(oracle, n_q, dim, dtype, agg):
     assert bool((mass2[torch.cat([out_a, out_b])] == -1.0).all())
     assert bool((mass2[same] == mass[same]).all())
     assert int(same.sum().item()) > 0
+
+    # ---- and with evictions in two parts: kvm_pack_begin, the frames copied out by the scoring launch ---------
+    m2 = 300
+    res2 = torch.nonzero((wl.slot_tbl >= 0) & ((wl.state & PROT) == 0)).flatten()
+    out_c = res2[torch.randperm(res2.numel(), generator=wl.gen, device=dev)[:m2]].contiguous()
+    frames_c = wl.slot_tbl[out_c].clone()
+    k_c = wl.k_pool[frames_c.long()].view(torch.uint8).cpu().numpy().reshape(m2, -1)
+    v_c = wl.v_pool[frames_c.long()].view(torch.uint8).cpu().numpy().reshape(m2, -1)
+    slots_c = torch.arange(m, m + m2, dtype=torch.int32, device=dev)
+    pf_frame = torch.full((m2,), -1, dtype=torch.int32, device=dev)
+    pf_host = torch.full((m2,), -1, dtype=torch.int64, device=dev)
+    kvm.kvm_pack_begin(pool, wl.slot_tbl, wl.state, out_c, m2, slots_c, 2 * m, pf_frame, pf_host, n_bad=n_bad)
+    mass3 = torch.full((n,), -1.0, dtype=torch.float32, device=dev)
+    ws.fill_(0x7F)
+    kvm.kvm_score_step_xfer(pool, rows, q, scale, mass3, ws, pf_frame, pf_host, m2, tier, agg=agg)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    assert bool((pf_frame == frames_c).all()) and bool((pf_host == (slots_c.long() | kvm.XFER_OUT_ONLY)).all())
+    assert bool((wl.slot_tbl[out_c] == -1 - slots_c).all())
+    assert bool(((wl.state[out_c] & 3) == 2).all())
+    tier_c = tier.numpy().reshape(2 * m, rec)[m:m + m2]
+    np.testing.assert_array_equal(tier_c[:, :shape.unit_k_bytes], k_c)
+    np.testing.assert_array_equal(tier_c[:, shape.unit_k_bytes:], v_c)
+    assert bool((mass3[out_c] == -1.0).all())
+    touched3 = torch.zeros(n_rows, dtype=torch.bool, device=dev)
+    touched3[uid_row[out_c]] = True
+    same3 = ~(touched3 | touched_rows)[uid_row]         # rows none of the three lists touched
+    assert bool((mass3[same3] == mass[same3]).all()) and int(same3.sum().item()) > 0
