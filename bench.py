@@ -711,9 +711,12 @@ def prepare_growing(args, kvm, synth, np):
                            "(as many as the next step's new units), pack")
 
 
-def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
+def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief=False):
     """A trace-driven workload (the heterogeneous fleet, or the growing Llama-3-8B-shaped batch): rows of one
-    or two architectures in ONE pool sized by kvm_size, per-step inputs from a plan replayed on the host."""
+    or two architectures in ONE pool sized by kvm_size, per-step inputs from a plan replayed on the host.
+    ahead: every step evicts what the step after next creates and the victims' bytes leave inside the next
+    scoring launch (evictions of more than 16,384 units, room for a whole prompt, still go out in line);
+    otherwise every step evicts what the next one creates and packs it out in line.  brief: the stepping only."""
     from paper_2604_26968_amd import fleet
     dev = "cuda"
     t_setup = time.time()
@@ -728,7 +731,7 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
     scratch = pinned.take(32768 * rec)[:32768 * rec]
     fd = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
                            prefetch_cap=prep["prefetch_cap"], window_tokens=prep["window_tokens"], decay=prep["decay"],
-                           seed=prep["seed"])
+                           seed=prep["seed"], ahead=ahead)
     n = plan.n_uids
     # per step: which uids belong to rows that decode (to count the units the scorer reads)
     act_uid = []
@@ -816,7 +819,7 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
     per_step = [marks[j].elapsed_time(marks[j + 1]) for j in range(args.steps)]
     scored_h = scored.cpu().numpy()[args.warmup:]
     pairs_h = pairs.cpu().numpy()[args.warmup:]
-    new_next = np.asarray(fd.n_new[args.warmup + 1:n_steps + 1])
+    new_next = np.asarray(fd.n_new[args.warmup + fd.lead:n_steps + fd.lead])      # units each timed step evicts
     scored_bytes = float(scored_h.sum()) * unit_k
     value = scored_bytes / elapsed / 1e9
     pass_ms = [pass_marks[j][0].elapsed_time(pass_marks[j][1]) for j in range(args.warmup, n_steps)]
@@ -850,20 +853,24 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
                    "new_units_per_step": [int(new_next.min()), int(new_next.max())],
                    "events_per_step": [min(len(e[0]) for e in plan.events), max(len(e[0]) for e in plan.events)],
                    "prefetch_pairs_per_step": [int(pairs_h.min()), int(pairs_h.max())],
-                   "step_order": prep["step_order"]},
+                   "step_order": prep["step_order"] + (
+                       "; every eviction is chosen two steps before its frames are needed: the victims leave the table "
+                       "at once (kvm_pack_begin), their bytes leave inside the next scoring launch (more than 16,384 "
+                       "units at once: in line)" if ahead else "; evictions packed out in line")},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "in_order_ms_per_step": round(elapsed / args.steps * 1e3, 4),
         "pass_without_transfers": {
             "ms": round(sum(pass_ms) / len(pass_ms), 4), "value": round(pass_value, 1),
             "frac_of_hbm_peak": round(pass_value / HBM_PEAK_GBPS, 4),
             "what": "beta + scoring + ema/priority + prefetch keys + the selections, from events on "
-                    "the stream; the arrivals' scatter and the victims' bytes over the host link (in line in "
-                    "ms_per_step) left out"},
+                    "the stream (with the victims' bytes of the last eviction inside the scoring launch); the "
+                    "arrivals' scatter, the in-line exchange and in-line evictions left out"},
         "steps_without_prompt_arrival": {
             "count": len(quiet), "ms_per_step": round(sum(quiet) / max(len(quiet), 1), 4),
             "value": round(sum(quiet_bytes) / max(sum(quiet), 1e-9) / 1e6, 1),
             "note": "steps whose eviction only makes room for the growth of decoding sequences; a step that makes "
                     "room for a whole arriving prompt is bound by the host link (its victims' bytes go out in line)"},
+        "eviction": "two steps ahead, bytes inside the next scoring launch" if ahead else "one step ahead, in line",
         "link_bytes_per_step_mean": int((new_next.sum() + 2 * pairs_h.sum()) * rec / args.steps),
         "roofline": {"kernel": "score_partial (all scoring launches of a step)", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -880,6 +887,8 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep):
                   "bulk_evict_frac_of_link": round(k0 * rec / t_bulk / 1e9 / link["d2h_GBps"], 3)},
         "host_link": link, "setup_s": round(setup_s, 1),
     }
+    if brief:
+        return out
     ceiling = read_ceiling(torch, kvm, fd.k_pool, dev)
     out["read_ceiling_GBps"] = round(ceiling, 1)
     out["roofline"]["frac_of_read_ceiling"] = round(achieved / ceiling, 4)
@@ -972,6 +981,14 @@ def main():
         t0 = time.time()
         if name in preps:
             rec = run_fleet(args, torch, np, kvm, synth, pinned, link, preps[name])
+            gc.collect()
+            torch.cuda.empty_cache()
+            alt = run_fleet(args, torch, np, kvm, synth, pinned, link, preps[name], ahead=False, brief=True)
+            keys = ("ms_per_step", "ms_per_step_median", "ms_per_step_min_max", "value", "frac_of_hbm_peak",
+                    "pass_without_transfers", "steps_without_prompt_arrival", "eviction")
+            rec["step_orders"] = {"ahead": {k: rec[k] for k in keys}, "in_line": {k: alt[k] for k in keys}}
+            rec["in_order_ms_per_step"] = rec["ms_per_step"]
+            del alt
         else:
             rec = run_uniform(name, args, torch, np, kvm, synth, pinned, link)
         rec["name"] = name

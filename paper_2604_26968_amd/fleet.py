@@ -276,13 +276,21 @@ class FleetDevice:
 
     `pool_units` frames (from the sizing call) hold the K and V of every unit that is in HBM; `tier` is
     the pinned host tier addressed by slot.  Frames for the units a step brings into existence are the
-    frames the previous step's victims left (`room`), so no free list is needed: each step evicts as many
-    units as the next one creates, plus up to `prefetch_cap` more that trade places with prefetched units.
+    frames earlier victims left (`rooms`), so no free list is needed: each step evicts as many units as a
+    later one creates, plus up to `prefetch_cap` more that trade places with prefetched units.
+
+    `ahead` False: step j evicts what step j + 1 creates and packs it out in line, after the selection.
+    `ahead` True: step j evicts what step j + 2 creates; the victims leave the table at once
+    (kvm_pack_begin) and their bytes leave inside step j + 1's first scoring launch, so the host link works
+    beside the scoring and the frames are free when step j + 2 starts.  An eviction of more than `ride_max`
+    units (room for a whole arriving prompt: more bytes than the link moves during one scoring launch) is
+    packed out in line all the same.
     """
 
     def __init__(self, plan: FleetPlan, kvm, torch, pool_units: int, head_weights: List[float], tier, tier_slots: int,
                  prefetch_cap: int, window_tokens: int, decay: float = 0.9, pos_decay: float = 0.9995, seed: int = 1,
-                 fresh_records: int = 65536, k_pool=None, v_pool=None):
+                 fresh_records: int = 65536, k_pool=None, v_pool=None, ahead: bool = False,
+                 ride_max: int = 16384):
         self.plan, self.kvm, self.torch = plan, kvm, torch
         dev = "cuda"
         sh0 = plan.shapes[0]
@@ -359,11 +367,17 @@ class FleetDevice:
         self.new_uids = [torch.from_numpy(u).to(dev) for u in plan.new_uids]
         self.prot_set = [torch.from_numpy(u).to(dev) for u in plan.prot_set]
         self.prot_clear = [torch.from_numpy(u).to(dev) for u in plan.prot_clear]
-        self.n_new = [len(u) for u in plan.new_uids] + [0]
+        self.ahead = bool(ahead)
+        self.ride_max = int(ride_max)
+        self.lead = 2 if self.ahead else 1                    # a step makes room for the arrivals of step j + lead
+        self.n_new = [len(u) for u in plan.new_uids] + [0, 0]
         k_max = max(self.n_new) + self.P
         self.victims = torch.full((max(k_max, 1),), -1, dtype=torch.int64, device=dev)
         self.pf_list = torch.full((max(self.P, 1),), -1, dtype=torch.int64, device=dev)
-        self.room = torch.full((max(max(self.n_new), 1),), -1, dtype=torch.int32, device=dev)
+        # frames for the arrivals of even and of odd steps
+        self.rooms = [torch.full((max(max(self.n_new), 1),), -1, dtype=torch.int32, device=dev) for _ in range(2)]
+        self.ride_host = torch.full((max(max(self.n_new), 1),), -1, dtype=torch.int64, device=dev)
+        self.ride = None                                       # (frames, host slots, count) waiting for a scoring launch
         self.fresh_records = int(min(fresh_records, max(max(self.n_new), 1)))
         self.fresh = torch.randn(self.fresh_records * self.rec // 2, generator=gen, device=dev,
                                  dtype=torch.float32).to(tdt).view(torch.uint8)
@@ -387,7 +401,7 @@ class FleetDevice:
         for lo in range(0, n, self.fresh_records):
             cnt = min(self.fresh_records, n - lo)
             kvm.kvm_unpack(self.pool, self.slot_tbl, self.state, self.new_uids[j][lo:lo + cnt], cnt,
-                           self.room[lo:lo + cnt], self.fresh, None, n_bad=self.n_bad)
+                           self.rooms[j % 2][lo:lo + cnt], self.fresh, None, n_bad=self.n_bad)
         if len(self.prot_clear[j]):
             self.state[self.prot_clear[j]] &= 255 - PROT
         if len(self.prot_set[j]):
@@ -399,9 +413,17 @@ class FleetDevice:
                                  n_bad=self.n_bad)
 
     def score(self, j: Optional[int], q_set: int = 0):
+        ride, self.ride = self.ride, None
         for a, d in enumerate(self.arch):
             if d["n_rows"]:
-                self.kvm.kvm_score_step(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass, self.ws)
+                if ride is not None:                       # the bytes of the last eviction leave inside this launch
+                    self.kvm.kvm_score_step_xfer(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass,
+                                                 self.ws, ride[0], ride[1], ride[2], self.tier)
+                    ride = None
+                else:
+                    self.kvm.kvm_score_step(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass,
+                                            self.ws)
+        assert ride is None, "an eviction in two parts needs a scoring launch to carry its bytes"
 
     def ema(self, j: Optional[int]):
         for a, d in enumerate(self.arch):
@@ -418,29 +440,37 @@ class FleetDevice:
                                            self.p_hat, self.pos_decay, self.key, self.cand)
 
     def select(self, j: int):
-        """One selection of victims over the shared pool (room for the next step's new units + the units
+        """One selection of victims over the shared pool (room for the new units of step j + lead + the units
         that trade places with prefetched ones) and one of the prefetch list."""
         kvm = self.kvm
         if self.P:
             kvm.kvm_select_victims(self.key, self.cand, self.pf_list, self.n_pf, self.ws, k=self.P)
-        k = self.n_new[j + 1] + self.P
+        k = self.n_new[j + self.lead] + self.P
         self.victims.fill_(-1)
         kvm.kvm_select_victims(self.prio, self.state, self.victims[:max(k, 1)], self.n_v, self.ws, k=k)
 
     def move(self, j: int):
-        """The first P victims trade places with the prefetch list in the slot-addressed tier; the others are
-        packed out to fresh tier slots and leave their frames to the next step's new units."""
+        """The first P victims trade places with the prefetch list in the slot-addressed tier; the others go
+        to fresh tier slots and leave their frames to the new units of step j + lead: packed out here, or
+        (`ahead`) taken out of the table here and copied out by the next scoring launch."""
         kvm = self.kvm
         P = self.P
         if P:
             kvm.kvm_exchange(self.pool, self.slot_tbl, self.state, self.victims[:P], self.pf_list, P, self.tier,
                              n_out_dev=self.n_v, n_in_dev=self.n_pf, n_bad=self.n_bad)
-        m = self.n_new[j + 1]
+        m = self.n_new[j + self.lead]
         if m:
             assert self.next_slot + m <= self.tier_slots, "host tier full"
             slots = self.torch.arange(self.next_slot, self.next_slot + m, dtype=self.torch.int32, device="cuda")
-            kvm.kvm_pack(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots, self.room[:m], None,
-                         self.tier[self.next_slot * self.rec:(self.next_slot + m) * self.rec], n_bad=self.n_bad)
+            room = self.rooms[(j + self.lead) % 2]
+            if self.ahead and m <= self.ride_max:
+                assert self.ride is None
+                kvm.kvm_pack_begin(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots,
+                                   self.tier_slots, room, self.ride_host, n_bad=self.n_bad)
+                self.ride = (room, self.ride_host, m)
+            else:
+                kvm.kvm_pack(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots, room[:m], None,
+                             self.tier[self.next_slot * self.rec:(self.next_slot + m) * self.rec], n_bad=self.n_bad)
             self.next_slot += m
 
     def step(self, j: int):
@@ -499,12 +529,17 @@ class FleetDevice:
         if k0 > keep:
             self.state[victims[keep:]] &= 255 - HOST
         self.next_slot = keep
-        # frames for the first window step's new units: the ones just freed, then frames never used
+        # frames for the new units of the first window step (with `ahead`: of the first two): the ones just
+        # freed, then frames never used
         frames = torch.cat([freed[:k0], self.free_frames]) if k0 else self.free_frames
-        assert frames.numel() >= self.n_new[0], "no room for the first step's new units"
-        if self.n_new[0]:
-            self.room[:self.n_new[0]] = frames[:self.n_new[0]]
-        self.spare_frames = frames[self.n_new[0]:]
+        at = 0
+        for j0 in range(self.lead):
+            m = self.n_new[j0]
+            assert frames.numel() >= at + m, "no room for the first steps' new units"
+            if m:
+                self.rooms[j0 % 2][:m] = frames[at:at + m]
+            at += m
+        self.spare_frames = frames[at:]
         torch.cuda.synchronize()
         return k0, victims
 

@@ -35,7 +35,8 @@ class FleetRef:
         self.next_slot = 0
         self.fresh = t(dev.fresh).reshape(-1, self.rec)
         self.n_new = list(dev.n_new)
-        self.room = np.full(max(max(self.n_new), 1), -1, np.int32)
+        self.lead = dev.lead            # victims of step j make room for the arrivals of step j + lead
+        self.rooms = [np.full(max(max(self.n_new), 1), -1, np.int32) for _ in range(2)]
         self.arch = []
         for a, d in enumerate(dev.arch):
             sh = d["shape"]
@@ -60,7 +61,7 @@ class FleetRef:
         for lo in range(0, n, step):
             cnt = min(step, n - lo)
             self.o.unpack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, uids[lo:lo + cnt],
-                          self.room[lo:lo + cnt], self.fresh[:cnt], n_bad=self.n_bad)
+                          self.rooms[j % 2][lo:lo + cnt], self.fresh[:cnt], n_bad=self.n_bad)
         self.state[self.plan.prot_clear[j]] &= 255 - PROT
         self.state[self.plan.prot_set[j]] |= PROT
 
@@ -92,7 +93,7 @@ class FleetRef:
 
     def select(self, j):
         self.pf_list = self.o.select_victims(self.key, self.cand, k=self.P) if self.P else np.zeros(0, np.int64)
-        self.victims = self.o.select_victims(self.prio, self.state, k=self.n_new[j + 1] + self.P)
+        self.victims = self.o.select_victims(self.prio, self.state, k=self.n_new[j + self.lead] + self.P)
 
     def move(self, j):
         P = self.P
@@ -100,15 +101,17 @@ class FleetRef:
         if n_pairs:
             self.o.exchange(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, self.victims[:n_pairs],
                             self.pf_list[:n_pairs], self.tier, n_bad=self.n_bad)
-        m = self.n_new[j + 1]
+        # whether the bytes leave now or inside the next scoring launch, tables, state and tier end up as a
+        # plain pack leaves them, and nothing reads the records or reuses the frames in between
+        m = self.n_new[j + self.lead]
         if m:
             out = self.victims[P:P + m]
-            assert len(out) == m, "fewer eligible victims than the next step needs frames"
+            assert len(out) == m, "fewer eligible victims than a later step needs frames"
             slots = np.arange(self.next_slot, self.next_slot + m, dtype=np.int32)
             staging, freed = self.o.pack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, out, slots,
                                          n_bad=self.n_bad)
             self.tier[self.next_slot:self.next_slot + m] = staging
-            self.room[:m] = freed
+            self.rooms[(j + self.lead) % 2][:m] = freed
             self.next_slot += m
 
     # ---- warm start ------------------------------------------------------------------------------------------
@@ -129,5 +132,9 @@ class FleetRef:
         self.state[victims[keep:]] &= 255 - HOST
         self.next_slot = keep
         frames = np.concatenate([freed[:k0], self.free_frames])
-        self.room[:self.n_new[0]] = frames[:self.n_new[0]]
+        at = 0
+        for j0 in range(self.lead):
+            m = self.n_new[j0]
+            self.rooms[j0 % 2][:m] = frames[at:at + m]
+            at += m
         return k0, victims

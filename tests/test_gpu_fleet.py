@@ -195,7 +195,7 @@ def fleet_twin_inputs(seed, n_requests, rate):
 
 
 def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=14, P=24, keep_all=True, inputs=None,
-                    pool_target_units=12000, expect=None):
+                    pool_target_units=12000, expect=None, ahead=False, ride_max=1 << 20):
     """The fleet as the benchmark drives it, at a size the oracle follows step by step: one pool sized by
     kvm_size shared by an MHA and an MQA model, a seeded request trace (Zipf prefix ids, lognormal lengths,
     multi-turn sessions with idle gaps), warm start (everything scored once, bulk eviction to the budget),
@@ -204,7 +204,9 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
     of each architecture, position-aware prefetch list, ONE victim selection over the shared pool, exchange
     and pack.  Every stage is compared with the oracle; the oracle's floating-point outputs are then handed
     to the GPU side so that both stay on the same trajectory and the integer outputs can be compared exactly.
-    `inputs` = (shapes, catalogues, requests) replaces the two-model trace (the growing single-model batch)."""
+    `inputs` = (shapes, catalogues, requests) replaces the two-model trace (the growing single-model batch).
+    `ahead`: every step makes room for the arrivals two steps on, and the victims' bytes leave inside the next
+    step's scoring launch (kvm_pack_begin + kvm_score_step_xfer) instead of in line."""
     from paper_2604_26968_amd import kvm, fleet
     from tests.fleet_ref import FleetRef
     shapes, cats, reqs = inputs if inputs is not None else fleet_twin_inputs(seed, n_requests, rate)
@@ -226,7 +228,7 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
     tier_slots = st["init_units"] + sum(st["new_units_per_step"]) + 8
     tier = torch.zeros(tier_slots * rec, dtype=torch.uint8).pin_memory()
     dev = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
-                            prefetch_cap=P, window_tokens=512, seed=seed, fresh_records=64)
+                            prefetch_cap=P, window_tokens=512, seed=seed, fresh_records=64, ahead=ahead, ride_max=ride_max)
     ref = FleetRef(oracle, dev, plan)
     n = plan.n_uids
     cpu = lambda x: x.detach().cpu().numpy()
@@ -267,10 +269,11 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
     assert k0 == k0_ref == n_res - budget
     same_tables("bulk eviction")
     np.testing.assert_array_equal(tier.numpy().reshape(tier_slots, rec)[:keep], ref.tier[:keep])
-    np.testing.assert_array_equal(cpu(dev.room)[:dev.n_new[0]], ref.room[:dev.n_new[0]])
+    for j0 in range(dev.lead):
+        np.testing.assert_array_equal(cpu(dev.rooms[j0 % 2])[:dev.n_new[j0]], ref.rooms[j0 % 2][:dev.n_new[j0]])
 
     # ---- the window -----------------------------------------------------------------------------------------
-    n_pf_seen = n_moved = 0
+    n_pf_seen = n_moved = n_rode = n_to_ride = 0
     for j in range(n_steps):
         tag = "step %d" % j
         dev.arrive(j)
@@ -282,7 +285,13 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
         np.testing.assert_array_equal(cpu(dev.misses).view(np.uint32), ref.misses)
         np.testing.assert_allclose(cpu(dev.p_hat), ref.p_hat, rtol=1e-6)
         dev.p_hat.copy_(torch.from_numpy(ref.p_hat))
+        riding = dev.ride
         floats_then_align(tag, j, j)
+        if riding is not None:                  # the records of the last eviction were written by the scoring launch
+            r_slots = (cpu(riding[1])[:riding[2]] & ~kvm.XFER_OUT_ONLY).astype(np.int64)
+            assert dev.ride is None and len(r_slots) == dev.n_new[j + 1] and r_slots.min() >= 0
+            np.testing.assert_array_equal(tier.numpy().reshape(tier_slots, rec)[r_slots], ref.tier[r_slots], err_msg=tag)
+            n_rode += len(r_slots)
         dev.prefetch_keys(j)
         ref.prefetch_keys(j)
         torch.cuda.synchronize()
@@ -295,7 +304,7 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
         dev.select(j)
         ref.select(j)
         torch.cuda.synchronize()
-        k = dev.n_new[j + 1] + P
+        k = dev.n_new[j + dev.lead] + P
         assert int(dev.n_v.item()) == len(ref.victims) == k, (tag, int(dev.n_v.item()), len(ref.victims), k)
         np.testing.assert_array_equal(cpu(dev.victims)[:k], ref.victims, err_msg=tag)
         n_pf = int(dev.n_pf.item())
@@ -306,8 +315,10 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
         ref.move(j)
         torch.cuda.synchronize()
         same_tables(tag + " move")
-        m = dev.n_new[j + 1]
-        np.testing.assert_array_equal(cpu(dev.room)[:m], ref.room[:m], err_msg=tag)
+        m = dev.n_new[j + dev.lead]
+        np.testing.assert_array_equal(cpu(dev.rooms[(j + dev.lead) % 2])[:m], ref.rooms[(j + dev.lead) % 2][:m], err_msg=tag)
+        assert (dev.ride is not None) == (ahead and 0 < m <= ride_max)
+        n_to_ride += m if dev.ride is not None else 0
         assert dev.next_slot == ref.next_slot
         n_moved += m
         assert int(dev.n_bad.item()) == 0 and int(ref.n_bad[0]) == 0, tag
@@ -325,6 +336,9 @@ def run_trace_fleet(oracle, seed, n_requests=260, rate=0.3, start=350, n_steps=1
     # the trace made the pass do all of its work: units were created and evicted, prefetch candidates were found
     # and traded (where a prefetch cap is set), both outcomes of a lookup occurred (two-model trace)
     assert n_moved > 0 and (n_pf_seen > 0 or P == 0)
+    assert dev.ride is None and n_rode == n_to_ride and (n_rode > 0) == ahead
+    if ahead and ride_max < (1 << 20):
+        assert n_rode < n_moved, "no eviction was large enough to be packed in line"
     if inputs is None:
         assert ref.hits.sum() > 0 and ref.misses.sum() > 0
     return dict(n_pf=n_pf_seen, moved=n_moved, steps_with_new=sum(1 for m in dev.n_new[:n_steps] if m))
@@ -340,8 +354,20 @@ def test_fleet_trace_twin_with_records_dropped_below_tier_one(oracle):
     run_trace_fleet(oracle, seed=131, rate=0.4, start=300, n_steps=10, P=16, keep_all=False)
 
 
-@pytest.mark.parametrize("P", [0, 12])
-def test_growing_batch_twin_matches_oracle_over_24_steps(oracle, P):
+def test_fleet_trace_twin_evicting_two_steps_ahead(oracle):
+    """The same trace with every eviction in two parts: the victims leave the table when they are chosen, their
+    bytes leave inside the next step's scoring launch, their frames go to the arrivals of the step after."""
+    run_trace_fleet(oracle, seed=90, ahead=True)
+
+
+def test_fleet_trace_twin_two_steps_ahead_with_large_evictions_in_line(oracle):
+    """As above, but an eviction of more than 150 units (room for an arriving prompt) is packed out in line."""
+    out = run_trace_fleet(oracle, seed=90, ahead=True, ride_max=150)
+    assert out["moved"] > 0
+
+
+@pytest.mark.parametrize("P,ahead", [(0, False), (12, False), (0, True), (12, True)])
+def test_growing_batch_twin_matches_oracle_over_24_steps(oracle, P, ahead):
     """Twin of the Llama-3-8B-shaped configuration as it decodes: every sequence appends one token per step, new
     blocks (hence new units in every layer and head) appear at block boundaries in the frames the previous step's
     victims left, the block being written is PROTECTED and the one before it no longer is; 24 steps, so every
@@ -349,5 +375,6 @@ def test_growing_batch_twin_matches_oracle_over_24_steps(oracle, P):
     prefetched each step."""
     shape = synth.Shape(2, 8, 2, 128, synth.BF16, True, [700, 2100, 333, 17, 1500, 1023])
     inputs = ([shape], [[synth.FleetPrefix(0.0, 2, 0)]], synth.growing_batch_requests(shape.seq_lens))
-    out = run_trace_fleet(oracle, seed=7 + P, start=1, n_steps=24, P=P, inputs=inputs, pool_target_units=1600)
+    out = run_trace_fleet(oracle, seed=7 + P, start=1, n_steps=24, P=P, inputs=inputs, pool_target_units=1600,
+                          ahead=ahead)
     assert out["steps_with_new"] >= 6

@@ -288,7 +288,7 @@ def test_fleet_full_size_sampled(oracle):
     tier = torch.empty(tier_slots * rec, dtype=torch.uint8, pin_memory=True)
     scratch = torch.empty(32768 * rec, dtype=torch.uint8, pin_memory=True)
     fd = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
-                           prefetch_cap=1024, window_tokens=2048, decay=0.9, seed=11)
+                           prefetch_cap=1024, window_tokens=2048, decay=0.9, seed=11, ahead=True)   # as bench.py runs it
     n = plan.n_uids
     rng = np.random.default_rng(5)
 
@@ -324,7 +324,8 @@ def test_fleet_full_size_sampled(oracle):
     assert k0 == n_res0 - budget and int(fd.n_bad.item()) == 0
     assert int((fd.state & RES).sum().item()) == budget
     assert int(((fd.state & HOST) != 0).sum().item()) == keep    # the other victims were demoted below tier 1
-    want_resident = budget
+    want_resident = budget          # the second step's arrivals take frames the bulk eviction left free
+    rides, rode = [], 0
     for j in range(3):
         fd.arrive(j)
         want_resident += fd.n_new[j]
@@ -332,6 +333,16 @@ def test_fleet_full_size_sampled(oracle):
         fd.mass.fill_(-1.0)
         fd.score(j, j)
         torch.cuda.synchronize()
+        if rides:                           # the last eviction's records were written by this scoring launch
+            frames, hosts = rides.pop()
+            pick_r = torch.from_numpy(rng.choice(frames.numel(), size=min(512, frames.numel()), replace=False)).to(dev)
+            fr = frames[pick_r].long()
+            hs = (hosts[pick_r] & ~kvm.XFER_OUT_ONLY).cpu().numpy()
+            assert bool((frames >= 0).all()) and hs.min() >= 0
+            want_rec = torch.cat([fd.k_pool[fr].view(torch.uint8).reshape(len(fr), -1),
+                                  fd.v_pool[fr].view(torch.uint8).reshape(len(fr), -1)], dim=1).cpu().numpy()
+            np.testing.assert_array_equal(tier.numpy().reshape(tier_slots, rec)[hs], want_rec)
+            rode += frames.numel()
         if j == 2:
             check_rows(j, "window step %d" % j)
         # only resident units of decoding rows are written; the masses of every decoding row sum to [1, g]
@@ -358,10 +369,16 @@ def test_fleet_full_size_sampled(oracle):
         fd.prefetch_keys(j)
         fd.select(j)
         torch.cuda.synchronize()
-        assert int(fd.n_v.item()) == fd.n_new[j + 1] + fd.P
+        assert int(fd.n_v.item()) == fd.n_new[j + fd.lead] + fd.P
         n_pairs = min(int(fd.n_pf.item()), fd.P)
         fd.move(j)
         torch.cuda.synchronize()
-        want_resident -= fd.n_new[j + 1]              # packed out; the exchange trades one for one
+        # out of the table at once, whether the bytes leave in line (more than ride_max units) or inside the
+        # next scoring launch; the exchange trades one for one
+        want_resident -= fd.n_new[j + fd.lead]
+        assert (fd.ride is not None) == (0 < fd.n_new[j + fd.lead] <= fd.ride_max)
+        if fd.ride is not None:
+            rides.append((fd.ride[0][:fd.ride[2]].clone(), fd.ride[1][:fd.ride[2]].clone()))
         assert int((fd.state & RES).sum().item()) == want_resident
         assert int(fd.n_bad.item()) == 0
+    assert not rides and (rode > 0 or fd.n_new[2] == 0 or fd.n_new[2] > fd.ride_max)
