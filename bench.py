@@ -664,7 +664,7 @@ def prepare_fleet(args, kvm, synth):
                 pinned_bytes=(tier_slots + 32768) * rec + 2 * 4096, desc=desc, budget=F["budget"], decay=F["decay"],
                 prefetch_cap=F["prefetch_cap"], window_tokens=F["window_tokens"], keep_records=F["keep_records"],
                 seed=F["seed"], sample_rows=[2048, 256],
-                step_order="arrivals into the frames made free, beta, score (2 launches), ema+priority (2), "
+                step_order="arrivals into free frames, beta, score (2 launches), ema+priority (2), "
                            "prefetch keys (2) + list, ONE victim selection, exchange, pack")
 
 
@@ -707,16 +707,16 @@ def prepare_growing(args, kvm, synth, np):
     return dict(shapes=[shape], sizing=sizing, plan=plan, rec=rec, tier_slots=tier_slots, pool_units=pool_units,
                 pinned_bytes=(tier_slots + 32768) * rec + 2 * 4096, desc=desc, budget=G["budget"], decay=G["decay"],
                 prefetch_cap=0, window_tokens=0, keep_records=0, seed=G["seed"], sample_rows=[4096],
-                step_order="new blocks into the frames made free, beta, score, ema+priority, ONE victim selection "
-                           "(as many as the next step's new units), pack")
+                step_order="new blocks into free frames, beta, score, ema+priority, ONE victim selection, eviction")
 
 
 def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief=False):
     """A trace-driven workload (the heterogeneous fleet, or the growing Llama-3-8B-shaped batch): rows of one
     or two architectures in ONE pool sized by kvm_size, per-step inputs from a plan replayed on the host.
-    ahead: every step evicts what the step after next creates and the victims' bytes leave inside the next
-    scoring launch (evictions of more than 16,384 units, room for a whole prompt, still go out in line);
-    otherwise every step evicts what the next one creates and packs it out in line.  brief: the stepping only."""
+    New units take free frames of the pool at once; every step then evicts what HBM holds beyond the budget.
+    ahead: the victims leave the table when chosen and their bytes leave inside the next scoring launch, at most
+    16,384 units per step (after a whole prompt has arrived HBM is back at the budget some steps later);
+    otherwise they are packed out in line, all at once.  brief: the stepping only."""
     from paper_2604_26968_amd import fleet
     dev = "cuda"
     t_setup = time.time()
@@ -731,7 +731,7 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
     scratch = pinned.take(32768 * rec)[:32768 * rec]
     fd = fleet.FleetDevice(plan, kvm, torch, pool_units, [float(s["head_weight"]) for s in sizing], tier, tier_slots,
                            prefetch_cap=prep["prefetch_cap"], window_tokens=prep["window_tokens"], decay=prep["decay"],
-                           seed=prep["seed"], ahead=ahead)
+                           seed=prep["seed"], ahead=ahead, ride_max=args.ride_max or 16384)
     n = plan.n_uids
     # per step: which uids belong to rows that decode (to count the units the scorer reads)
     act_uid = []
@@ -789,7 +789,9 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
         if fd.P:
             pairs[j] = torch.minimum(fd.n_pf[0], fd.n_v[0]).clamp(max=fd.P)
         fd.move(j)
+        over_h.append(fd.resident - fd.budget)
 
+    over_h = []
     kvm.kvm_timing_only(None)
     kvm.kvm_timing_reset()
     kvm.kvm_timing_enable(True)
@@ -815,18 +817,21 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
     kvm.kvm_timing_only(None)
     cnt, sp_ms = kvm.kvm_timing_read("score_partial")
     kvm.kvm_timing_reset()
+    fd.flush()
+    torch.cuda.synchronize()
     assert int(fd.n_bad.item()) == 0, int(fd.n_bad.item())
     per_step = [marks[j].elapsed_time(marks[j + 1]) for j in range(args.steps)]
     scored_h = scored.cpu().numpy()[args.warmup:]
     pairs_h = pairs.cpu().numpy()[args.warmup:]
-    new_next = np.asarray(fd.n_new[args.warmup + fd.lead:n_steps + fd.lead])      # units each timed step evicts
+    new_next = np.asarray(fd.evicted[args.warmup:n_steps])      # units each timed step evicts
+    arrived = np.asarray(fd.n_new[args.warmup:n_steps])
     scored_bytes = float(scored_h.sum()) * unit_k
     value = scored_bytes / elapsed / 1e9
     pass_ms = [pass_marks[j][0].elapsed_time(pass_marks[j][1]) for j in range(args.warmup, n_steps)]
     pass_value = scored_bytes / (sum(pass_ms) * 1e-3) / 1e9
     # steps without an arrival of a whole prompt: growth of the decoding sequences only
-    quiet = [t for t, m in zip(per_step, new_next) if m < 65536]
-    quiet_bytes = [b * unit_k for b, m in zip(scored_h, new_next) if m < 65536]
+    quiet = [t for t, m in zip(per_step, arrived) if m < 65536]
+    quiet_bytes = [b * unit_k for b, m in zip(scored_h, arrived) if m < 65536]
     # roofline of the two scoring launches of a step together (g 1 rows on the dot-product kernel, g 32 rows on
     # the matrix-core kernel): algorithmic bytes = K frames + masses of the units read, table entries of the
     # decoding rows' blocks, their queries
@@ -850,13 +855,17 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
                    "lookup_hits": st["hits"], "lookup_misses": st["misses"], "retired_before_window": st["retired"],
                    "decoding_sequences_per_step": [int(min(st["active_per_step"])), int(max(st["active_per_step"]))],
                    "units_scored_per_step": [int(scored_h.min()), int(scored_h.max())],
-                   "new_units_per_step": [int(new_next.min()), int(new_next.max())],
+                   "new_units_per_step": [int(arrived.min()), int(arrived.max())],
+                   "evicted_units_per_step": [int(new_next.min()), int(new_next.max())],
                    "events_per_step": [min(len(e[0]) for e in plan.events), max(len(e[0]) for e in plan.events)],
                    "prefetch_pairs_per_step": [int(pairs_h.min()), int(pairs_h.max())],
                    "step_order": prep["step_order"] + (
-                       "; every eviction is chosen two steps before its frames are needed: the victims leave the table "
-                       "at once (kvm_pack_begin), their bytes leave inside the next scoring launch (more than 16,384 "
-                       "units at once: in line)" if ahead else "; evictions packed out in line")},
+                       "; new units take free frames of the pool, what HBM then holds beyond the budget is evicted: the "
+                       "victims leave the table at once (kvm_pack_begin), their bytes leave inside the next scoring "
+                       "launch, at most %d units per step" % fd.ride_max if ahead else
+                       "; new units take free frames of the pool, what HBM then holds beyond the budget is packed out "
+                       "in line"),
+                   "units_over_budget_after_step": [int(x) for x in over_h[args.warmup:]]},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "in_order_ms_per_step": round(elapsed / args.steps * 1e3, 4),
         "pass_without_transfers": {
@@ -870,7 +879,8 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
             "value": round(sum(quiet_bytes) / max(sum(quiet), 1e-9) / 1e6, 1),
             "note": "steps whose eviction only makes room for the growth of decoding sequences; a step that makes "
                     "room for a whole arriving prompt is bound by the host link (its victims' bytes go out in line)"},
-        "eviction": "two steps ahead, bytes inside the next scoring launch" if ahead else "one step ahead, in line",
+        "eviction": "bytes inside the next scoring launch, at most %d units per step" % fd.ride_max if ahead
+                    else "in line, all at once",
         "link_bytes_per_step_mean": int((new_next.sum() + 2 * pairs_h.sum()) * rec / args.steps),
         "roofline": {"kernel": "score_partial (all scoring launches of a step)", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -943,6 +953,9 @@ def main():
     ap.add_argument("--refined", action="store_true",
                     help="also time the pass with every refinement switched on (single-architecture workloads; "
                          "keeps all of tier 1 in pinned memory)")
+    ap.add_argument("--ride-max", type=int, default=0,
+                    help="trace-driven workloads: units evicted per step at most, their bytes inside the next scoring "
+                         "launch (0 = 16384)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")

@@ -275,16 +275,17 @@ class FleetDevice:
     """Per-unit state of the fleet on the GPU and the library calls of one step, in stages.
 
     `pool_units` frames (from the sizing call) hold the K and V of every unit that is in HBM; `tier` is
-    the pinned host tier addressed by slot.  Frames for the units a step brings into existence are the
-    frames earlier victims left (`rooms`), so no free list is needed: each step evicts as many units as a
-    later one creates, plus up to `prefetch_cap` more that trade places with prefetched units.
+    the pinned host tier addressed by slot.  The pool has more frames than the budget lets units stay in
+    HBM, so a unit that comes into existence takes a frame from the free frames at once (a log of frame
+    numbers: arrivals read it from the front, evictions append to it), and each step then evicts what HBM
+    holds beyond the budget, plus up to `prefetch_cap` units that trade places with prefetched ones.
 
-    `ahead` False: step j evicts what step j + 1 creates and packs it out in line, after the selection.
-    `ahead` True: step j evicts what step j + 2 creates; the victims leave the table at once
-    (kvm_pack_begin) and their bytes leave inside step j + 1's first scoring launch, so the host link works
-    beside the scoring and the frames are free when step j + 2 starts.  An eviction of more than `ride_max`
-    units (room for a whole arriving prompt: more bytes than the link moves during one scoring launch) is
-    packed out in line all the same.
+    `ahead` False: the victims are packed out in line, after the selection.
+    `ahead` True: the victims leave the table at once (kvm_pack_begin) and their bytes leave inside the
+    next step's first scoring launch, so the host link works beside the scoring; a step evicts at most
+    `ride_max` units (what the link moves during one scoring launch), so after a whole prompt has arrived
+    HBM is back at the budget some steps later.  Their frames are handed out again from the step after
+    that launch.
     """
 
     def __init__(self, plan: FleetPlan, kvm, torch, pool_units: int, head_weights: List[float], tier, tier_slots: int,
@@ -369,15 +370,19 @@ class FleetDevice:
         self.prot_clear = [torch.from_numpy(u).to(dev) for u in plan.prot_clear]
         self.ahead = bool(ahead)
         self.ride_max = int(ride_max)
-        self.lead = 2 if self.ahead else 1                    # a step makes room for the arrivals of step j + lead
-        self.n_new = [len(u) for u in plan.new_uids] + [0, 0]
-        k_max = max(self.n_new) + self.P
+        self.n_new = [len(u) for u in plan.new_uids]
+        k_max = sum(self.n_new) + self.P
         self.victims = torch.full((max(k_max, 1),), -1, dtype=torch.int64, device=dev)
         self.pf_list = torch.full((max(self.P, 1),), -1, dtype=torch.int64, device=dev)
-        # frames for the arrivals of even and of odd steps
-        self.rooms = [torch.full((max(max(self.n_new), 1),), -1, dtype=torch.int32, device=dev) for _ in range(2)]
-        self.ride_host = torch.full((max(max(self.n_new), 1),), -1, dtype=torch.int64, device=dev)
-        self.ride = None                                       # (frames, host slots, count) waiting for a scoring launch
+        # the log of free frames: [free_head, free_ready) may be handed to arrivals, [free_ready, free_tail)
+        # belong to victims whose bytes have not left yet; evict_to_budget() fills it first
+        self.free = None
+        self.free_head = self.free_ready = self.free_tail = 0
+        self.budget = self.resident = 0
+        self.evict_now = 0                                     # victims of the current step beyond the exchange
+        self.evicted = []                                      # per step, for whoever accounts for the link
+        self.ride_host = torch.full((max(sum(self.n_new), 1),), -1, dtype=torch.int64, device=dev)
+        self.ride = None                                       # (frames, host slots, count, log position behind them)
         self.fresh_records = int(min(fresh_records, max(max(self.n_new), 1)))
         self.fresh = torch.randn(self.fresh_records * self.rec // 2, generator=gen, device=dev,
                                  dtype=torch.float32).to(tdt).view(torch.uint8)
@@ -393,15 +398,18 @@ class FleetDevice:
 
     # ---- stages -------------------------------------------------------------------------------------------
     def arrive(self, j: int):
-        """The units that come into existence at step j take the frames the previous step made room in, with
-        freshly written K and V; the blocks being written are marked PROTECTED, the ones no longer written to
-        are released."""
+        """The units that come into existence at step j take free frames, with freshly written K and V; the
+        blocks being written are marked PROTECTED, the ones no longer written to are released."""
         kvm = self.kvm
         n = self.n_new[j]
+        assert self.free_head + n <= self.free_ready, "no free frame for a new unit"
+        frames = self.free[self.free_head:self.free_head + n]
+        self.free_head += n
+        self.resident += n
         for lo in range(0, n, self.fresh_records):
             cnt = min(self.fresh_records, n - lo)
             kvm.kvm_unpack(self.pool, self.slot_tbl, self.state, self.new_uids[j][lo:lo + cnt], cnt,
-                           self.rooms[j % 2][lo:lo + cnt], self.fresh, None, n_bad=self.n_bad)
+                           frames[lo:lo + cnt], self.fresh, None, n_bad=self.n_bad)
         if len(self.prot_clear[j]):
             self.state[self.prot_clear[j]] &= 255 - PROT
         if len(self.prot_set[j]):
@@ -419,6 +427,7 @@ class FleetDevice:
                 if ride is not None:                       # the bytes of the last eviction leave inside this launch
                     self.kvm.kvm_score_step_xfer(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass,
                                                  self.ws, ride[0], ride[1], ride[2], self.tier)
+                    self.free_ready = ride[3]          # later launches on the stream may reuse those frames
                     ride = None
                 else:
                     self.kvm.kvm_score_step(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass,
@@ -440,38 +449,56 @@ class FleetDevice:
                                            self.p_hat, self.pos_decay, self.key, self.cand)
 
     def select(self, j: int):
-        """One selection of victims over the shared pool (room for the new units of step j + lead + the units
-        that trade places with prefetched ones) and one of the prefetch list."""
+        """One selection of victims over the shared pool (what HBM holds beyond the budget + the units that
+        trade places with prefetched ones) and one of the prefetch list."""
         kvm = self.kvm
         if self.P:
             kvm.kvm_select_victims(self.key, self.cand, self.pf_list, self.n_pf, self.ws, k=self.P)
-        k = self.n_new[j + self.lead] + self.P
+        over = max(self.resident - self.budget, 0)
+        self.evict_now = min(over, self.ride_max) if self.ahead else over
+        k = self.evict_now + self.P
         self.victims.fill_(-1)
         kvm.kvm_select_victims(self.prio, self.state, self.victims[:max(k, 1)], self.n_v, self.ws, k=k)
 
     def move(self, j: int):
         """The first P victims trade places with the prefetch list in the slot-addressed tier; the others go
-        to fresh tier slots and leave their frames to the new units of step j + lead: packed out here, or
-        (`ahead`) taken out of the table here and copied out by the next scoring launch."""
+        to fresh tier slots and their frames to the free log: packed out here, or (`ahead`) taken out of the
+        table here and copied out by the next scoring launch."""
         kvm = self.kvm
         P = self.P
         if P:
             kvm.kvm_exchange(self.pool, self.slot_tbl, self.state, self.victims[:P], self.pf_list, P, self.tier,
                              n_out_dev=self.n_v, n_in_dev=self.n_pf, n_bad=self.n_bad)
-        m = self.n_new[j + self.lead]
+        m = self.evict_now
+        self.evicted.append(m)
         if m:
             assert self.next_slot + m <= self.tier_slots, "host tier full"
+            assert self.free_tail + m <= self.free.numel(), "free log full"
             slots = self.torch.arange(self.next_slot, self.next_slot + m, dtype=self.torch.int32, device="cuda")
-            room = self.rooms[(j + self.lead) % 2]
-            if self.ahead and m <= self.ride_max:
+            freed = self.free[self.free_tail:self.free_tail + m]
+            if self.ahead:
                 assert self.ride is None
                 kvm.kvm_pack_begin(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots,
-                                   self.tier_slots, room, self.ride_host, n_bad=self.n_bad)
-                self.ride = (room, self.ride_host, m)
+                                   self.tier_slots, freed, self.ride_host, n_bad=self.n_bad)
+                self.ride = (freed, self.ride_host, m, self.free_tail + m)
             else:
-                kvm.kvm_pack(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots, room[:m], None,
+                kvm.kvm_pack(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots, freed, None,
                              self.tier[self.next_slot * self.rec:(self.next_slot + m) * self.rec], n_bad=self.n_bad)
+                self.free_ready = self.free_tail + m
+            self.free_tail += m
             self.next_slot += m
+            self.resident -= m
+
+    def flush(self):
+        """Bytes of a last eviction that no scoring launch has carried yet leave in a launch of their own."""
+        if self.ride is None:
+            return
+        ride, self.ride = self.ride, None
+        d = self.arch[0]
+        none = self.kvm.make_rows(d["init_ntok"][:0], d["off"][:0], d["q_off"][:0], self.slot_tbl, d["g"], 0)
+        self.kvm.kvm_score_step_xfer(self.pool, none, d["q"][0], self.scale, self.mass, self.ws, ride[0], ride[1],
+                                     ride[2], self.tier)
+        self.free_ready = ride[3]
 
     def step(self, j: int):
         self.arrive(j)
@@ -529,17 +556,13 @@ class FleetDevice:
         if k0 > keep:
             self.state[victims[keep:]] &= 255 - HOST
         self.next_slot = keep
-        # frames for the new units of the first window step (with `ahead`: of the first two): the ones just
-        # freed, then frames never used
+        # the free log starts with the frames just freed, then the frames never used; room behind them for
+        # every frame the window's evictions can free
         frames = torch.cat([freed[:k0], self.free_frames]) if k0 else self.free_frames
-        at = 0
-        for j0 in range(self.lead):
-            m = self.n_new[j0]
-            assert frames.numel() >= at + m, "no room for the first steps' new units"
-            if m:
-                self.rooms[j0 % 2][:m] = frames[at:at + m]
-            at += m
-        self.spare_frames = frames[at:]
+        self.free = torch.full((frames.numel() + sum(self.n_new) + 8,), -1, dtype=torch.int32, device="cuda")
+        self.free[:frames.numel()] = frames
+        self.free_head, self.free_ready, self.free_tail = 0, frames.numel(), frames.numel()
+        self.budget = self.resident = n_res - k0
         torch.cuda.synchronize()
         return k0, victims
 

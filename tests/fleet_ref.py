@@ -35,8 +35,13 @@ class FleetRef:
         self.next_slot = 0
         self.fresh = t(dev.fresh).reshape(-1, self.rec)
         self.n_new = list(dev.n_new)
-        self.lead = dev.lead            # victims of step j make room for the arrivals of step j + lead
-        self.rooms = [np.full(max(max(self.n_new), 1), -1, np.int32) for _ in range(2)]
+        # the free-frame log and the residency bookkeeping, kept here independently of the driver's
+        self.ahead, self.ride_max = dev.ahead, dev.ride_max
+        self.free = np.zeros(0, np.int32)
+        self.free_head = self.free_ready = self.free_tail = 0
+        self.pending_ready = None
+        self.budget = self.resident = 0
+        self.evict_now = 0
         self.arch = []
         for a, d in enumerate(dev.arch):
             sh = d["shape"]
@@ -57,11 +62,15 @@ class FleetRef:
     def arrive(self, j):
         n = self.n_new[j]
         uids = self.plan.new_uids[j]
+        assert self.free_head + n <= self.free_ready
+        frames = self.free[self.free_head:self.free_head + n]
+        self.free_head += n
+        self.resident += n
         step = len(self.fresh)
         for lo in range(0, n, step):
             cnt = min(step, n - lo)
             self.o.unpack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, uids[lo:lo + cnt],
-                          self.rooms[j % 2][lo:lo + cnt], self.fresh[:cnt], n_bad=self.n_bad)
+                          frames[lo:lo + cnt], self.fresh[:cnt], n_bad=self.n_bad)
         self.state[self.plan.prot_clear[j]] &= 255 - PROT
         self.state[self.plan.prot_set[j]] |= PROT
 
@@ -70,11 +79,18 @@ class FleetRef:
         self.p_hat = self.o.beta_update(p, o_, self.hits, self.misses)
 
     def score(self, j, q_set=0):
+        if self.pending_ready is not None:          # the driver's scoring launch carries the last eviction's bytes
+            self.free_ready, self.pending_ready = self.pending_ready, None
         for a, d in enumerate(self.arch):
             if d["n_rows"]:
                 ntok, act = self._rows(a, j)
                 self.o.score_step(self.k16, self.dim, self.dtype, ntok, d["off"], d["q_off"], self.tbl,
                                   d["q"][q_set % 4], d["g"], self.scale, self.mass, row_active=act)
+
+    def score_none(self):
+        """The driver's flush: bytes move, nothing is scored."""
+        if self.pending_ready is not None:
+            self.free_ready, self.pending_ready = self.pending_ready, None
 
     def ema(self, j):
         for a, d in enumerate(self.arch):
@@ -93,7 +109,9 @@ class FleetRef:
 
     def select(self, j):
         self.pf_list = self.o.select_victims(self.key, self.cand, k=self.P) if self.P else np.zeros(0, np.int64)
-        self.victims = self.o.select_victims(self.prio, self.state, k=self.n_new[j + self.lead] + self.P)
+        over = max(self.resident - self.budget, 0)
+        self.evict_now = min(over, self.ride_max) if self.ahead else over
+        self.victims = self.o.select_victims(self.prio, self.state, k=self.evict_now + self.P)
 
     def move(self, j):
         P = self.P
@@ -103,16 +121,22 @@ class FleetRef:
                             self.pf_list[:n_pairs], self.tier, n_bad=self.n_bad)
         # whether the bytes leave now or inside the next scoring launch, tables, state and tier end up as a
         # plain pack leaves them, and nothing reads the records or reuses the frames in between
-        m = self.n_new[j + self.lead]
+        m = self.evict_now
         if m:
             out = self.victims[P:P + m]
-            assert len(out) == m, "fewer eligible victims than a later step needs frames"
+            assert len(out) == m, "fewer eligible victims than HBM holds units beyond the budget"
             slots = np.arange(self.next_slot, self.next_slot + m, dtype=np.int32)
             staging, freed = self.o.pack(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, out, slots,
                                          n_bad=self.n_bad)
             self.tier[self.next_slot:self.next_slot + m] = staging
-            self.rooms[(j + self.lead) % 2][:m] = freed
+            self.free[self.free_tail:self.free_tail + m] = freed
+            if self.ahead:
+                self.pending_ready = self.free_tail + m
+            else:
+                self.free_ready = self.free_tail + m
+            self.free_tail += m
             self.next_slot += m
+            self.resident -= m
 
     # ---- warm start ------------------------------------------------------------------------------------------
     def first_pass(self):
@@ -132,9 +156,8 @@ class FleetRef:
         self.state[victims[keep:]] &= 255 - HOST
         self.next_slot = keep
         frames = np.concatenate([freed[:k0], self.free_frames])
-        at = 0
-        for j0 in range(self.lead):
-            m = self.n_new[j0]
-            self.rooms[j0 % 2][:m] = frames[at:at + m]
-            at += m
+        self.free = np.full(len(frames) + sum(self.n_new) + 8, -1, np.int32)
+        self.free[:len(frames)] = frames
+        self.free_head, self.free_ready, self.free_tail = 0, len(frames), len(frames)
+        self.budget = self.resident = int((self.state & RES).sum())
         return k0, victims

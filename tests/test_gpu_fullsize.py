@@ -324,7 +324,8 @@ def test_fleet_full_size_sampled(oracle):
     assert k0 == n_res0 - budget and int(fd.n_bad.item()) == 0
     assert int((fd.state & RES).sum().item()) == budget
     assert int(((fd.state & HOST) != 0).sum().item()) == keep    # the other victims were demoted below tier 1
-    want_resident = budget          # the second step's arrivals take frames the bulk eviction left free
+    want_resident = budget
+    assert fd.budget == fd.resident == budget
     rides, rode = [], 0
     for j in range(3):
         fd.arrive(j)
@@ -369,16 +370,20 @@ def test_fleet_full_size_sampled(oracle):
         fd.prefetch_keys(j)
         fd.select(j)
         torch.cuda.synchronize()
-        assert int(fd.n_v.item()) == fd.n_new[j + fd.lead] + fd.P
+        # what HBM holds beyond the budget goes, at most ride_max units per step
+        m = min(want_resident - budget, fd.ride_max)
+        assert fd.evict_now == m and int(fd.n_v.item()) == m + fd.P
         n_pairs = min(int(fd.n_pf.item()), fd.P)
         fd.move(j)
         torch.cuda.synchronize()
-        # out of the table at once, whether the bytes leave in line (more than ride_max units) or inside the
-        # next scoring launch; the exchange trades one for one
-        want_resident -= fd.n_new[j + fd.lead]
-        assert (fd.ride is not None) == (0 < fd.n_new[j + fd.lead] <= fd.ride_max)
+        # out of the table at once, the bytes leave inside the next scoring launch; the exchange trades one for one
+        want_resident -= m
+        assert (fd.ride is not None) == (m > 0) and fd.resident == want_resident
         if fd.ride is not None:
             rides.append((fd.ride[0][:fd.ride[2]].clone(), fd.ride[1][:fd.ride[2]].clone()))
         assert int((fd.state & RES).sum().item()) == want_resident
         assert int(fd.n_bad.item()) == 0
-    assert not rides and (rode > 0 or fd.n_new[2] == 0 or fd.n_new[2] > fd.ride_max)
+    assert rode > 0 and len(rides) <= 1
+    fd.flush()
+    torch.cuda.synchronize()
+    assert fd.ride is None and fd.free_ready == fd.free_tail and int(fd.n_bad.item()) == 0
