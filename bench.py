@@ -782,6 +782,7 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
         fd.beta(j)
         fd.score(j, j)
         fd.ema(j)
+        fd.settle()
         fd.prefetch_keys(j)
         fd.select(j)
         pass_marks[j][1].record(main)

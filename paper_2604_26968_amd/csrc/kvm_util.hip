@@ -106,7 +106,7 @@ extern "C" {
 
 const char* kvm_last_error(void) { return kvm::g_err; }
 
-const char* kvm_version(void) { return "0.3"; }
+const char* kvm_version(void) { return "0.4"; }
 
 int kvm_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) {
     using namespace kvm;

@@ -281,11 +281,12 @@ class FleetDevice:
     holds beyond the budget, plus up to `prefetch_cap` units that trade places with prefetched ones.
 
     `ahead` False: the victims are packed out in line, after the selection.
-    `ahead` True: the victims leave the table at once (kvm_pack_begin) and their bytes leave inside the
-    next step's first scoring launch, so the host link works beside the scoring; a step evicts at most
-    `ride_max` units (what the link moves during one scoring launch), so after a whole prompt has arrived
-    HBM is back at the budget some steps later.  Their frames are handed out again from the step after
-    that launch.
+    `ahead` True: the victims leave the table at once (kvm_pack_begin, kvm_exchange_begin) and the bytes
+    of both move inside the next step's first scoring launch, so the host link works beside the scoring; a
+    step evicts at most `ride_max` units (what the link moves during one scoring launch), so after a whole
+    prompt has arrived HBM is back at the budget some steps later.  The frames are handed out again from
+    the step after that launch, and the prefetched units are in HBM from that step's selection on
+    (kvm_exchange_end after its EMA: they were not scored in that launch).
     """
 
     def __init__(self, plan: FleetPlan, kvm, torch, pool_units: int, head_weights: List[float], tier, tier_slots: int,
@@ -381,8 +382,11 @@ class FleetDevice:
         self.budget = self.resident = 0
         self.evict_now = 0                                     # victims of the current step beyond the exchange
         self.evicted = []                                      # per step, for whoever accounts for the link
-        self.ride_host = torch.full((max(sum(self.n_new), 1),), -1, dtype=torch.int64, device=dev)
-        self.ride = None                                       # (frames, host slots, count, log position behind them)
+        n_ride = max(sum(self.n_new), 1) + self.P
+        self.ride_frame = torch.full((n_ride,), -1, dtype=torch.int32, device=dev)
+        self.ride_host = torch.full((n_ride,), -1, dtype=torch.int64, device=dev)
+        self.ride = None               # (pairs, log position behind the freed frames) waiting for a scoring launch
+        self.settle_pairs = 0          # swap pairs whose prefetched units still wait for their table entries
         self.fresh_records = int(min(fresh_records, max(max(self.n_new), 1)))
         self.fresh = torch.randn(self.fresh_records * self.rec // 2, generator=gen, device=dev,
                                  dtype=torch.float32).to(tdt).view(torch.uint8)
@@ -424,10 +428,10 @@ class FleetDevice:
         ride, self.ride = self.ride, None
         for a, d in enumerate(self.arch):
             if d["n_rows"]:
-                if ride is not None:                       # the bytes of the last eviction leave inside this launch
+                if ride is not None:                       # the bytes of the last step's moves travel inside this launch
                     self.kvm.kvm_score_step_xfer(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass,
-                                                 self.ws, ride[0], ride[1], ride[2], self.tier)
-                    self.free_ready = ride[3]          # later launches on the stream may reuse those frames
+                                                 self.ws, self.ride_frame, self.ride_host, ride[0], self.tier)
+                    self.free_ready = ride[1]          # later launches on the stream may reuse those frames
                     ride = None
                 else:
                     self.kvm.kvm_score_step(self.pool, self.rows(a, j), d["q"][q_set % 4], self.scale, self.mass,
@@ -439,6 +443,12 @@ class FleetDevice:
             if d["n_rows"]:
                 self.kvm.kvm_ema_update(self.rows(a, j), self.mass, self.decay, d["weight"], self.pair, self.p_hat,
                                         self.state, self.S, self.prio)
+
+    def settle(self):
+        """The units prefetched by the exchange whose bytes the last scoring launch moved get their frames."""
+        if self.settle_pairs:
+            self.kvm.kvm_exchange_end(self.slot_tbl, self.state, self.pf_list, self.ride_frame, self.settle_pairs)
+            self.settle_pairs = 0
 
     def prefetch_keys(self, j: int):
         if not self.P:
@@ -466,7 +476,12 @@ class FleetDevice:
         table here and copied out by the next scoring launch."""
         kvm = self.kvm
         P = self.P
-        if P:
+        assert self.ride is None and self.settle_pairs == 0
+        if P and self.ahead:
+            kvm.kvm_exchange_begin(self.pool, self.slot_tbl, self.state, self.victims[:P], self.pf_list, P,
+                                   self.tier_slots, self.ride_frame[:P], self.ride_host[:P], n_out_dev=self.n_v,
+                                   n_in_dev=self.n_pf, n_bad=self.n_bad)
+        elif P:
             kvm.kvm_exchange(self.pool, self.slot_tbl, self.state, self.victims[:P], self.pf_list, P, self.tier,
                              n_out_dev=self.n_v, n_in_dev=self.n_pf, n_bad=self.n_bad)
         m = self.evict_now
@@ -477,10 +492,10 @@ class FleetDevice:
             slots = self.torch.arange(self.next_slot, self.next_slot + m, dtype=self.torch.int32, device="cuda")
             freed = self.free[self.free_tail:self.free_tail + m]
             if self.ahead:
-                assert self.ride is None
                 kvm.kvm_pack_begin(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots,
-                                   self.tier_slots, freed, self.ride_host, n_bad=self.n_bad)
-                self.ride = (freed, self.ride_host, m, self.free_tail + m)
+                                   self.tier_slots, self.ride_frame[P:P + m], self.ride_host[P:P + m],
+                                   n_bad=self.n_bad)
+                freed.copy_(self.ride_frame[P:P + m])
             else:
                 kvm.kvm_pack(self.pool, self.slot_tbl, self.state, self.victims[P:P + m], m, slots, freed, None,
                              self.tier[self.next_slot * self.rec:(self.next_slot + m) * self.rec], n_bad=self.n_bad)
@@ -488,23 +503,27 @@ class FleetDevice:
             self.free_tail += m
             self.next_slot += m
             self.resident -= m
+        if self.ahead and P + m:
+            self.ride = (P + m, self.free_tail)
+            self.settle_pairs = P
 
     def flush(self):
-        """Bytes of a last eviction that no scoring launch has carried yet leave in a launch of their own."""
-        if self.ride is None:
-            return
-        ride, self.ride = self.ride, None
-        d = self.arch[0]
-        none = self.kvm.make_rows(d["init_ntok"][:0], d["off"][:0], d["q_off"][:0], self.slot_tbl, d["g"], 0)
-        self.kvm.kvm_score_step_xfer(self.pool, none, d["q"][0], self.scale, self.mass, self.ws, ride[0], ride[1],
-                                     ride[2], self.tier)
-        self.free_ready = ride[3]
+        """Bytes that no scoring launch has carried yet move in a launch of their own."""
+        if self.ride is not None:
+            ride, self.ride = self.ride, None
+            d = self.arch[0]
+            none = self.kvm.make_rows(d["init_ntok"][:0], d["off"][:0], d["q_off"][:0], self.slot_tbl, d["g"], 0)
+            self.kvm.kvm_score_step_xfer(self.pool, none, d["q"][0], self.scale, self.mass, self.ws, self.ride_frame,
+                                         self.ride_host, ride[0], self.tier)
+            self.free_ready = ride[1]
+        self.settle()
 
     def step(self, j: int):
         self.arrive(j)
         self.beta(j)
         self.score(j, j)
         self.ema(j)
+        self.settle()
         self.prefetch_keys(j)
         self.select(j)
         self.move(j)

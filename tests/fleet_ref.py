@@ -40,6 +40,7 @@ class FleetRef:
         self.free = np.zeros(0, np.int32)
         self.free_head = self.free_ready = self.free_tail = 0
         self.pending_ready = None
+        self.pending_in = None          # (prefetched uids, their frames): in HBM once the driver settles the exchange
         self.budget = self.resident = 0
         self.evict_now = 0
         self.arch = []
@@ -99,6 +100,14 @@ class FleetRef:
                 self.o.ema_update(ntok, d["off"], self.mass, self.decay, d["weight"], self.pair, self.p_hat, self.state,
                                   self.S, self.prio, row_active=act)
 
+    def settle(self):
+        """The prefetched units of an exchange in three parts get their frames (what kvm_exchange_end does)."""
+        if self.pending_in is not None:
+            uids, frames = self.pending_in
+            self.tbl[uids] = frames
+            self.state[uids] = (self.state[uids] & (255 - HOST)) | RES
+            self.pending_in = None
+
     def prefetch_keys(self, j):
         if not self.P:
             return
@@ -117,8 +126,18 @@ class FleetRef:
         P = self.P
         n_pairs = min(P, len(self.victims), len(self.pf_list))
         if n_pairs:
+            ins = self.pf_list[:n_pairs]
+            before = self.tbl[ins].copy()
             self.o.exchange(self.k8, self.v8, self.uk, self.uv, self.tbl, self.state, self.victims[:n_pairs],
-                            self.pf_list[:n_pairs], self.tier, n_bad=self.n_bad)
+                            ins, self.tier, n_bad=self.n_bad)
+            if self.ahead:
+                # in three parts the bytes move inside the next scoring launch and the prefetched units get their
+                # table entries after that step's EMA: until then they read as on the host, at their old slot
+                # (nothing looks at the frames or the records meanwhile: neither unit of a pair is in HBM)
+                done = self.tbl[ins] >= 0
+                self.pending_in = (ins[done], self.tbl[ins[done]].copy())
+                self.tbl[ins[done]] = before[done]
+                self.state[ins[done]] = (self.state[ins[done]] & (255 - RES)) | HOST
         # whether the bytes leave now or inside the next scoring launch, tables, state and tier end up as a
         # plain pack leaves them, and nothing reads the records or reuses the frames in between
         m = self.evict_now

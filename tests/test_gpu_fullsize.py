@@ -326,7 +326,7 @@ def test_fleet_full_size_sampled(oracle):
     assert int(((fd.state & HOST) != 0).sum().item()) == keep    # the other victims were demoted below tier 1
     want_resident = budget
     assert fd.budget == fd.resident == budget
-    rides, rode = [], 0
+    rides, rode, in_flight = [], 0, 0
     for j in range(3):
         fd.arrive(j)
         want_resident += fd.n_new[j]
@@ -336,6 +336,7 @@ def test_fleet_full_size_sampled(oracle):
         torch.cuda.synchronize()
         if rides:                           # the last eviction's records were written by this scoring launch
             frames, hosts = rides.pop()
+            frames, hosts = frames[fd.P:], hosts[fd.P:]        # behind the swap pairs of the exchange
             pick_r = torch.from_numpy(rng.choice(frames.numel(), size=min(512, frames.numel()), replace=False)).to(dev)
             fr = frames[pick_r].long()
             hs = (hosts[pick_r] & ~kvm.XFER_OUT_ONLY).cpu().numpy()
@@ -348,7 +349,8 @@ def test_fleet_full_size_sampled(oracle):
             check_rows(j, "window step %d" % j)
         # only resident units of decoding rows are written; the masses of every decoding row sum to [1, g]
         resident = (fd.state & RES) != 0
-        assert int(resident.sum().item()) == want_resident, (j, int(resident.sum().item()), want_resident)
+        # (the units the last exchange brings in get their frames when it is settled, after this step's EMA)
+        assert int(resident.sum().item()) == want_resident - in_flight, (j, int(resident.sum().item()), want_resident)
         written = fd.mass >= 0
         assert bool((written <= resident).all())
         for a, d in enumerate(fd.arch):
@@ -367,6 +369,8 @@ def test_fleet_full_size_sampled(oracle):
             chk = rows_on & has_res
             assert float(sums[chk].min()) > 1.0 - 1e-4 and float(sums[chk].max()) < d["g"] + 1e-3, (j, a)
         fd.ema(j)
+        fd.settle()
+        in_flight = 0
         fd.prefetch_keys(j)
         fd.select(j)
         torch.cuda.synchronize()
@@ -378,12 +382,13 @@ def test_fleet_full_size_sampled(oracle):
         torch.cuda.synchronize()
         # out of the table at once, the bytes leave inside the next scoring launch; the exchange trades one for one
         want_resident -= m
-        assert (fd.ride is not None) == (m > 0) and fd.resident == want_resident
-        if fd.ride is not None:
-            rides.append((fd.ride[0][:fd.ride[2]].clone(), fd.ride[1][:fd.ride[2]].clone()))
-        assert int((fd.state & RES).sum().item()) == want_resident
+        assert fd.ride is not None and fd.ride[0] == fd.P + m and fd.resident == want_resident
+        rides.append((fd.ride_frame[:fd.ride[0]].clone(), fd.ride_host[:fd.ride[0]].clone()))
+        in_flight = n_pairs              # out of the table, their partners not yet in
+        assert int((fd.state & RES).sum().item()) == want_resident - in_flight
         assert int(fd.n_bad.item()) == 0
     assert rode > 0 and len(rides) <= 1
     fd.flush()
     torch.cuda.synchronize()
     assert fd.ride is None and fd.free_ready == fd.free_tail and int(fd.n_bad.item()) == 0
+    assert int((fd.state & RES).sum().item()) == want_resident
