@@ -54,12 +54,10 @@ DEFAULT_ORDER = ["llama70b", "llama8b", "mla", "fleet"]
 # whose kernels were profiled: a run of any other version, size or step count reports traffic null, because the
 # counters no longer describe what it launches.
 PROFILED_TRAFFIC = {
-    "llama70b": ("0.3", "profiles/score_row_dot2_llama70b.md", int(21062935.6 * 2048 + 147102.7 * 1024)),
-    "llama8b": ("0.3", "profiles/score_tile_dot2_llama8b_growing.md", int((6612857.2 + 18.0) * 2048 + 22260.8 * 1024)),
-    "mla": ("0.3", "profiles/score_tile_wide_mla.md",
-            int((14707484.5 + 416518.4) * 2048 + (840307.0 + 15347.0) * 1024)),
-    "fleet": ("0.3", "profiles/score_tile_fleet.md",
-              int(((11188650.8 + 7090.9 + 784008.8 + 11504.3) * 2048 + (27588.5 + 1875.3 + 23777.2 + 701.1) * 1024) / 2)),
+    "llama70b": ("0.4", "profiles/score_row_llama70b.md", int(21056580.6 * 2048 + 147102.6 * 1024)),
+    "llama8b": ("0.4", "profiles/score_tile_dot2_llama8b_growing.md", int(6616992.0 * 2048 + 29938.1 * 1024)),
+    "mla": ("0.4", "profiles/score_tile_wide_mla.md", int(15123149.8 * 2048 + 855654.0 * 1024)),
+    "fleet": ("0.4", "profiles/score_tile_fleet.md", int((12314068.4 * 2048 + 201429.7 * 1024) / 2)),
 }
 KERNEL_NAMES = ("score_plan", "score_partial", "score_finalize", "ema_prio", "beta", "select_hist", "select_emit",
                 "pack", "unpack", "swap", "span", "prefetch_keys", "hash", "dedup", "exchange_flip")
@@ -842,7 +840,7 @@ def run_fleet(args, torch, np, kvm, synth, pinned, link, prep, ahead=True, brief
     algo = float(scored_h.sum()) * (unit_k + 4) + blocks_active * 4 + q_bytes
     achieved = algo / (sp_ms * 1e-3) / 1e9
     prof = PROFILED_TRAFFIC.get(prep["name"])
-    at_defaults = args.steps == 20 and args.warmup == 5 and not args.n_seq
+    at_defaults = args.steps == 20 and args.warmup == 5 and not args.n_seq and not args.ride_max and ahead
     traffic = prof[2] if (prof and prof[0] == kvm.kvm_version() and at_defaults) else None
     warm["score_partial"] = round(sp_ms / max(cnt, 1), 4)
     out = {
