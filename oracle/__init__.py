@@ -308,3 +308,29 @@ def decode(bits: int, dtype: int) -> float:
     f = lib().kvm_ref_decode
     f.restype = C.c_double
     return float(f(C.c_uint16(bits), C.c_int(dtype)))
+
+
+def dedup_share(slot_tbl, state, n_slots, uids, canon, frame_refs, n_bad=None):
+    """Duplicates give up their frames and read their canonical unit's.  Returns freed frames per item (-1: none)."""
+    n = len(uids)
+    freed = np.zeros(max(n, 1), np.int32)
+    rc = lib().kvm_ref_dedup_share(_p(slot_tbl, np.int32), _p(state, np.uint8), C.c_int64(len(state)),
+                                   C.c_uint64(n_slots), _p(uids, np.int64), _p(canon, np.int64), C.c_int64(n),
+                                   _p(frame_refs, np.uint32), _p(freed, np.int32), _p(n_bad, np.uint32))
+    _check(rc, "kvm_ref_dedup_share")
+    return freed[:n]
+
+
+def dedup_unshare(k_pool, v_pool, unit_k_bytes, unit_v_bytes, slot_tbl, state, uids, new_frames, frame_refs,
+                  n_bad=None):
+    """Units get frames of their own again.  Returns per item the frame that is free afterwards (-1: none)."""
+    n = len(uids)
+    freed = np.zeros(max(n, 1), np.int32)
+    n_slots = k_pool.size // unit_k_bytes
+    rc = lib().kvm_ref_dedup_unshare(
+        _p(k_pool.reshape(-1), np.uint8), _p(None if v_pool is None else v_pool.reshape(-1), np.uint8),
+        C.c_uint64(n_slots), C.c_uint32(unit_k_bytes), C.c_uint32(unit_v_bytes), _p(slot_tbl, np.int32),
+        _p(state, np.uint8), C.c_int64(len(state)), _p(uids, np.int64), _p(new_frames, np.int32), C.c_int64(n),
+        _p(frame_refs, np.uint32), _p(freed, np.int32), _p(n_bad, np.uint32))
+    _check(rc, "kvm_ref_dedup_unshare")
+    return freed[:n]

@@ -52,7 +52,7 @@
 #define REF_OK      0
 #define REF_EINVAL (-1)
 
-enum { ST_RESIDENT = 1, ST_ON_HOST = 2, ST_PROTECTED = 4, ST_SCORED = 8 };
+enum { ST_RESIDENT = 1, ST_ON_HOST = 2, ST_PROTECTED = 4, ST_SCORED = 8, ST_SHARED = 16 };
 
 /* ---------------------------------------------------------------- formats */
 
@@ -421,7 +421,7 @@ int kvm_ref_select_victims(const float* prio, const uint8_t* state, int64_t n_ui
     int64_t n_el = 0, n_res = 0;
     for (int64_t u = 0; u < n_uids; ++u) {
         if (state[u] & ST_RESIDENT) ++n_res;
-        if ((state[u] & ST_RESIDENT) && !(state[u] & ST_PROTECTED) && (state[u] & ST_SCORED)) {
+        if ((state[u] & ST_RESIDENT) && !(state[u] & (ST_PROTECTED | ST_SHARED)) && (state[u] & ST_SCORED)) {
             float p = prio[u];
             if (isnan(p)) p = INFINITY;      /* NaN ranks last */
             c[n_el].prio = p;                /* -0 == +0 under float comparison */
@@ -548,6 +548,9 @@ int kvm_ref_prefetch_keys(int n_rows, int block_tokens, int64_t n_uids,
 }
 
 /* ---------------------------------------------------------- pack / unpack */
+/* A unit that shares its frame with others (ST_SHARED, kvm_ref_dedup_share) is refused by pack
+ * and as the outgoing half of an exchange, like a unit that is not in HBM: its frame must not
+ * be handed out while others read it.  The victim selection never names such a unit. */
 
 int kvm_ref_pack(const uint8_t* k_pool, const uint8_t* v_pool, uint64_t n_slots,
                  uint32_t unit_k_bytes, uint32_t unit_v_bytes,
@@ -560,7 +563,7 @@ int kvm_ref_pack(const uint8_t* k_pool, const uint8_t* v_pool, uint64_t n_slots,
     for (int64_t i = 0; i < n; ++i) {
         const int64_t uid = uids[i];
         int32_t slot = -1;
-        if (uid >= 0 && uid < n_uids && (state[uid] & ST_RESIDENT)) slot = slot_tbl[uid];
+        if (uid >= 0 && uid < n_uids && (state[uid] & ST_RESIDENT) && !(state[uid] & ST_SHARED)) slot = slot_tbl[uid];
         if (slot < 0 || (uint64_t)slot >= n_slots) {
             freed_slots[i] = -1;
             if (n_bad) ++*n_bad;
@@ -619,7 +622,8 @@ int kvm_ref_exchange(uint8_t* k_pool, uint8_t* v_pool, uint64_t n_slots,
     for (int64_t i = 0; i < n; ++i) {
         const int64_t uo = out_uids[i], ui = in_uids[i];
         int ok = uo >= 0 && uo < n_uids && ui >= 0 && ui < n_uids && uo != ui;
-        ok = ok && (state[uo] & ST_RESIDENT) && slot_tbl[uo] >= 0 && (uint64_t)slot_tbl[uo] < n_slots;
+        ok = ok && (state[uo] & ST_RESIDENT) && !(state[uo] & ST_SHARED) && slot_tbl[uo] >= 0 &&
+             (uint64_t)slot_tbl[uo] < n_slots;
         ok = ok && (state[ui] & ST_ON_HOST) && !(state[ui] & ST_RESIDENT) && slot_tbl[ui] < 0 &&
              (uint64_t)(-1 - (int64_t)slot_tbl[ui]) < tier_slots;
         if (!ok) { if (n_bad) ++*n_bad; continue; }
@@ -793,6 +797,70 @@ int kvm_ref_dedup_release(const uint8_t* st_digest, uint32_t* st_refs, int64_t s
         while (e < st_n && memcmp(st_digest + 32 * e, digests + 32 * i, 32) != 0) ++e;
         if (e == st_n || st_refs[e] == 0) { if (n_bad) ++*n_bad; continue; }
         st_refs[e] -= 1;
+    }
+    return REF_OK;
+}
+
+/* Frames shared by units of equal content (section 3.6: a block whose content the pool already
+ * holds is referenced instead of being stored again).  Items in list order; canon[i] is what
+ * kvm_ref_dedup_insert reported for uids[i].  Item i with canon[i] != uids[i] whose two units are
+ * in range, RESIDENT and not PROTECTED (content still being written), whose duplicate is not
+ * SHARED already (others may read its frame) and whose frames are inside the pool and differ:
+ * the duplicate gives up its frame (freed[i]) and reads the canonical unit's from now on
+ * (slot_tbl[uid] = slot_tbl[canon]); both units get SHARED, which keeps them out of the victim
+ * selection and makes pack and exchange refuse them, so a frame that several units read is never
+ * handed out again; frame_refs[frame] = number of units reading it (2 after the first sharing,
+ * one more for each further duplicate; 0 for frames that are not shared).  Every other item:
+ * freed[i] = -1; a uid or canonical uid outside [0, n_uids) is counted in *n_bad. */
+int kvm_ref_dedup_share(int32_t* slot_tbl, uint8_t* state, int64_t n_uids, uint64_t n_slots,
+                        const int64_t* uids, const int64_t* canon, int64_t n, uint32_t* frame_refs,
+                        int32_t* freed, uint32_t* n_bad) {
+    if (!slot_tbl || !state || !frame_refs || n < 0 || (n > 0 && (!uids || !canon || !freed))) return REF_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t u = uids[i], c = canon[i];
+        freed[i] = -1;
+        if (u < 0 || u >= n_uids || c < 0 || c >= n_uids) { if (n_bad) ++*n_bad; continue; }
+        if (u == c) continue;
+        if (!(state[u] & ST_RESIDENT) || !(state[c] & ST_RESIDENT)) continue;
+        if ((state[u] & (ST_PROTECTED | ST_SHARED)) || (state[c] & ST_PROTECTED)) continue;
+        const int32_t fu = slot_tbl[u], fc = slot_tbl[c];
+        if (fu < 0 || (uint64_t)fu >= n_slots || fc < 0 || (uint64_t)fc >= n_slots || fu == fc) continue;
+        slot_tbl[u] = fc;
+        freed[i] = fu;
+        state[u] |= ST_SHARED;
+        state[c] |= ST_SHARED;
+        frame_refs[fc] += frame_refs[fc] == 0 ? 2u : 1u;
+    }
+    return REF_OK;
+}
+
+/* A unit gets a frame of its own again (before it may be evicted, or before its content is
+ * written to).  Item i with uids[i] in range, RESIDENT and SHARED, its frame and new_frames[i]
+ * inside the pool: the bytes it reads are copied to frame new_frames[i], slot_tbl[uid] =
+ * new_frames[i], SHARED is cleared, frame_refs[old frame] -= 1 (a unit left as the only reader
+ * of a frame keeps SHARED until it is unshared itself); when the count reaches 0 the old frame
+ * is free: freed[i] = old frame, otherwise -1.  Every other item: freed[i] = new_frames[i] (the
+ * frame comes back unused); out-of-range uids and frames are counted in *n_bad. */
+int kvm_ref_dedup_unshare(uint8_t* k_pool, uint8_t* v_pool, uint64_t n_slots, uint32_t unit_k_bytes,
+                          uint32_t unit_v_bytes, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                          const int64_t* uids, const int32_t* new_frames, int64_t n, uint32_t* frame_refs,
+                          int32_t* freed, uint32_t* n_bad) {
+    if (!k_pool || (unit_v_bytes && !v_pool) || !slot_tbl || !state || !frame_refs || n < 0) return REF_EINVAL;
+    if (n > 0 && (!uids || !new_frames || !freed)) return REF_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t u = uids[i];
+        const int32_t nf = new_frames[i];
+        freed[i] = nf;
+        if (u < 0 || u >= n_uids || nf < 0 || (uint64_t)nf >= n_slots) { if (n_bad) ++*n_bad; continue; }
+        if (!(state[u] & ST_RESIDENT) || !(state[u] & ST_SHARED)) continue;
+        const int32_t f = slot_tbl[u];
+        if (f < 0 || (uint64_t)f >= n_slots || f == nf || frame_refs[f] == 0) continue;
+        memcpy(k_pool + (size_t)nf * unit_k_bytes, k_pool + (size_t)f * unit_k_bytes, unit_k_bytes);
+        if (unit_v_bytes) memcpy(v_pool + (size_t)nf * unit_v_bytes, v_pool + (size_t)f * unit_v_bytes, unit_v_bytes);
+        slot_tbl[u] = nf;
+        state[u] &= (uint8_t)~ST_SHARED;
+        frame_refs[f] -= 1;
+        freed[i] = frame_refs[f] == 0 ? f : -1;
     }
     return REF_OK;
 }

@@ -119,3 +119,153 @@ def test_first_occurrence_is_canonical_and_duplicates_point_to_it(oracle):
     assert canon[0] == 99 and store.as_dict()[a.tobytes()] == (99, 1)
     with pytest.raises(oracle.OracleError):                                 # list full
         store.insert(np.arange(32 * 8, dtype=np.uint8).reshape(8, 32), np.arange(8, dtype=np.int64))
+
+
+# ------------------------------------------------------------------ frames shared by duplicates
+RES, HOST, PROT, SCORED, SHARED = 1, 2, 4, 8, 16
+
+
+class SharingModel:
+    """Frame sharing written out with Python containers: who reads which frame, by content.  The frame of a
+    unit is looked up in a dictionary, the readers of a frame are a set; nothing else."""
+
+    def __init__(self, frame_of, flags):
+        self.frame_of = dict(frame_of)                 # uid -> frame, units in HBM only
+        self.flags = dict(flags)                       # uid -> set of flag names
+        self.readers = {}
+        for u, f in self.frame_of.items():
+            self.readers.setdefault(f, set()).add(u)
+
+    def share(self, u, c, n_uids):
+        if not (0 <= u < n_uids and 0 <= c < n_uids):
+            return "bad"
+        if u == c or u not in self.frame_of or c not in self.frame_of:
+            return None
+        if "prot" in self.flags[u] or "shared" in self.flags[u] or "prot" in self.flags[c]:
+            return None
+        fu, fc = self.frame_of[u], self.frame_of[c]
+        if fu == fc:
+            return None
+        self.readers[fu].discard(u)
+        self.readers[fc].add(u)
+        self.frame_of[u] = fc
+        self.flags[u].add("shared")
+        self.flags[c].add("shared")
+        return fu
+
+    def unshare(self, u, nf, n_uids, n_slots):
+        if not (0 <= u < n_uids and 0 <= nf < n_slots):
+            return "bad", nf
+        if u not in self.frame_of or "shared" not in self.flags[u]:
+            return None, nf
+        f = self.frame_of[u]
+        self.readers[f].discard(u)
+        self.readers.setdefault(nf, set()).add(u)
+        self.frame_of[u] = nf
+        self.flags[u].discard("shared")
+        return "moved", (f if not self.readers[f] else -1)
+
+
+def sharing_case(seed, n_uids=60, n_slots=80, n_contents=9):
+    rng = np.random.default_rng(seed)
+    content = rng.integers(0, n_contents, size=n_uids)             # which content a unit holds
+    in_hbm = rng.random(n_uids) < 0.8
+    frames = rng.permutation(n_slots)[:n_uids].astype(np.int32)
+    tbl = np.where(in_hbm, frames, -1 - np.arange(n_uids)).astype(np.int32)
+    state = np.where(in_hbm, RES | SCORED, HOST).astype(np.uint8)
+    state[rng.random(n_uids) < 0.1] |= PROT
+    uk, uv = 64, 64
+    k = np.zeros((n_slots, uk), np.uint8)
+    v = np.zeros((n_slots, uv), np.uint8)
+    for u in range(n_uids):
+        if in_hbm[u]:
+            k[tbl[u]] = content[u] * 3 + 1
+            v[tbl[u]] = content[u] * 3 + 2
+    # canonical copy of a content = its first unit (what the store reports in list order)
+    first = {}
+    canon = np.array([first.setdefault(int(c), u) for u, c in enumerate(content)], np.int64)
+    return rng, content, tbl, state, k, v, uk, uv, canon
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_sharing_against_a_model_with_sets_of_readers(oracle, seed):
+    rng, content, tbl, state, k, v, uk, uv, canon = sharing_case(seed)
+    n_uids, n_slots = len(tbl), len(k)
+    model = SharingModel({u: int(tbl[u]) for u in range(n_uids) if state[u] & RES},
+                         {u: ({"prot"} if state[u] & PROT else set()) for u in range(n_uids)})
+    refs = np.zeros(n_slots, np.uint32)
+    uids = rng.permutation(n_uids).astype(np.int64)
+    uids = np.r_[uids, [-3, n_uids + 5]].astype(np.int64)          # two malformed entries
+    cn = np.r_[canon[uids[:-2]], [0, 1]].astype(np.int64)
+    bad = np.zeros(1, np.uint32)
+    freed = oracle.dedup_share(tbl, state, n_slots, uids, cn, refs, n_bad=bad)
+    want = [model.share(int(u), int(c), n_uids) for u, c in zip(uids, cn)]
+    assert bad[0] == 2 == sum(1 for w in want if w == "bad")
+    np.testing.assert_array_equal(freed, [w if isinstance(w, int) else -1 for w in want])
+    assert (freed >= 0).sum() > 5                                   # the case does share
+    for u in range(n_uids):
+        if state[u] & RES:
+            assert tbl[u] == model.frame_of[u]
+            assert bool(state[u] & SHARED) == ("shared" in model.flags[u])
+            # what a unit reads is still its own content
+            assert k[tbl[u], 0] == content[u] * 3 + 1 and v[tbl[u], 0] == content[u] * 3 + 2
+    for f in range(n_slots):
+        r = len(model.readers.get(f, ()))
+        assert refs[f] == (r if r >= 2 else 0), (f, refs[f], r)
+    # a frame given up is read by nobody; frames in use + frames given up = frames in use before
+    in_use = {int(tbl[u]) for u in range(n_uids) if state[u] & RES}
+    assert not in_use & set(int(f) for f in freed if f >= 0)
+    # a second call with the same list changes nothing: the duplicates are SHARED already
+    t2, s2, r2 = tbl.copy(), state.copy(), refs.copy()
+    again = oracle.dedup_share(tbl, state, n_slots, uids[:-2], cn[:-2], refs)
+    assert (again == -1).all() and (tbl == t2).all() and (state == s2).all() and (refs == r2).all()
+
+    # ---- and back: every shared unit gets a frame of its own, in a random order
+    free = [f for f in range(n_slots) if f not in in_use]
+    shared = np.array([u for u in range(n_uids) if state[u] & SHARED], np.int64)
+    rng.shuffle(shared)
+    extra = np.array([u for u in range(n_uids) if not (state[u] & SHARED)][:3], np.int64)     # not shared: skipped
+    lst = np.r_[shared, extra, [n_uids + 1]].astype(np.int64)
+    assert len(free) >= len(lst)
+    nf = np.array(free[:len(lst)], np.int32)
+    bad[:] = 0
+    got = oracle.dedup_unshare(k, v, uk, uv, tbl, state, lst, nf, refs, n_bad=bad)
+    assert bad[0] == 1
+    for i, (u, f_new) in enumerate(zip(lst, nf)):
+        kind, f = model.unshare(int(u), int(f_new), n_uids, n_slots)
+        assert got[i] == f, (i, kind, got[i], f)
+    assert not (state & SHARED).any() and not refs.any()
+    frames = [int(tbl[u]) for u in range(n_uids) if state[u] & RES]
+    assert len(frames) == len(set(frames))                            # every unit has a frame of its own again
+    for u in range(n_uids):
+        if state[u] & RES:
+            assert (k[tbl[u]] == content[u] * 3 + 1).all() and (v[tbl[u]] == content[u] * 3 + 2).all()
+    # frames free afterwards: the ones that came back + the ones never handed out = all frames not in use
+    back = set(int(f) for f in got if f >= 0) | set(free[len(lst):])
+    assert back == set(range(n_slots)) - set(frames)
+
+
+def test_shared_units_are_never_victims_and_cannot_be_packed(oracle):
+    """A frame that several units read must not be handed out: the selection skips SHARED units even at the
+    lowest priority, pack and the outgoing half of an exchange refuse them."""
+    n = 12
+    prio = np.arange(n, dtype=np.float32)
+    state = np.full(n, RES | SCORED, np.uint8)
+    state[[0, 1, 5]] |= SHARED
+    got = oracle.select_victims(prio, state, k=4)
+    np.testing.assert_array_equal(got, [2, 3, 4, 6])
+    got = oracle.select_victims(prio, state, k=-1, budget_units=2)      # 12 in HBM, 9 may go: all that are eligible
+    np.testing.assert_array_equal(got, [2, 3, 4, 6, 7, 8, 9, 10, 11])
+    uk = uv = 64
+    k = np.arange(n * uk, dtype=np.uint8).reshape(n, uk).copy()
+    v = k[::-1].copy()
+    tbl = np.arange(n, dtype=np.int32)
+    tbl[1] = 0                                                            # units 0 and 1 read frame 0
+    bad = np.zeros(1, np.uint32)
+    staging, freed = oracle.pack(k, v, uk, uv, tbl, state, np.array([1, 2], np.int64), np.array([7, 8], np.int32), n_bad=bad)
+    np.testing.assert_array_equal(freed, [-1, 2])
+    assert bad[0] == 1 and tbl[1] == 0 and state[1] == RES | SCORED | SHARED and tbl[2] == -9
+    tier = np.zeros((4, uk + uv), np.uint8)
+    state[3], tbl[3] = HOST, -1 - 1                                        # unit 3 on the host in slot 1
+    oracle.exchange(k, v, uk, uv, tbl, state, np.array([5], np.int64), np.array([3], np.int64), tier, n_bad=bad)
+    assert bad[0] == 2 and tbl[5] == 5 and state[3] == HOST
