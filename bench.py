@@ -192,6 +192,8 @@ def run_refined(args, torch, np, kvm, v):
     digests = torch.zeros((swap, 32), dtype=torch.uint8, device=dev)
     canon = torch.zeros(swap, dtype=torch.int64, device=dev)
     dedup_ws = torch.zeros(swap, dtype=torch.int64, device=dev)
+    frame_refs = torch.zeros(int(pool.n_slots), dtype=torch.int32, device=dev)
+    given_up = torch.full((swap,), -1, dtype=torch.int32, device=dev)
 
     def step(i):
         ev = evs[i % n_q_sets]
@@ -207,6 +209,8 @@ def run_refined(args, torch, np, kvm, v):
         kvm.kvm_score_step_xfer(pool, rows, qs[i % n_q_sets], scale, mass, ws, xf_frame, xf_host, swap, host_tier)
         main.wait_stream(side)
         kvm.kvm_dedup_insert(store, digests, arrived, swap, canon, dedup_ws)
+        # duplicates would give up their frames here (the synthetic K and V are random: there are none)
+        kvm.kvm_dedup_share(wl.slot_tbl, wl.state, int(pool.n_slots), arrived, canon, swap, frame_refs, given_up)
         kvm.kvm_ema_update_ex(rows, mass, decay, ex, row_weight, wl.pair, p_blend, wl.state, S, prio)
         kvm.kvm_span_update(rows, row_layer, mass, wl.state, 9, 10, span_sum, span_cnt, 256, 1 << 30, layer_window,
                             ws_span)
@@ -224,6 +228,7 @@ def run_refined(args, torch, np, kvm, v):
     torch.cuda.synchronize()
     assert int(n_bad.item()) == 0, int(n_bad.item())
     res["value"] = round(budget * shape.unit_k_bytes / (res["ms_per_step"] * 1e-3) / 1e9, 1)
+    res["frames_shared"] = int((frame_refs > 0).sum().item())
     res["note"] = "all refinements on; selection, estimates and content hashes beside the scoring launch"
     # bulk hashing rate (checkpoint-style pass over many units): integer-ALU bound, one lane per unit
     n_bulk = min(1 << 18, budget)

@@ -79,6 +79,8 @@ extern "C" {
 #define KVM_ST_ON_HOST   2u   /* unit has been packed to the host tier           */
 #define KVM_ST_PROTECTED 4u   /* never a victim (e.g. the block being written)   */
 #define KVM_ST_SCORED    8u   /* S holds at least one observation                */
+#define KVM_ST_SHARED   16u   /* reads a frame that other units read too (section 3.6): never a victim,
+                                 refused by pack / swap / exchange until kvm_dedup_unshare           */
 
 /* ---- group aggregation in kvm_score_step -------------------------------- */
 #define KVM_AGG_MAX  0        /* max over the query heads sharing the KV head    */
@@ -575,6 +577,41 @@ int kvm_dedup_insert(const kvm_store_t* store /* host struct of dev pointers */,
                      int64_t* canon_out /* dev [n] out */, uint32_t* n_full /* dev [1] in/out, or NULL */,
                      uint32_t* n_collide /* dev [1] in/out, or NULL */, void* ws, size_t ws_bytes, void* stream);
 int kvm_dedup_release(const kvm_store_t* store, const uint8_t* digests /* dev [n][32] */, int64_t n,
+                      uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+
+/* Frames shared by units of equal content (section 3.6: a block whose content the
+ * pool already holds is referenced instead of being stored again).
+ * kvm_dedup_share: canon[i] is what kvm_dedup_insert reported for uids[i].  Item i
+ * with canon[i] != uids[i] whose two units are in range, RESIDENT and not
+ * PROTECTED (content still being written), whose duplicate is not SHARED already
+ * (others may read its frame) and whose frames are inside the pool and differ: the
+ * duplicate gives up its frame (freed[i]) and reads the canonical unit's from now
+ * on (slot_tbl[uid] = slot_tbl[canon]); both units get KVM_ST_SHARED;
+ * frame_refs[frame] = number of units that read it (2 after the first sharing, one
+ * more per further duplicate; 0 for frames that are not shared; the caller zeroes
+ * the array once).  Every other item: freed[i] = -1; a uid or canonical uid
+ * outside [0, n_uids) is counted in *n_bad.  Within one call no uid may repeat in
+ * uids and no unit may be both a duplicate and somebody's canonical copy (what
+ * kvm_dedup_insert reports never is).  Scoring, EMA and hashing read shared frames
+ * like any other; selection, pack, swap and exchange leave SHARED units alone.
+ * kvm_dedup_unshare: a unit gets a frame of its own again (before it may be
+ * evicted or written to).  Item i with uids[i] in range, RESIDENT and SHARED and
+ * new_frames[i] inside the pool: the bytes it reads are copied to frame
+ * new_frames[i], slot_tbl[uid] = new_frames[i], SHARED is cleared,
+ * frame_refs[old frame] -= 1; a unit left as the only reader of a frame keeps
+ * SHARED until it is unshared itself.  freed[i] = the old frame if nobody reads it
+ * any more, else -1 (when the last readers of a frame are unshared in one call,
+ * which of their items reports the frame is not defined; exactly one does).
+ * Every other item: freed[i] = new_frames[i] (the frame comes back unused);
+ * out-of-range uids and frames are counted in *n_bad.  No uid may repeat.
+ * Errors: KVM_EINVAL (null buffers, negative counts), KVM_ESHAPE (unit sizes).  */
+int kvm_dedup_share(int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */, int64_t n_uids,
+                    uint64_t n_slots, const int64_t* uids /* dev [n] */, const int64_t* canon /* dev [n] */,
+                    int64_t n, uint32_t* frame_refs /* dev [n_slots] in/out */, int32_t* freed /* dev [n] out */,
+                    uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
+int kvm_dedup_unshare(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
+                      int64_t n_uids, const int64_t* uids /* dev [n] */, const int32_t* new_frames /* dev [n] */,
+                      int64_t n, uint32_t* frame_refs /* dev [n_slots] in/out */, int32_t* freed /* dev [n] out */,
                       uint32_t* n_bad /* dev [1] in/out, or NULL */, void* stream);
 
 /* ======================================================================== *

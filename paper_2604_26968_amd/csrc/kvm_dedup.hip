@@ -246,8 +246,132 @@ int check_store(const char* who, const kvm_store_t* st, Store* out) {
     return KVM_OK;
 }
 
+// ---- frames shared by duplicates ------------------------------------------------------------------
+// Two launches: the first moves the duplicates (every item writes only its own unit's entries), the second
+// flags the canonical units.  Several duplicates of one canonical unit then store the same byte, and no
+// launch reads a state byte that another of its threads may be changing.
+
+__global__ __launch_bounds__(256) void dedup_share_kernel(int32_t* __restrict__ slot_tbl, uint8_t* __restrict__ state,
+                                                          int64_t n_uids, uint32_t n_slots,
+                                                          const int64_t* __restrict__ uids,
+                                                          const int64_t* __restrict__ canon, int64_t n,
+                                                          uint32_t* __restrict__ frame_refs,
+                                                          int32_t* __restrict__ freed, uint32_t* n_bad) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int64_t u = uids[i], c = canon[i];
+    int32_t out = -1;
+    if (u < 0 || u >= n_uids || c < 0 || c >= n_uids) {
+        if (n_bad) atomicAdd(n_bad, 1u);
+    } else if (u != c) {
+        const uint8_t su = state[u], sc = state[c];
+        const int32_t fu = slot_tbl[u], fc = slot_tbl[c];
+        if ((su & KVM_ST_RESIDENT) && (sc & KVM_ST_RESIDENT) && !(su & (KVM_ST_PROTECTED | KVM_ST_SHARED)) &&
+            !(sc & KVM_ST_PROTECTED) && (uint32_t)fu < n_slots && (uint32_t)fc < n_slots && fu != fc) {
+            slot_tbl[u] = fc;
+            out = fu;
+            state[u] = su | KVM_ST_SHARED;
+            // the canonical unit's own reading is counted by whichever duplicate comes first
+            if (atomicAdd(&frame_refs[fc], 1u) == 0) atomicAdd(&frame_refs[fc], 1u);
+        }
+    }
+    freed[i] = out;
+}
+
+__global__ __launch_bounds__(256) void dedup_share_flag_kernel(uint8_t* __restrict__ state, const int64_t* __restrict__ canon,
+                                                               int64_t n, const int32_t* __restrict__ freed) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n || freed[i] < 0) return;           // an accepted item: its canonical uid was checked by the first launch
+    state[canon[i]] |= KVM_ST_SHARED;
+}
+
+// One workgroup per item: thread 0 decides, everyone copies.
+__global__ __launch_bounds__(256) void dedup_unshare_kernel(uint4* __restrict__ k_pool, uint4* __restrict__ v_pool,
+                                                            uint32_t n_slots, uint32_t k_v4, uint32_t v_v4,
+                                                            int32_t* __restrict__ slot_tbl, uint8_t* __restrict__ state,
+                                                            int64_t n_uids, const int64_t* __restrict__ uids,
+                                                            const int32_t* __restrict__ new_frames,
+                                                            uint32_t* __restrict__ frame_refs,
+                                                            int32_t* __restrict__ freed, uint32_t* n_bad) {
+    __shared__ int32_t s_from;
+    const int64_t i = blockIdx.x;
+    const int32_t nf = new_frames[i];
+    if (threadIdx.x == 0) {
+        const int64_t u = uids[i];
+        int32_t from = -1;
+        if (u < 0 || u >= n_uids || (uint32_t)nf >= n_slots) {
+            if (n_bad) atomicAdd(n_bad, 1u);
+        } else if ((state[u] & (KVM_ST_RESIDENT | KVM_ST_SHARED)) == (KVM_ST_RESIDENT | KVM_ST_SHARED)) {
+            const int32_t f = slot_tbl[u];
+            if ((uint32_t)f < n_slots && f != nf && frame_refs[f] != 0) from = f;
+        }
+        s_from = from;
+        if (from < 0) freed[i] = nf;
+    }
+    __syncthreads();
+    const int32_t f = s_from;
+    if (f < 0) return;
+    const uint4* ks = k_pool + (size_t)f * k_v4;
+    uint4* kd = k_pool + (size_t)nf * k_v4;
+    for (uint32_t v = threadIdx.x; v < k_v4; v += 256) kd[v] = ks[v];
+    if (v_v4) {
+        const uint4* vs = v_pool + (size_t)f * v_v4;
+        uint4* vd = v_pool + (size_t)nf * v_v4;
+        for (uint32_t v = threadIdx.x; v < v_v4; v += 256) vd[v] = vs[v];
+    }
+    __syncthreads();                       // the copy has been read before the old frame may be reported free
+    if (threadIdx.x == 0) {
+        const int64_t u = uids[i];
+        slot_tbl[u] = nf;
+        state[u] &= (uint8_t)~KVM_ST_SHARED;
+        freed[i] = atomicSub(&frame_refs[f], 1u) == 1u ? f : -1;
+    }
+}
+
 }  // namespace
 }  // namespace kvm
+
+extern "C" int kvm_dedup_share(int32_t* slot_tbl, uint8_t* state, int64_t n_uids, uint64_t n_slots, const int64_t* uids,
+                               const int64_t* canon, int64_t n, uint32_t* frame_refs, int32_t* freed, uint32_t* n_bad,
+                               void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(n >= 0 && n_uids >= 0, KVM_EINVAL, "kvm_dedup_share: negative count");
+    KVM_REQUIRE(n_slots <= 0x7fffffffull, KVM_EINVAL, "kvm_dedup_share: n_slots exceeds int32 slot ids");
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(slot_tbl && state && uids && canon && frame_refs && freed, KVM_EINVAL, "kvm_dedup_share: null buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("dedup", st);
+    dedup_share_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(slot_tbl, state, n_uids, (uint32_t)n_slots, uids,
+                                                                     canon, n, frame_refs, freed, n_bad);
+    dedup_share_flag_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(state, canon, n, freed);
+    return launch_status("dedup_share");
+}
+
+extern "C" int kvm_dedup_unshare(const kvm_pool_t* pool, int32_t* slot_tbl, uint8_t* state, int64_t n_uids,
+                                 const int64_t* uids, const int32_t* new_frames, int64_t n, uint32_t* frame_refs,
+                                 int32_t* freed, uint32_t* n_bad, void* stream) {
+    using namespace kvm;
+    clear_error();
+    KVM_REQUIRE(pool, KVM_EINVAL, "kvm_dedup_unshare: null pool");
+    KVM_REQUIRE(n >= 0 && n_uids >= 0 && n <= 0x7fffffffll, KVM_EINVAL, "kvm_dedup_unshare: count out of range");
+    KVM_REQUIRE(pool->unit_k_bytes > 0 && pool->unit_k_bytes % 16 == 0 && pool->unit_v_bytes % 16 == 0, KVM_ESHAPE,
+                "kvm_dedup_unshare: unit sizes (%u, %u) must be multiples of 16", pool->unit_k_bytes,
+                pool->unit_v_bytes);
+    KVM_REQUIRE(pool->n_slots <= 0x7fffffffull, KVM_EINVAL, "kvm_dedup_unshare: n_slots exceeds int32 slot ids");
+    if (n == 0) return KVM_OK;
+    KVM_REQUIRE(pool->k_pool && (pool->v_pool || pool->unit_v_bytes == 0), KVM_EINVAL,
+                "kvm_dedup_unshare: null pool memory");
+    KVM_REQUIRE(slot_tbl && state && uids && new_frames && frame_refs && freed, KVM_EINVAL,
+                "kvm_dedup_unshare: null buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TimedLaunch tl("dedup", st);
+    dedup_unshare_kernel<<<(unsigned)n, 256, 0, st>>>(static_cast<uint4*>(pool->k_pool), static_cast<uint4*>(pool->v_pool),
+                                                      (uint32_t)pool->n_slots, pool->unit_k_bytes / 16,
+                                                      pool->unit_v_bytes / 16, slot_tbl, state, n_uids, uids, new_frames,
+                                                      frame_refs, freed, n_bad);
+    return launch_status("dedup_unshare");
+}
 
 extern "C" int kvm_hash_units(const kvm_pool_t* pool, const int32_t* slot_tbl, const uint8_t* state, int64_t n_uids,
                               const int64_t* uids, int64_t n, uint8_t* digests, uint32_t* n_bad, void* stream) {

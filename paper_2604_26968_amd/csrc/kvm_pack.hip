@@ -14,6 +14,12 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// A unit may leave HBM only from a frame of its own: one that shares its frame with units of equal content
+// (KVM_ST_SHARED) is refused like a unit that is not in HBM, so that frame is never handed out while read.
+__device__ __forceinline__ bool in_own_frame(uint8_t st) {
+    return (st & (KVM_ST_RESIDENT | KVM_ST_SHARED)) == KVM_ST_RESIDENT;
+}
+
 // first .. first + count of the list; record i lands at staging + (i - first) * rec.
 __global__ __launch_bounds__(kThreads) void pack_kernel(const uint4* __restrict__ k_pool,
                                                         const uint4* __restrict__ v_pool, uint32_t n_slots,
@@ -30,7 +36,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const uint4* __restrict_
     if (threadIdx.x == 0) {
         const int64_t uid = uids[i];
         int32_t slot = -1;
-        if (uid >= 0 && uid < n_uids && (state[uid] & KVM_ST_RESIDENT)) slot = slot_tbl[uid];
+        if (uid >= 0 && uid < n_uids && in_own_frame(state[uid])) slot = slot_tbl[uid];
         if ((uint32_t)slot >= n_slots) slot = -1;
         s_slot = slot;
         freed_slots[i] = slot;
@@ -106,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void swap_kernel(uint4* __restrict__ k_po
     if (threadIdx.x == 0) {
         const int64_t uo = out_uids[i], ui = in_uids[i];
         int32_t slot = -1;
-        if (uo >= 0 && uo < n_uids && (state[uo] & KVM_ST_RESIDENT)) slot = slot_tbl[uo];
+        if (uo >= 0 && uo < n_uids && in_own_frame(state[uo])) slot = slot_tbl[uo];
         if ((uint32_t)slot >= n_slots) slot = -1;
         freed_slots[i] = slot;
         int refill = 0;
@@ -174,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void exchange_kernel(uint4* __restrict__ 
         const int64_t uo = out_uids[i], ui = in_uids[i];
         int32_t slot = -1;
         int64_t host = -1;
-        if (uo >= 0 && uo < n_uids && (state[uo] & KVM_ST_RESIDENT)) slot = slot_tbl[uo];
+        if (uo >= 0 && uo < n_uids && in_own_frame(state[uo])) slot = slot_tbl[uo];
         if ((uint32_t)slot >= n_slots) slot = -1;
         if (ui >= 0 && ui < n_uids && ui != uo && (state[ui] & KVM_ST_ON_HOST) && !(state[ui] & KVM_ST_RESIDENT) &&
             slot_tbl[ui] < 0)
@@ -228,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void exchange_begin_kernel(uint32_t n_slo
     int64_t h = -1;
     if (!((n_out_dev && i >= *n_out_dev) || (n_in_dev && i >= *n_in_dev))) {
         const int64_t uo = out_uids[i], ui = in_uids[i];
-        if (uo >= 0 && uo < n_uids && (state[uo] & KVM_ST_RESIDENT)) slot = slot_tbl[uo];
+        if (uo >= 0 && uo < n_uids && in_own_frame(state[uo])) slot = slot_tbl[uo];
         if ((uint32_t)slot >= n_slots) slot = -1;
         if (ui >= 0 && ui < n_uids && ui != uo && (state[ui] & KVM_ST_ON_HOST) && !(state[ui] & KVM_ST_RESIDENT) &&
             slot_tbl[ui] < 0)
@@ -262,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void pack_begin_kernel(uint32_t n_slots, 
     if (!(n_dev && i >= *n_dev)) {
         const int64_t uid = uids[i];
         h = host_slots[i];
-        if (uid >= 0 && uid < n_uids && (state[uid] & KVM_ST_RESIDENT)) slot = slot_tbl[uid];
+        if (uid >= 0 && uid < n_uids && in_own_frame(state[uid])) slot = slot_tbl[uid];
         if ((uint32_t)slot >= n_slots || (uint64_t)h >= tier_slots) slot = -1;
         if (slot >= 0) {
             slot_tbl[uid] = (int32_t)(-1 - h);

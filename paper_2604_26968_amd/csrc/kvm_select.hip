@@ -40,7 +40,8 @@ struct Ctrl {
 };
 
 __device__ __forceinline__ bool eligible(uint8_t st) {
-    return (st & (KVM_ST_RESIDENT | KVM_ST_PROTECTED | KVM_ST_SCORED)) == (KVM_ST_RESIDENT | KVM_ST_SCORED);
+    return (st & (KVM_ST_RESIDENT | KVM_ST_PROTECTED | KVM_ST_SCORED | KVM_ST_SHARED)) ==
+           (KVM_ST_RESIDENT | KVM_ST_SCORED);
 }
 
 // Monotone map fp32 -> uint32 (a < b as floats  <=>  key(a) < key(b)); NaN ranks

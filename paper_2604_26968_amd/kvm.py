@@ -19,7 +19,7 @@ from ._build import LIB_PATH, build  # noqa: F401  (re-exported)
 OK, EINVAL, ESHAPE, ENOSPC, EHIP = 0, -1, -2, -3, -4
 BF16, FP16 = 0, 1
 ARCH_MHA, ARCH_GQA, ARCH_MQA, ARCH_MLA = 0, 1, 2, 3
-ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED = 1, 2, 4, 8
+ST_RESIDENT, ST_ON_HOST, ST_PROTECTED, ST_SCORED, ST_SHARED = 1, 2, 4, 8, 16
 AGG_MAX, AGG_MEAN = 0, 1
 OP_SCORE, OP_SELECT, OP_SPAN = 0, 1, 2
 SELECT_STATIC_MAX_UIDS = 1 << 26
@@ -27,7 +27,7 @@ XFER_OUT_ONLY = 1 << 62
 
 EXPORTS = ["kvm_size", "kvm_score_step", "kvm_score_step_xfer", "kvm_exchange_begin", "kvm_exchange_end", "kvm_pack_begin", "kvm_beta_update", "kvm_beta_blend_update", "kvm_ema_update",
            "kvm_ema_update_ex", "kvm_select_victims", "kvm_select_victims_static", "kvm_pack", "kvm_unpack", "kvm_swap", "kvm_exchange", "kvm_span_update",
-           "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_workspace_bytes", "kvm_last_error", "kvm_version", "kvm_probe_read",
+           "kvm_prefetch_keys", "kvm_hash_units", "kvm_dedup_insert", "kvm_dedup_release", "kvm_dedup_share", "kvm_dedup_unshare", "kvm_workspace_bytes", "kvm_last_error", "kvm_version", "kvm_probe_read",
            "kvm_timing_enable", "kvm_timing_only", "kvm_timing_reset", "kvm_timing_read"]
 
 
@@ -125,6 +125,10 @@ def _load() -> C.CDLL:
     lib.kvm_exchange_begin.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                        C.c_int64, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p]
+    lib.kvm_dedup_share.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_int64,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvm_dedup_unshare.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                      C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_pack_begin.argtypes = [C.POINTER(Pool), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                                    C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvm_exchange_end.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
@@ -379,6 +383,20 @@ def kvm_pack_begin(pool: Pool, slot_tbl, state, uids, n: int, host_slots, tier_s
 def kvm_exchange_end(slot_tbl, state, in_uids, frame, n: int, stream=None):
     _check(lib.kvm_exchange_end(_ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
                                 _ptr(in_uids, torch.int64), _ptr(frame, torch.int32), n, _stream(stream)))
+
+
+def kvm_dedup_share(slot_tbl, state, n_slots: int, uids, canon, n: int, frame_refs, freed, n_bad=None, stream=None):
+    _check(lib.kvm_dedup_share(_ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(), n_slots,
+                               _ptr(uids, torch.int64), _ptr(canon, torch.int64), n, _ptr(frame_refs, torch.int32),
+                               _ptr(freed, torch.int32), _ptr(n_bad, torch.int32), _stream(stream)))
+
+
+def kvm_dedup_unshare(pool: Pool, slot_tbl, state, uids, new_frames, n: int, frame_refs, freed, n_bad=None,
+                      stream=None):
+    _check(lib.kvm_dedup_unshare(C.byref(pool), _ptr(slot_tbl, torch.int32), _ptr(state, torch.uint8), state.numel(),
+                                 _ptr(uids, torch.int64), _ptr(new_frames, torch.int32), n,
+                                 _ptr(frame_refs, torch.int32), _ptr(freed, torch.int32), _ptr(n_bad, torch.int32),
+                                 _stream(stream)))
 
 
 def kvm_probe_read(buf, sink, stream=None):

@@ -148,6 +148,12 @@ def test_device_entry_points_validate_before_launching(kvm):
     assert lib.kvm_exchange(C.byref(pool), None, None, 8, None, None, 4, None, None, None, 4, None, None) == kvm.EINVAL
     assert lib.kvm_exchange_begin(C.byref(pool), None, None, 8, None, None, 4, None, None, 4, None, None, None,
                                   None) == kvm.EINVAL
+    assert lib.kvm_dedup_share(None, None, 8, 4, None, None, 3, None, None, None, None) == kvm.EINVAL
+    assert lib.kvm_dedup_share(None, None, 8, 4, None, None, 0, None, None, None, None) == kvm.OK
+    assert lib.kvm_dedup_share(None, None, 8, 1 << 40, None, None, 0, None, None, None, None) == kvm.EINVAL
+    assert lib.kvm_dedup_unshare(None, None, None, 8, None, None, 3, None, None, None, None) == kvm.EINVAL
+    assert lib.kvm_dedup_unshare(C.byref(pool), None, None, 8, None, None, 3, None, None, None, None) == kvm.EINVAL
+    assert lib.kvm_dedup_unshare(C.byref(pool), None, None, 8, None, None, 0, None, None, None, None) == kvm.OK
     assert lib.kvm_pack_begin(None, None, None, 8, None, 4, None, None, 4, None, None, None, None) == kvm.EINVAL
     assert lib.kvm_pack_begin(C.byref(pool), None, None, 8, None, 4, None, None, 4, None, None, None, None) == kvm.EINVAL
     assert lib.kvm_pack_begin(C.byref(pool), None, None, 8, None, 0, None, None, 4, None, None, None, None) == kvm.OK

@@ -566,6 +566,137 @@ def test_hash_then_dedup_finds_the_planted_duplicates(oracle):
         assert len(set(canon[np.searchsorted(uids, grp)])) == 1 and canon[np.searchsorted(uids, grp)][0] == grp.min()
 
 
+@pytest.mark.parametrize("shape", [
+    synth.Shape(2, 8, 2, 128, synth.BF16, True, [1000, 400]),
+    synth.Shape(2, 128, 1, 576, synth.BF16, False, [700]),          # latent units, no V
+])
+def test_duplicates_share_frames_and_get_their_own_back(oracle, shape):
+    """hash -> insert -> kvm_dedup_share: the duplicates read their canonical unit's frame, their own frames
+    come back free, tables / state / reader counts equal the oracle's; scoring gives the same masses as before
+    (same bytes); the selection never names a unit that shares a frame and pack refuses one; kvm_dedup_unshare
+    gives every such unit a frame of its own with the same bytes, tables equal the oracle's."""
+    from paper_2604_26968_amd import kvm
+    from tests.harness import oracle_score
+    SHARED = kvm.ST_SHARED
+    case = synth.make_case(shape, seed=45, spare_slots=20)
+    rng = np.random.default_rng(8)
+    groups = duplicate_some_frames(case, rng, 12, 4)
+    # (the canonical copy of a group is its first unit in list order, i.e. its smallest uid)
+    case.state[np.sort(groups[0])[1]] |= PROT            # a duplicate whose block is still being written
+    case.state[np.sort(groups[1])[0]] |= PROT            # a canonical copy that is
+    dev = DeviceCase(case)
+    k8, v8 = host_pools(case)
+    uk, uv = shape.unit_k_bytes, shape.unit_v_bytes
+    n_slots = case.n_slots
+    uids = np.flatnonzero(case.state & RES).astype(np.int64)
+    n = len(uids)
+    q = synth.make_queries(case, 3)
+    scale = 1.0 / np.sqrt(shape.dim)
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws)
+    torch.cuda.synchronize()
+    mass_before = dev.mass.cpu().numpy()
+    # digests and canonical uids on both sides
+    d = torch.zeros((n, 32), dtype=torch.uint8, device="cuda")
+    kvm.kvm_hash_units(dev.pool, dev.slot_tbl, dev.state, dev_of(uids), n, d)
+    store = kvm.make_store(1 << 12)
+    canon = torch.zeros(n, dtype=torch.int64, device="cuda")
+    ws = torch.full((n,), 0x7F7F7F7F7F7F7F7F, dtype=torch.int64, device="cuda")
+    kvm.kvm_dedup_insert(store, d, dev_of(uids), n, canon, ws)
+    ref_store = oracle.DedupStore(n)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    want_canon = ref_store.insert(oracle.hash_units(k8, v8, uk, uv, tbl, st, uids), uids)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(canon.cpu().numpy(), want_canon)
+    # share: the whole list plus two malformed entries
+    lst = np.r_[uids, [-2, case.n_uids + 3]].astype(np.int64)
+    cn = np.r_[want_canon, [0, 1]].astype(np.int64)
+    refs = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+    freed = torch.full((len(lst),), -7, dtype=torch.int32, device="cuda")
+    kvm.kvm_dedup_share(dev.slot_tbl, dev.state, n_slots, dev_of(lst), dev_of(cn), len(lst), refs, freed,
+                        n_bad=dev.n_bad)
+    o_refs = np.zeros(n_slots, np.uint32)
+    bad = np.zeros(1, np.uint32)
+    o_freed = oracle.dedup_share(tbl, st, n_slots, lst, cn, o_refs, n_bad=bad)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(freed.cpu().numpy(), o_freed)
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    np.testing.assert_array_equal(refs.cpu().numpy().view(np.uint32), o_refs)
+    assert int(dev.n_bad.item()) == int(bad[0]) == 2
+    n_shared = int((o_freed >= 0).sum())
+    is_dup = want_canon != uids
+    want_shared = is_dup & ((case.state[uids] & PROT) == 0) & ((case.state[want_canon] & PROT) == 0)
+    assert n_shared == int(want_shared.sum()) and 20 <= n_shared < int(is_dup.sum()) == 12 * 3
+    assert int(o_refs.sum()) == n_shared + len(np.unique(want_canon[want_shared]))
+    # same bytes behind every unit: same masses, bit for bit
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dev.mass.cpu().numpy(), mass_before)
+    want_mass = oracle_score(oracle, case, q, scale, fill=-1.0, slot_tbl=tbl)
+    w = want_mass != -1.0
+    np.testing.assert_allclose(mass_before[w], want_mass[w], rtol=1e-3, atol=1e-9)
+    # units that share a frame are never victims, whatever their priority, and pack refuses them
+    shared = np.flatnonzero(st & SHARED)
+    assert len(shared) == n_shared + len(np.unique(want_canon[want_shared]))
+    st_sel = st.copy()
+    st_sel[(st_sel & RES) != 0] |= SCORED
+    prio = rng.random(case.n_uids).astype(np.float32) + 1.0
+    prio[shared] = 0.0
+    from tests.test_gpu_parity import select_both
+    dcase = DeviceCase(synth.tiny_gqa(1))
+    got = select_both(oracle, dcase, prio, st_sel, k=len(uids))
+    assert not np.intersect1d(got, shared).size and len(got) == int(((st_sel & (RES | PROT | SCORED | SHARED)) == (RES | SCORED)).sum())
+    some = np.r_[shared[:5], got[:5]].astype(np.int64)
+    hs = np.arange(len(some), dtype=np.int32)
+    want_staging, want_freed = oracle.pack(k8, v8, uk, uv, tbl, st, some, hs, n_bad=bad)
+    got_staging, got_freed = dev.pack(some, hs, direct=True)
+    np.testing.assert_array_equal(got_freed, want_freed)
+    np.testing.assert_array_equal(got_freed[:5], -1)
+    np.testing.assert_array_equal(got_staging[5:], want_staging[5:])
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    # ---- every sharing unit gets a frame of its own again (the frames given up, then the spare ones) ---------
+    free = np.r_[o_freed[o_freed >= 0], want_freed[want_freed >= 0], np.setdiff1d(np.arange(n_slots), case.slot_tbl[case.slot_tbl >= 0])]
+    order = rng.permutation(len(shared))
+    ul = np.r_[shared[order], got[5:7], [case.n_uids + 9]].astype(np.int64)       # two units that share nothing, one bad
+    assert len(free) >= len(ul)
+    nf = free[:len(ul)].astype(np.int32)
+    back = torch.full((len(ul),), -7, dtype=torch.int32, device="cuda")
+    dev.n_bad.zero_()
+    kvm.kvm_dedup_unshare(dev.pool, dev.slot_tbl, dev.state, dev_of(ul), dev_of(nf), len(ul), refs, back,
+                          n_bad=dev.n_bad)
+    bad[:] = 0
+    o_back = oracle.dedup_unshare(k8, v8, uk, uv, tbl, st, ul, nf, o_refs, n_bad=bad)
+    torch.cuda.synchronize()
+    g_back = back.cpu().numpy()
+    # which item of the last readers of a frame reports it free is not defined: compare per frame
+    np.testing.assert_array_equal(np.sort(g_back), np.sort(o_back))
+    moved = np.arange(len(shared))
+    assert np.all((g_back[moved] == -1) | (g_back[moved] >= 0)) and np.array_equal(g_back[len(shared):], o_back[len(shared):])
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    assert not refs.any().item() and not o_refs.any() and not (st & SHARED).any()
+    assert int(dev.n_bad.item()) == int(bad[0]) == 1
+    gk, gv = dev.pools_host()
+    res = np.flatnonzero(st & RES)
+    np.testing.assert_array_equal(gk[tbl[res]], k8[tbl[res]])
+    if v8 is not None:
+        np.testing.assert_array_equal(gv[tbl[res]], v8[tbl[res]])
+    assert len(np.unique(tbl[res])) == len(res)
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step(dev.pool, dev.rows(), dev_of(q.view(np.int16)), scale, dev.mass, dev.ws)
+    torch.cuda.synchronize()
+    m_after = dev.mass.cpu().numpy()
+    # rows that lost a unit to the pack above are renormalised; every other unit reads the same bytes as at the start
+    case.k_pool[:] = k8.view(np.uint16).reshape(case.k_pool.shape)         # the pool as the oracle's unshare left it
+    want_after = oracle_score(oracle, case, q, scale, fill=-1.0, slot_tbl=tbl)
+    w = want_after != -1.0
+    np.testing.assert_array_equal(m_after != -1.0, w)
+    np.testing.assert_allclose(m_after[w], want_after[w], rtol=1e-3, atol=1e-9)
+
+
 def test_dedup_table_too_small_reports_it():
     from paper_2604_26968_amd import kvm
     rng = np.random.default_rng(7)
