@@ -37,6 +37,8 @@
 //     reductions for the block maximum and sum), and
 //   - the A operand of v_mfma_f32_16x16x32 for k-step kk (row = token, k = channel), so
 //     K goes from the load straight into the matrix core.
+#include <atomic>
+
 #include "kvm_internal.h"
 
 namespace kvm {
@@ -1764,8 +1766,17 @@ int launch_dot2_path(const ScoreArgs& a) {
 template <int G, int DIM, int DT>
 int launch_row_path(const ScoreArgs& a) {
     auto kern = score_row_kernel<G, DIM, DT>;
-    KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kRowLdsBytes));
+    // the kernel's 160 KB of dynamic LDS have to be allowed once per device (the attribute belongs to the
+    // function as loaded on that device); later calls, also under stream capture, only launch
+    static std::atomic<unsigned long long> allowed{0};
+    int dev = 0;
+    KVM_HIP_TRY(hipGetDevice(&dev));
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev > 63 || !(allowed.load(std::memory_order_acquire) & bit)) {
+        KVM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kRowLdsBytes));
+        if (dev <= 63) allowed.fetch_or(bit, std::memory_order_release);
+    }
     RowArgs ra{a.rows->slot_tbl, static_cast<const uint4*>(a.pool->k_pool), (uint32_t)a.pool->n_slots,
                static_cast<const uint16_t*>(a.q), a.scale, a.out.agg, a.out.mass, a.w.part};
     TimedLaunch tl("score_partial", a.st);
