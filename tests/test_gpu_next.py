@@ -883,6 +883,48 @@ def test_pack_in_two_parts_rides_along_with_scoring(oracle, shape, n_pairs, n_ou
     np.testing.assert_array_equal(dev.state.cpu().numpy(), st_f)
 
 
+def test_pack_begin_takes_its_count_from_the_device_and_moves_without_rows(oracle):
+    """kvm_pack_begin with a device-side list length shorter than the list (entries beyond it are left alone and
+    get -1), then the transfer in a launch that scores nothing (no rows): the records still arrive."""
+    from paper_2604_26968_amd import kvm
+    shape = synth.Shape(1, 4, 2, 64, synth.FP16, True, [512, 100])
+    case = synth.make_case(shape, seed=12)
+    k8, v8 = host_pools(case)
+    dev = DeviceCase(case)
+    uk, uv = shape.unit_k_bytes, shape.unit_v_bytes
+    rec = uk + uv
+    rng = np.random.default_rng(2)
+    res = np.flatnonzero(case.state & RES)
+    uids = rng.choice(res, size=20, replace=False).astype(np.int64)
+    n_dev = torch.tensor([13], dtype=torch.int64, device="cuda")
+    slots = np.arange(5, 25, dtype=np.int32)
+    n_tier = 30
+    d_tier = torch.zeros(n_tier * rec, dtype=torch.uint8).pin_memory()
+    frame = torch.full((20,), -5, dtype=torch.int32, device="cuda")
+    host = torch.full((20,), -5, dtype=torch.int64, device="cuda")
+    kvm.kvm_pack_begin(dev.pool, dev.slot_tbl, dev.state, dev_of(uids), 20, dev_of(slots), n_tier, frame, host,
+                       n_dev=n_dev, n_bad=dev.n_bad)
+    tbl, st = case.slot_tbl.copy(), case.state.copy()
+    want_staging, want_freed = oracle.pack(k8, v8, uk, uv, tbl, st, uids[:13], slots[:13])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(frame.cpu().numpy(), np.r_[want_freed, np.full(7, -1)])
+    np.testing.assert_array_equal(host.cpu().numpy(), np.r_[slots[:13].astype(np.int64) | kvm.XFER_OUT_ONLY, np.full(7, -1)])
+    np.testing.assert_array_equal(dev.slot_tbl.cpu().numpy(), tbl)
+    np.testing.assert_array_equal(dev.state.cpu().numpy(), st)
+    assert int(dev.n_bad.item()) == 0
+    none = kvm.make_rows(dev.row_ntok[:0], dev.row_off[:0], dev.row_q_off[:0], dev.slot_tbl, shape.g, 0)
+    q = torch.zeros(8, dtype=torch.int16, device="cuda")
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step_xfer(dev.pool, none, q, 1.0, dev.mass, dev.ws, frame, host, 20, d_tier)
+    torch.cuda.synchronize()
+    got = d_tier.numpy().reshape(n_tier, rec)
+    np.testing.assert_array_equal(got[slots[:13]], want_staging)
+    assert not got[np.setdiff1d(np.arange(n_tier), slots[:13])].any() and bool((dev.mass == -1.0).all())
+    gk, gv = dev.pools_host()
+    np.testing.assert_array_equal(gk, k8)
+    np.testing.assert_array_equal(gv, v8)
+
+
 def test_end_to_end_overlapped_exchange_dynamics(oracle):
     """The pass as the bench runs it by default, five steps on a twin of the Llama-3-8B-shaped workload:
     beta -> score (with the previous step's exchange bytes in the same launch) -> ema -> exchange_end ->
