@@ -307,7 +307,7 @@ int kvm_ema_update_ex(const kvm_rows_t* rows, const float* mass /* dev [n_uids] 
  * 4. Victim selection — the unit whose head-weighted importance is smallest goes
  *    first (section 3.4), generalised to the k smallest under a capacity budget.
  *
- * eligible = RESIDENT and not PROTECTED and SCORED.
+ * eligible = RESIDENT and SCORED and neither PROTECTED nor SHARED.
  * k = k_or_neg1 if >= 0, else max(0, #RESIDENT - budget_units);
  * k is then clipped to #eligible and to victims_cap.
  * Output: the k eligible uids smallest under the total order (prio, uid)
@@ -350,8 +350,9 @@ int kvm_select_victims_static(const float* prio /* dev [n_uids] */, const uint8_
  *   staging[i] = K frame `slot` (unit_k_bytes) followed by V frame `slot`
  *   (unit_v_bytes); freed_slots[i] = slot; slot_tbl[uid] = -1 - host_slots[i];
  *   state[uid]: clear RESIDENT, set ON_HOST.
- * Entries whose uid is outside [0, n_uids) or not resident (or whose slot is
- * outside the pool) move nothing, get freed_slots[i] = -1, leave their staging
+ * Entries whose uid is outside [0, n_uids), not resident or SHARED (a frame that
+ * other units read is never handed out; kvm_dedup_unshare first), or whose slot is
+ * outside the pool, move nothing, get freed_slots[i] = -1, leave their staging
  * record untouched and are counted in *n_bad.  uids must be distinct.
  * n_dev, if not NULL, is a device-side list length (e.g. kvm_select_victims'
  * n_victims): entries i >= *n_dev are ignored entirely (their freed_slots and
@@ -416,8 +417,8 @@ int kvm_swap(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t
  * No spare frame or host slot is used, so a prefetch list produced on the
  * device (kvm_prefetch_keys + kvm_select_victims) can be served without the
  * host gathering records first.  A pair is skipped and counted in *n_bad when
- * out is not resident, in is not on the host (or equals out), or a frame / slot
- * id is out of range.  Units must not repeat within or across the lists.
+ * out is not resident or is SHARED, in is not on the host (or equals out), or a
+ * frame / slot id is out of range.  Units must not repeat within or across the lists.
  * Errors: KVM_EINVAL, KVM_ESHAPE as kvm_pack.                               */
 int kvm_exchange(const kvm_pool_t* pool, int32_t* slot_tbl /* dev in/out */, uint8_t* state /* dev in/out */,
                  int64_t n_uids, const int64_t* out_uids /* dev [n] */, const int64_t* in_uids /* dev [n] */, int64_t n,
