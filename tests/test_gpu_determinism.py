@@ -159,8 +159,57 @@ def _whole_path(shape, seed):
                    freed[cnt:2 * cnt].contiguous(), sdev, host_b, n_bad=dev.n_bad)
     torch.cuda.synchronize()
     out.update(staging_a=torch.from_numpy(host_a.numpy().copy()), staging_b=torch.from_numpy(host_b.numpy().copy()),
-               staging_c=torch.from_numpy(host_c.numpy().copy()), freed=freed, tbl_final=dev.slot_tbl,
-               state_final=dev.state, k_pool_final=dev.k_pool, n_bad=dev.n_bad)
+               staging_c=torch.from_numpy(host_c.numpy().copy()), freed=freed.clone(), tbl_swapped=dev.slot_tbl.clone(),
+               state_swapped=dev.state.clone())
+
+    # eviction in two parts riding in a scoring launch, the selection with the built-in scratch
+    res_now = torch.nonzero(dev.state & RES).flatten()
+    res_now = res_now[(dev.state[res_now] & PROT) == 0]
+    e_uids = res_now[-29:].contiguous()
+    e_slots = torch.arange(n_tier - 29, n_tier, dtype=torch.int32, device="cuda")       # records nobody needs any more
+    e_frame = torch.full((29,), -1, dtype=torch.int32, device="cuda")
+    e_host = torch.full((29,), -1, dtype=torch.int64, device="cuda")
+    kvm.kvm_pack_begin(dev.pool, dev.slot_tbl, dev.state, e_uids, 29, e_slots, n_tier, e_frame, e_host, n_bad=dev.n_bad)
+    dev.mass.fill_(-1.0)
+    kvm.kvm_score_step_xfer(dev.pool, dev.rows(), q, scale, dev.mass, dev.ws, e_frame, e_host, 29, tier)
+    v2 = torch.full((n,), -1, dtype=torch.int64, device="cuda")
+    nv2 = torch.zeros(1, dtype=torch.int64, device="cuda")
+    kvm.kvm_select_victims_static(dev.prio, dev.state, v2, nv2, k=n // 7)
+    torch.cuda.synchronize()
+    out.update(e_frame=e_frame, e_host=e_host, mass_evict=dev.mass.clone(), victims_static=v2, n_victims_static=nv2,
+               tier_after_evict=torch.from_numpy(tier.numpy().copy()))
+
+    # frames shared by duplicates: copy the frames of a few units over others, hash, insert, share, unshare
+    res_now = torch.nonzero(dev.state & RES).flatten()
+    res_now = res_now[(dev.state[res_now] & PROT) == 0][:40].contiguous()
+    fr = dev.slot_tbl[res_now].long()
+    for grp in range(8):                                   # groups of five units with the content of their first
+        dev.k_pool[fr[5 * grp + 1:5 * grp + 5]] = dev.k_pool[fr[5 * grp]].clone()
+        if dev.v_pool is not None:
+            dev.v_pool[fr[5 * grp + 1:5 * grp + 5]] = dev.v_pool[fr[5 * grp]].clone()
+    d2 = torch.zeros((40, 32), dtype=torch.uint8, device="cuda")
+    kvm.kvm_hash_units(dev.pool, dev.slot_tbl, dev.state, res_now, 40, d2, n_bad=dev.n_bad)
+    store2 = kvm.make_store(1 << 8)
+    canon2 = torch.zeros(40, dtype=torch.int64, device="cuda")
+    kvm.kvm_dedup_insert(store2, d2, res_now, 40, canon2, torch.zeros(40, dtype=torch.int64, device="cuda"))
+    refs = torch.zeros(case.n_slots, dtype=torch.int32, device="cuda")
+    given = torch.full((40,), -9, dtype=torch.int32, device="cuda")
+    kvm.kvm_dedup_share(dev.slot_tbl, dev.state, case.n_slots, res_now, canon2, 40, refs, given, n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    out.update(canon2=canon2, given=given.clone(), refs_shared=refs.clone(), tbl_shared=dev.slot_tbl.clone(),
+               state_shared=dev.state.clone())
+    sharers = torch.nonzero((dev.state & 16) != 0).flatten().contiguous()
+    ns = sharers.numel()
+    new_frames = given[given >= 0]
+    extra = e_frame[e_frame >= 0]                          # frames the eviction above left free
+    new_frames = torch.cat([new_frames, extra])[:ns].contiguous()
+    back = torch.full((ns,), -9, dtype=torch.int32, device="cuda")
+    kvm.kvm_dedup_unshare(dev.pool, dev.slot_tbl, dev.state, sharers, new_frames, ns, refs, back, n_bad=dev.n_bad)
+    torch.cuda.synchronize()
+    # which of a frame's last readers reports it free may differ from run to run: compare the frames as a set
+    out.update(back_sorted=torch.sort(back).values, refs_final=refs, tbl_final=dev.slot_tbl, state_final=dev.state,
+               k_pool_final=dev.k_pool, n_bad=dev.n_bad)
+    assert ns == 40 and int((given >= 0).sum().item()) == 32 and not bool(refs.any().item())
     if dev.v_pool is not None:
         out["v_pool_final"] = dev.v_pool
     torch.cuda.synchronize()
